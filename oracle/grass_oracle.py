@@ -1,0 +1,242 @@
+"""Plain CPU oracle for per-sample gradient compression (GraSS / FactGraSS).
+
+TEST INFRASTRUCTURE ONLY: a slow, obviously-correct NumPy float64 statement of
+what the compression path computes, written from the paper.  It shares no code
+with the HIP kernels and must never be imported by the product package.
+
+Every function cites the passage of the paper it follows.  Where the paper
+leaves a choice to the implementer (which random generator, how ties and
+orders are resolved, normalisation) the choice is stated in the docstring as a
+"reading"; the same readings bind the GPU path.
+
+Pins (see tests/test_oracle_*.py): published splitmix64 outputs; brute force
+on tiny inputs; an explicitly materialised dense projection matrix; linearity;
+the Kronecker/vec identity of Eq. (2)/(3); closed-form first and second
+moments of the count-sketch norm; limits k'=p and k'=k of Sec. 3.3.1.
+Parity unpinned: absolute output values (the paper prints no worked example).
+"""
+from __future__ import annotations
+
+import numpy as np
+
+# ----------------------------------------------------------------------------
+# Counter-based random numbers.
+#
+# Reading (the paper only says indices and signs are "sampled", App. B.4.1):
+# all randomness comes from the splitmix64 generator (Steele, Lea, Flood,
+# "Fast splittable pseudorandom number generators", OOPSLA 2014; the constants
+# are those of the public-domain reference).  Its n-th output depends only on
+# seed + (n+1)*gamma, so any output can be computed without the earlier ones.
+# ----------------------------------------------------------------------------
+_U64 = np.uint64
+GOLDEN_GAMMA = _U64(0x9E3779B97F4A7C15)
+_MUL_A = _U64(0xBF58476D1CE4E5B9)
+_MUL_B = _U64(0x94D049BB133111EB)
+
+
+def _as_u64(a):
+    return np.atleast_1d(np.asarray(a, dtype=np.uint64))
+
+
+def _finalise(z):
+    """The splitmix64 output function (two xor-shift-multiply rounds and a
+    final xor-shift), on a uint64 array, arithmetic modulo 2**64."""
+    with np.errstate(over="ignore"):
+        z = (z ^ (z >> _U64(30))) * _MUL_A
+        z = (z ^ (z >> _U64(27))) * _MUL_B
+        return z ^ (z >> _U64(31))
+
+
+def splitmix64_sequence(seed: int, count: int) -> np.ndarray:
+    """First `count` outputs of the sequential splitmix64 generator whose
+    state starts at `seed`: state += gamma; output = finalise(state)."""
+    out = np.empty(count, dtype=np.uint64)
+    state = _as_u64(seed).copy()
+    with np.errstate(over="ignore"):
+        for i in range(count):
+            state = state + GOLDEN_GAMMA
+            out[i] = _finalise(state)[0]
+    return out
+
+
+def sm(seed, counter) -> np.ndarray:
+    """Counter form: the `counter`-th (0-based) output of splitmix64 seeded
+    with `seed`, i.e. finalise(seed + (counter+1)*gamma)."""
+    seed = _as_u64(seed)
+    counter = _as_u64(counter)
+    with np.errstate(over="ignore"):
+        return _finalise(seed + (counter + _U64(1)) * GOLDEN_GAMMA)
+
+
+def stream_hash(seed: int, stream: int, counter) -> np.ndarray:
+    """H(seed, stream, c) = sm(sm(seed, stream), c): an independent
+    sub-generator per `stream` id (mask, SJLT, per-layer roles)."""
+    sub = sm(seed, stream)[0]
+    return sm(sub, counter)
+
+
+# Stream ids (a reading; the paper names no generator).  General vectors use
+# 0 for the mask and 1 for the SJLT; linear layer l uses 16+4l (input mask),
+# 17+4l (output-gradient mask) and 18+4l (SJLT).
+STREAM_MASK = 0
+STREAM_SJLT = 1
+
+
+def layer_streams(layer: int):
+    return 16 + 4 * layer, 17 + 4 * layer, 18 + 4 * layer
+
+
+# ----------------------------------------------------------------------------
+# Random Mask (Sec. 3.2, "Random Mask"): a random subset of k' of the p
+# coordinates; as a matrix, a binary selection matrix with one non-repeating
+# non-zero per row.
+# ----------------------------------------------------------------------------
+def mask_indices(seed: int, stream: int, p: int, kprime: int) -> np.ndarray:
+    """Indices kept by the Random Mask, ascending, int32.
+
+    Reading: coordinate j draws key_j = H(seed, stream, j); the k' coordinates
+    with the smallest (key_j, j) pairs are kept (ties on the key go to the
+    smaller j), reported in ascending order of j.  This is a uniform draw
+    without replacement, independent of any evaluation order, and k' = p
+    returns 0..p-1 (the GraSS -> SJLT limit of Sec. 3.3.1).
+    """
+    if not (0 < kprime <= p):
+        raise ValueError("need 0 < k' <= p")
+    j = np.arange(p, dtype=np.uint64)
+    key = stream_hash(seed, stream, j)
+    order = np.lexsort((j, key))          # primary key, secondary j
+    kept = np.sort(order[:kprime])
+    return kept.astype(np.int32)
+
+
+def mask(g: np.ndarray, idx: np.ndarray) -> np.ndarray:
+    """Mask_k'(g) = M g: the sub-vector g[idx] of every row (Sec. 3.2).  No
+    rescaling is applied: the paper's M is binary."""
+    g = np.asarray(g)
+    return g[..., np.asarray(idx, dtype=np.int64)]
+
+
+# ----------------------------------------------------------------------------
+# SJLT (Sec. 3.1, "Sparse Johnson-Lindenstrauss Transform"): P has s non-zero
+# +-1 entries per column; equivalently scan g and let each g(j) add itself to,
+# or subtract itself from, s chosen output coordinates.
+# ----------------------------------------------------------------------------
+def sjlt_tables(seed: int, stream: int, d: int, k: int, s: int):
+    """bucket[j, r] in [0, k) and sign[j, r] in {+1, -1} for input position j
+    and r in [0, s).
+
+    Reading (block construction of the sparser-JL paper the text cites): s
+    divides k, m = k/s, and the r-th non-zero of column j falls in block r:
+        h      = H(seed, stream, j*s + r)
+        bucket = r*m + floor((h >> 32) * m / 2**32)
+        sign   = +1 if the lowest bit of h is 0, else -1
+    so that every column has exactly s non-zeros in distinct rows.
+    """
+    if s <= 0 or k <= 0 or k % s:
+        raise ValueError("need s >= 1 dividing k")
+    m = k // s
+    c = np.arange(d * s, dtype=np.uint64)
+    h = stream_hash(seed, stream, c).reshape(d, s)
+    hi = h >> _U64(32)
+    within = (hi * _U64(m)) >> _U64(32)                      # < m, no overflow: hi, m < 2**32
+    bucket = within + (np.arange(s, dtype=np.uint64) * _U64(m))[None, :]
+    sign = np.where((h & _U64(1)) == 0, 1, -1).astype(np.int8)
+    return bucket.astype(np.uint32), sign
+
+
+def sjlt_scan(g_row, bucket, sign, k: int) -> np.ndarray:
+    """The scan of Sec. 3.1 written out for one vector: start from zero, visit
+    j = 0..d-1, add sign*g(j)/sqrt(s) to each of its s buckets.  Pure Python:
+    small inputs only."""
+    d, s = bucket.shape
+    out = [0.0] * k
+    scale = 1.0 / np.sqrt(float(s))
+    for j in range(d):
+        v = float(g_row[j])
+        for r in range(s):
+            out[int(bucket[j, r])] += float(sign[j, r]) * v * scale
+    return np.asarray(out, dtype=np.float64)
+
+
+def sjlt(g: np.ndarray, k: int, s: int, seed: int, stream: int = STREAM_SJLT) -> np.ndarray:
+    """SJLT_k of every row of g (n x d) -> n x k float64, scale 1/sqrt(s) so
+    that squared norms are preserved in expectation.  Same scan as
+    `sjlt_scan`, carried out by NumPy's in-order unbuffered add."""
+    g = np.asarray(g, dtype=np.float64)
+    if g.ndim == 1:
+        return sjlt(g[None, :], k, s, seed, stream)[0]
+    n, d = g.shape
+    bucket, sign = sjlt_tables(seed, stream, d, k, s)
+    out = np.zeros((n, k), dtype=np.float64)
+    scale = 1.0 / np.sqrt(float(s))
+    for i in range(n):
+        for r in range(s):
+            np.add.at(out[i], bucket[:, r], sign[:, r] * g[i] * scale)
+    return out
+
+
+def grass(g: np.ndarray, idx: np.ndarray, k: int, s: int, seed: int,
+          stream: int = STREAM_SJLT) -> np.ndarray:
+    """GraSS = SJLT_k o Mask_k' (Sec. 3.3.1): sparsify to g' = g[idx], then
+    SJLT g'.  The SJLT sees only the k'-vector, so its hash key is the
+    position inside g', not the original coordinate."""
+    return sjlt(mask(g, idx), k, s, seed, stream)
+
+
+# ----------------------------------------------------------------------------
+# FactGraSS (Sec. 3.3.2, "Factorized GraSS"; Eq. (2), Eq. (3)).
+# ----------------------------------------------------------------------------
+def factgrass_sparsified_gradient(x: np.ndarray, gout: np.ndarray,
+                                  idx_in: np.ndarray, idx_out: np.ndarray) -> np.ndarray:
+    """Stages 1 and 2: mask every token's layer input x_t (d_in) and
+    pre-activation gradient g_t (d_out) separately, then sum over tokens the
+    Kronecker products (masked x_t) (x) (masked g_t).  x is (n, T, d_in), gout
+    is (n, T, d_out); returns n x (k_in' * k_out') with flat index
+    a'*k_out' + b' -- the order Eq. (2) gives vec(DW)."""
+    xs = np.asarray(x, dtype=np.float64)[..., np.asarray(idx_in, dtype=np.int64)]
+    gs = np.asarray(gout, dtype=np.float64)[..., np.asarray(idx_out, dtype=np.int64)]
+    n, T, ka = xs.shape
+    kb = gs.shape[-1]
+    v = np.zeros((n, ka * kb), dtype=np.float64)
+    for i in range(n):
+        for t in range(T):
+            v[i] += np.kron(xs[i, t], gs[i, t])
+    return v
+
+
+def factgrass_linear(x, gout, idx_in, idx_out, k: int, s: int, seed: int, stream: int) -> np.ndarray:
+    """FactGraSS for one linear layer: SJLT_k of the sparsified gradient; the
+    layer gradient itself (d_out x d_in) is never formed."""
+    v = factgrass_sparsified_gradient(x, gout, idx_in, idx_out)
+    return sjlt(v, k, s, seed, stream)
+
+
+# ----------------------------------------------------------------------------
+# Attribute stage (Sec. 2.1): all-pair inner products of compressed gradients,
+# without a preconditioner (GradDot).
+# ----------------------------------------------------------------------------
+def score(train: np.ndarray, test: np.ndarray) -> np.ndarray:
+    """scores[m, i] = <test_m, train_i>; train is N x K, test is M x K."""
+    return np.asarray(test, dtype=np.float64) @ np.asarray(train, dtype=np.float64).T
+
+
+# ----------------------------------------------------------------------------
+# Dense random projection baseline (Sec. 2.2): g_hat = P g with P handed in as
+# data (k x p), so that no transcendental function has to agree bit for bit.
+# ----------------------------------------------------------------------------
+def gauss_project(g: np.ndarray, P: np.ndarray) -> np.ndarray:
+    return np.asarray(g, dtype=np.float64) @ np.asarray(P, dtype=np.float64).T
+
+
+# ----------------------------------------------------------------------------
+# Error measure used by every parity test: per row, the largest absolute
+# difference divided by the largest absolute oracle value of that row.
+# (Element-wise relative error is meaningless for a signed sum that can cancel
+# to ~0 in individual buckets.)
+# ----------------------------------------------------------------------------
+def max_rel_err(got: np.ndarray, want: np.ndarray) -> float:
+    got = np.asarray(got, dtype=np.float64).reshape(-1, want.shape[-1])
+    want = np.asarray(want, dtype=np.float64).reshape(-1, want.shape[-1])
+    denom = np.abs(want).max(axis=1)
+    denom = np.where(denom == 0.0, 1.0, denom)
+    return float((np.abs(got - want).max(axis=1) / denom).max())
