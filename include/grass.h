@@ -1,0 +1,170 @@
+/* grass.h -- C ABI of the GraSS / FactGraSS per-sample gradient compression
+ * library for AMD MI355X (gfx950).
+ *
+ * Conventions shared by every entry point
+ *   - Pointers are DEVICE pointers unless the parameter name starts with
+ *     `host_`.  Matrices are row-major; `ld*` is the distance between rows in
+ *     ELEMENTS.  The caller owns every buffer; the library allocates nothing.
+ *   - Scratch memory is a caller-supplied workspace `ws` of at least the size
+ *     the matching `*_workspace_bytes` query returns for the same dimension
+ *     arguments (a query may return 0, then `ws` may be NULL).  Workspace
+ *     contents are undefined on return.  `ws` must be 256-byte aligned.
+ *   - Every call enqueues its kernels on `stream` (a hipStream_t passed as an
+ *     opaque pointer; NULL is the default stream) and returns without
+ *     synchronising.  Outputs are overwritten, never accumulated into, and
+ *     are valid once the stream has been synchronised.
+ *   - Errors are reported through the return value only.  All argument checks
+ *     run on the host before anything is launched, so a call that returns
+ *     GRASS_EINVAL, GRASS_EWORKSPACE or GRASS_EUNSUPPORTED has done nothing.
+ *     n == 0 is a successful no-op.  Index arrays (`idx*`) are trusted to be
+ *     ascending, distinct and in range; `grass_check_indices` verifies that.
+ *   - Randomness: every index, bucket and sign is a pure function of
+ *     (seed, stream_id, counter) through the splitmix64 generator
+ *         sm(seed, c)            = finalise(seed + (c + 1) * 0x9E3779B97F4A7C15)
+ *         H(seed, stream_id, c)  = sm(sm(seed, stream_id), c)
+ *     evaluated in registers; no table is ever stored on the hot path.
+ *     Suggested stream ids: 0 mask and 1 SJLT for general vectors; for linear
+ *     layer l, 16+4l input mask, 17+4l output-gradient mask, 18+4l SJLT.
+ *   - Determinism: integer outputs (indices, tables) are bit-reproducible.
+ *     Floating-point outputs use a fixed cross-block reduction order; inside
+ *     a block, additions into LDS buckets happen in hardware-arbitrated order,
+ *     so results can differ between runs in the last bits.
+ */
+#ifndef GRASS_H
+#define GRASS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GRASS_OK = 0,
+    GRASS_EINVAL = 1,       /* a size or pointer argument is invalid            */
+    GRASS_EWORKSPACE = 2,   /* workspace missing, misaligned or too small        */
+    GRASS_EHIP = 3,         /* the HIP runtime reported an error at launch       */
+    GRASS_EUNSUPPORTED = 4  /* valid request outside what the kernels cover      */
+} grass_status;
+
+typedef void* grass_stream;
+
+/* Largest SJLT output dimension k the LDS-resident accumulators cover. */
+#define GRASS_MAX_K 32768u
+/* Largest masked factor width (k_in', k_out') of factgrass_linear. */
+#define GRASS_MAX_FACTOR 128u
+
+const char* grass_strerror(int status);
+int grass_version(void);
+
+/* ---------------------------------------------------------------- Random Mask
+ * Sec. 3.2 "Random Mask": keep a uniformly random subset of k' of the p
+ * coordinates.  Coordinate j draws key_j = H(seed, stream_id, j); the k'
+ * smallest (key_j, j) pairs are kept and written to idx[0..k') in ascending
+ * order of j (k' == p yields 0..p-1).  p < 2^31.
+ * One-time set-up per (seed, stream_id, p, k').                              */
+grass_status grass_mask_indices_workspace_bytes(uint64_t p, uint32_t kprime, size_t* host_bytes);
+grass_status grass_mask_indices(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t kprime,
+                                int32_t* idx, void* ws, size_t ws_bytes, grass_stream stream);
+
+/* Debug helper: *host_ok = 1 iff idx[0..kprime) is strictly ascending and
+ * within [0, p).  Synchronises the stream.                                   */
+grass_status grass_check_indices(const int32_t* idx, uint32_t kprime, uint64_t p, int* host_ok,
+                                 grass_stream stream);
+
+/* Sec. 3.2: Mask_k'(g) = M g, the sub-vector g[idx] of every row (Random Mask
+ * or Selective Mask indices, supplied by the caller).
+ * g: n x p fp32 (ldg >= p); out: n x kprime fp32 (ldo >= kprime).            */
+grass_status grass_mask(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
+                        const int32_t* idx, uint32_t kprime,
+                        float* out, uint64_t ldo, grass_stream stream);
+
+/* ----------------------------------------------------------------------- SJLT
+ * Sec. 3.1 "Sparse Johnson-Lindenstrauss Transform": out = P g with s
+ * non-zeros of magnitude 1/sqrt(s) per column of P.  s must divide k; with
+ * m = k/s, the r-th non-zero (r in [0,s)) of input position j is
+ *     h = H(seed, stream_id, j*s + r);  row = r*m + floor((h >> 32) * m / 2^32);
+ *     sign = +1 if (h & 1) == 0 else -1.
+ *
+ * grass_sjlt_tables writes these for j in [0,d): bucket[j*s + r], sign[j*s + r]
+ * (tests and inspection only; the hot path recomputes them in registers).    */
+grass_status grass_sjlt_tables(uint64_t seed, uint64_t stream_id, uint64_t d, uint32_t k, uint32_t s,
+                               uint32_t* bucket, int8_t* sign, grass_stream stream);
+
+/* grass_sjlt: idx == NULL  -> SJLT_k of every row of g (n x p), input dim p.
+ *             idx != NULL  -> GraSS = SJLT_k o Mask_k' (Sec. 3.3.1), fused: the
+ *                             masked vector g[:, idx] (k' entries) is never
+ *                             written; the hash key is the position inside it.
+ * g: n x p fp32, ldg >= p.  kprime is ignored when idx == NULL.
+ * out: n x k fp32, ldo >= k.  k <= GRASS_MAX_K.
+ * Fastest when g and ldg are 16-byte aligned (ldg % 4 == 0); any alignment
+ * of at least 4 bytes works.                                                 */
+grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint32_t kprime_or_0,
+                                        uint32_t k, uint32_t s, size_t* host_bytes);
+grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
+                        const int32_t* idx, uint32_t kprime,
+                        uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                        float* out, uint64_t ldo,
+                        void* ws, size_t ws_bytes, grass_stream stream);
+
+/* ------------------------------------------------------------------ FactGraSS
+ * Sec. 3.3.2 "Factorized GraSS" for one linear layer, using Eq. (2)/(3):
+ *   1. mask every token's layer input x_t (d_in) to idx_in (k_in' entries) and
+ *      its pre-activation gradient g_t (d_out) to idx_out (k_out' entries);
+ *   2. v[a*k_out' + b] = sum_t x_t[idx_in[a]] * g_t[idx_out[b]]  (fp32 accumulate
+ *      of exact bf16 products; the d_out x d_in gradient is never formed);
+ *   3. out_i = SJLT_k(v) with input dimension k_in'*k_out' (hash as above).
+ * x: (n, T, d_in) bf16, gout: (n, T, d_out) bf16, both contiguous.
+ * out: n x k fp32 with row distance ldo (lets the caller place layer l at a
+ * column offset of a concatenated row).  k_in', k_out' <= GRASS_MAX_FACTOR.  */
+grass_status factgrass_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
+                                              uint32_t k, uint32_t s, size_t* host_bytes);
+grass_status factgrass_linear(const void* x, const void* gout,
+                              uint64_t n, uint64_t T, uint32_t d_in, uint32_t d_out,
+                              const int32_t* idx_in, uint32_t kin_p,
+                              const int32_t* idx_out, uint32_t kout_p,
+                              uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                              float* out, uint64_t ldo,
+                              void* ws, size_t ws_bytes, grass_stream stream);
+
+/* ---------------------------------------------------------------------- score
+ * Sec. 2.1, attribute stage: scores[m, i] = <test_m, train_i> for all pairs of
+ * compressed gradients (no preconditioner).
+ * train: N x K fp32 (ld_train >= K), test: M x K fp32, scores: M x N fp32.
+ * compute_mode 0: fp32 MFMA.  1: inputs rounded to bf16 (nearest-even) on
+ * load, bf16 MFMA with fp32 accumulation.                                    */
+grass_status grass_score(const float* train, const float* test, int compute_mode,
+                         uint64_t N, uint64_t M, uint64_t K,
+                         uint64_t ld_train, uint64_t ld_test,
+                         float* scores, uint64_t ld_scores, grass_stream stream);
+
+/* ---------------------------------------------- dense Gaussian baseline (Sec. 2.2)
+ * g_hat = P g with P (k x p), P_ab ~ N(0, 1/k), generated from the counter
+ * hash by Box-Muller: entry (a, b) uses H(seed, stream_id, a*p + b).
+ * grass_gauss_matrix writes columns [p0, p0+pc) of P as a k x pc fp32 matrix
+ * (ldP >= pc); grass_gauss_project computes out = g P^T (n x k fp32) in
+ * p-chunks of at most p_chunk columns, regenerating P chunk by chunk in the
+ * workspace.  compute_mode as in grass_score.                                */
+grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t k,
+                                uint64_t p0, uint64_t pc, float* P, uint64_t ldP, grass_stream stream);
+grass_status grass_gauss_project_workspace_bytes(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk,
+                                                 size_t* host_bytes);
+grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
+                                 uint32_t k, uint64_t seed, uint64_t stream_id,
+                                 uint64_t p_chunk, int compute_mode,
+                                 float* out, uint64_t ldo,
+                                 void* ws, size_t ws_bytes, grass_stream stream);
+
+/* ------------------------------------------------------------------- tuning
+ * Overrides the launch heuristics of grass_sjlt for experiments: rows per
+ * block (1,2,4,8), column chunks per row group and threads per block
+ * (256,512,1024); 0 restores the heuristic for that field.  Process-wide.    */
+void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads);
+/* Same for factgrass_linear: tokens per block (multiple of 32; 0 = heuristic). */
+void grass_set_factgrass_tuning(int tokens_per_block);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRASS_H */

@@ -1,0 +1,242 @@
+"""ctypes binding of libgrass.so: argument marshalling only.
+
+Every function mirrors one C entry point of include/grass.h with the same
+name.  Tensors are torch CUDA (ROCm) tensors used purely as device memory;
+their `data_ptr()` and the current HIP stream are handed to the library.  No
+step of the compression path runs in Python or in torch ops, and there is no
+fallback: if the library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libgrass.so")
+
+GRASS_OK, GRASS_EINVAL, GRASS_EWORKSPACE, GRASS_EHIP, GRASS_EUNSUPPORTED = range(5)
+GRASS_MAX_K = 32768
+GRASS_MAX_FACTOR = 128
+
+_u64, _u32, _sz, _vp, _int = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int
+
+# name -> (restype, argtypes); the list the ABI test checks against the header.
+SIGNATURES = {
+    "grass_strerror": (ctypes.c_char_p, [_int]),
+    "grass_version": (_int, []),
+    "grass_mask_indices_workspace_bytes": (_int, [_u64, _u32, ctypes.POINTER(_sz)]),
+    "grass_mask_indices": (_int, [_u64, _u64, _u64, _u32, _vp, _vp, _sz, _vp]),
+    "grass_check_indices": (_int, [_vp, _u32, _u64, ctypes.POINTER(_int), _vp]),
+    "grass_mask": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _vp, _u64, _vp]),
+    "grass_sjlt_tables": (_int, [_u64, _u64, _u64, _u32, _u32, _vp, _vp, _vp]),
+    "grass_sjlt_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
+    "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
+    "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
+    "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
+                                _vp, _u64, _vp, _sz, _vp]),
+    "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
+    "grass_gauss_matrix": (_int, [_u64, _u64, _u64, _u32, _u64, _u64, _vp, _u64, _vp]),
+    "grass_gauss_project_workspace_bytes": (_int, [_u64, _u64, _u32, _u64, ctypes.POINTER(_sz)]),
+    "grass_gauss_project": (_int, [_vp, _u64, _u64, _u64, _u32, _u64, _u64, _u64, _int, _vp, _u64, _vp, _sz, _vp]),
+    "grass_set_sjlt_tuning": (None, [_int, _int, _int]),
+    "grass_set_factgrass_tuning": (None, [_int]),
+}
+
+_lib = None
+
+
+class GrassError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+def load_library() -> ctypes.CDLL:
+    """Loads libgrass.so from the package directory.  Raises if it was not built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2505_18976_amd.build` "
+            "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    for name, (res, args) in SIGNATURES.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def strerror(status: int) -> str:
+    return load_library().grass_strerror(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != GRASS_OK:
+        raise GrassError(status, where)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(0 if t is None else t.data_ptr())
+
+
+def _ld(t: torch.Tensor) -> int:
+    assert t.dim() == 2 and t.stride(1) == 1, "row-major matrix expected"
+    return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def _workspace(nbytes: int, device) -> torch.Tensor | None:
+    if nbytes == 0:
+        return None
+    return torch.empty(nbytes, dtype=torch.uint8, device=device)   # torch allocations are >= 256-byte aligned
+
+
+def grass_version() -> int:
+    return load_library().grass_version()
+
+
+def grass_mask_indices_workspace_bytes(p: int, kprime: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_mask_indices_workspace_bytes(p, kprime, ctypes.byref(out)),
+           "grass_mask_indices_workspace_bytes")
+    return out.value
+
+
+def grass_mask_indices(seed: int, stream_id: int, p: int, kprime: int, device="cuda") -> torch.Tensor:
+    ws = _workspace(grass_mask_indices_workspace_bytes(p, kprime), device)
+    idx = torch.empty(kprime, dtype=torch.int32, device=device)
+    _check(load_library().grass_mask_indices(seed, stream_id, p, kprime, _ptr(idx), _ptr(ws),
+                                             0 if ws is None else ws.numel(), _stream()), "grass_mask_indices")
+    return idx
+
+
+def grass_check_indices(idx: torch.Tensor, p: int) -> bool:
+    ok = _int(0)
+    _check(load_library().grass_check_indices(_ptr(idx), idx.numel(), p, ctypes.byref(ok), _stream()),
+           "grass_check_indices")
+    return bool(ok.value)
+
+
+def grass_mask(g: torch.Tensor, idx: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    assert g.dtype == torch.float32 and idx.dtype == torch.int32
+    n, p = g.shape
+    kprime = idx.numel()
+    if out is None:
+        out = torch.empty((n, kprime), dtype=torch.float32, device=g.device)
+    _check(load_library().grass_mask(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, _ptr(out), _ld(out), _stream()),
+           "grass_mask")
+    return out
+
+
+def grass_sjlt_tables(seed: int, stream_id: int, d: int, k: int, s: int, device="cuda"):
+    bucket = torch.empty((d, s), dtype=torch.int32, device=device)     # uint32 payload
+    sign = torch.empty((d, s), dtype=torch.int8, device=device)
+    _check(load_library().grass_sjlt_tables(seed, stream_id, d, k, s, _ptr(bucket), _ptr(sign), _stream()),
+           "grass_sjlt_tables")
+    return bucket, sign
+
+
+def grass_sjlt_workspace_bytes(n: int, p: int, kprime_or_0: int, k: int, s: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_sjlt_workspace_bytes(n, p, kprime_or_0, k, s, ctypes.byref(out)),
+           "grass_sjlt_workspace_bytes")
+    return out.value
+
+
+def grass_sjlt(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, idx: torch.Tensor | None = None,
+               out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """SJLT_k of the rows of g, or fused GraSS when idx is given."""
+    assert g.dtype == torch.float32
+    n, p = g.shape
+    kprime = 0 if idx is None else idx.numel()
+    if out is None:
+        out = torch.empty((n, k), dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s), g.device)
+    _check(load_library().grass_sjlt(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
+                                     _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "grass_sjlt")
+    return out
+
+
+def factgrass_linear_workspace_bytes(n: int, T: int, kin_p: int, kout_p: int, k: int, s: int) -> int:
+    out = _sz(0)
+    _check(load_library().factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, k, s, ctypes.byref(out)),
+           "factgrass_linear_workspace_bytes")
+    return out.value
+
+
+def factgrass_linear(x: torch.Tensor, gout: torch.Tensor, idx_in: torch.Tensor, idx_out: torch.Tensor,
+                     k: int, s: int, seed: int, stream_id: int, out: torch.Tensor | None = None,
+                     ws: torch.Tensor | None = None) -> torch.Tensor:
+    assert x.dtype == torch.bfloat16 and gout.dtype == torch.bfloat16
+    assert x.is_contiguous() and gout.is_contiguous()
+    n, T, d_in = x.shape
+    d_out = gout.shape[2]
+    assert gout.shape[0] == n and gout.shape[1] == T
+    if out is None:
+        out = torch.empty((n, k), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(factgrass_linear_workspace_bytes(n, T, idx_in.numel(), idx_out.numel(), k, s), x.device)
+    _check(load_library().factgrass_linear(_ptr(x), _ptr(gout), n, T, d_in, d_out, _ptr(idx_in), idx_in.numel(),
+                                           _ptr(idx_out), idx_out.numel(), k, s, seed, stream_id, _ptr(out),
+                                           _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "factgrass_linear")
+    return out
+
+
+def grass_score(train: torch.Tensor, test: torch.Tensor, compute_mode: int = 0,
+                out: torch.Tensor | None = None) -> torch.Tensor:
+    assert train.dtype == torch.float32 and test.dtype == torch.float32
+    N, K = train.shape
+    M = test.shape[0]
+    assert test.shape[1] == K
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=train.device)
+    _check(load_library().grass_score(_ptr(train), _ptr(test), compute_mode, N, M, K, _ld(train), _ld(test),
+                                      _ptr(out), _ld(out), _stream()), "grass_score")
+    return out
+
+
+def grass_gauss_matrix(seed: int, stream_id: int, p: int, k: int, p0: int, pc: int, device="cuda") -> torch.Tensor:
+    P = torch.empty((k, pc), dtype=torch.float32, device=device)
+    _check(load_library().grass_gauss_matrix(seed, stream_id, p, k, p0, pc, _ptr(P), _ld(P), _stream()),
+           "grass_gauss_matrix")
+    return P
+
+
+def grass_gauss_project_workspace_bytes(n: int, p: int, k: int, p_chunk: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_gauss_project_workspace_bytes(n, p, k, p_chunk, ctypes.byref(out)),
+           "grass_gauss_project_workspace_bytes")
+    return out.value
+
+
+def grass_gauss_project(g: torch.Tensor, k: int, seed: int, stream_id: int, p_chunk: int, compute_mode: int = 0,
+                        out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    assert g.dtype == torch.float32
+    n, p = g.shape
+    if out is None:
+        out = torch.empty((n, k), dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = _workspace(grass_gauss_project_workspace_bytes(n, p, k, p_chunk), g.device)
+    _check(load_library().grass_gauss_project(_ptr(g), n, p, _ld(g), k, seed, stream_id, p_chunk, compute_mode,
+                                              _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(),
+                                              _stream()), "grass_gauss_project")
+    return out
+
+
+def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0) -> None:
+    load_library().grass_set_sjlt_tuning(rows_per_block, column_chunks, threads)
+
+
+def grass_set_factgrass_tuning(tokens_per_block: int = 0) -> None:
+    load_library().grass_set_factgrass_tuning(tokens_per_block)

@@ -1,0 +1,257 @@
+// FactGraSS for one linear layer (Sec. 3.3.2, Eq. (2) and Eq. (3)).
+//
+// Stage 1 (sparsification): gather k_in' columns of every token's layer input
+// and k_out' columns of its pre-activation gradient.  Stage 2 (reconstruction):
+// v[a*k_out' + b] = sum_t x'_t[a] * g'_t[b], a (k_in' x T)(T x k_out') contraction
+// done on the matrix cores in bf16 with fp32 accumulation.  Stage 3 (sparse
+// projection): SJLT of the k_in'*k_out' accumulator straight from registers into
+// k LDS buckets.  The d_out x d_in layer gradient is never formed.
+//
+// A workgroup (4 wavefronts) owns one sample and one chunk of its tokens.
+// Because the SJLT is linear, each chunk is projected on its own and the
+// per-chunk k-vectors are added in a fixed order by a second kernel.
+#include "grass_device.h"
+
+namespace grass {
+
+static int g_tune_tokens = 0;
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kTokTile = 32;              // tokens staged per step (two MFMA k-steps of 16)
+constexpr int kTokStride = kTokTile + 8;  // bf16 elements per LDS row: 80 bytes keeps 16-byte reads conflict-free
+constexpr int kFgThreads = 256;
+
+struct FgArgs {
+    const uint16_t* x;      // (n, T, d_in) bf16 bits
+    const uint16_t* g;      // (n, T, d_out) bf16 bits
+    const int32_t* idx_in;
+    const int32_t* idx_out;
+    float* dst;
+    uint64_t T;
+    uint64_t ld_dst, chunk_stride;
+    uint64_t sub;
+    uint32_t d_in, d_out, ka, kb;
+    uint32_t k, s, m;
+    uint32_t tokens_per_block;
+    float scale;
+};
+
+// TA, TB: number of 32-wide tiles covering k_in' and k_out'.
+template <int TA, int TB>
+__global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                 // [TA*32][kTokStride]
+    uint16_t* gs = xs + TA * 32 * kTokStride;                          // [TB*32][kTokStride]
+    float* sk = reinterpret_cast<float*>(smem);                        // [k], reuses the staging area afterwards
+
+    constexpr int KA = TA * 32, KB = TB * 32;
+    constexpr int NT = TA * TB;                    // output tiles
+    constexpr int TPW = (NT + 3) / 4;              // tiles per wavefront
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint64_t sample = blockIdx.y;
+    const uint64_t t_begin = (uint64_t)blockIdx.x * a.tokens_per_block;
+    const uint64_t t_end = t_begin + a.tokens_per_block < a.T ? t_begin + a.tokens_per_block : a.T;
+
+    // each thread gathers a fixed column of x and a fixed column of g
+    const int xa = tid % KA, xt0 = tid / KA;       // kFgThreads % KA == 0
+    const int gb = tid % KB, gt0 = tid / KB;
+    constexpr int XSTEP = kFgThreads / KA, GSTEP = kFgThreads / KB;
+    const int32_t xcol = (uint32_t)xa < a.ka ? a.idx_in[xa] : -1;
+    const int32_t gcol = (uint32_t)gb < a.kb ? a.idx_out[gb] : -1;
+    const uint16_t* xrow = a.x + sample * a.T * a.d_in;
+    const uint16_t* grow = a.g + sample * a.T * a.d_out;
+
+    f32x16 acc[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+
+    for (uint64_t t0 = t_begin; t0 < t_end; t0 += kTokTile) {
+        uint16_t xv[kTokTile / XSTEP], gv[kTokTile / GSTEP];
+#pragma unroll
+        for (int i = 0; i < kTokTile / XSTEP; ++i) {
+            const uint64_t t = t0 + xt0 + i * XSTEP;
+            xv[i] = (xcol >= 0 && t < t_end) ? xrow[t * a.d_in + xcol] : (uint16_t)0;
+        }
+#pragma unroll
+        for (int i = 0; i < kTokTile / GSTEP; ++i) {
+            const uint64_t t = t0 + gt0 + i * GSTEP;
+            gv[i] = (gcol >= 0 && t < t_end) ? grow[t * a.d_out + gcol] : (uint16_t)0;
+        }
+        __syncthreads();   // previous tile's MFMA reads are done
+#pragma unroll
+        for (int i = 0; i < kTokTile / XSTEP; ++i) xs[xa * kTokStride + xt0 + i * XSTEP] = xv[i];
+#pragma unroll
+        for (int i = 0; i < kTokTile / GSTEP; ++i) gs[gb * kTokStride + gt0 + i * GSTEP] = gv[i];
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < TPW; ++i) {
+            const int tile = wave + 4 * i;
+            if (tile < NT) {
+                const int ta = tile / TB, tb = tile % TB;
+#pragma unroll
+                for (int ks = 0; ks < kTokTile / 16; ++ks) {
+                    const bf16x8 af = *reinterpret_cast<const bf16x8*>(
+                        xs + (ta * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
+                    const bf16x8 bf = *reinterpret_cast<const bf16x8*>(
+                        gs + (tb * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
+                    acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[i], 0, 0, 0);
+                }
+            }
+        }
+    }
+    __syncthreads();
+    for (uint32_t b = tid; b < a.k; b += kFgThreads) sk[b] = 0.0f;
+    __syncthreads();
+
+    // SJLT of this chunk's partial v.  Accumulator element e of a lane sits at
+    // row (a') = 8*(e/4) + 4*(lane/32) + e%4 and column (b') = lane%32 of its tile.
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+        const int tile = wave + 4 * i;
+        if (tile < NT) {
+            const int ta = tile / TB, tb = tile % TB;
+            const uint32_t bq = tb * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const uint32_t aq = ta * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const float val = acc[i][e];
+                if (aq < a.ka && bq < a.kb && val != 0.0f) {
+                    uint64_t c = ((uint64_t)aq * a.kb + bq) * a.s;
+                    for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
+                        const uint64_t h = sm(a.sub, c);
+                        const uint32_t bucket = rr * a.m + bucket_of(h, a.m);
+                        __hip_atomic_fetch_add(sk + bucket, __uint_as_float(__float_as_uint(val) ^ signbit_of(h)),
+                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    float* o = a.dst + (uint64_t)blockIdx.x * a.chunk_stride + sample * a.ld_dst;
+    for (uint32_t b = tid; b < a.k; b += kFgThreads) o[b] = sk[b] * a.scale;
+}
+
+struct FgPlan {
+    int TA, TB;
+    uint32_t tokens_per_block, chunks;
+    size_t lds_bytes, ws_bytes;
+};
+
+static int tiles_for(uint32_t kq) { return kq <= 32 ? 1 : (kq <= 64 ? 2 : 4); }
+
+static bool plan_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, FgPlan* pl) {
+    if (ka == 0 || kb == 0 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR) return false;
+    pl->TA = tiles_for(ka);
+    pl->TB = tiles_for(kb);
+    // tokens per workgroup: aim at two workgroups per CU, never below one staging tile
+    uint64_t tpb = T;
+    const uint64_t want_chunks = ceil_div(2 * kNumCU, n);
+    if (want_chunks > 1) tpb = ceil_div(T, want_chunks);
+    tpb = ceil_div(tpb, kTokTile) * kTokTile;
+    if (g_tune_tokens > 0) tpb = ceil_div((uint64_t)g_tune_tokens, kTokTile) * kTokTile;
+    uint64_t chunks = ceil_div(T, tpb);
+    if (chunks > 65535) { chunks = 65535; tpb = ceil_div(ceil_div(T, chunks), kTokTile) * kTokTile; chunks = ceil_div(T, tpb); }
+    pl->tokens_per_block = (uint32_t)tpb;
+    pl->chunks = (uint32_t)chunks;
+    const size_t stage = (size_t)(pl->TA + pl->TB) * 32 * kTokStride * sizeof(uint16_t);
+    const size_t buckets = (size_t)k * sizeof(float);
+    pl->lds_bytes = stage > buckets ? stage : buckets;
+    pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * sizeof(float) : 0;
+    return pl->lds_bytes <= kLdsBytes - 1024;
+}
+
+template <int TA, int TB>
+static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
+    auto kern = factgrass_kernel<TA, TB>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(pl.chunks, (uint32_t)n), dim3(kFgThreads), pl.lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace grass
+
+using namespace grass;
+
+extern "C" void grass_set_factgrass_tuning(int tokens_per_block) { g_tune_tokens = tokens_per_block; }
+
+static grass_status check_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, uint32_t s) {
+    if (T == 0 || ka == 0 || kb == 0 || k == 0 || s == 0 || k % s != 0) return GRASS_EINVAL;
+    if (n > 65535 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR || k > GRASS_MAX_K) return GRASS_EUNSUPPORTED;
+    return GRASS_OK;
+}
+
+extern "C" grass_status factgrass_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
+                                                         uint32_t k, uint32_t s, size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) { *host_bytes = 0; return GRASS_OK; }
+    FgPlan pl;
+    if (!plan_fg(n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    *host_bytes = pl.ws_bytes;
+    return GRASS_OK;
+}
+
+extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64_t n, uint64_t T, uint32_t d_in,
+                                         uint32_t d_out, const int32_t* idx_in, uint32_t kin_p,
+                                         const int32_t* idx_out, uint32_t kout_p, uint32_t k, uint32_t s,
+                                         uint64_t seed, uint64_t stream_id, float* out, uint64_t ldo, void* ws,
+                                         size_t ws_bytes, grass_stream stream) {
+    grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
+    if (st != GRASS_OK) return st;
+    if (kin_p > d_in || kout_p > d_out) return GRASS_EINVAL;
+    if (n == 0) return GRASS_OK;
+    if (!x || !gout || !idx_in || !idx_out || !out || ldo < k) return GRASS_EINVAL;
+    FgPlan pl;
+    if (!plan_fg(n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
+
+    FgArgs a;
+    a.x = static_cast<const uint16_t*>(x);
+    a.g = static_cast<const uint16_t*>(gout);
+    a.idx_in = idx_in; a.idx_out = idx_out;
+    a.T = T; a.d_in = d_in; a.d_out = d_out; a.ka = kin_p; a.kb = kout_p;
+    a.k = k; a.s = s; a.m = k / s;
+    a.sub = substream(seed, stream_id);
+    a.tokens_per_block = pl.tokens_per_block;
+    const float scale = 1.0f / sqrtf((float)s);
+    if (pl.chunks == 1) {
+        a.dst = out; a.ld_dst = ldo; a.chunk_stride = 0; a.scale = scale;
+    } else {
+        a.dst = static_cast<float*>(ws); a.ld_dst = k; a.chunk_stride = n * k; a.scale = 1.0f;
+    }
+    hipStream_t hs = as_stream(stream);
+    hipError_t e = hipErrorInvalidValue;
+    const int key = pl.TA * 10 + pl.TB;
+    switch (key) {
+        case 11: e = launch_fg<1, 1>(a, pl, n, hs); break;
+        case 12: e = launch_fg<1, 2>(a, pl, n, hs); break;
+        case 14: e = launch_fg<1, 4>(a, pl, n, hs); break;
+        case 21: e = launch_fg<2, 1>(a, pl, n, hs); break;
+        case 22: e = launch_fg<2, 2>(a, pl, n, hs); break;
+        case 24: e = launch_fg<2, 4>(a, pl, n, hs); break;
+        case 41: e = launch_fg<4, 1>(a, pl, n, hs); break;
+        case 42: e = launch_fg<4, 2>(a, pl, n, hs); break;
+        case 44: e = launch_fg<4, 4>(a, pl, n, hs); break;
+        default: return GRASS_EUNSUPPORTED;
+    }
+    if (e != hipSuccess) return GRASS_EHIP;
+    if (pl.chunks > 1) {
+        const uint64_t total = n * k;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, hs,
+                           static_cast<const float*>(ws), n, k, pl.chunks, scale, out, ldo);
+        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+    }
+    return GRASS_OK;
+}

@@ -1,0 +1,67 @@
+// Shared device/host helpers of the GraSS kernels: the counter hash, status
+// plumbing and small launch utilities.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "grass.h"
+
+namespace grass {
+
+// splitmix64 (Steele, Lea, Flood 2014).  The paper only says that indices and
+// signs are sampled (App. B.4.1); every random choice here is the c-th output
+// of the generator seeded with a per-role sub-seed, computed in registers.
+constexpr uint64_t kGamma = 0x9E3779B97F4A7C15ull;
+
+__host__ __device__ __forceinline__ uint64_t finalise(uint64_t z) {
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+}
+
+// c-th output (0-based) of the generator seeded with `seed`.
+__host__ __device__ __forceinline__ uint64_t sm(uint64_t seed, uint64_t c) {
+    return finalise(seed + (c + 1) * kGamma);
+}
+
+// Sub-seed of a stream: H(seed, stream, c) = sm(substream(seed, stream), c).
+inline uint64_t substream(uint64_t seed, uint64_t stream_id) { return sm(seed, stream_id); }
+
+// Bucket inside a block of m rows and sign bit (already shifted to bit 31)
+// from one hash value (Sec. 3.1: each input coordinate picks its output
+// coordinates and whether to add or subtract).
+__device__ __forceinline__ uint32_t bucket_of(uint64_t h, uint32_t m) {
+    return __umulhi((uint32_t)(h >> 32), m);
+}
+__device__ __forceinline__ uint32_t signbit_of(uint64_t h) { return ((uint32_t)h & 1u) << 31; }
+
+inline hipStream_t as_stream(grass_stream s) { return reinterpret_cast<hipStream_t>(s); }
+
+inline grass_status launch_status() {
+    return hipGetLastError() == hipSuccess ? GRASS_OK : GRASS_EHIP;
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+inline uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
+
+// out[i, b] = scale * sum_c partial[c][i][b] with c ascending: the fixed-order
+// cross-workgroup reduction used instead of global floating-point atomics.
+static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float* partial, uint64_t n, uint32_t k,
+                                                                     uint32_t chunks, float scale, float* out,
+                                                                     uint64_t ldo) {
+    const uint64_t total = n * k;
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const uint64_t i = t / k;
+    const uint32_t b = (uint32_t)(t - i * k);
+    float sum = 0.0f;
+    for (uint32_t c = 0; c < chunks; ++c) sum += partial[(uint64_t)c * total + t];
+    out[i * ldo + b] = sum * scale;
+}
+
+constexpr int kNumCU = 256;                 // MI355X
+constexpr size_t kLdsBytes = 160 * 1024;    // per CU and per workgroup on gfx950
+
+}  // namespace grass

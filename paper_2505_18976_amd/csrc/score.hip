@@ -1,0 +1,309 @@
+// Dense contractions on the matrix cores: the attribute-stage score GEMM
+// (Sec. 2.1: all-pair inner products of compressed gradients) and the dense
+// Gaussian projection baseline (Sec. 2.2: g_hat = P g, P_ij ~ N(0, 1/k)).
+//
+// Both are C[M x N] (+)= A[M x K] * B[N x K]^T with A and B row-major and K
+// contiguous ("NT" GEMM).  A workgroup of 4 wavefronts (2 x 2) computes a
+// 128 x 128 tile of C; each wavefront owns 64 x 64 = 2 x 2 MFMA tiles of 32 x 32.
+// K is consumed in slices of 32 staged through LDS, with the next slice
+// prefetched into registers while the current one feeds the MFMAs.
+//   mode 0: v_mfma_f32_32x32x2_f32, LDS holds fp32 laid out [k][m].
+//   mode 1: operands rounded to bf16 (nearest even) when staged,
+//           v_mfma_f32_32x32x16_bf16 with fp32 accumulation, LDS laid out [m][k].
+// Workgroup ids are remapped so that each XCD (ids are dealt round-robin to the
+// 8 XCDs) walks a contiguous range of tiles and re-uses its operands in its L2.
+#include "grass_device.h"
+
+namespace grass {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int kGemmThreads = 256;
+constexpr int kLdF32 = BM + 2;     // floats per k-row in mode 0 (see bank note below)
+constexpr int kLdBf16 = BK + 8;    // bf16 per m-row in mode 1 (80 bytes)
+
+struct GemmArgs {
+    const float* A;   // M x K
+    const float* B;   // N x K
+    float* C;         // M x N
+    uint64_t M, N, K, lda, ldb, ldc;
+    uint32_t tiles_m, tiles_n;
+    int accumulate;   // C += instead of C =
+};
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);   // NaN stays NaN
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Loads 4 consecutive k of one row with the widest access the alignment allows;
+// out-of-range rows and k read as zero.
+template <int V>
+__device__ __forceinline__ float4 load4(const float* base, uint64_t ld, uint64_t row, uint64_t rows, uint64_t k0,
+                                        uint64_t K) {
+    float4 r = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (row >= rows) return r;
+    const float* p = base + row * ld + k0;
+    if (k0 + 4 <= K) {
+        if constexpr (V == 4) {
+            r = *reinterpret_cast<const float4*>(p);
+        } else if constexpr (V == 2) {
+            const float2 a = *reinterpret_cast<const float2*>(p);
+            const float2 b = *reinterpret_cast<const float2*>(p + 2);
+            r = make_float4(a.x, a.y, b.x, b.y);
+        } else {
+            r = make_float4(p[0], p[1], p[2], p[3]);
+        }
+    } else {
+        if (k0 + 0 < K) r.x = p[0];
+        if (k0 + 1 < K) r.y = p[1];
+        if (k0 + 2 < K) r.z = p[2];
+        if (k0 + 3 < K) r.w = p[3];
+    }
+    return r;
+}
+
+template <int MODE, int V>
+__global__ void __launch_bounds__(kGemmThreads) gemm_nt_kernel(GemmArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+
+    // XCD-aware tile order: consecutive logical tiles share the same B (train) tile.
+    const uint32_t total = a.tiles_m * a.tiles_n;
+    const uint32_t bid = blockIdx.x;
+    const uint32_t per_xcd = (total + 7) / 8;
+    uint32_t logical = (bid % 8) * per_xcd + bid / 8;
+    if (total % 8 != 0) logical = bid;              // ragged grids keep the plain order
+    if (logical >= total) return;
+    const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
+    const uint64_t m0 = (uint64_t)tm * BM, n0 = (uint64_t)tn * BN;
+
+    // staging map: 8 lanes cover the 32 k of one row (coalesced 128-byte rows)
+    const int kq = tid & 7;            // which group of 4 k
+    const int r0 = tid >> 3;           // row 0..31, +32 per step
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    float4 ra[4], rb[4];
+    auto fetch = [&](uint64_t k0) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            ra[i] = load4<V>(a.A, a.lda, m0 + r0 + 32 * i, a.M, k0 + kq * 4, a.K);
+            rb[i] = load4<V>(a.B, a.ldb, n0 + r0 + 32 * i, a.N, k0 + kq * 4, a.K);
+        }
+    };
+
+    const uint64_t nkt = (a.K + BK - 1) / BK;
+    fetch(0);
+    for (uint64_t kt = 0; kt < nkt; ++kt) {
+        __syncthreads();    // everyone is done reading the previous slice
+        if constexpr (MODE == 0) {
+            float* As = reinterpret_cast<float*>(smem);            // [BK][kLdF32]
+            float* Bs = As + BK * kLdF32;
+            // bank of (k, m) = (k*kLdF32 + m) % 32; kLdF32 = 130 puts the 8 k-groups of a
+            // wavefront 8 banks apart, so a store sees at most 2 lanes per bank.
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = r0 + 32 * i;
+                As[(kq * 4 + 0) * kLdF32 + row] = ra[i].x; As[(kq * 4 + 1) * kLdF32 + row] = ra[i].y;
+                As[(kq * 4 + 2) * kLdF32 + row] = ra[i].z; As[(kq * 4 + 3) * kLdF32 + row] = ra[i].w;
+                Bs[(kq * 4 + 0) * kLdF32 + row] = rb[i].x; Bs[(kq * 4 + 1) * kLdF32 + row] = rb[i].y;
+                Bs[(kq * 4 + 2) * kLdF32 + row] = rb[i].z; Bs[(kq * 4 + 3) * kLdF32 + row] = rb[i].w;
+            }
+        } else {
+            uint16_t* As = reinterpret_cast<uint16_t*>(smem);      // [BM][kLdBf16]
+            uint16_t* Bs = As + BM * kLdBf16;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int row = r0 + 32 * i;
+                ushort4 pa, pb;
+                pa.x = f32_to_bf16_rne(ra[i].x); pa.y = f32_to_bf16_rne(ra[i].y);
+                pa.z = f32_to_bf16_rne(ra[i].z); pa.w = f32_to_bf16_rne(ra[i].w);
+                pb.x = f32_to_bf16_rne(rb[i].x); pb.y = f32_to_bf16_rne(rb[i].y);
+                pb.z = f32_to_bf16_rne(rb[i].z); pb.w = f32_to_bf16_rne(rb[i].w);
+                *reinterpret_cast<ushort4*>(As + row * kLdBf16 + kq * 4) = pa;
+                *reinterpret_cast<ushort4*>(Bs + row * kLdBf16 + kq * 4) = pb;
+            }
+        }
+        __syncthreads();
+        if (kt + 1 < nkt) fetch((kt + 1) * BK);
+
+        if constexpr (MODE == 0) {
+            const float* As = reinterpret_cast<const float*>(smem);
+            const float* Bs = As + BK * kLdF32;
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 2) {
+                const int krow = kk + (lane >> 5);
+                float fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) fa[i] = As[krow * kLdF32 + wm * 64 + i * 32 + (lane & 31)];
+#pragma unroll
+                for (int j = 0; j < 2; ++j) fb[j] = Bs[krow * kLdF32 + wn * 64 + j * 32 + (lane & 31)];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        } else {
+            const uint16_t* As = reinterpret_cast<const uint16_t*>(smem);
+            const uint16_t* Bs = As + BM * kLdBf16;
+#pragma unroll
+            for (int kk = 0; kk < BK; kk += 16) {
+                bf16x8 fa[2], fb[2];
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    fa[i] = *reinterpret_cast<const bf16x8*>(As + (wm * 64 + i * 32 + (lane & 31)) * kLdBf16 + kk +
+                                                             (lane >> 5) * 8);
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    fb[j] = *reinterpret_cast<const bf16x8*>(Bs + (wn * 64 + j * 32 + (lane & 31)) * kLdBf16 + kk +
+                                                             (lane >> 5) * 8);
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+        }
+    }
+
+    // accumulator element e of a lane: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint64_t col = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const uint64_t row = m0 + wm * 64 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row < a.M && col < a.N) {
+                    float* c = a.C + row * a.ldc + col;
+                    *c = a.accumulate ? *c + acc[i][j][e] : acc[i][j][e];
+                }
+            }
+        }
+}
+
+static int vec_width(const float* p, uint64_t ld) {
+    if (aligned(p, 16) && ld % 4 == 0) return 4;
+    if (aligned(p, 8) && ld % 2 == 0) return 2;
+    return 1;
+}
+
+static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st) {
+    GemmArgs g = a;
+    g.tiles_m = (uint32_t)ceil_div(a.M, BM);
+    g.tiles_n = (uint32_t)ceil_div(a.N, BN);
+    const uint64_t total = (uint64_t)g.tiles_m * g.tiles_n;
+    if (total == 0 || total > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    int v = vec_width(a.A, a.lda);
+    const int vb = vec_width(a.B, a.ldb);
+    if (vb < v) v = vb;
+    const size_t lds = mode == 0 ? (size_t)2 * BK * kLdF32 * sizeof(float) : (size_t)2 * BM * kLdBf16 * sizeof(uint16_t);
+    dim3 grid((uint32_t)total), block(kGemmThreads);
+#define GRASS_GEMM(MODE, V) hipLaunchKernelGGL((gemm_nt_kernel<MODE, V>), grid, block, lds, st, g)
+    if (mode == 0) {
+        if (v == 4) GRASS_GEMM(0, 4); else if (v == 2) GRASS_GEMM(0, 2); else GRASS_GEMM(0, 1);
+    } else {
+        if (v == 4) GRASS_GEMM(1, 4); else if (v == 2) GRASS_GEMM(1, 2); else GRASS_GEMM(1, 1);
+    }
+#undef GRASS_GEMM
+    return hipGetLastError();
+}
+
+// P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.
+__global__ void __launch_bounds__(256) gauss_matrix_kernel(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0,
+                                                           uint64_t pc, float* P, uint64_t ldP, float inv_sqrt_k) {
+    const uint64_t total = (uint64_t)k * pc;
+    uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; t < total; t += stride) {
+        const uint64_t row = t / pc, col = t - row * pc;
+        const uint64_t h = sm(sub, row * p + p0 + col);
+        const float u1 = ((float)(uint32_t)(h >> 40) + 0.5f) * (1.0f / 16777216.0f);          // (0, 1)
+        const float u2 = (float)(uint32_t)((h >> 16) & 0xFFFFFFu) * (1.0f / 16777216.0f);      // [0, 1)
+        const float rad = sqrtf(-2.0f * logf(u1));
+        P[row * ldP + col] = rad * cospif(2.0f * u2) * inv_sqrt_k;
+    }
+}
+
+}  // namespace grass
+
+using namespace grass;
+
+extern "C" grass_status grass_score(const float* train, const float* test, int compute_mode, uint64_t N, uint64_t M,
+                                    uint64_t K, uint64_t ld_train, uint64_t ld_test, float* scores,
+                                    uint64_t ld_scores, grass_stream stream) {
+    if (K == 0 || (compute_mode != 0 && compute_mode != 1)) return GRASS_EINVAL;
+    if (N == 0 || M == 0) return GRASS_OK;
+    if (!train || !test || !scores || ld_train < K || ld_test < K || ld_scores < N) return GRASS_EINVAL;
+    GemmArgs a;
+    a.A = test; a.B = train; a.C = scores;
+    a.M = M; a.N = N; a.K = K; a.lda = ld_test; a.ldb = ld_train; a.ldc = ld_scores;
+    a.accumulate = 0;
+    return launch_gemm(a, compute_mode, as_stream(stream)) == hipSuccess ? GRASS_OK : GRASS_EHIP;
+}
+
+extern "C" grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t k, uint64_t p0,
+                                           uint64_t pc, float* P, uint64_t ldP, grass_stream stream) {
+    if (p == 0 || k == 0 || pc == 0 || p0 + pc > p || !P || ldP < pc) return GRASS_EINVAL;
+    const uint64_t total = (uint64_t)k * pc;
+    const uint32_t blocks = (uint32_t)(ceil_div(total, 256) > 16384 ? 16384 : ceil_div(total, 256));
+    hipLaunchKernelGGL(gauss_matrix_kernel, dim3(blocks), dim3(256), 0, as_stream(stream),
+                       substream(seed, stream_id), p, k, p0, pc, P, ldP, 1.0f / sqrtf((float)k));
+    return launch_status();
+}
+
+static uint64_t gauss_chunk(uint64_t p, uint64_t p_chunk) {
+    uint64_t pc = p_chunk == 0 ? 8192 : p_chunk;
+    pc = (pc + 3) / 4 * 4;                 // keeps every chunk of P 16-byte aligned
+    return pc > p ? (p + 3) / 4 * 4 : pc;
+}
+
+extern "C" grass_status grass_gauss_project_workspace_bytes(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk,
+                                                            size_t* host_bytes) {
+    (void)n;
+    if (!host_bytes || p == 0 || k == 0) return GRASS_EINVAL;
+    *host_bytes = (size_t)k * gauss_chunk(p, p_chunk) * sizeof(float);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t p, uint64_t ldg, uint32_t k,
+                                            uint64_t seed, uint64_t stream_id, uint64_t p_chunk, int compute_mode,
+                                            float* out, uint64_t ldo, void* ws, size_t ws_bytes,
+                                            grass_stream stream) {
+    if (p == 0 || k == 0 || (compute_mode != 0 && compute_mode != 1)) return GRASS_EINVAL;
+    if (n == 0) return GRASS_OK;
+    if (!g || !out || ldg < p || ldo < k) return GRASS_EINVAL;
+    const uint64_t pc = gauss_chunk(p, p_chunk);
+    if (!ws || ws_bytes < (size_t)k * pc * sizeof(float) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    float* P = static_cast<float*>(ws);
+    hipStream_t hs = as_stream(stream);
+    const uint64_t sub = substream(seed, stream_id);
+    const float inv_sqrt_k = 1.0f / sqrtf((float)k);
+    for (uint64_t p0 = 0; p0 < p; p0 += pc) {
+        const uint64_t cur = p0 + pc <= p ? pc : p - p0;
+        const uint64_t total = (uint64_t)k * cur;
+        const uint32_t blocks = (uint32_t)(ceil_div(total, 256) > 16384 ? 16384 : ceil_div(total, 256));
+        hipLaunchKernelGGL(gauss_matrix_kernel, dim3(blocks), dim3(256), 0, hs, sub, p, k, p0, cur, P, pc,
+                           inv_sqrt_k);
+        GemmArgs a;
+        a.A = g + p0; a.B = P; a.C = out;
+        a.M = n; a.N = k; a.K = cur; a.lda = ldg; a.ldb = pc; a.ldc = ldo;
+        a.accumulate = p0 != 0;
+        if (launch_gemm(a, compute_mode, hs) != hipSuccess) return GRASS_EHIP;
+    }
+    return launch_status();
+}

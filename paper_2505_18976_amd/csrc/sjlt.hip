@@ -1,0 +1,317 @@
+// SJLT and fused GraSS (mask + SJLT) kernels.
+//
+// Sec. 3.1: SJLT scans the input and lets every coordinate add itself to, or
+// subtract itself from, s output coordinates.  Sec. 3.3.1: GraSS applies the
+// same scan to the masked sub-vector g[idx].
+//
+// Mapping to the GPU: a workgroup owns R consecutive rows (samples) and one
+// contiguous chunk of the SJLT's input positions.  It keeps an R x k fp32
+// accumulator in LDS.  A thread reads the same V consecutive positions of all R
+// rows (coalesced 4V-byte loads; a gather through idx in the fused case),
+// evaluates the hash of each position once in registers and reuses bucket and
+// sign for the R rows.  Exact zeros are skipped (the sparsity of per-sample
+// gradients reduces LDS traffic, not HBM traffic).  If the input positions are
+// split over several chunks the per-chunk partial rows go to the workspace and
+// a second kernel adds them in a fixed order; no global atomics anywhere.
+#include "grass_device.h"
+
+namespace grass {
+
+static int g_tune_rows = 0, g_tune_chunks = 0, g_tune_threads = 0;
+
+struct SjltArgs {
+    const float* g;
+    const int32_t* idx;   // nullptr: positions are columns
+    float* dst;           // out (direct) or partial workspace
+    uint64_t ldg;
+    uint64_t n;
+    uint64_t d;           // number of SJLT input positions (p or k')
+    uint64_t ld_dst;      // row distance in dst
+    uint64_t chunk_stride;  // elements between consecutive chunks in dst (0 when direct)
+    uint64_t pos_per_chunk;
+    uint64_t sub;         // sub-seed of the SJLT stream
+    uint32_t k, s, m;
+    float scale;          // applied when writing directly
+};
+
+__device__ __forceinline__ void lds_add(float* addr, float v) {
+    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+template <int R>
+__device__ __forceinline__ void scatter_position(float* acc, const float (&v)[R], uint64_t pos,
+                                                 const SjltArgs& a) {
+    bool any = false;
+#pragma unroll
+    for (int r = 0; r < R; ++r) any |= (v[r] != 0.0f);
+    if (!any) return;
+    uint64_t c = pos * a.s;
+    for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
+        const uint64_t h = sm(a.sub, c);
+        const uint32_t b = rr * a.m + bucket_of(h, a.m);
+        const uint32_t sg = signbit_of(h);
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (v[r] != 0.0f) lds_add(acc + (uint32_t)r * a.k + b, __uint_as_float(__float_as_uint(v[r]) ^ sg));
+        }
+    }
+}
+
+template <int V> struct VecT;
+template <> struct VecT<1> { using type = float; };
+template <> struct VecT<2> { using type = float2; };
+template <> struct VecT<4> { using type = float4; };
+
+template <int V>
+__device__ __forceinline__ void unpack(const typename VecT<V>::type& x, float* o);
+template <> __device__ __forceinline__ void unpack<1>(const float& x, float* o) { o[0] = x; }
+template <> __device__ __forceinline__ void unpack<2>(const float2& x, float* o) { o[0] = x.x; o[1] = x.y; }
+template <> __device__ __forceinline__ void unpack<4>(const float4& x, float* o) {
+    o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w;
+}
+
+// R rows per workgroup, V positions per load (unmasked only), U loads in flight
+// per row and thread.
+template <int R, int V, int U, bool MASKED>
+__global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
+    extern __shared__ float acc[];
+    const uint32_t nt = blockDim.x;
+    const uint64_t row0 = (uint64_t)blockIdx.x * R;
+    const int nrows = (int)((a.n - row0) < (uint64_t)R ? (a.n - row0) : (uint64_t)R);
+    for (uint32_t t = threadIdx.x; t < (uint32_t)R * a.k; t += nt) acc[t] = 0.0f;
+    __syncthreads();
+
+    const uint64_t begin = (uint64_t)blockIdx.y * a.pos_per_chunk;
+    const uint64_t end = (begin + a.pos_per_chunk < a.d) ? begin + a.pos_per_chunk : a.d;
+    const float* rowp[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) rowp[r] = a.g + (row0 + (r < nrows ? r : 0)) * a.ldg;
+
+    if constexpr (MASKED) {
+        // one position per thread and step; U steps in flight
+        for (uint64_t base = begin + threadIdx.x; base < end; base += (uint64_t)nt * U) {
+            int32_t col[U];
+            float v[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t pos = base + (uint64_t)u * nt;
+                col[u] = pos < end ? a.idx[pos] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int r = 0; r < R; ++r)
+                    v[u][r] = (col[u] >= 0 && r < nrows) ? rowp[r][col[u]] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) scatter_position<R>(acc, v[u], base + (uint64_t)u * nt, a);
+        }
+    } else {
+        using VT = typename VecT<V>::type;
+        // full vectors: positions [begin, vend); begin is a multiple of V
+        const uint64_t nvec = (end - begin) / V;
+        for (uint64_t vb = threadIdx.x; vb < nvec; vb += (uint64_t)nt * U) {
+            VT x[U][R];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t vi = vb + (uint64_t)u * nt;
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (vi < nvec && r < nrows)
+                        x[u][r] = *reinterpret_cast<const VT*>(rowp[r] + begin + vi * V);
+                    else
+                        x[u][r] = VT{};
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t vi = vb + (uint64_t)u * nt;
+                if (vi >= nvec) break;
+                float e[R][V];
+#pragma unroll
+                for (int r = 0; r < R; ++r) unpack<V>(x[u][r], e[r]);
+#pragma unroll
+                for (int c = 0; c < V; ++c) {
+                    float v[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) v[r] = e[r][c];
+                    scatter_position<R>(acc, v, begin + vi * V + c, a);
+                }
+            }
+        }
+        // ragged tail of fewer than V positions
+        const uint64_t tail = begin + nvec * V + threadIdx.x;
+        if (tail < end) {
+            float v[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) v[r] = r < nrows ? rowp[r][tail] : 0.0f;
+            scatter_position<R>(acc, v, tail, a);
+        }
+    }
+    __syncthreads();
+
+    float* dst = a.dst + (uint64_t)blockIdx.y * a.chunk_stride;
+    for (int r = 0; r < nrows; ++r) {
+        float* o = dst + (row0 + r) * a.ld_dst;
+        const float* src = acc + (uint32_t)r * a.k;
+        for (uint32_t b = threadIdx.x; b < a.k; b += nt) o[b] = src[b] * a.scale;
+    }
+}
+
+struct SjltPlan {
+    int R, V, threads;
+    uint32_t chunks;
+    uint64_t pos_per_chunk;
+    size_t lds_bytes;
+    size_t ws_bytes;
+};
+
+static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const float* g, uint64_t ldg,
+                      SjltPlan* pl) {
+    if ((size_t)k * 4 > 128 * 1024) return false;
+    int R = 8;
+    while (R > 1 && (size_t)R * k * 4 > 128 * 1024) R >>= 1;
+    // no point holding more rows than there are samples
+    while (R > 1 && (uint64_t)R > n) R >>= 1;
+    if (g_tune_rows == 1 || g_tune_rows == 2 || g_tune_rows == 4 || g_tune_rows == 8) {
+        if ((size_t)g_tune_rows * k * 4 <= kLdsBytes - 1024) R = g_tune_rows;
+    }
+    int threads = 1024;
+    if ((size_t)R * k * 4 <= 64 * 1024) threads = 512;       // two or more groups per CU anyway
+    if (g_tune_threads == 256 || g_tune_threads == 512 || g_tune_threads == 1024) threads = g_tune_threads;
+    int V = 1;
+    if (!masked) {
+        if (aligned(g, 16) && ldg % 4 == 0) V = 4;
+        else if (aligned(g, 8) && ldg % 2 == 0) V = 2;
+    }
+    const uint64_t row_groups = ceil_div(n, R);
+    // chunks: enough workgroups to fill the chip, but keep the partial-sum
+    // traffic (2 * chunks * n * k * 4 bytes) small against the input traffic.
+    const uint64_t step = (uint64_t)threads * V * 2;
+    uint64_t max_chunks_work = d / (step * 2);
+    if (max_chunks_work < 1) max_chunks_work = 1;
+    uint64_t max_chunks_traffic = (d * (masked ? 8 : 1)) / (8ull * k);
+    if (max_chunks_traffic < 1) max_chunks_traffic = 1;
+    uint64_t chunks = ceil_div(2 * kNumCU, row_groups);
+    if (chunks > max_chunks_work) chunks = max_chunks_work;
+    if (chunks > max_chunks_traffic) chunks = max_chunks_traffic;
+    if (g_tune_chunks > 0) chunks = g_tune_chunks;
+    if (chunks > 65535) chunks = 65535;
+    uint64_t ppc = ceil_div(d, chunks);
+    ppc = ceil_div(ppc, step) * step;             // keeps chunk starts V-aligned
+    chunks = ceil_div(d, ppc);
+    if (chunks < 1) chunks = 1;
+    pl->R = R; pl->V = V; pl->threads = threads;
+    pl->chunks = (uint32_t)chunks;
+    pl->pos_per_chunk = ppc;
+    pl->lds_bytes = (size_t)R * k * 4;
+    pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * 4 : 0;
+    return true;
+}
+
+template <int R, int V, int U, bool MASKED>
+static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
+    auto kern = sjlt_kernel<R, V, U, MASKED>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsBytes));
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    dim3 grid((uint32_t)ceil_div(a.n, R), pl.chunks);
+    hipLaunchKernelGGL(kern, grid, dim3(pl.threads), pl.lds_bytes, st, a);
+    return hipGetLastError();
+}
+
+template <int R>
+static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
+    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true>(a, pl, st);
+    switch (pl.V) {
+        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false>(a, pl, st);
+        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false>(a, pl, st);
+        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false>(a, pl, st);
+    }
+}
+
+}  // namespace grass
+
+using namespace grass;
+
+extern "C" void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads) {
+    g_tune_rows = rows_per_block;
+    g_tune_chunks = column_chunks;
+    g_tune_threads = threads;
+}
+
+static grass_status check_sjlt_dims(uint64_t n, uint64_t p, bool masked, uint32_t kprime, uint32_t k, uint32_t s) {
+    (void)n;
+    if (p == 0 || p >= (1ull << 31)) return GRASS_EINVAL;
+    if (k == 0 || s == 0 || k % s != 0) return GRASS_EINVAL;
+    if (masked && (kprime == 0 || kprime > p)) return GRASS_EINVAL;
+    if (k > GRASS_MAX_K) return GRASS_EUNSUPPORTED;
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint32_t kprime_or_0, uint32_t k,
+                                                   uint32_t s, size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    const bool masked = kprime_or_0 != 0;
+    grass_status st = check_sjlt_dims(n, p, masked, kprime_or_0, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) { *host_bytes = 0; return GRASS_OK; }
+    // the vector width depends on the alignment of g, which is unknown here: chunking
+    // uses the widest step, so take the largest chunk count any width can give.
+    size_t worst = 0;
+    for (int v = 1; v <= 4; v *= 2) {
+        SjltPlan pl;
+        const float* fake = reinterpret_cast<const float*>((uintptr_t)(v * 4));
+        if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, fake, v, &pl)) return GRASS_EUNSUPPORTED;
+        if (pl.ws_bytes > worst) worst = pl.ws_bytes;
+    }
+    *host_bytes = worst;
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
+                                   uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                                   float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+    const bool masked = idx != nullptr;
+    grass_status st = check_sjlt_dims(n, p, masked, kprime, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) return GRASS_OK;
+    if (!g || !out || ldg < p || ldo < k || !aligned(g, 4) || !aligned(out, 4)) return GRASS_EINVAL;
+    if (n * ldg >= (1ull << 62)) return GRASS_EINVAL;
+    const uint64_t d = masked ? kprime : p;
+    SjltPlan pl;
+    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl)) return GRASS_EUNSUPPORTED;
+    if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
+
+    SjltArgs a;
+    a.g = g; a.idx = idx; a.ldg = ldg; a.n = n; a.d = d;
+    a.k = k; a.s = s; a.m = k / s;
+    a.sub = substream(seed, stream_id);
+    a.pos_per_chunk = pl.pos_per_chunk;
+    const float scale = 1.0f / sqrtf((float)s);
+    if (pl.chunks == 1) {
+        a.dst = out; a.ld_dst = ldo; a.chunk_stride = 0; a.scale = scale;
+    } else {
+        a.dst = static_cast<float*>(ws); a.ld_dst = k; a.chunk_stride = n * k; a.scale = 1.0f;
+    }
+    hipStream_t hs = as_stream(stream);
+    hipError_t e;
+    switch (pl.R) {
+        case 8: e = launch_r<8>(a, pl, masked, hs); break;
+        case 4: e = launch_r<4>(a, pl, masked, hs); break;
+        case 2: e = launch_r<2>(a, pl, masked, hs); break;
+        default: e = launch_r<1>(a, pl, masked, hs); break;
+    }
+    if (e != hipSuccess) return GRASS_EHIP;
+    if (pl.chunks > 1) {
+        const uint64_t total = n * k;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, hs,
+                           static_cast<const float*>(ws), n, k, pl.chunks, scale, out, ldo);
+        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+    }
+    return GRASS_OK;
+}

@@ -1,0 +1,99 @@
+"""The C-ABI library loads and exports every symbol include/grass.h declares;
+host-side argument checks answer without touching a GPU (CPU only)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "grass.h")
+
+
+def _declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^(?:grass_status|const char\*|int|void)\s+(\w+)\s*\(", text, flags=re.M)
+    return sorted(set(names))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_2505_18976_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return binding.load_library()
+
+
+def test_header_declares_the_four_entry_points():
+    names = _declared_functions()
+    for required in ("grass_mask", "grass_sjlt", "factgrass_linear", "grass_score"):
+        assert required in names
+
+
+def test_every_declared_symbol_is_exported_and_bound(lib):
+    from paper_2505_18976_amd import binding
+    declared = _declared_functions()
+    assert declared == sorted(binding.SIGNATURES)
+    for name in declared:
+        assert getattr(lib, name) is not None
+
+
+def test_version_and_strerror(lib):
+    assert lib.grass_version() >= 100
+    assert lib.grass_strerror(0) == b"ok"
+    assert b"invalid" in lib.grass_strerror(1)
+    assert b"unknown" in lib.grass_strerror(99)
+
+
+def test_workspace_queries_validate_on_the_host(lib):
+    from paper_2505_18976_amd import binding as b
+    out = ctypes.c_size_t(123)
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, ctypes.byref(out)) == b.GRASS_OK
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 0, 1, ctypes.byref(out)) == b.GRASS_EINVAL      # k = 0
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 0, ctypes.byref(out)) == b.GRASS_EINVAL     # s = 0
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 3, ctypes.byref(out)) == b.GRASS_EINVAL     # s does not divide k
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 2000, 64, 1, ctypes.byref(out)) == b.GRASS_EINVAL  # k' > p
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 1 << 20, 1, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, None) == b.GRASS_EINVAL
+    assert lib.grass_mask_indices_workspace_bytes(1000, 10, ctypes.byref(out)) == b.GRASS_OK
+    assert out.value > 4 * 65536 * 4
+    assert lib.grass_mask_indices_workspace_bytes(1000, 1001, ctypes.byref(out)) == b.GRASS_EINVAL
+    assert lib.grass_mask_indices_workspace_bytes(1 << 31, 10, ctypes.byref(out)) == b.GRASS_EINVAL
+    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 64, 1024, 1, ctypes.byref(out)) == b.GRASS_OK
+    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 129, 1024, 1, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
+    assert lib.factgrass_linear_workspace_bytes(8, 0, 64, 64, 1024, 1, ctypes.byref(out)) == b.GRASS_EINVAL
+
+
+def test_bad_arguments_are_rejected_before_any_launch(lib):
+    """These calls must return on the host: this process has no GPU."""
+    from paper_2505_18976_amd import binding as b
+    null = ctypes.c_void_p(0)
+    fake = ctypes.c_void_p(4096)
+    # null pointers
+    assert lib.grass_sjlt(null, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EINVAL
+    # leading dimension smaller than the row
+    assert lib.grass_sjlt(fake, 4, 100, 99, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EINVAL
+    assert lib.grass_sjlt(fake, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 15, null, 0, null) == b.GRASS_EINVAL
+    # n = 0 is a no-op
+    assert lib.grass_sjlt(fake, 0, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_OK
+    assert lib.grass_mask(fake, 0, 100, 100, fake, 10, fake, 10, null) == b.GRASS_OK
+    assert lib.grass_mask(fake, 4, 100, 100, fake, 101, fake, 101, null) == b.GRASS_EINVAL
+    assert lib.grass_mask(fake, 4, 100, 100, null, 10, fake, 10, null) == b.GRASS_EINVAL
+    # workspace required but missing: many chunks for a single long row
+    assert lib.grass_sjlt(fake, 1, 1 << 22, 1 << 22, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EWORKSPACE
+    assert lib.grass_mask_indices(0, 0, 1000, 10, fake, null, 0, null) == b.GRASS_EWORKSPACE
+    assert lib.grass_score(fake, fake, 2, 8, 8, 8, 8, 8, fake, 8, null) == b.GRASS_EINVAL
+    assert lib.grass_score(fake, fake, 0, 8, 8, 8, 7, 8, fake, 8, null) == b.GRASS_EINVAL
+    assert lib.factgrass_linear(fake, fake, 2, 16, 64, 64, fake, 65, fake, 8, 32, 1, 0, 18, fake, 32, null, 0,
+                                null) == b.GRASS_EINVAL                                                  # k_in' > d_in
+    assert lib.grass_gauss_project(fake, 2, 64, 64, 8, 0, 2, 0, 0, fake, 8, null, 0, null) == b.GRASS_EWORKSPACE
+
+
+def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):
+    from paper_2505_18976_amd import binding
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(binding, "LIB_PATH", str(tmp_path / "missing.so"))
+    with pytest.raises(ImportError):
+        binding.load_library()

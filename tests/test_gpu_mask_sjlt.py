@@ -1,0 +1,186 @@
+"""GPU parity: Random Mask indices, hash tables, mask gather, SJLT and fused
+GraSS against the CPU oracle, through the C ABI.
+
+Bars: bit-exact for indices, buckets and signs and for the gather (a copy);
+max relative error (largest absolute difference in a row over the largest
+absolute oracle value of that row) <= 1e-5 for fp32 SJLT / GraSS outputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import grass_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+TOL_SJLT = 1e-5
+
+
+@pytest.fixture(scope="module")
+def grass():
+    import paper_2505_18976_amd as g
+    g.load_library()
+    yield g
+    g.grass_set_sjlt_tuning(0, 0, 0)
+
+
+def _dev():
+    return torch.device("cuda:0")
+
+
+# ------------------------------------------------------------------ tables
+@pytest.mark.parametrize("d,k,s,seed,stream", [(1, 1, 1, 0, 1), (1000, 1024, 1, 0, 1), (4099, 4096, 4, 7, 18),
+                                               (65536, 1000, 2, 3, 1), (300, 64, 64, 1, 22), (70001, 8192, 1, 0, 1)])
+def test_sjlt_tables_bit_exact(grass, d, k, s, seed, stream):
+    bucket, sign = grass.grass_sjlt_tables(seed, stream, d, k, s, device=_dev())
+    torch.cuda.synchronize()
+    rb, rs = orc.sjlt_tables(seed, stream, d, k, s)
+    assert np.array_equal(bucket.cpu().numpy().view(np.uint32), rb)
+    assert np.array_equal(sign.cpu().numpy(), rs)
+
+
+# ------------------------------------------------------------ mask indices
+@pytest.mark.parametrize("p,kp,seed,stream", [(1, 1, 0, 0), (2, 1, 1, 0), (100, 10, 0, 0), (2048, 2048, 5, 0),
+                                              (2049, 1, 2, 16), (4096, 64, 0, 16), (4096, 64, 0, 17),
+                                              (65536, 8192, 0, 0), (100003, 99999, 4, 0),
+                                              (1863690, 65536, 0, 0)])
+def test_mask_indices_bit_exact(grass, p, kp, seed, stream):
+    idx = grass.grass_mask_indices(seed, stream, p, kp, device=_dev())
+    torch.cuda.synchronize()
+    ref = orc.mask_indices(seed, stream, p, kp)
+    assert np.array_equal(idx.cpu().numpy(), ref)
+    assert grass.grass_check_indices(idx, p)
+
+
+def test_mask_indices_resnet_scale(grass):
+    p, kp = 11173962, 32768
+    idx = grass.grass_mask_indices(0, 0, p, kp, device=_dev())
+    torch.cuda.synchronize()
+    assert np.array_equal(idx.cpu().numpy(), orc.mask_indices(0, 0, p, kp))
+
+
+def test_check_indices_flags_bad_input(grass):
+    good = torch.tensor([0, 3, 9], dtype=torch.int32, device=_dev())
+    assert grass.grass_check_indices(good, 10)
+    assert not grass.grass_check_indices(good, 9)                                   # out of range
+    bad = torch.tensor([0, 3, 3], dtype=torch.int32, device=_dev())
+    assert not grass.grass_check_indices(bad, 10)                                   # repeated
+    bad2 = torch.tensor([4, 3, 9], dtype=torch.int32, device=_dev())
+    assert not grass.grass_check_indices(bad2, 10)                                  # not ascending
+
+
+# ------------------------------------------------------------------ gather
+@pytest.mark.parametrize("n,p,kp,pad", [(1, 10, 10, 0), (5, 1000, 37, 3), (64, 65536, 8192, 0), (19, 5000, 4999, 1)])
+def test_mask_gather_exact(grass, n, p, kp, pad):
+    full = synth.bernoulli_sparse_normal(n, p + pad, 0.5, 1.0, seed=11, device=_dev())
+    g = full[:, :p]
+    idx = grass.grass_mask_indices(0, 0, p, kp, device=_dev())
+    out = grass.grass_mask(g, idx)
+    torch.cuda.synchronize()
+    want = orc.mask(g.cpu().numpy(), idx.cpu().numpy())
+    assert np.array_equal(out.cpu().numpy(), want)
+
+
+# -------------------------------------------------------------------- SJLT
+SJLT_CASES = [
+    # n, d, k, s, row padding (changes alignment / vector width)
+    (1, 1, 8, 1, 0),
+    (3, 5, 8, 2, 0),
+    (8, 1000, 1000, 1, 0),
+    (13, 4099, 1024, 1, 1),
+    (13, 4099, 1024, 4, 2),
+    (5, 70001, 4096, 1, 3),
+    (9, 70002, 4096, 2, 0),
+    (6, 33000, 8192, 1, 0),
+    (2, 20000, 32768, 1, 0),
+    (64, 65536, 1024, 1, 0),
+    (17, 8192, 16, 1, 0),
+]
+
+
+@pytest.mark.parametrize("n,d,k,s,pad", SJLT_CASES)
+def test_sjlt_parity(grass, n, d, k, s, pad):
+    grass.grass_set_sjlt_tuning(0, 0, 0)
+    full = synth.bernoulli_sparse_normal(n, d + pad, 0.6, 1.0, seed=21, device=_dev())
+    g = full[:, :d]
+    out = grass.grass_sjlt(g, k, s, seed=0, stream_id=1)
+    torch.cuda.synchronize()
+    ref = orc.sjlt(g.cpu().numpy(), k, s, 0, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+
+
+@pytest.mark.parametrize("rows,chunks,threads", [(1, 1, 256), (2, 3, 512), (4, 7, 1024), (8, 2, 256), (8, 1, 1024)])
+def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads):
+    n, d, k, s = 11, 50001, 2048, 2
+    g = synth.bernoulli_sparse_normal(n, d, 0.3, 1.0, seed=22, device=_dev())
+    ref = orc.sjlt(g.cpu().numpy(), k, s, 5, 1)
+    grass.grass_set_sjlt_tuning(rows, chunks, threads)
+    try:
+        out = grass.grass_sjlt(g, k, s, seed=5, stream_id=1)
+        torch.cuda.synchronize()
+    finally:
+        grass.grass_set_sjlt_tuning(0, 0, 0)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+
+
+def test_sjlt_dense_zero_and_offset_output(grass):
+    n, d, k = 4, 3000, 256
+    g = torch.zeros((n, d), dtype=torch.float32, device=_dev())
+    wide = torch.full((n, 3 * k), 7.0, dtype=torch.float32, device=_dev())
+    out = grass.grass_sjlt(g, k, 1, seed=0, out=wide[:, k:2 * k])                  # ldo = 3k
+    torch.cuda.synchronize()
+    w = wide.cpu().numpy()
+    assert not w[:, k:2 * k].any()
+    assert np.all(w[:, :k] == 7.0) and np.all(w[:, 2 * k:] == 7.0)                   # neighbours untouched
+    assert out.data_ptr() == wide[:, k:2 * k].data_ptr()
+
+
+# ------------------------------------------------------------------- GraSS
+GRASS_CASES = [
+    # n, p, k', k, s
+    (1, 10, 10, 4, 1),
+    (7, 3000, 500, 64, 2),
+    (64, 65536, 8192, 1024, 1),          # the tiny config of the benchmark suite
+    (10, 100003, 9973, 4096, 4),
+    (5, 20000, 20000, 1000, 1),          # k' = p: plain SJLT
+    (3, 50000, 128, 128, 1),             # k' = k: sparsification only (signed scatter)
+]
+
+
+@pytest.mark.parametrize("n,p,kp,k,s", GRASS_CASES)
+def test_fused_grass_parity(grass, n, p, kp, k, s):
+    g = synth.bernoulli_sparse_normal(n, p, 0.8, 1.0, seed=1001, device=_dev())
+    idx = grass.grass_mask_indices(0, 0, p, kp, device=_dev())
+    out = grass.grass_sjlt(g, k, s, seed=0, stream_id=1, idx=idx)
+    torch.cuda.synchronize()
+    ref = orc.grass(g.cpu().numpy(), idx.cpu().numpy(), k, s, 0, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+    # fused == two-step through the library's own gather
+    two = grass.grass_sjlt(grass.grass_mask(g, idx), k, s, seed=0, stream_id=1)
+    torch.cuda.synchronize()
+    assert orc.max_rel_err(two.cpu().numpy(), ref) <= TOL_SJLT
+
+
+def test_fused_grass_with_caller_supplied_indices(grass):
+    """Selective Mask: the caller brings the indices (Sec. 3.2); any ascending set works."""
+    n, p, k = 6, 40000, 512
+    g = synth.bernoulli_sparse_normal(n, p, 0.5, 1.0, seed=31, device=_dev())
+    idx_np = np.sort(np.random.default_rng(0).choice(p, size=3001, replace=False)).astype(np.int32)
+    idx = torch.from_numpy(idx_np).to(_dev())
+    out = grass.grass_sjlt(g, k, 1, seed=9, stream_id=1, idx=idx)
+    torch.cuda.synchronize()
+    ref = orc.grass(g.cpu().numpy(), idx_np, k, 1, 9, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+
+
+def test_runtime_argument_errors(grass):
+    g = torch.zeros((4, 100), dtype=torch.float32, device=_dev())
+    with pytest.raises(grass.GrassError) as e:
+        grass.grass_sjlt(g, 48, 5, seed=0)                       # s does not divide k
+    assert e.value.status == grass.GRASS_EINVAL
+    with pytest.raises(grass.GrassError) as e:
+        grass.grass_sjlt(g, 1 << 16, 1, seed=0)                  # k beyond the LDS-resident range
+    assert e.value.status == grass.GRASS_EUNSUPPORTED
+    empty = torch.zeros((0, 100), dtype=torch.float32, device=_dev())
+    assert grass.grass_sjlt(empty, 16, 1, seed=0).shape == (0, 16)
