@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the GraSS compression hot path on one MI355X.
+
+Headline workload ("mlp_mask_sjlt"): n = 4,096 per-sample gradients of an MLP
+784-1024-1024-10 (p = 1,863,690 fp32, ReLU-style zeros), Random Mask to
+k' = 65,536, SJLT to k = 4,096 with s = 1, fused (Sec. 3.3.1).  A step is one
+call of grass_sjlt with the mask indices over the whole batch, inputs resident
+in HBM.  Prints ONE JSON line; see the design doc for how each field is derived.
+
+The other paths (s = 4, the plain gather, ResNet-scale SJLT, FactGraSS, score
+GEMM) are timed briefly afterwards and reported under "extras".
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+MFMA_PEAK_F32_TFLOPS = 157.3     # MI355X published dense fp32 matrix rate
+MFMA_PEAK_BF16_TFLOPS = 2500.0
+
+# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc
+# (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a plain copy of known
+# size; see profiles/sjlt_fused_mlp_pmc.txt.  None until measured.
+MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": None}
+
+
+def _timed(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        fn()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    total_ms = evs[0].elapsed_time(evs[steps])
+    return total_ms, per, wall_ms
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--no-extras", action="store_true", help="time the headline workload only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (samples are independent; see DESIGN.md "
+              "for how the path would shard); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2505_18976_amd as grass
+    import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    grass.load_library()          # fails loudly if libgrass.so was not built
+
+    if args.copy_reference:
+        nbytes = 1 << 30
+        a = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+        b = torch.empty_like(a)
+        t, _, _ = _timed(lambda: b.copy_(a), 5, 2, torch)
+        print(json.dumps({"copy_reference_bytes_read": nbytes, "copy_reference_bytes_written": nbytes,
+                          "ms": round(t / 5, 4), "GBps_read_plus_write": round(2 * nbytes / (t / 5 * 1e-3) / 1e9, 1)}))
+        return 0
+
+    # ------------------------------------------------------------ headline
+    n, p, kp, k, s, seed = 4096, synth.mlp_num_params(), 65536, 4096, 1, 0
+    g = synth.mlp_relu_gradients(n, seed=1002, device=dev)
+    idx = grass.grass_mask_indices(seed, 0, p, kp, device=dev)
+    out = torch.empty((n, k), dtype=torch.float32, device=dev)
+    ws_bytes = grass.grass_sjlt_workspace_bytes(n, p, kp, k, s)
+    ws = torch.empty(max(ws_bytes, 1), dtype=torch.uint8, device=dev)
+
+    def step():
+        grass.grass_sjlt(g, k, s, seed, 1, idx=idx, out=out, ws=ws)
+
+    total_ms, per, _ = _timed(step, args.steps, args.warmup, torch)
+    ms_per_step = total_ms / args.steps
+    kernel_ms = float(np.mean(per))       # one launch per step when the workspace query is 0
+    samples_per_s = n / (ms_per_step * 1e-3)
+
+    alg_bytes = n * (4 * kp + 4 * k) + 4 * kp          # useful reads + writes + the index vector once
+    achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
+    roofline = {"bound": "hbm", "kernel": "sjlt_kernel (fused mask gather + SJLT)", "achieved": round(achieved, 2),
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
+                "traffic": MEASURED_TRAFFIC_BYTES["mlp_mask_sjlt_s1"], "kernel_ms": round(kernel_ms, 4),
+                "algorithmic_bytes_per_launch": alg_bytes, "launches_per_step": 1 if ws_bytes == 0 else 2}
+
+    result = {
+        "metric": "compressed per-sample gradients/sec at 1 GPU",
+        "value": round(samples_per_s, 1), "unit": "samples/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "mlp_mask_sjlt_s1", "n": n, "p": p, "kprime": kp, "k": k, "s": s,
+                   "zeros": "ReLU dead-neuron runs, ~50%", "fused": True},
+        "roofline": roofline,
+    }
+
+    # --------------------------------------------------------- CPU baseline
+    if not args.no_cpu_baseline:
+        from oracle import grass_oracle as orc
+        idx_h = idx.cpu().numpy()
+        rows_done, t_used, batch = 0, 0.0, 32
+        err = 0.0
+        while t_used < 12.0 and rows_done < n:
+            rows = slice(rows_done, min(n, rows_done + batch))
+            gh = g[rows].cpu().numpy()
+            t0 = time.perf_counter()
+            ref = orc.grass(gh, idx_h, k, s, seed, 1)
+            t_used += time.perf_counter() - t0
+            err = max(err, orc.max_rel_err(out[rows].cpu().numpy(), ref))
+            rows_done += gh.shape[0]
+        result["cpu_baseline"] = {"value": round(rows_done / t_used, 2), "unit": "samples/s", "cores": 1,
+                                  "kind": "oracle", "sample": f"first {rows_done} of {n} rows, NumPy float64, 1 thread",
+                                  "host_cores_visible": os.cpu_count(), "gpu_vs_oracle_max_rel_err": err}
+
+    # --------------------------------------------------------------- extras
+    if not args.no_extras:
+        extras = {}
+        st = max(5, min(args.steps, 20))
+        # s = 4 on the same batch
+        ws4 = torch.empty(max(grass.grass_sjlt_workspace_bytes(n, p, kp, k, 4), 1), dtype=torch.uint8, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_sjlt(g, k, 4, seed, 1, idx=idx, out=out, ws=ws4), st, 2, torch)
+        extras["mlp_mask_sjlt_s4"] = {"ms": round(t / st, 4), "samples_per_s": round(n / (t / st * 1e-3), 1)}
+        # plain gather
+        gm = torch.empty((n, kp), dtype=torch.float32, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_mask(g, idx, out=gm), st, 2, torch)
+        extras["mlp_mask_gather"] = {"ms": round(t / st, 4), "useful_GBps": round(2 * n * kp * 4 / (t / st * 1e-3) / 1e9, 1)}
+        # mask index generation (one-time set-up)
+        t, _, _ = _timed(lambda: grass.grass_mask_indices(seed, 0, p, kp, device=dev), 5, 1, torch)
+        extras["mask_indices_p1863690"] = {"ms": round(t / 5, 4)}
+        del g, gm, out, ws, ws4
+        torch.cuda.empty_cache()
+
+        # ResNet-scale unmasked SJLT
+        n3, p3, k3 = 1024, 11173962, 8192
+        g3 = synth.laplace_sparse(n3, p3, 0.3, 1e-3, seed=1003, device=dev)
+        o3 = torch.empty((n3, k3), dtype=torch.float32, device=dev)
+        w3 = torch.empty(max(grass.grass_sjlt_workspace_bytes(n3, p3, 0, k3, 1), 1), dtype=torch.uint8, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_sjlt(g3, k3, 1, seed, 1, out=o3, ws=w3), 10, 2, torch)
+        gbps = n3 * (4 * p3 + 4 * k3) / (t / 10 * 1e-3) / 1e9
+        extras["resnet_sjlt_s1"] = {"ms": round(t / 10, 4), "samples_per_s": round(n3 / (t / 10 * 1e-3), 1),
+                                    "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
+        del g3, o3, w3
+        torch.cuda.empty_cache()
+
+        # FactGraSS on one 4096 x 4096 linear layer
+        n4, T4, d4, kf, k4 = 32, 512, 4096, 64, 1024
+        x4, go4 = synth.linear_layer_factors(n4, T4, d4, d4, seed=1004, device=dev)
+        ii = grass.grass_mask_indices(seed, 16, d4, kf, device=dev)
+        io = grass.grass_mask_indices(seed, 17, d4, kf, device=dev)
+        o4 = torch.empty((n4, k4), dtype=torch.float32, device=dev)
+        w4 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n4, T4, kf, kf, k4, 1), 1), dtype=torch.uint8,
+                         device=dev)
+        t, _, _ = _timed(lambda: grass.factgrass_linear(x4, go4, ii, io, k4, 1, seed, 18, out=o4, ws=w4), 20, 3, torch)
+        extras["factgrass_linear_4096"] = {"ms": round(t / 20, 4), "samples_per_s": round(n4 / (t / 20 * 1e-3), 1),
+                                           "tokens_per_s": round(n4 * T4 / (t / 20 * 1e-3), 1),
+                                           "useful_GBps": round(2 * n4 * T4 * 2 * kf * 2 / 2 / (t / 20 * 1e-3) / 1e9, 2)}
+        del x4, go4
+        # score GEMM, one layer block of compressed gradients
+        N5, M5, K5 = 65536, 1024, 4096
+        tr = synth.dense_normal(N5, K5, seed=1005, device=dev)
+        te = synth.dense_normal(M5, K5, seed=1006, device=dev)
+        sc = torch.empty((M5, N5), dtype=torch.float32, device=dev)
+        for mode, peak in ((0, MFMA_PEAK_F32_TFLOPS), (1, MFMA_PEAK_BF16_TFLOPS)):
+            t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=mode, out=sc), 5, 1, torch)
+            tf = 2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12
+            extras[f"score_gemm_mode{mode}"] = {"ms": round(t / 5, 4), "TFLOPs": round(tf, 2),
+                                                "frac_of_mfma_peak": round(tf / peak, 4)}
+        result["extras"] = extras
+
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

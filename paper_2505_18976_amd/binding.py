@@ -40,7 +40,7 @@ SIGNATURES = {
     "grass_gauss_matrix": (_int, [_u64, _u64, _u64, _u32, _u64, _u64, _vp, _u64, _vp]),
     "grass_gauss_project_workspace_bytes": (_int, [_u64, _u64, _u32, _u64, ctypes.POINTER(_sz)]),
     "grass_gauss_project": (_int, [_vp, _u64, _u64, _u64, _u32, _u64, _u64, _u64, _int, _vp, _u64, _vp, _sz, _vp]),
-    "grass_set_sjlt_tuning": (None, [_int, _int, _int]),
+    "grass_set_sjlt_tuning": (None, [_int, _int, _int, _int]),
     "grass_set_factgrass_tuning": (None, [_int]),
 }
 
@@ -234,8 +234,9 @@ def grass_gauss_project(g: torch.Tensor, k: int, seed: int, stream_id: int, p_ch
     return out
 
 
-def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0) -> None:
-    load_library().grass_set_sjlt_tuning(rows_per_block, column_chunks, threads)
+def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0,
+                          accumulator: int = 0) -> None:
+    load_library().grass_set_sjlt_tuning(rows_per_block, column_chunks, threads, accumulator)
 
 
 def grass_set_factgrass_tuning(tokens_per_block: int = 0) -> None:

@@ -13,11 +13,25 @@
 // gradients reduces LDS traffic, not HBM traffic).  If the input positions are
 // split over several chunks the per-chunk partial rows go to the workspace and
 // a second kernel adds them in a fixed order; no global atomics anywhere.
+//
+// How a value is added to its LDS bucket is a template policy, because on
+// gfx950 the native fp32 LDS atomic add retires about one lane every three
+// cycles per CU, an order of magnitude below the other LDS operations:
+//   ACC_F64: fp64 accumulators updated with the fp64 LDS atomic add (fast,
+//            order-insensitive to well below fp32 resolution, half as many rows
+//            fit in LDS);
+//   ACC_CAS: fp32 accumulators updated with a compare-and-swap loop;
+//   ACC_F32: fp32 accumulators with the native fp32 atomic add (kept for
+//            comparison).
 #include "grass_device.h"
 
 namespace grass {
 
-static int g_tune_rows = 0, g_tune_chunks = 0, g_tune_threads = 0;
+static int g_tune_rows = 0, g_tune_chunks = 0, g_tune_threads = 0, g_tune_acc = 0;
+
+enum { ACC_F32 = 1, ACC_CAS = 2, ACC_F64 = 3 };
+template <int ACC> struct AccT { using type = float; };
+template <> struct AccT<ACC_F64> { using type = double; };
 
 struct SjltArgs {
     const float* g;
@@ -34,25 +48,37 @@ struct SjltArgs {
     float scale;          // applied when writing directly
 };
 
-__device__ __forceinline__ void lds_add(float* addr, float v) {
-    __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+template <int ACC>
+__device__ __forceinline__ void lds_add(typename AccT<ACC>::type* addr, float v) {
+    if constexpr (ACC == ACC_F64) {
+        __hip_atomic_fetch_add(addr, (double)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else if constexpr (ACC == ACC_F32) {
+        __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    } else {
+        uint32_t* p = reinterpret_cast<uint32_t*>(addr);
+        uint32_t old = *reinterpret_cast<volatile uint32_t*>(p), assumed;
+        do {
+            assumed = old;
+            old = atomicCAS(p, assumed, __float_as_uint(__uint_as_float(assumed) + v));
+        } while (old != assumed);
+    }
 }
 
-template <int R>
-__device__ __forceinline__ void scatter_position(float* acc, const float (&v)[R], uint64_t pos,
+template <int R, int ACC>
+__device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, const float (&v)[R], uint64_t pos,
                                                  const SjltArgs& a) {
     bool any = false;
 #pragma unroll
     for (int r = 0; r < R; ++r) any |= (v[r] != 0.0f);
     if (!any) return;
-    uint64_t c = pos * a.s;
-    for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
-        const uint64_t h = sm(a.sub, c);
+    uint64_t z = a.sub + (pos * a.s + 1) * kGamma;
+    for (uint32_t rr = 0; rr < a.s; ++rr, z += kGamma) {
+        const uint64_t h = finalise(z);
         const uint32_t b = rr * a.m + bucket_of(h, a.m);
         const uint32_t sg = signbit_of(h);
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (v[r] != 0.0f) lds_add(acc + (uint32_t)r * a.k + b, __uint_as_float(__float_as_uint(v[r]) ^ sg));
+            if (v[r] != 0.0f) lds_add<ACC>(acc + (uint32_t)r * a.k + b, __uint_as_float(__float_as_uint(v[r]) ^ sg));
         }
     }
 }
@@ -72,13 +98,15 @@ template <> __device__ __forceinline__ void unpack<4>(const float4& x, float* o)
 
 // R rows per workgroup, V positions per load (unmasked only), U loads in flight
 // per row and thread.
-template <int R, int V, int U, bool MASKED>
+template <int R, int V, int U, bool MASKED, int ACC>
 __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
-    extern __shared__ float acc[];
+    using acc_t = typename AccT<ACC>::type;
+    extern __shared__ __align__(16) unsigned char smem[];
+    acc_t* acc = reinterpret_cast<acc_t*>(smem);
     const uint32_t nt = blockDim.x;
     const uint64_t row0 = (uint64_t)blockIdx.x * R;
     const int nrows = (int)((a.n - row0) < (uint64_t)R ? (a.n - row0) : (uint64_t)R);
-    for (uint32_t t = threadIdx.x; t < (uint32_t)R * a.k; t += nt) acc[t] = 0.0f;
+    for (uint32_t t = threadIdx.x; t < (uint32_t)R * a.k; t += nt) acc[t] = (acc_t)0;
     __syncthreads();
 
     const uint64_t begin = (uint64_t)blockIdx.y * a.pos_per_chunk;
@@ -104,7 +132,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     v[u][r] = (col[u] >= 0 && r < nrows) ? rowp[r][col[u]] : 0.0f;
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) scatter_position<R>(acc, v[u], base + (uint64_t)u * nt, a);
+            for (int u = 0; u < U; ++u) scatter_position<R, ACC>(acc, v[u], base + (uint64_t)u * nt, a);
         }
     } else {
         using VT = typename VecT<V>::type;
@@ -135,7 +163,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     float v[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) v[r] = e[r][c];
-                    scatter_position<R>(acc, v, begin + vi * V + c, a);
+                    scatter_position<R, ACC>(acc, v, begin + vi * V + c, a);
                 }
             }
         }
@@ -145,7 +173,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             float v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) v[r] = r < nrows ? rowp[r][tail] : 0.0f;
-            scatter_position<R>(acc, v, tail, a);
+            scatter_position<R, ACC>(acc, v, tail, a);
         }
     }
     __syncthreads();
@@ -153,13 +181,13 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
     float* dst = a.dst + (uint64_t)blockIdx.y * a.chunk_stride;
     for (int r = 0; r < nrows; ++r) {
         float* o = dst + (row0 + r) * a.ld_dst;
-        const float* src = acc + (uint32_t)r * a.k;
-        for (uint32_t b = threadIdx.x; b < a.k; b += nt) o[b] = src[b] * a.scale;
+        const acc_t* src = acc + (uint32_t)r * a.k;
+        for (uint32_t b = threadIdx.x; b < a.k; b += nt) o[b] = (float)src[b] * a.scale;
     }
 }
 
 struct SjltPlan {
-    int R, V, threads;
+    int R, V, threads, acc;
     uint32_t chunks;
     uint64_t pos_per_chunk;
     size_t lds_bytes;
@@ -169,15 +197,20 @@ struct SjltPlan {
 static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const float* g, uint64_t ldg,
                       SjltPlan* pl) {
     if ((size_t)k * 4 > 128 * 1024) return false;
+    int acc = ACC_F64;
+    if ((size_t)k * 8 > 128 * 1024) acc = ACC_CAS;            // fp64 buckets of one row no longer fit
+    if (g_tune_acc >= ACC_F32 && g_tune_acc <= ACC_F64 && (size_t)k * (g_tune_acc == ACC_F64 ? 8 : 4) <= 128 * 1024)
+        acc = g_tune_acc;
+    const size_t esz = acc == ACC_F64 ? 8 : 4;
     int R = 8;
-    while (R > 1 && (size_t)R * k * 4 > 128 * 1024) R >>= 1;
+    while (R > 1 && (size_t)R * k * esz > 128 * 1024) R >>= 1;
     // no point holding more rows than there are samples
     while (R > 1 && (uint64_t)R > n) R >>= 1;
     if (g_tune_rows == 1 || g_tune_rows == 2 || g_tune_rows == 4 || g_tune_rows == 8) {
-        if ((size_t)g_tune_rows * k * 4 <= kLdsBytes - 1024) R = g_tune_rows;
+        if ((size_t)g_tune_rows * k * esz <= kLdsBytes) R = g_tune_rows;
     }
     int threads = 1024;
-    if ((size_t)R * k * 4 <= 64 * 1024) threads = 512;       // two or more groups per CU anyway
+    if ((size_t)R * k * esz <= 64 * 1024) threads = 512;      // two or more groups per CU anyway
     if (g_tune_threads == 256 || g_tune_threads == 512 || g_tune_threads == 1024) threads = g_tune_threads;
     int V = 1;
     if (!masked) {
@@ -201,17 +234,17 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const flo
     ppc = ceil_div(ppc, step) * step;             // keeps chunk starts V-aligned
     chunks = ceil_div(d, ppc);
     if (chunks < 1) chunks = 1;
-    pl->R = R; pl->V = V; pl->threads = threads;
+    pl->R = R; pl->V = V; pl->threads = threads; pl->acc = acc;
     pl->chunks = (uint32_t)chunks;
     pl->pos_per_chunk = ppc;
-    pl->lds_bytes = (size_t)R * k * 4;
+    pl->lds_bytes = (size_t)R * k * esz;
     pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * 4 : 0;
     return true;
 }
 
-template <int R, int V, int U, bool MASKED>
+template <int R, int V, int U, bool MASKED, int ACC>
 static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
-    auto kern = sjlt_kernel<R, V, U, MASKED>;
+    auto kern = sjlt_kernel<R, V, U, MASKED, ACC>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -224,13 +257,22 @@ static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t 
     return hipGetLastError();
 }
 
+template <int R, int ACC>
+static hipError_t launch_ra(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
+    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true, ACC>(a, pl, st);
+    switch (pl.V) {
+        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false, ACC>(a, pl, st);
+        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false, ACC>(a, pl, st);
+        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false, ACC>(a, pl, st);
+    }
+}
+
 template <int R>
 static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
-    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true>(a, pl, st);
-    switch (pl.V) {
-        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false>(a, pl, st);
-        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false>(a, pl, st);
-        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false>(a, pl, st);
+    switch (pl.acc) {
+        case ACC_F32: return launch_ra<R, ACC_F32>(a, pl, masked, st);
+        case ACC_CAS: return launch_ra<R, ACC_CAS>(a, pl, masked, st);
+        default: return launch_ra<R, ACC_F64>(a, pl, masked, st);
     }
 }
 
@@ -238,10 +280,11 @@ static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, h
 
 using namespace grass;
 
-extern "C" void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads) {
+extern "C" void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads, int accumulator) {
     g_tune_rows = rows_per_block;
     g_tune_chunks = column_chunks;
     g_tune_threads = threads;
+    g_tune_acc = accumulator;
 }
 
 static grass_status check_sjlt_dims(uint64_t n, uint64_t p, bool masked, uint32_t kprime, uint32_t k, uint32_t s) {

@@ -22,7 +22,7 @@ def grass():
     import paper_2505_18976_amd as g
     g.load_library()
     yield g
-    g.grass_set_sjlt_tuning(0, 0, 0)
+    g.grass_set_sjlt_tuning(0, 0, 0, 0)
 
 
 def _dev():
@@ -101,7 +101,7 @@ SJLT_CASES = [
 
 @pytest.mark.parametrize("n,d,k,s,pad", SJLT_CASES)
 def test_sjlt_parity(grass, n, d, k, s, pad):
-    grass.grass_set_sjlt_tuning(0, 0, 0)
+    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     full = synth.bernoulli_sparse_normal(n, d + pad, 0.6, 1.0, seed=21, device=_dev())
     g = full[:, :d]
     out = grass.grass_sjlt(g, k, s, seed=0, stream_id=1)
@@ -110,17 +110,18 @@ def test_sjlt_parity(grass, n, d, k, s, pad):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
-@pytest.mark.parametrize("rows,chunks,threads", [(1, 1, 256), (2, 3, 512), (4, 7, 1024), (8, 2, 256), (8, 1, 1024)])
-def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads):
+@pytest.mark.parametrize("rows,chunks,threads,acc", [(1, 1, 256, 0), (2, 3, 512, 1), (4, 7, 1024, 2), (8, 2, 256, 3),
+                                                     (8, 1, 1024, 2), (4, 1, 512, 1), (2, 5, 1024, 3)])
+def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
     n, d, k, s = 11, 50001, 2048, 2
     g = synth.bernoulli_sparse_normal(n, d, 0.3, 1.0, seed=22, device=_dev())
     ref = orc.sjlt(g.cpu().numpy(), k, s, 5, 1)
-    grass.grass_set_sjlt_tuning(rows, chunks, threads)
+    grass.grass_set_sjlt_tuning(rows, chunks, threads, acc)
     try:
         out = grass.grass_sjlt(g, k, s, seed=5, stream_id=1)
         torch.cuda.synchronize()
     finally:
-        grass.grass_set_sjlt_tuning(0, 0, 0)
+        grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
