@@ -159,9 +159,9 @@ grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t p, uint64_
 /* ------------------------------------------------------------------- tuning
  * Overrides the launch heuristics of grass_sjlt for experiments: rows per
  * block (1,2,4,8), column chunks per row group, threads per block
- * (256,512,1024) and the LDS accumulator (1 fp32 atomic add, 2 fp32
- * compare-and-swap, 3 fp64 atomic add); 0 restores the heuristic for that
- * field.  Process-wide; changes the workspace size the query reports.         */
+ * (256,512,1024) and the LDS accumulator (2 fp32 compare-and-swap, 3 fp64
+ * atomic add); 0 or any other value restores the heuristic for that field.
+ * Process-wide; changes the workspace size the query reports.                  */
 void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads, int accumulator);
 /* Same for factgrass_linear: tokens per block (multiple of 32; 0 = heuristic). */
 void grass_set_factgrass_tuning(int tokens_per_block);

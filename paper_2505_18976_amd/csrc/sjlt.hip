@@ -5,8 +5,10 @@
 // same scan to the masked sub-vector g[idx].
 //
 // Mapping to the GPU: a workgroup owns R consecutive rows (samples) and one
-// contiguous chunk of the SJLT's input positions.  It keeps an R x k fp32
-// accumulator in LDS.  A thread reads the same V consecutive positions of all R
+// contiguous chunk of the SJLT's input positions.  It keeps an R x k accumulator
+// in LDS (row-major: for a fixed row, random buckets spread evenly over the LDS
+// banks; a bucket-major layout would confine each row to 1/R of the banks).
+// A thread reads the same V consecutive positions of all R
 // rows (coalesced 4V-byte loads; a gather through idx in the fused case),
 // evaluates the hash of each position once in registers and reuses bucket and
 // sign for the R rows.  Exact zeros are skipped (the sparsity of per-sample
@@ -20,16 +22,14 @@
 //   ACC_F64: fp64 accumulators updated with the fp64 LDS atomic add (fast,
 //            order-insensitive to well below fp32 resolution, half as many rows
 //            fit in LDS);
-//   ACC_CAS: fp32 accumulators updated with a compare-and-swap loop;
-//   ACC_F32: fp32 accumulators with the native fp32 atomic add (kept for
-//            comparison).
+//   ACC_CAS: fp32 accumulators updated with a compare-and-swap loop.
 #include "grass_device.h"
 
 namespace grass {
 
 static int g_tune_rows = 0, g_tune_chunks = 0, g_tune_threads = 0, g_tune_acc = 0;
 
-enum { ACC_F32 = 1, ACC_CAS = 2, ACC_F64 = 3 };
+enum { ACC_CAS = 2, ACC_F64 = 3 };
 template <int ACC> struct AccT { using type = float; };
 template <> struct AccT<ACC_F64> { using type = double; };
 
@@ -45,6 +45,7 @@ struct SjltArgs {
     uint64_t pos_per_chunk;
     uint64_t sub;         // sub-seed of the SJLT stream
     uint32_t k, s, m;
+    uint32_t shift;       // 32 - log2(m) when m is a power of two >= 2
     float scale;          // applied when writing directly
 };
 
@@ -52,8 +53,6 @@ template <int ACC>
 __device__ __forceinline__ void lds_add(typename AccT<ACC>::type* addr, float v) {
     if constexpr (ACC == ACC_F64) {
         __hip_atomic_fetch_add(addr, (double)v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    } else if constexpr (ACC == ACC_F32) {
-        __hip_atomic_fetch_add(addr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
     } else {
         uint32_t* p = reinterpret_cast<uint32_t*>(addr);
         uint32_t old = *reinterpret_cast<volatile uint32_t*>(p), assumed;
@@ -64,21 +63,35 @@ __device__ __forceinline__ void lds_add(typename AccT<ACC>::type* addr, float v)
     }
 }
 
-template <int R, int ACC>
-__device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, const float (&v)[R], uint64_t pos,
+// Adds the R values of one input position to their buckets.  z is the generator
+// state of the position's first non-zero, i.e. sub + (pos*s + 1)*gamma.
+// FAST: s == 1 and m a power of two >= 2 (bucket by shift, no loop over s).
+template <int R, int ACC, bool FAST>
+__device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, const float (&v)[R], uint64_t z,
                                                  const SjltArgs& a) {
     bool any = false;
 #pragma unroll
     for (int r = 0; r < R; ++r) any |= (v[r] != 0.0f);
     if (!any) return;
-    uint64_t z = a.sub + (pos * a.s + 1) * kGamma;
-    for (uint32_t rr = 0; rr < a.s; ++rr, z += kGamma) {
+    if constexpr (FAST) {
         const uint64_t h = finalise(z);
-        const uint32_t b = rr * a.m + bucket_of(h, a.m);
+        const uint32_t b = (uint32_t)(h >> 32) >> a.shift;
         const uint32_t sg = signbit_of(h);
+        typename AccT<ACC>::type* slot = acc + b;
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (v[r] != 0.0f) lds_add<ACC>(acc + (uint32_t)r * a.k + b, __uint_as_float(__float_as_uint(v[r]) ^ sg));
+            if (v[r] != 0.0f) lds_add<ACC>(slot + (uint32_t)r * a.k, __uint_as_float(__float_as_uint(v[r]) ^ sg));
+        }
+    } else {
+        for (uint32_t rr = 0; rr < a.s; ++rr, z += kGamma) {
+            const uint64_t h = finalise(z);
+            const uint32_t b = rr * a.m + bucket_of(h, a.m);
+            const uint32_t sg = signbit_of(h);
+            typename AccT<ACC>::type* slot = acc + b;
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                if (v[r] != 0.0f) lds_add<ACC>(slot + (uint32_t)r * a.k, __uint_as_float(__float_as_uint(v[r]) ^ sg));
+            }
         }
     }
 }
@@ -105,7 +118,7 @@ __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontempo
 
 // R rows per workgroup, V positions per load (unmasked only), U loads in flight
 // per row and thread.
-template <int R, int V, int U, bool MASKED, int ACC>
+template <int R, int V, int U, bool MASKED, int ACC, bool FAST>
 __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
     using acc_t = typename AccT<ACC>::type;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -122,9 +135,14 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
 #pragma unroll
     for (int r = 0; r < R; ++r) rowp[r] = a.g + (row0 + (r < nrows ? r : 0)) * a.ldg;
 
+    const uint64_t zpos = (uint64_t)a.s * kGamma;             // generator-state distance between positions
+
     if constexpr (MASKED) {
         // one position per thread and step; U steps in flight
-        for (uint64_t base = begin + threadIdx.x; base < end; base += (uint64_t)nt * U) {
+        const uint64_t zstep = zpos * nt;
+        uint64_t base = begin + threadIdx.x;
+        uint64_t z = a.sub + (base * a.s + 1) * kGamma;
+        for (; base < end; base += (uint64_t)nt * U, z += zstep * U) {
             int32_t col[U];
             float v[U][R];
 #pragma unroll
@@ -139,13 +157,16 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     v[u][r] = (col[u] >= 0 && r < nrows) ? stream_load(rowp[r] + col[u]) : 0.0f;
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) scatter_position<R, ACC>(acc, v[u], base + (uint64_t)u * nt, a);
+            for (int u = 0; u < U; ++u) scatter_position<R, ACC, FAST>(acc, v[u], z + zstep * u, a);
         }
     } else {
         using VT = typename VecT<V>::type;
-        // full vectors: positions [begin, vend); begin is a multiple of V
+        // full vectors: positions [begin, begin + nvec*V); begin is a multiple of V
         const uint64_t nvec = (end - begin) / V;
-        for (uint64_t vb = threadIdx.x; vb < nvec; vb += (uint64_t)nt * U) {
+        const uint64_t zstep = zpos * V * nt;
+        uint64_t vb = threadIdx.x;
+        uint64_t z = a.sub + ((begin + vb * V) * a.s + 1) * kGamma;
+        for (; vb < nvec; vb += (uint64_t)nt * U, z += zstep * U) {
             VT x[U][R];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
@@ -160,8 +181,6 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const uint64_t vi = vb + (uint64_t)u * nt;
-                if (vi >= nvec) break;
                 float e[R][V];
 #pragma unroll
                 for (int r = 0; r < R; ++r) unpack<V>(x[u][r], e[r]);
@@ -170,7 +189,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     float v[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) v[r] = e[r][c];
-                    scatter_position<R, ACC>(acc, v, begin + vi * V + c, a);
+                    scatter_position<R, ACC, FAST>(acc, v, z + zstep * u + zpos * c, a);   // all-zero past nvec: skipped
                 }
             }
         }
@@ -180,7 +199,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             float v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) v[r] = r < nrows ? rowp[r][tail] : 0.0f;
-            scatter_position<R, ACC>(acc, v, tail, a);
+            scatter_position<R, ACC, FAST>(acc, v, a.sub + (tail * a.s + 1) * kGamma, a);
         }
     }
     __syncthreads();
@@ -188,8 +207,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
     float* dst = a.dst + (uint64_t)blockIdx.y * a.chunk_stride;
     for (int r = 0; r < nrows; ++r) {
         float* o = dst + (row0 + r) * a.ld_dst;
-        const acc_t* src = acc + (uint32_t)r * a.k;
-        for (uint32_t b = threadIdx.x; b < a.k; b += nt) o[b] = (float)src[b] * a.scale;
+        for (uint32_t b = threadIdx.x; b < a.k; b += nt) o[b] = (float)acc[(uint32_t)r * a.k + b] * a.scale;
     }
 }
 
@@ -206,7 +224,7 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const flo
     if ((size_t)k * 4 > 128 * 1024) return false;
     int acc = ACC_F64;
     if ((size_t)k * 8 > 128 * 1024) acc = ACC_CAS;            // fp64 buckets of one row no longer fit
-    if (g_tune_acc >= ACC_F32 && g_tune_acc <= ACC_F64 && (size_t)k * (g_tune_acc == ACC_F64 ? 8 : 4) <= 128 * 1024)
+    if ((g_tune_acc == ACC_CAS || g_tune_acc == ACC_F64) && (size_t)k * (g_tune_acc == ACC_F64 ? 8 : 4) <= 128 * 1024)
         acc = g_tune_acc;
     const size_t esz = acc == ACC_F64 ? 8 : 4;
     int R = 8;
@@ -249,9 +267,9 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const flo
     return true;
 }
 
-template <int R, int V, int U, bool MASKED, int ACC>
+template <int R, int V, int U, bool MASKED, int ACC, bool FAST>
 static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
-    auto kern = sjlt_kernel<R, V, U, MASKED, ACC>;
+    auto kern = sjlt_kernel<R, V, U, MASKED, ACC, FAST>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -264,23 +282,21 @@ static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t 
     return hipGetLastError();
 }
 
-template <int R, int ACC>
-static hipError_t launch_ra(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
-    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true, ACC>(a, pl, st);
+template <int R, int ACC, bool FAST>
+static hipError_t launch_raf(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
+    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true, ACC, FAST>(a, pl, st);
     switch (pl.V) {
-        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false, ACC>(a, pl, st);
-        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false, ACC>(a, pl, st);
-        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false, ACC>(a, pl, st);
+        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
+        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
+        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
     }
 }
 
 template <int R>
-static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
-    switch (pl.acc) {
-        case ACC_F32: return launch_ra<R, ACC_F32>(a, pl, masked, st);
-        case ACC_CAS: return launch_ra<R, ACC_CAS>(a, pl, masked, st);
-        default: return launch_ra<R, ACC_F64>(a, pl, masked, st);
-    }
+static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, bool fast, hipStream_t st) {
+    if (pl.acc == ACC_CAS)
+        return fast ? launch_raf<R, ACC_CAS, true>(a, pl, masked, st) : launch_raf<R, ACC_CAS, false>(a, pl, masked, st);
+    return fast ? launch_raf<R, ACC_F64, true>(a, pl, masked, st) : launch_raf<R, ACC_F64, false>(a, pl, masked, st);
 }
 
 }  // namespace grass
@@ -340,6 +356,14 @@ extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint6
     SjltArgs a;
     a.g = g; a.idx = idx; a.ldg = ldg; a.n = n; a.d = d;
     a.k = k; a.s = s; a.m = k / s;
+    a.shift = 0;
+    bool fast = false;
+    if (s == 1 && a.m >= 2 && (a.m & (a.m - 1)) == 0) {
+        uint32_t lg = 0;
+        while ((1u << lg) < a.m) ++lg;
+        a.shift = 32 - lg;
+        fast = true;
+    }
     a.sub = substream(seed, stream_id);
     a.pos_per_chunk = pl.pos_per_chunk;
     const float scale = 1.0f / sqrtf((float)s);
@@ -351,10 +375,10 @@ extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint6
     hipStream_t hs = as_stream(stream);
     hipError_t e;
     switch (pl.R) {
-        case 8: e = launch_r<8>(a, pl, masked, hs); break;
-        case 4: e = launch_r<4>(a, pl, masked, hs); break;
-        case 2: e = launch_r<2>(a, pl, masked, hs); break;
-        default: e = launch_r<1>(a, pl, masked, hs); break;
+        case 8: e = launch_r<8>(a, pl, masked, fast, hs); break;
+        case 4: e = launch_r<4>(a, pl, masked, fast, hs); break;
+        case 2: e = launch_r<2>(a, pl, masked, fast, hs); break;
+        default: e = launch_r<1>(a, pl, masked, fast, hs); break;
     }
     if (e != hipSuccess) return GRASS_EHIP;
     if (pl.chunks > 1) {
