@@ -179,7 +179,56 @@ def main() -> int:
         extras["factgrass_linear_4096"] = {"ms": round(t / 20, 4), "samples_per_s": round(n4 / (t / 20 * 1e-3), 1),
                                            "tokens_per_s": round(n4 * T4 / (t / 20 * 1e-3), 1),
                                            "useful_GBps": round(2 * n4 * T4 * 2 * kf * 2 / 2 / (t / 20 * 1e-3) / 1e9, 2)}
-        del x4, go4
+        del x4, go4, o4, w4
+
+        # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
+        # one input buffer per distinct layer shape, per-layer masks and SJLT streams, outputs concatenated
+        n5, T5, kl = 8, 1024, 4096
+        bufs, layers = {}, []
+        for name, d_in, d_out in synth.LLAMA_BLOCK_LINEARS:
+            if (d_in, d_out) not in bufs:
+                bufs[(d_in, d_out)] = synth.linear_layer_factors(n5, T5, d_in, d_out, seed=1005 + len(bufs), device=dev)
+        for layer in range(16 * 7):
+            name, d_in, d_out = synth.LLAMA_BLOCK_LINEARS[layer % 7]
+            layers.append((bufs[(d_in, d_out)], grass.grass_mask_indices(seed, 16 + 4 * layer, d_in, kf, device=dev),
+                           grass.grass_mask_indices(seed, 17 + 4 * layer, d_out, kf, device=dev), 18 + 4 * layer))
+        cat = torch.empty((n5, kl * len(layers)), dtype=torch.float32, device=dev)
+        w5 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n5, T5, kf, kf, kl, 1), 1), dtype=torch.uint8,
+                         device=dev)
+
+        def llama_pass():
+            for l, ((xl, gl), a_in, a_out, stream_id) in enumerate(layers):
+                grass.factgrass_linear(xl, gl, a_in, a_out, kl, 1, seed, stream_id, out=cat[:, l * kl:(l + 1) * kl], ws=w5)
+
+        t, _, wall = _timed(llama_pass, 5, 2, torch)
+        extras["factgrass_llama_112_layers"] = {"ms": round(t / 5, 4), "tokens_per_s": round(n5 * T5 / (t / 5 * 1e-3), 1),
+                                                "layer_calls_per_pass": len(layers)}
+        del bufs, layers, cat, w5
+        torch.cuda.empty_cache()
+
+        # dense Gaussian projection baseline on a 131,072-column slice of the ResNet-scale problem
+        ng, pg, kg = 1024, 131072, 8192
+        gg = synth.laplace_sparse(ng, pg, 0.3, 1e-3, seed=1003, device=dev)
+        og = torch.empty((ng, kg), dtype=torch.float32, device=dev)
+        wg = torch.empty(grass.grass_gauss_project_workspace_bytes(ng, pg, kg, 32768), dtype=torch.uint8, device=dev)
+        for mode, peak in ((0, MFMA_PEAK_F32_TFLOPS), (1, MFMA_PEAK_BF16_TFLOPS)):
+            t, _, _ = _timed(lambda: grass.grass_gauss_project(gg, kg, seed, 2, 32768, compute_mode=mode, out=og, ws=wg),
+                             3, 1, torch)
+            tf = 2.0 * ng * pg * kg / (t / 3 * 1e-3) / 1e12
+            extras[f"gauss_project_slice_mode{mode}"] = {"ms": round(t / 3, 3), "TFLOPs_incl_generation": round(tf, 2),
+                                                          "samples_per_s_extrapolated_to_p_11173962":
+                                                              round(ng / (t / 3 * 1e-3) * pg / 11173962, 1)}
+        del gg, og, wg
+        torch.cuda.empty_cache()
+
+        # tiny config: n = 64, p = 65,536, k' = 8,192, k = 1,024 (launch-latency bound)
+        g1 = synth.bernoulli_sparse_normal(64, 65536, 0.8, 1.0, seed=1001, device=dev)
+        i1 = grass.grass_mask_indices(seed, 0, 65536, 8192, device=dev)
+        o1 = torch.empty((64, 1024), dtype=torch.float32, device=dev)
+        w1 = torch.empty(max(grass.grass_sjlt_workspace_bytes(64, 65536, 8192, 1024, 1), 1), dtype=torch.uint8, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_sjlt(g1, 1024, 1, seed, 1, idx=i1, out=o1, ws=w1), 50, 5, torch)
+        extras["tiny_mask_sjlt"] = {"ms": round(t / 50, 4), "samples_per_s": round(64 / (t / 50 * 1e-3), 1)}
+
         # score GEMM, one layer block of compressed gradients
         N5, M5, K5 = 65536, 1024, 4096
         tr = synth.dense_normal(N5, K5, seed=1005, device=dev)

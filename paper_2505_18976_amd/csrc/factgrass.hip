@@ -5,11 +5,16 @@
 // v[a*k_out' + b] = sum_t x'_t[a] * g'_t[b], a (k_in' x T)(T x k_out') contraction
 // done on the matrix cores in bf16 with fp32 accumulation.  Stage 3 (sparse
 // projection): SJLT of the k_in'*k_out' accumulator straight from registers into
-// k LDS buckets.  The d_out x d_in layer gradient is never formed.
+// k LDS buckets (fp64 buckets with the fp64 LDS atomic add when they fit, which
+// is an order of magnitude faster on gfx950 than the native fp32 LDS atomic add;
+// fp32 buckets with a compare-and-swap loop otherwise).  The d_out x d_in layer
+// gradient is never formed.
 //
 // A workgroup (4 wavefronts) owns one sample and one chunk of its tokens.
 // Because the SJLT is linear, each chunk is projected on its own and the
 // per-chunk k-vectors are added in a fixed order by a second kernel.
+#include <type_traits>
+
 #include "grass_device.h"
 
 namespace grass {
@@ -39,12 +44,13 @@ struct FgArgs {
 };
 
 // TA, TB: number of 32-wide tiles covering k_in' and k_out'.
-template <int TA, int TB>
+template <int TA, int TB, bool F64>
 __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
+    using bucket_t = typename std::conditional<F64, double, float>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                 // [TA*32][kTokStride]
     uint16_t* gs = xs + TA * 32 * kTokStride;                          // [TB*32][kTokStride]
-    float* sk = reinterpret_cast<float*>(smem);                        // [k], reuses the staging area afterwards
+    bucket_t* sk = reinterpret_cast<bucket_t*>(smem);                  // [k], reuses the staging area afterwards
 
     constexpr int KA = TA * 32, KB = TB * 32;
     constexpr int NT = TA * TB;                    // output tiles
@@ -104,7 +110,7 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
         }
     }
     __syncthreads();
-    for (uint32_t b = tid; b < a.k; b += kFgThreads) sk[b] = 0.0f;
+    for (uint32_t b = tid; b < a.k; b += kFgThreads) sk[b] = (bucket_t)0;
     __syncthreads();
 
     // SJLT of this chunk's partial v.  Accumulator element e of a lane sits at
@@ -124,8 +130,18 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
                     for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
                         const uint64_t h = sm(a.sub, c);
                         const uint32_t bucket = rr * a.m + bucket_of(h, a.m);
-                        __hip_atomic_fetch_add(sk + bucket, __uint_as_float(__float_as_uint(val) ^ signbit_of(h)),
-                                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                        const float sv = __uint_as_float(__float_as_uint(val) ^ signbit_of(h));
+                        if constexpr (F64) {
+                            __hip_atomic_fetch_add(sk + bucket, (double)sv, __ATOMIC_RELAXED,
+                                                   __HIP_MEMORY_SCOPE_WORKGROUP);
+                        } else {
+                            uint32_t* pb = reinterpret_cast<uint32_t*>(sk + bucket);
+                            uint32_t old = *reinterpret_cast<volatile uint32_t*>(pb), assumed;
+                            do {
+                                assumed = old;
+                                old = atomicCAS(pb, assumed, __float_as_uint(__uint_as_float(assumed) + sv));
+                            } while (old != assumed);
+                        }
                     }
                 }
             }
@@ -133,11 +149,12 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
     }
     __syncthreads();
     float* o = a.dst + (uint64_t)blockIdx.x * a.chunk_stride + sample * a.ld_dst;
-    for (uint32_t b = tid; b < a.k; b += kFgThreads) o[b] = sk[b] * a.scale;
+    for (uint32_t b = tid; b < a.k; b += kFgThreads) o[b] = (float)sk[b] * a.scale;
 }
 
 struct FgPlan {
     int TA, TB;
+    bool f64;
     uint32_t tokens_per_block, chunks;
     size_t lds_bytes, ws_bytes;
 };
@@ -148,26 +165,30 @@ static bool plan_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k
     if (ka == 0 || kb == 0 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR) return false;
     pl->TA = tiles_for(ka);
     pl->TB = tiles_for(kb);
-    // tokens per workgroup: aim at two workgroups per CU, never below one staging tile
-    uint64_t tpb = T;
-    const uint64_t want_chunks = ceil_div(2 * kNumCU, n);
-    if (want_chunks > 1) tpb = ceil_div(T, want_chunks);
-    tpb = ceil_div(tpb, kTokTile) * kTokTile;
+    // tokens per workgroup: every workgroup pays a fixed price (SJLT of its partial
+    // accumulator, one k-vector written and re-read), so take the largest of
+    // 128 / 64 / 32 tokens that still yields at least half a workgroup per CU.
+    uint64_t tpb = 32;
+    for (uint64_t cand : {128ull, 64ull}) {
+        if (n * ceil_div(T, cand) >= (uint64_t)kNumCU / 2) { tpb = cand; break; }
+    }
+    if (tpb > ceil_div(T, kTokTile) * kTokTile) tpb = ceil_div(T, kTokTile) * kTokTile;
     if (g_tune_tokens > 0) tpb = ceil_div((uint64_t)g_tune_tokens, kTokTile) * kTokTile;
     uint64_t chunks = ceil_div(T, tpb);
     if (chunks > 65535) { chunks = 65535; tpb = ceil_div(ceil_div(T, chunks), kTokTile) * kTokTile; chunks = ceil_div(T, tpb); }
     pl->tokens_per_block = (uint32_t)tpb;
     pl->chunks = (uint32_t)chunks;
     const size_t stage = (size_t)(pl->TA + pl->TB) * 32 * kTokStride * sizeof(uint16_t);
-    const size_t buckets = (size_t)k * sizeof(float);
+    pl->f64 = (size_t)k * sizeof(double) <= 64 * 1024;      // keeps at least two workgroups per CU
+    const size_t buckets = (size_t)k * (pl->f64 ? sizeof(double) : sizeof(float));
     pl->lds_bytes = stage > buckets ? stage : buckets;
     pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * sizeof(float) : 0;
     return pl->lds_bytes <= kLdsBytes - 1024;
 }
 
-template <int TA, int TB>
-static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
-    auto kern = factgrass_kernel<TA, TB>;
+template <int TA, int TB, bool F64>
+static hipError_t launch_fg2(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
+    auto kern = factgrass_kernel<TA, TB, F64>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -177,6 +198,11 @@ static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, hipSt
     }
     hipLaunchKernelGGL(kern, dim3(pl.chunks, (uint32_t)n), dim3(kFgThreads), pl.lds_bytes, st, a);
     return hipGetLastError();
+}
+
+template <int TA, int TB>
+static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
+    return pl.f64 ? launch_fg2<TA, TB, true>(a, pl, n, st) : launch_fg2<TA, TB, false>(a, pl, n, st);
 }
 
 }  // namespace grass
