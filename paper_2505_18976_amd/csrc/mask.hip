@@ -204,8 +204,11 @@ __global__ void __launch_bounds__(256) mask_gather_kernel(const float* g, uint64
     const uint64_t r1 = r0 + rows_per_block < n ? r0 + rows_per_block : n;
     uint64_t r = r0;
     for (; r + 4 <= r1; r += 4) {
-        const float a = g[(r + 0) * ldg + col], b = g[(r + 1) * ldg + col];
-        const float c = g[(r + 2) * ldg + col], d = g[(r + 3) * ldg + col];
+        // read-once data: non-temporal loads sustain a higher rate on scattered lines
+        const float a = __builtin_nontemporal_load(g + (r + 0) * ldg + col);
+        const float b = __builtin_nontemporal_load(g + (r + 1) * ldg + col);
+        const float c = __builtin_nontemporal_load(g + (r + 2) * ldg + col);
+        const float d = __builtin_nontemporal_load(g + (r + 3) * ldg + col);
         out[(r + 0) * ldo + jp] = a; out[(r + 1) * ldo + jp] = b;
         out[(r + 2) * ldo + jp] = c; out[(r + 3) * ldo + jp] = d;
     }

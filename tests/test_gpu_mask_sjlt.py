@@ -96,6 +96,8 @@ SJLT_CASES = [
     (2, 20000, 32768, 1, 0),
     (64, 65536, 1024, 1, 0),
     (17, 8192, 16, 1, 0),
+    (3, 100, 8, 8, 0),                   # s = k: every row of P is hit (dense Rademacher limit)
+    (4, 9000, 3000, 3, 0),               # m not a power of two
 ]
 
 
