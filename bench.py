@@ -239,6 +239,13 @@ def main() -> int:
             tf = 2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12
             extras[f"score_gemm_mode{mode}"] = {"ms": round(t / 5, 4), "TFLOPs": round(tf, 2),
                                                 "frac_of_mfma_peak": round(tf / peak, 4)}
+        trb, teb = grass.grass_to_bf16(tr), grass.grass_to_bf16(te)
+        t, _, _ = _timed(lambda: grass.grass_score_bf16(trb, teb, out=sc), 10, 2, torch)
+        tf = 2.0 * N5 * M5 * K5 / (t / 10 * 1e-3) / 1e12
+        extras["score_gemm_bf16_inputs"] = {"ms": round(t / 10, 4), "TFLOPs": round(tf, 2),
+                                            "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4)}
+        t, _, _ = _timed(lambda: grass.grass_to_bf16(tr, out=trb), 5, 1, torch)
+        extras["to_bf16_train_rows"] = {"ms": round(t / 5, 4)}
         result["extras"] = extras
 
     print(json.dumps(result))

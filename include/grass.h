@@ -139,6 +139,19 @@ grass_status grass_score(const float* train, const float* test, int compute_mode
                          uint64_t ld_train, uint64_t ld_test,
                          float* scores, uint64_t ld_scores, grass_stream stream);
 
+/* The same scores for callers that keep compressed gradients in bf16 (Sec. 2.1;
+ * halves the bytes of the attribute stage): train N x K and test M x K are bf16
+ * bit patterns, products are exact in fp32, accumulation is fp32.  Requires
+ * K, ld_train and ld_test to be multiples of 8 and 16-byte aligned bases
+ * (GRASS_EUNSUPPORTED otherwise).  grass_to_bf16 converts an fp32 matrix
+ * (rows x cols) to bf16 with round-to-nearest-even.                           */
+grass_status grass_to_bf16(const float* src, uint64_t rows, uint64_t cols, uint64_t ld_src,
+                           void* dst, uint64_t ld_dst, grass_stream stream);
+grass_status grass_score_bf16(const void* train, const void* test,
+                              uint64_t N, uint64_t M, uint64_t K,
+                              uint64_t ld_train, uint64_t ld_test,
+                              float* scores, uint64_t ld_scores, grass_stream stream);
+
 /* ---------------------------------------------- dense Gaussian baseline (Sec. 2.2)
  * g_hat = P g with P (k x p), P_ab ~ N(0, 1/k), generated from the counter
  * hash by Box-Muller: entry (a, b) uses H(seed, stream_id, a*p + b).

@@ -37,6 +37,8 @@ SIGNATURES = {
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
                                 _vp, _u64, _vp, _sz, _vp]),
     "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
+    "grass_to_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u64, _vp]),
+    "grass_score_bf16": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_gauss_matrix": (_int, [_u64, _u64, _u64, _u32, _u64, _u64, _vp, _u64, _vp]),
     "grass_gauss_project_workspace_bytes": (_int, [_u64, _u64, _u32, _u64, ctypes.POINTER(_sz)]),
     "grass_gauss_project": (_int, [_vp, _u64, _u64, _u64, _u32, _u64, _u64, _u64, _int, _vp, _u64, _vp, _sz, _vp]),
@@ -203,6 +205,28 @@ def grass_score(train: torch.Tensor, test: torch.Tensor, compute_mode: int = 0,
         out = torch.empty((M, N), dtype=torch.float32, device=train.device)
     _check(load_library().grass_score(_ptr(train), _ptr(test), compute_mode, N, M, K, _ld(train), _ld(test),
                                       _ptr(out), _ld(out), _stream()), "grass_score")
+    return out
+
+
+def grass_to_bf16(src: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    assert src.dtype == torch.float32
+    rows, cols = src.shape
+    if out is None:
+        out = torch.empty((rows, cols), dtype=torch.bfloat16, device=src.device)
+    _check(load_library().grass_to_bf16(_ptr(src), rows, cols, _ld(src), _ptr(out), _ld(out), _stream()),
+           "grass_to_bf16")
+    return out
+
+
+def grass_score_bf16(train: torch.Tensor, test: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    assert train.dtype == torch.bfloat16 and test.dtype == torch.bfloat16
+    N, K = train.shape
+    M = test.shape[0]
+    assert test.shape[1] == K
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=train.device)
+    _check(load_library().grass_score_bf16(_ptr(train), _ptr(test), N, M, K, _ld(train), _ld(test), _ptr(out),
+                                           _ld(out), _stream()), "grass_score_bf16")
     return out
 
 

@@ -1,0 +1,372 @@
+// Score GEMM on bf16 operands (Sec. 2.1, attribute stage: all-pair inner
+// products of compressed gradients), for callers that keep the compressed
+// gradients in bf16, plus the fp32 -> bf16 conversion they need.
+//
+// C[M x N] = A[M x K] * B[N x K]^T, A and B row-major bf16 with K contiguous,
+// fp32 accumulation.  One workgroup of 8 wavefronts (2 x 4) owns a 256 x 256 tile
+// of C; each wavefront owns 128 x 64 = 4 x 2 MFMA tiles (v_mfma_f32_32x32x16_bf16,
+// 128 accumulator registers per lane).  Two wavefronts per SIMD are needed: one
+// wavefront alone sustains only about one 16-byte-per-lane LDS read every 64
+// cycles (measured), exactly what a 128 x 128 tile would ask of it.
+// K is consumed in slices of 32 through three LDS stages and four register
+// sets: in iteration t the MFMAs read stage t, slice t+2 moves from its register
+// set to stage t+2, the global loads of slice t+6 are issued into the freed set
+// (four iterations of MFMA work cover the HBM/L2 latency), and the first
+// fragments of slice t+1 (complete since the previous barrier) are prefetched, so
+// the matrix pipe waits neither for the barrier nor for memory.  LDS rows are
+// padded to 80 bytes so that the 16-byte fragment reads (one row per lane) are
+// bank-conflict free.  Workgroup ids are dealt round-robin to the 8 XCDs; the
+// tile order gives every XCD a contiguous range of tiles in which the M-tiles
+// sharing a B tile are adjacent.
+#include "grass_device.h"
+
+namespace grass {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int TM = 256, TN = 256, TK = 32;
+constexpr int RS = TK + 8;                       // bf16 elements per LDS row (80 bytes)
+constexpr int kStageElems = (TM + TN) * RS;      // one stage: A tile then B tile
+constexpr int kStages = 3;
+constexpr int kBf16Threads = 512;
+
+struct GemmBf16Args {
+    const uint16_t* A;    // M x K
+    const uint16_t* B;    // N x K
+    float* C;             // M x N
+    uint64_t M, N, K, lda, ldb, ldc;
+    uint32_t tiles_m, tiles_n;
+};
+
+struct Frags {
+    bf16x8 a[4], b[2];
+};
+
+__global__ void __launch_bounds__(kBf16Threads) gemm_bf16_nt_kernel(GemmBf16Args a) {
+    extern __shared__ __align__(16) uint16_t lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    const uint32_t total = a.tiles_m * a.tiles_n;
+    const uint32_t bid = blockIdx.x;
+    uint32_t logical = bid;
+    if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;
+    const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
+    const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
+
+    // staging map: 4 lanes cover the 64 bytes of one row slice, a wavefront covers 16 rows
+    constexpr int NS = 2;             // row steps per thread and operand
+    const int srow = tid >> 2;        // 0..127, +128 per step
+    const int skc = tid & 3;          // 16-byte chunk inside the 32-element slice
+    const uint16_t* arow[NS];
+    const uint16_t* brow[NS];
+#pragma unroll
+    for (int i = 0; i < NS; ++i) {
+        uint64_t r = m0 + srow + 128 * i;
+        arow[i] = a.A + (r < a.M ? r : a.M - 1) * a.lda + skc * 8;     // rows past the edge re-read the last row;
+        r = n0 + srow + 128 * i;                                        // their products are never stored
+        brow[i] = a.B + (r < a.N ? r : a.N - 1) * a.ldb + skc * 8;
+    }
+
+    constexpr int kSets = 4;          // register sets of global loads in flight
+    u32x4 ra[kSets][NS], rb[kSets][NS];
+    const uint64_t nkt = (a.K + TK - 1) / TK;
+    auto fetch = [&](u32x4 (&xa)[NS], u32x4 (&xb)[NS], uint64_t slice) {
+        const uint64_t k0 = slice * TK;
+        const bool in_k = slice < nkt && k0 + skc * 8 < a.K;      // K is a multiple of 8: a chunk is all in or all out
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            xa[i] = in_k ? *reinterpret_cast<const u32x4*>(arow[i] + k0) : u32x4(0u);
+            xb[i] = in_k ? *reinterpret_cast<const u32x4*>(brow[i] + k0) : u32x4(0u);
+        }
+    };
+    auto stash = [&](const u32x4 (&xa)[NS], const u32x4 (&xb)[NS], int stage) {
+        uint16_t* sa = lds + stage * kStageElems;
+        uint16_t* sb = sa + TM * RS;
+#pragma unroll
+        for (int i = 0; i < NS; ++i) {
+            *reinterpret_cast<u32x4*>(sa + (srow + 128 * i) * RS + skc * 8) = xa[i];
+            *reinterpret_cast<u32x4*>(sb + (srow + 128 * i) * RS + skc * 8) = xb[i];
+        }
+    };
+    const int a_off = (wm * 128 + (lane & 31)) * RS + (lane >> 5) * 8;
+    const int b_off = TM * RS + (wn * 64 + (lane & 31)) * RS + (lane >> 5) * 8;
+    auto load_frags = [&](Frags& f, int stage, int ks) {
+        const uint16_t* base = lds + stage * kStageElems + ks * 16;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(base + a_off + i * 32 * RS);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(base + b_off + j * 32 * RS);
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    auto mma = [&](const Frags& f) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[i], f.b[j], acc[i][j], 0, 0, 0);
+    };
+
+    // prologue: slices 0 and 1 go straight to stages 0 and 1; slices 2..5 start travelling.
+    // Slice j always uses register set j % 4.
+    fetch(ra[0], rb[0], 0);
+    fetch(ra[1], rb[1], 1);
+    stash(ra[0], rb[0], 0);
+    stash(ra[1], rb[1], 1);
+    fetch(ra[2], rb[2], 2);
+    fetch(ra[3], rb[3], 3);
+    fetch(ra[0], rb[0], 4);
+    fetch(ra[1], rb[1], 5);
+    __syncthreads();
+    Frags f0, f1;
+    load_frags(f0, 0, 0);
+    int s_cur = 0, s_next = 1, s_fill = 2;
+    for (uint64_t kt = 0; kt < nkt; kt += kSets) {
+#pragma unroll
+        for (int u = 0; u < kSets; ++u) {
+            const uint64_t it = kt + u;
+            if (it < nkt) {                                     // uniform
+                constexpr int kDummy = 0; (void)kDummy;
+                const int q = (u + 2) % kSets;                  // register set of slice it+2 (kt is a multiple of 4)
+                if (it + 2 < nkt) stash(ra[q], rb[q], s_fill);  // stage last read in iteration it-1
+                fetch(ra[q], rb[q], it + 2 + kSets);
+                load_frags(f1, s_cur, 1);
+                mma(f0);
+                if (it + 1 < nkt) load_frags(f0, s_next, 0);    // complete since the previous barrier
+                mma(f1);
+                __syncthreads();
+                const int t = s_cur; s_cur = s_next; s_next = s_fill; s_fill = t;
+            }
+        }
+    }
+
+    // accumulator element e of a lane: row 8*(e/4) + 4*(lane/32) + e%4, column lane%32
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint64_t col = n0 + wn * 64 + j * 32 + (lane & 31);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const uint64_t row = m0 + wm * 128 + i * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                if (row < a.M && col < a.N) a.C[row * a.ldc + col] = acc[i][j][e];
+            }
+        }
+}
+
+// ---------------------------------------------------------------------------
+// Fast path (K a multiple of 32): the K slices travel HBM/L2 -> LDS directly
+// (global_load_lds_dwordx4: lane i of a wavefront deposits its 16 bytes at
+// LDS base + 16*i), so no registers are spent on staging and four LDS stages of
+// 32 KB keep two slices in flight behind the one being multiplied.  Rows are
+// stored unpadded (64 bytes); the 16-byte chunk kc of row r sits at position
+// kc ^ ((r >> 1) & 3), which makes the fragment reads of 8 consecutive rows hit
+// 8 distinct 16-byte bank groups.
+constexpr int kDmaStages = 4;
+constexpr int kDmaStageBytes = (TM + TN) * TK * 2;     // 32 KB
+
+__device__ __forceinline__ void wait_vmcnt_le4() { __builtin_amdgcn_s_waitcnt(0x0F74); }   // vmcnt<=4, others free
+__device__ __forceinline__ void wait_vmcnt_0() { __builtin_amdgcn_s_waitcnt(0x0F70); }     // vmcnt==0, others free
+// Workgroup barrier without the memory fence of __syncthreads(): the fence would
+// wait for every outstanding direct-to-LDS load, including the slices that are
+// meant to stay in flight.  Each wavefront waits for its own loads of the slice
+// that must be visible (vmcnt) before it arrives here, which is all the ordering
+// the pipeline needs; the empty asm statements keep the compiler from moving LDS
+// accesses across the barrier.
+__device__ __forceinline__ void bare_barrier() {
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+__global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Args a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 2, wn = wave & 3;
+
+    const uint32_t total = a.tiles_m * a.tiles_n;
+    const uint32_t bid = blockIdx.x;
+    uint32_t logical = bid;
+    if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;
+    const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
+    const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
+
+    // DMA map: the stage is 512 rows (A then B) = 32 groups of 16 rows; wavefront w moves groups 4w..4w+3,
+    // lane i moves row 16*group + i/4, LDS chunk position i%4, i.e. global chunk (i%4) ^ swizzle(row).
+    const uint16_t* gsrc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int grp = wave * 4 + j;
+        const int r = grp * 16 + (lane >> 2);                      // 0..511
+        const int kc = (lane & 3) ^ ((r >> 1) & 3);
+        if (r < TM) {
+            const uint64_t row = m0 + r;
+            gsrc[j] = a.A + (row < a.M ? row : a.M - 1) * a.lda + kc * 8;     // rows past the edge re-read the last row;
+        } else {                                                              // their products are never stored
+            const uint64_t row = n0 + (r - TM);
+            gsrc[j] = a.B + (row < a.N ? row : a.N - 1) * a.ldb + kc * 8;
+        }
+    }
+    auto dma = [&](uint64_t slice, int stage) {
+        unsigned char* base = smem + stage * kDmaStageBytes + wave * 4096;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            __builtin_amdgcn_global_load_lds(gsrc[j] + slice * TK, reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
+    };
+
+    // fragment addresses: row*64 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
+    const int fl = (lane >> 1) & 3;
+    const int koff0 = (((lane >> 5)) ^ fl) * 16, koff1 = ((2 + (lane >> 5)) ^ fl) * 16;
+    const int a_row = (wm * 128 + (lane & 31)) * 64;
+    const int b_row = (TM + wn * 64 + (lane & 31)) * 64;
+    auto load_frags = [&](Frags& f, int stage, int ks) {
+        const unsigned char* base = smem + stage * kDmaStageBytes + (ks ? koff1 : koff0);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(base + a_row + i * 32 * 64);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(base + b_row + j * 32 * 64);
+    };
+
+    f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    auto mma_half = [&](const Frags& f, int half) {       // rows 64*half .. 64*half+63 of the wavefront tile
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                acc[2 * half + i][j] =
+                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[2 * half + i], f.b[j], acc[2 * half + i][j], 0, 0, 0);
+    };
+
+    const uint64_t nkt = a.K / TK;            // K is a multiple of 32 here
+    // invariant at the top of iteration kt: slices <= kt+1 are in LDS and visible, slice kt+2 is in flight
+    dma(0, 0);
+    if (nkt > 1) dma(1, 1);
+    if (nkt > 2) { dma(2, 2); wait_vmcnt_le4(); } else { wait_vmcnt_0(); }
+    bare_barrier();
+    Frags f0, f1;
+    load_frags(f0, 0, 0);
+    for (uint64_t kt = 0; kt < nkt; ++kt) {
+        const int cur = (int)(kt & 3), nxt = (int)((kt + 1) & 3);
+        const bool issue = kt + 3 < nkt;
+        if (issue) dma(kt + 3, (int)((kt + 3) & 3));          // that stage was last read in iteration kt-1
+        load_frags(f1, cur, 1);
+        mma_half(f0, 0);
+        mma_half(f0, 1);
+        mma_half(f1, 0);                                      // queued MFMA work hides the latency of the next reads
+        if (kt + 1 < nkt) load_frags(f0, nxt, 0);
+        mma_half(f1, 1);
+        if (issue) wait_vmcnt_le4(); else wait_vmcnt_0();     // this wavefront's part of slice kt+2 has landed
+        bare_barrier();
+    }
+
+    const bool interior = m0 + TM <= a.M && n0 + TN <= a.N;     // uniform
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const uint64_t col = n0 + wn * 64 + j * 32 + (lane & 31);
+            const uint64_t rbase = m0 + wm * 128 + i * 32 + 4 * (lane >> 5);
+            if (interior) {
+                float* c = a.C + rbase * a.ldc + col;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) c[(uint64_t)(8 * (e >> 2) + (e & 3)) * a.ldc] = acc[i][j][e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const uint64_t row = rbase + 8 * (e >> 2) + (e & 3);
+                    if (row < a.M && col < a.N) a.C[row * a.ldc + col] = acc[i][j][e];
+                }
+            }
+        }
+}
+
+// fp32 -> bf16, round to nearest even; 4 elements per thread.
+__global__ void __launch_bounds__(256) to_bf16_kernel(const float* src, uint64_t rows, uint64_t cols, uint64_t ld_src,
+                                                      uint16_t* dst, uint64_t ld_dst) {
+    const uint64_t quads = (cols + 3) / 4;
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * quads) return;
+    const uint64_t r = t / quads, c0 = (t - r * quads) * 4;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        if (c0 + j < cols) {
+            uint32_t u = __float_as_uint(src[r * ld_src + c0 + j]);
+            uint16_t h;
+            if ((u & 0x7FFFFFFFu) > 0x7F800000u) h = (uint16_t)((u >> 16) | 0x40u);
+            else { u += 0x7FFFu + ((u >> 16) & 1u); h = (uint16_t)(u >> 16); }
+            dst[r * ld_dst + c0 + j] = h;
+        }
+    }
+}
+
+}  // namespace grass
+
+using namespace grass;
+
+extern "C" grass_status grass_to_bf16(const float* src, uint64_t rows, uint64_t cols, uint64_t ld_src, void* dst,
+                                      uint64_t ld_dst, grass_stream stream) {
+    if (cols == 0) return GRASS_EINVAL;
+    if (rows == 0) return GRASS_OK;
+    if (!src || !dst || ld_src < cols || ld_dst < cols) return GRASS_EINVAL;
+    const uint64_t total = rows * ((cols + 3) / 4);
+    if (ceil_div(total, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    hipLaunchKernelGGL(to_bf16_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, as_stream(stream), src, rows,
+                       cols, ld_src, static_cast<uint16_t*>(dst), ld_dst);
+    return launch_status();
+}
+
+extern "C" grass_status grass_score_bf16(const void* train, const void* test, uint64_t N, uint64_t M, uint64_t K,
+                                         uint64_t ld_train, uint64_t ld_test, float* scores, uint64_t ld_scores,
+                                         grass_stream stream) {
+    if (K == 0) return GRASS_EINVAL;
+    if (N == 0 || M == 0) return GRASS_OK;
+    if (!train || !test || !scores || ld_train < K || ld_test < K || ld_scores < N) return GRASS_EINVAL;
+    // 16-byte chunks: K and the leading dimensions in multiples of 8 elements, 16-byte aligned bases
+    if (K % 8 != 0 || ld_train % 8 != 0 || ld_test % 8 != 0 || !aligned(train, 16) || !aligned(test, 16))
+        return GRASS_EUNSUPPORTED;
+    GemmBf16Args a;
+    a.A = static_cast<const uint16_t*>(test);
+    a.B = static_cast<const uint16_t*>(train);
+    a.C = scores;
+    a.M = M; a.N = N; a.K = K; a.lda = ld_test; a.ldb = ld_train; a.ldc = ld_scores;
+    a.tiles_m = (uint32_t)ceil_div(M, TM);
+    a.tiles_n = (uint32_t)ceil_div(N, TN);
+    const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n;
+    if (total > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    static bool attr_done = false;
+    const size_t lds_bytes = (size_t)kStages * kStageElems * sizeof(uint16_t);
+    if (!attr_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_nt_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
+            return GRASS_EHIP;
+        attr_done = true;
+    }
+    static bool attr_dma_done = false;
+    if (!attr_dma_done) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_dma_kernel),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
+            return GRASS_EHIP;
+        attr_dma_done = true;
+    }
+    if (K % TK == 0)
+        hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3((uint32_t)total), dim3(kBf16Threads),
+                           (size_t)kDmaStages * kDmaStageBytes, as_stream(stream), a);
+    else
+        hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((uint32_t)total), dim3(kBf16Threads), lds_bytes, as_stream(stream), a);
+    return launch_status();
+}

@@ -128,6 +128,32 @@ def test_score_parity(grass, N, M, K, mode):
         _check_bf16_mode(sc.cpu().numpy(), test.cpu().numpy(), train.cpu().numpy())
 
 
+BF16_SCORE_CASES = [(1, 1, 8), (300, 200, 1000), (256, 256, 64), (257, 255, 72), (1024, 512, 4096), (700, 1024, 136)]
+
+
+@pytest.mark.parametrize("N,M,K", BF16_SCORE_CASES)
+def test_score_bf16_inputs_parity(grass, N, M, K):
+    """bf16 operands are exact inputs: only the fp32 accumulation order differs from the oracle."""
+    train = synth.dense_normal(N, K, seed=76, device=_dev())
+    test = synth.dense_normal(M, K, seed=77, device=_dev())
+    trb, teb = grass.grass_to_bf16(train), grass.grass_to_bf16(test)
+    torch.cuda.synchronize()
+    # the conversion is round-to-nearest-even, bit for bit what torch does
+    assert torch.equal(trb, train.to(torch.bfloat16)) and torch.equal(teb, test.to(torch.bfloat16))
+    sc = grass.grass_score_bf16(trb, teb)
+    torch.cuda.synchronize()
+    ref = orc.score(trb.float().cpu().numpy(), teb.float().cpu().numpy())
+    assert sc.shape == (M, N)
+    assert orc.max_rel_err(sc.cpu().numpy(), ref) <= TOL_F32
+
+
+def test_score_bf16_rejects_unaligned_k(grass):
+    tr = torch.zeros((16, 12), dtype=torch.bfloat16, device=_dev())
+    with pytest.raises(grass.GrassError) as e:
+        grass.grass_score_bf16(tr, tr)
+    assert e.value.status == grass.GRASS_EUNSUPPORTED
+
+
 def test_score_unaligned_leading_dimensions(grass):
     N, M, K = 70, 40, 50
     tr = synth.dense_normal(N, K + 1, seed=72, device=_dev())[:, :K]
