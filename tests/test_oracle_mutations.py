@@ -1,0 +1,141 @@
+"""The pins bite: each plausible mistake planted in the oracle (CPU only) makes
+at least one pin fail.  Mistakes are planted by monkeypatching the oracle, never
+the GPU path."""
+import importlib.util
+import os
+
+import numpy as np
+import pytest
+
+from oracle import grass_oracle as orc
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _load(name):
+    spec = importlib.util.spec_from_file_location(name, os.path.join(HERE, name + ".py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    return mod
+
+
+pins_sjlt = _load("test_oracle_sjlt")
+pins_mask = _load("test_oracle_hash_mask")
+pins_fact = _load("test_oracle_factgrass_score")
+
+_U64 = np.uint64
+
+
+def _tables_variant(flip_sign=False, low_bits=False, no_block_offset=False, counter_transposed=False):
+    def tables(seed, stream, d, k, s):
+        m = k // s
+        if counter_transposed:
+            c = (np.arange(d, dtype=np.uint64)[:, None] + np.arange(s, dtype=np.uint64)[None, :] * _U64(d)).ravel()
+        else:
+            c = np.arange(d * s, dtype=np.uint64)
+        h = orc.stream_hash(seed, stream, c).reshape(d, s)
+        word = (h & _U64(0xFFFFFFFF)) if low_bits else (h >> _U64(32))
+        within = (word * _U64(m)) >> _U64(32)
+        off = np.zeros(s, dtype=np.uint64) if no_block_offset else np.arange(s, dtype=np.uint64) * _U64(m)
+        bucket = (within + off[None, :]).astype(np.uint32)
+        plus = (h & _U64(1)) == (1 if flip_sign else 0)
+        return bucket, np.where(plus, 1, -1).astype(np.int8)
+    return tables
+
+
+@pytest.mark.parametrize("kwargs", [dict(flip_sign=True), dict(low_bits=True), dict(counter_transposed=True)])
+def test_wrong_hash_use_is_caught_by_the_integer_brute_force(monkeypatch, kwargs):
+    monkeypatch.setattr(orc, "sjlt_tables", _tables_variant(**kwargs))
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_tables_brute_force_from_sequential_generator()
+
+
+def test_missing_block_offset_is_caught_by_the_structure_pin(monkeypatch):
+    monkeypatch.setattr(orc, "sjlt_tables", _tables_variant(no_block_offset=True))
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_tables_structure(200, 12, 4)
+
+
+def test_missing_scale_is_caught_by_the_norm_pin(monkeypatch):
+    def sjlt_unscaled(g, k, s, seed, stream=orc.STREAM_SJLT):
+        g = np.asarray(g, dtype=np.float64)
+        if g.ndim == 1:
+            return sjlt_unscaled(g[None, :], k, s, seed, stream)[0]
+        bucket, sign = orc.sjlt_tables(seed, stream, g.shape[1], k, s)
+        out = np.zeros((g.shape[0], k))
+        for i in range(g.shape[0]):
+            for r in range(s):
+                np.add.at(out[i], bucket[:, r], sign[:, r] * g[i])
+        return out
+    monkeypatch.setattr(orc, "sjlt", sjlt_unscaled)
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_sjlt_preserves_squared_norm_in_expectation(4)
+
+
+def test_dropped_sign_is_caught_by_the_dense_matrix_pin(monkeypatch):
+    real = orc.sjlt_tables
+
+    def all_plus(seed, stream, d, k, s):
+        b, sg = real(seed, stream, d, k, s)
+        return b, np.ones_like(sg)
+    # the dense matrix is built from the same tables, so that pin alone cannot see it ...
+    monkeypatch.setattr(orc, "sjlt_tables", all_plus)
+    pins_sjlt.test_sjlt_equals_dense_matrix_product(97, 16, 1)
+    # ... the sign-balance and integer brute-force pins do
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_bucket_histogram_uniform_and_signs_balanced()
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_tables_brute_force_from_sequential_generator()
+
+
+def test_swapped_kronecker_order_is_caught(monkeypatch):
+    def swapped(x, gout, idx_in, idx_out):
+        xs = np.asarray(x, dtype=np.float64)[..., np.asarray(idx_in, dtype=np.int64)]
+        gs = np.asarray(gout, dtype=np.float64)[..., np.asarray(idx_out, dtype=np.int64)]
+        return np.einsum("nta,ntb->nba", xs, gs).reshape(xs.shape[0], -1)      # g (x) x instead of x (x) g
+    monkeypatch.setattr(orc, "factgrass_sparsified_gradient", swapped)
+    with pytest.raises(AssertionError):
+        pins_fact.test_factgrass_equals_materialise_mask_sjlt()
+    with pytest.raises(AssertionError):
+        pins_fact.test_swapping_factors_changes_the_order()
+
+
+def test_dropped_token_is_caught(monkeypatch):
+    real = orc.factgrass_sparsified_gradient
+    monkeypatch.setattr(orc, "factgrass_sparsified_gradient",
+                        lambda x, g, ii, io: real(np.asarray(x)[:, :-1], np.asarray(g)[:, :-1], ii, io))
+    with pytest.raises(AssertionError):
+        pins_fact.test_vec_identity_of_eq2()
+
+
+def test_mask_taking_largest_keys_is_caught(monkeypatch):
+    def largest(seed, stream, p, kprime):
+        j = np.arange(p, dtype=np.uint64)
+        key = orc.stream_hash(seed, stream, j)
+        order = np.lexsort((j, key))[::-1]
+        return np.sort(order[:kprime]).astype(np.int32)
+    monkeypatch.setattr(orc, "mask_indices", largest)
+    with pytest.raises(AssertionError):
+        pins_mask.test_mask_indices_brute_force(100, 10, 3, 0)
+
+
+def test_grass_keyed_by_original_coordinate_is_caught(monkeypatch):
+    def grass_wrong_key(g, idx, k, s, seed, stream=orc.STREAM_SJLT):
+        g = np.asarray(g, dtype=np.float64)
+        p = g.shape[-1]
+        bucket, sign = orc.sjlt_tables(seed, stream, p, k, s)          # tables over [p), not over [k')
+        out = np.zeros((g.shape[0], k))
+        for i in range(g.shape[0]):
+            for r in range(s):
+                np.add.at(out[i], bucket[idx, r], sign[idx, r] * g[i, idx] / np.sqrt(s))
+        return out
+    monkeypatch.setattr(orc, "grass", grass_wrong_key)
+    with pytest.raises(AssertionError):
+        pins_sjlt.test_grass_equals_masked_matrix_product()
+
+
+def test_mask_with_rescaling_is_caught(monkeypatch):
+    real = orc.mask
+    monkeypatch.setattr(orc, "mask", lambda g, idx: real(g, idx) * np.sqrt(np.asarray(g).shape[-1] / len(idx)))
+    with pytest.raises(AssertionError):
+        pins_mask.test_mask_norm_expectation()
