@@ -182,15 +182,14 @@ def main() -> int:
         del x4, go4, o4, w4
 
         # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
-        # one input buffer per distinct layer shape, per-layer masks and SJLT streams, outputs concatenated
+        # every layer with its own activations and gradients (12.3 GB in total, so nothing is served from
+        # cache), per-layer masks and SJLT streams, outputs concatenated
         n5, T5, kl = 8, 1024, 4096
-        bufs, layers = {}, []
-        for name, d_in, d_out in synth.LLAMA_BLOCK_LINEARS:
-            if (d_in, d_out) not in bufs:
-                bufs[(d_in, d_out)] = synth.linear_layer_factors(n5, T5, d_in, d_out, seed=1005 + len(bufs), device=dev)
+        layers = []
         for layer in range(16 * 7):
             name, d_in, d_out = synth.LLAMA_BLOCK_LINEARS[layer % 7]
-            layers.append((bufs[(d_in, d_out)], grass.grass_mask_indices(seed, 16 + 4 * layer, d_in, kf, device=dev),
+            layers.append((synth.linear_layer_factors(n5, T5, d_in, d_out, seed=2000 + layer, device=dev),
+                           grass.grass_mask_indices(seed, 16 + 4 * layer, d_in, kf, device=dev),
                            grass.grass_mask_indices(seed, 17 + 4 * layer, d_out, kf, device=dev), 18 + 4 * layer))
         cat = torch.empty((n5, kl * len(layers)), dtype=torch.float32, device=dev)
         w5 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n5, T5, kf, kf, kl, 1), 1), dtype=torch.uint8,
@@ -203,7 +202,14 @@ def main() -> int:
         t, _, wall = _timed(llama_pass, 5, 2, torch)
         extras["factgrass_llama_112_layers"] = {"ms": round(t / 5, 4), "tokens_per_s": round(n5 * T5 / (t / 5 * 1e-3), 1),
                                                 "layer_calls_per_pass": len(layers)}
-        del bufs, layers, cat, w5
+        batched = [(xl, gl, a_in, a_out, stream_id) for ((xl, gl), a_in, a_out, stream_id) in layers]
+        wb = torch.empty(max(grass.factgrass_layers_workspace_bytes(len(layers), n5, T5, kf, kf, kl, 1), 1),
+                         dtype=torch.uint8, device=dev)
+        t, _, wall = _timed(lambda: grass.factgrass_layers(batched, kl, 1, seed, cat, ws=wb), 5, 2, torch)
+        extras["factgrass_llama_112_layers_one_launch"] = {"ms": round(t / 5, 4),
+                                                           "tokens_per_s": round(n5 * T5 / (t / 5 * 1e-3), 1)}
+        del wb, batched
+        del layers, cat, w5
         torch.cuda.empty_cache()
 
         # dense Gaussian projection baseline on a 131,072-column slice of the ResNet-scale problem

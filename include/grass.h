@@ -128,6 +128,28 @@ grass_status factgrass_linear(const void* x, const void* gout,
                               float* out, uint64_t ldo,
                               void* ws, size_t ws_bytes, grass_stream stream);
 
+/* The same for many linear layers of one model pass in a single launch (the
+ * per-layer gradients are compressed independently, Sec. 3.3.2; concatenating
+ * the blocks gives k = sum_l k_l).  All layers share n, T, the mask widths, k
+ * and s; each brings its own shapes, indices, SJLT stream id and output block.
+ * host_layers is a HOST array; every pointer inside it is a device pointer.
+ * The table is copied into the workspace on `stream` before the kernels run.   */
+typedef struct {
+    const void* x;            /* (n, T, d_in)  bf16 */
+    const void* gout;         /* (n, T, d_out) bf16 */
+    const int32_t* idx_in;    /* kin_p ascending indices into [0, d_in)  */
+    const int32_t* idx_out;   /* kout_p ascending indices into [0, d_out) */
+    uint32_t d_in, d_out;
+    uint64_t stream_id;       /* SJLT stream of this layer */
+    float* out;               /* n x k block of this layer, row distance ldo */
+} factgrass_layer;
+grass_status factgrass_layers_workspace_bytes(uint32_t n_layers, uint64_t n, uint64_t T, uint32_t kin_p,
+                                              uint32_t kout_p, uint32_t k, uint32_t s, size_t* host_bytes);
+grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_layers,
+                              uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
+                              uint32_t k, uint32_t s, uint64_t seed, uint64_t ldo,
+                              void* ws, size_t ws_bytes, grass_stream stream);
+
 /* ---------------------------------------------------------------------- score
  * Sec. 2.1, attribute stage: scores[m, i] = <test_m, train_i> for all pairs of
  * compressed gradients (no preconditioner).

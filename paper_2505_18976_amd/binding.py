@@ -22,6 +22,12 @@ GRASS_MAX_FACTOR = 128
 
 _u64, _u32, _sz, _vp, _int = ctypes.c_uint64, ctypes.c_uint32, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_int
 
+class FactgrassLayer(ctypes.Structure):
+    """Mirror of `factgrass_layer` in include/grass.h."""
+    _fields_ = [("x", _vp), ("gout", _vp), ("idx_in", _vp), ("idx_out", _vp),
+                ("d_in", _u32), ("d_out", _u32), ("stream_id", _u64), ("out", _vp)]
+
+
 # name -> (restype, argtypes); the list the ABI test checks against the header.
 SIGNATURES = {
     "grass_strerror": (ctypes.c_char_p, [_int]),
@@ -36,6 +42,9 @@ SIGNATURES = {
     "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
                                 _vp, _u64, _vp, _sz, _vp]),
+    "factgrass_layers_workspace_bytes": (_int, [_u32, _u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
+    "factgrass_layers": (_int, [ctypes.POINTER(FactgrassLayer), _u32, _u64, _u64, _u32, _u32, _u32, _u32, _u64, _u64,
+                                _vp, _sz, _vp]),
     "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_to_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_score_bf16": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
@@ -192,6 +201,31 @@ def factgrass_linear(x: torch.Tensor, gout: torch.Tensor, idx_in: torch.Tensor, 
                                            _ptr(idx_out), idx_out.numel(), k, s, seed, stream_id, _ptr(out),
                                            _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "factgrass_linear")
+    return out
+
+
+def factgrass_layers_workspace_bytes(n_layers: int, n: int, T: int, kin_p: int, kout_p: int, k: int, s: int) -> int:
+    out = _sz(0)
+    _check(load_library().factgrass_layers_workspace_bytes(n_layers, n, T, kin_p, kout_p, k, s, ctypes.byref(out)),
+           "factgrass_layers_workspace_bytes")
+    return out.value
+
+
+def factgrass_layers(layers, k: int, s: int, seed: int, out: torch.Tensor, ws: torch.Tensor | None = None):
+    """layers: list of (x, gout, idx_in, idx_out, stream_id); layer l is written to out[:, l*k:(l+1)*k]."""
+    n, T = layers[0][0].shape[0], layers[0][0].shape[1]
+    kin_p, kout_p = layers[0][2].numel(), layers[0][3].numel()
+    assert out.dtype == torch.float32 and out.shape[0] == n and out.shape[1] >= k * len(layers)
+    table = (FactgrassLayer * len(layers))()
+    for l, (x, g, ii, io, stream_id) in enumerate(layers):
+        assert x.dtype == torch.bfloat16 and g.dtype == torch.bfloat16 and x.is_contiguous() and g.is_contiguous()
+        assert x.shape[:2] == (n, T) and g.shape[:2] == (n, T) and ii.numel() == kin_p and io.numel() == kout_p
+        table[l] = FactgrassLayer(x.data_ptr(), g.data_ptr(), ii.data_ptr(), io.data_ptr(), x.shape[2], g.shape[2],
+                                  stream_id, out.data_ptr() + 4 * l * k)
+    if ws is None:
+        ws = _workspace(factgrass_layers_workspace_bytes(len(layers), n, T, kin_p, kout_p, k, s), out.device)
+    _check(load_library().factgrass_layers(table, len(layers), n, T, kin_p, kout_p, k, s, seed, _ld(out), _ptr(ws),
+                                           0 if ws is None else ws.numel(), _stream()), "factgrass_layers")
     return out
 
 

@@ -13,7 +13,14 @@
 // A workgroup (4 wavefronts) owns one sample and one chunk of its tokens.
 // Because the SJLT is linear, each chunk is projected on its own and the
 // per-chunk k-vectors are added in a fixed order by a second kernel.
+//
+// factgrass_layers runs many layers of one model pass (same n, T, mask widths
+// and k; per-layer shapes, indices, SJLT stream and output block) in a single
+// launch: blockIdx.z selects the layer descriptor, so the gather latency of one
+// workgroup overlaps with the matrix and SJLT phases of the others and the
+// launch cost is paid once.
 #include <type_traits>
+#include <vector>
 
 #include "grass_device.h"
 
@@ -28,18 +35,26 @@ constexpr int kTokTile = 32;              // tokens staged per step (two MFMA k-
 constexpr int kTokStride = kTokTile + 8;  // bf16 elements per LDS row: 80 bytes keeps 16-byte reads conflict-free
 constexpr int kFgThreads = 256;
 
-struct FgArgs {
+// Per-layer part of the arguments (device-resident array in the many-layer call).
+struct FgLayer {
     const uint16_t* x;      // (n, T, d_in) bf16 bits
     const uint16_t* g;      // (n, T, d_out) bf16 bits
     const int32_t* idx_in;
     const int32_t* idx_out;
-    float* dst;
-    uint64_t T;
-    uint64_t ld_dst, chunk_stride;
-    uint64_t sub;
-    uint32_t d_in, d_out, ka, kb;
+    float* out;             // n x k block of this layer (row distance ldo), used when there is one chunk
+    uint64_t sub;           // sub-seed of the layer's SJLT stream
+    uint32_t d_in, d_out;
+};
+
+struct FgArgs {
+    FgLayer one;            // the layer, when `many` is null
+    const FgLayer* many;    // device array indexed by blockIdx.z
+    float* partial;         // [layer][chunk][n][k] when chunks > 1
+    uint64_t T, n;
+    uint64_t ldo;
+    uint32_t ka, kb;
     uint32_t k, s, m;
-    uint32_t tokens_per_block;
+    uint32_t tokens_per_block, chunks;
     float scale;
 };
 
@@ -56,6 +71,7 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
     constexpr int NT = TA * TB;                    // output tiles
     constexpr int TPW = (NT + 3) / 4;              // tiles per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const FgLayer L = a.many ? a.many[blockIdx.z] : a.one;       // uniform
     const uint64_t sample = blockIdx.y;
     const uint64_t t_begin = (uint64_t)blockIdx.x * a.tokens_per_block;
     const uint64_t t_end = t_begin + a.tokens_per_block < a.T ? t_begin + a.tokens_per_block : a.T;
@@ -64,10 +80,10 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
     const int xa = tid % KA, xt0 = tid / KA;       // kFgThreads % KA == 0
     const int gb = tid % KB, gt0 = tid / KB;
     constexpr int XSTEP = kFgThreads / KA, GSTEP = kFgThreads / KB;
-    const int32_t xcol = (uint32_t)xa < a.ka ? a.idx_in[xa] : -1;
-    const int32_t gcol = (uint32_t)gb < a.kb ? a.idx_out[gb] : -1;
-    const uint16_t* xrow = a.x + sample * a.T * a.d_in;
-    const uint16_t* grow = a.g + sample * a.T * a.d_out;
+    const int32_t xcol = (uint32_t)xa < a.ka ? L.idx_in[xa] : -1;
+    const int32_t gcol = (uint32_t)gb < a.kb ? L.idx_out[gb] : -1;
+    const uint16_t* xrow = L.x + sample * a.T * L.d_in;
+    const uint16_t* grow = L.g + sample * a.T * L.d_out;
 
     f32x16 acc[TPW];
 #pragma unroll
@@ -80,12 +96,12 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
 #pragma unroll
         for (int i = 0; i < kTokTile / XSTEP; ++i) {
             const uint64_t t = t0 + xt0 + i * XSTEP;
-            xv[i] = (xcol >= 0 && t < t_end) ? xrow[t * a.d_in + xcol] : (uint16_t)0;
+            xv[i] = (xcol >= 0 && t < t_end) ? xrow[t * L.d_in + xcol] : (uint16_t)0;
         }
 #pragma unroll
         for (int i = 0; i < kTokTile / GSTEP; ++i) {
             const uint64_t t = t0 + gt0 + i * GSTEP;
-            gv[i] = (gcol >= 0 && t < t_end) ? grow[t * a.d_out + gcol] : (uint16_t)0;
+            gv[i] = (gcol >= 0 && t < t_end) ? grow[t * L.d_out + gcol] : (uint16_t)0;
         }
         __syncthreads();   // previous tile's MFMA reads are done
 #pragma unroll
@@ -128,7 +144,7 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
                 if (aq < a.ka && bq < a.kb && val != 0.0f) {
                     uint64_t c = ((uint64_t)aq * a.kb + bq) * a.s;
                     for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
-                        const uint64_t h = sm(a.sub, c);
+                        const uint64_t h = sm(L.sub, c);
                         const uint32_t bucket = rr * a.m + bucket_of(h, a.m);
                         const float sv = __uint_as_float(__float_as_uint(val) ^ signbit_of(h));
                         if constexpr (F64) {
@@ -148,8 +164,29 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
         }
     }
     __syncthreads();
-    float* o = a.dst + (uint64_t)blockIdx.x * a.chunk_stride + sample * a.ld_dst;
-    for (uint32_t b = tid; b < a.k; b += kFgThreads) o[b] = (float)sk[b] * a.scale;
+    float* o;
+    float scale = a.scale;
+    if (a.chunks == 1) {
+        o = L.out + sample * a.ldo;
+    } else {
+        o = a.partial + (((uint64_t)blockIdx.z * a.chunks + blockIdx.x) * a.n + sample) * a.k;
+        scale = 1.0f;
+    }
+    for (uint32_t b = tid; b < a.k; b += kFgThreads) o[b] = (float)sk[b] * scale;
+}
+
+// out_l[i, b] = scale * sum_c partial[l][c][i][b], c ascending (fixed order).
+__global__ void __launch_bounds__(256) fg_reduce_kernel(FgArgs a) {
+    const FgLayer L = a.many ? a.many[blockIdx.y] : a.one;
+    const uint64_t total = a.n * a.k;
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= total) return;
+    const uint64_t i = t / a.k;
+    const uint32_t b = (uint32_t)(t - i * a.k);
+    const float* p = a.partial + (uint64_t)blockIdx.y * a.chunks * total + t;
+    float sum = 0.0f;
+    for (uint32_t c = 0; c < a.chunks; ++c) sum += p[(uint64_t)c * total];
+    L.out[i * a.ldo + b] = sum * a.scale;
 }
 
 struct FgPlan {
@@ -161,7 +198,7 @@ struct FgPlan {
 
 static int tiles_for(uint32_t kq) { return kq <= 32 ? 1 : (kq <= 64 ? 2 : 4); }
 
-static bool plan_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, FgPlan* pl) {
+static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, FgPlan* pl) {
     if (ka == 0 || kb == 0 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR) return false;
     pl->TA = tiles_for(ka);
     pl->TB = tiles_for(kb);
@@ -170,7 +207,7 @@ static bool plan_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k
     // 128 / 64 / 32 tokens that still yields at least half a workgroup per CU.
     uint64_t tpb = 32;
     for (uint64_t cand : {128ull, 64ull}) {
-        if (n * ceil_div(T, cand) >= (uint64_t)kNumCU / 2) { tpb = cand; break; }
+        if (n_layers * n * ceil_div(T, cand) >= (uint64_t)kNumCU / 2) { tpb = cand; break; }
     }
     if (tpb > ceil_div(T, kTokTile) * kTokTile) tpb = ceil_div(T, kTokTile) * kTokTile;
     if (g_tune_tokens > 0) tpb = ceil_div((uint64_t)g_tune_tokens, kTokTile) * kTokTile;
@@ -182,12 +219,12 @@ static bool plan_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k
     pl->f64 = (size_t)k * sizeof(double) <= 64 * 1024;      // keeps at least two workgroups per CU
     const size_t buckets = (size_t)k * (pl->f64 ? sizeof(double) : sizeof(float));
     pl->lds_bytes = stage > buckets ? stage : buckets;
-    pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * sizeof(float) : 0;
+    pl->ws_bytes = chunks > 1 ? (size_t)n_layers * chunks * n * k * sizeof(float) : 0;
     return pl->lds_bytes <= kLdsBytes - 1024;
 }
 
 template <int TA, int TB, bool F64>
-static hipError_t launch_fg2(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
+static hipError_t launch_fg2(const FgArgs& a, const FgPlan& pl, uint64_t n, uint32_t n_layers, hipStream_t st) {
     auto kern = factgrass_kernel<TA, TB, F64>;
     static bool attr_done = false;
     if (!attr_done) {
@@ -196,13 +233,37 @@ static hipError_t launch_fg2(const FgArgs& a, const FgPlan& pl, uint64_t n, hipS
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3(pl.chunks, (uint32_t)n), dim3(kFgThreads), pl.lds_bytes, st, a);
+    hipLaunchKernelGGL(kern, dim3(pl.chunks, (uint32_t)n, n_layers), dim3(kFgThreads), pl.lds_bytes, st, a);
     return hipGetLastError();
 }
 
 template <int TA, int TB>
-static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, hipStream_t st) {
-    return pl.f64 ? launch_fg2<TA, TB, true>(a, pl, n, st) : launch_fg2<TA, TB, false>(a, pl, n, st);
+static hipError_t launch_fg(const FgArgs& a, const FgPlan& pl, uint64_t n, uint32_t n_layers, hipStream_t st) {
+    return pl.f64 ? launch_fg2<TA, TB, true>(a, pl, n, n_layers, st) : launch_fg2<TA, TB, false>(a, pl, n, n_layers, st);
+}
+
+// Launches the compression kernel and, when tokens were chunked, the fixed-order reduction.
+static grass_status run_fg(FgArgs& a, const FgPlan& pl, uint32_t n_layers, hipStream_t hs) {
+    hipError_t e = hipErrorInvalidValue;
+    switch (pl.TA * 10 + pl.TB) {
+        case 11: e = launch_fg<1, 1>(a, pl, a.n, n_layers, hs); break;
+        case 12: e = launch_fg<1, 2>(a, pl, a.n, n_layers, hs); break;
+        case 14: e = launch_fg<1, 4>(a, pl, a.n, n_layers, hs); break;
+        case 21: e = launch_fg<2, 1>(a, pl, a.n, n_layers, hs); break;
+        case 22: e = launch_fg<2, 2>(a, pl, a.n, n_layers, hs); break;
+        case 24: e = launch_fg<2, 4>(a, pl, a.n, n_layers, hs); break;
+        case 41: e = launch_fg<4, 1>(a, pl, a.n, n_layers, hs); break;
+        case 42: e = launch_fg<4, 2>(a, pl, a.n, n_layers, hs); break;
+        case 44: e = launch_fg<4, 4>(a, pl, a.n, n_layers, hs); break;
+        default: return GRASS_EUNSUPPORTED;
+    }
+    if (e != hipSuccess) return GRASS_EHIP;
+    if (pl.chunks > 1) {
+        const uint64_t total = a.n * a.k;
+        hipLaunchKernelGGL(fg_reduce_kernel, dim3((uint32_t)ceil_div(total, 256), n_layers), dim3(256), 0, hs, a);
+        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+    }
+    return GRASS_OK;
 }
 
 }  // namespace grass
@@ -224,9 +285,18 @@ extern "C" grass_status factgrass_linear_workspace_bytes(uint64_t n, uint64_t T,
     if (st != GRASS_OK) return st;
     if (n == 0) { *host_bytes = 0; return GRASS_OK; }
     FgPlan pl;
-    if (!plan_fg(n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
     *host_bytes = pl.ws_bytes;
     return GRASS_OK;
+}
+
+static void fill_common(FgArgs& a, const FgPlan& pl, uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k,
+                        uint32_t s, uint64_t ldo) {
+    a.many = nullptr; a.partial = nullptr;
+    a.T = T; a.n = n; a.ldo = ldo; a.ka = ka; a.kb = kb;
+    a.k = k; a.s = s; a.m = k / s;
+    a.tokens_per_block = pl.tokens_per_block; a.chunks = pl.chunks;
+    a.scale = 1.0f / sqrtf((float)s);
 }
 
 extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64_t n, uint64_t T, uint32_t d_in,
@@ -240,44 +310,72 @@ extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64
     if (n == 0) return GRASS_OK;
     if (!x || !gout || !idx_in || !idx_out || !out || ldo < k) return GRASS_EINVAL;
     FgPlan pl;
-    if (!plan_fg(n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
 
     FgArgs a;
-    a.x = static_cast<const uint16_t*>(x);
-    a.g = static_cast<const uint16_t*>(gout);
-    a.idx_in = idx_in; a.idx_out = idx_out;
-    a.T = T; a.d_in = d_in; a.d_out = d_out; a.ka = kin_p; a.kb = kout_p;
-    a.k = k; a.s = s; a.m = k / s;
-    a.sub = substream(seed, stream_id);
-    a.tokens_per_block = pl.tokens_per_block;
-    const float scale = 1.0f / sqrtf((float)s);
-    if (pl.chunks == 1) {
-        a.dst = out; a.ld_dst = ldo; a.chunk_stride = 0; a.scale = scale;
-    } else {
-        a.dst = static_cast<float*>(ws); a.ld_dst = k; a.chunk_stride = n * k; a.scale = 1.0f;
+    fill_common(a, pl, n, T, kin_p, kout_p, k, s, ldo);
+    a.one.x = static_cast<const uint16_t*>(x);
+    a.one.g = static_cast<const uint16_t*>(gout);
+    a.one.idx_in = idx_in; a.one.idx_out = idx_out; a.one.out = out;
+    a.one.sub = substream(seed, stream_id);
+    a.one.d_in = d_in; a.one.d_out = d_out;
+    a.partial = static_cast<float*>(ws);
+    return run_fg(a, pl, 1, as_stream(stream));
+}
+
+static size_t layers_table_bytes(uint32_t n_layers) { return ((size_t)n_layers * sizeof(FgLayer) + 255) / 256 * 256; }
+
+extern "C" grass_status factgrass_layers_workspace_bytes(uint32_t n_layers, uint64_t n, uint64_t T, uint32_t kin_p,
+                                                         uint32_t kout_p, uint32_t k, uint32_t s, size_t* host_bytes) {
+    if (!host_bytes || n_layers == 0) return GRASS_EINVAL;
+    if (n_layers > 65535) return GRASS_EUNSUPPORTED;
+    grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) { *host_bytes = 0; return GRASS_OK; }
+    FgPlan pl;
+    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    *host_bytes = layers_table_bytes(n_layers) + pl.ws_bytes;
+    return GRASS_OK;
+}
+
+extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_layers, uint64_t n, uint64_t T,
+                                         uint32_t kin_p, uint32_t kout_p, uint32_t k, uint32_t s, uint64_t seed,
+                                         uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+    if (!host_layers || n_layers == 0) return GRASS_EINVAL;
+    if (n_layers > 65535) return GRASS_EUNSUPPORTED;
+    grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) return GRASS_OK;
+    if (ldo < k) return GRASS_EINVAL;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const factgrass_layer& h = host_layers[l];
+        if (!h.x || !h.gout || !h.idx_in || !h.idx_out || !h.out) return GRASS_EINVAL;
+        if (kin_p > h.d_in || kout_p > h.d_out) return GRASS_EINVAL;
+    }
+    FgPlan pl;
+    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    const size_t table = layers_table_bytes(n_layers);
+    if (!ws || ws_bytes < table + pl.ws_bytes || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+
+    // the descriptor table travels to the head of the workspace; it is built in a
+    // host vector that outlives the (pageable, hence host-synchronous) copy call
+    std::vector<FgLayer> dev(n_layers);
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const factgrass_layer& h = host_layers[l];
+        dev[l].x = static_cast<const uint16_t*>(h.x);
+        dev[l].g = static_cast<const uint16_t*>(h.gout);
+        dev[l].idx_in = h.idx_in; dev[l].idx_out = h.idx_out; dev[l].out = h.out;
+        dev[l].sub = substream(seed, h.stream_id);
+        dev[l].d_in = h.d_in; dev[l].d_out = h.d_out;
     }
     hipStream_t hs = as_stream(stream);
-    hipError_t e = hipErrorInvalidValue;
-    const int key = pl.TA * 10 + pl.TB;
-    switch (key) {
-        case 11: e = launch_fg<1, 1>(a, pl, n, hs); break;
-        case 12: e = launch_fg<1, 2>(a, pl, n, hs); break;
-        case 14: e = launch_fg<1, 4>(a, pl, n, hs); break;
-        case 21: e = launch_fg<2, 1>(a, pl, n, hs); break;
-        case 22: e = launch_fg<2, 2>(a, pl, n, hs); break;
-        case 24: e = launch_fg<2, 4>(a, pl, n, hs); break;
-        case 41: e = launch_fg<4, 1>(a, pl, n, hs); break;
-        case 42: e = launch_fg<4, 2>(a, pl, n, hs); break;
-        case 44: e = launch_fg<4, 4>(a, pl, n, hs); break;
-        default: return GRASS_EUNSUPPORTED;
-    }
-    if (e != hipSuccess) return GRASS_EHIP;
-    if (pl.chunks > 1) {
-        const uint64_t total = n * k;
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, hs,
-                           static_cast<const float*>(ws), n, k, pl.chunks, scale, out, ldo);
-        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
-    }
-    return GRASS_OK;
+    if (hipMemcpyAsync(ws, dev.data(), (size_t)n_layers * sizeof(FgLayer), hipMemcpyHostToDevice, hs) != hipSuccess)
+        return GRASS_EHIP;
+    FgArgs a;
+    fill_common(a, pl, n, T, kin_p, kout_p, k, s, ldo);
+    a.one = dev[0];
+    a.many = static_cast<const FgLayer*>(ws);
+    a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + table);
+    return run_fg(a, pl, n_layers, hs);
 }

@@ -109,6 +109,32 @@ def test_factgrass_concatenated_layers(grass):
         assert orc.max_rel_err(got[:, l * k_l:(l + 1) * k_l], ref) <= TOL_FACT
 
 
+@pytest.mark.parametrize("tokens", [0, 32])
+def test_factgrass_many_layers_in_one_launch(grass, tokens):
+    """factgrass_layers == factgrass_linear layer by layer == the oracle."""
+    n, T, k_l, kf = 3, 80, 512, 64
+    shapes = [(128, 128), (128, 512), (512, 128), (256, 192), (128, 128)]
+    cat = torch.full((n, k_l * len(shapes) + 7), -1.0, dtype=torch.float32, device=_dev())
+    layers, refs = [], []
+    for l, (d_in, d_out) in enumerate(shapes):
+        x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=90 + l, device=_dev())
+        s_in, s_out, s_sjlt = orc.layer_streams(l)
+        ii = grass.grass_mask_indices(0, s_in, d_in, kf, device=_dev())
+        io = grass.grass_mask_indices(0, s_out, d_out, kf, device=_dev())
+        layers.append((x, g, ii, io, s_sjlt))
+        refs.append(orc.factgrass_linear(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy(), k_l, 1, 0, s_sjlt))
+    grass.grass_set_factgrass_tuning(tokens)
+    try:
+        grass.factgrass_layers(layers, k_l, 1, 0, cat)
+        torch.cuda.synchronize()
+    finally:
+        grass.grass_set_factgrass_tuning(0)
+    got = cat.cpu().numpy()
+    for l, ref in enumerate(refs):
+        assert orc.max_rel_err(got[:, l * k_l:(l + 1) * k_l], ref) <= TOL_FACT
+    assert np.all(got[:, k_l * len(shapes):] == -1.0)          # columns beyond the last block are untouched
+
+
 # ------------------------------------------------------------------- score
 SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70)]
 
