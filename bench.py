@@ -179,7 +179,16 @@ def main() -> int:
         extras["factgrass_linear_4096"] = {"ms": round(t / 20, 4), "samples_per_s": round(n4 / (t / 20 * 1e-3), 1),
                                            "tokens_per_s": round(n4 * T4 / (t / 20 * 1e-3), 1),
                                            "useful_GBps": round(2 * n4 * T4 * 2 * kf * 2 / 2 / (t / 20 * 1e-3) / 1e9, 2)}
-        del x4, go4, o4, w4
+        # LoGra baseline (dense factorised projection to 64 x 64) on the same layer, for the speed ratio
+        Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 40, d4, kf, 0, d4, device=dev))
+        Po = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 41, d4, kf, 0, d4, device=dev))
+        ol = torch.empty((n4, kf * kf), dtype=torch.float32, device=dev)
+        wl = torch.empty(max(grass.logra_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
+        tl, _, _ = _timed(lambda: grass.logra_linear(x4, go4, Pi, Po, out=ol, ws=wl), 20, 3, torch)
+        extras["logra_linear_4096"] = {"ms": round(tl / 20, 4), "tokens_per_s": round(n4 * T4 / (tl / 20 * 1e-3), 1),
+                                       "algorithmic_GBps": round(2 * n4 * T4 * d4 * 2 / (tl / 20 * 1e-3) / 1e9, 1),
+                                       "factgrass_speedup": round((tl / 20) / extras["factgrass_linear_4096"]["ms"], 2)}
+        del x4, go4, o4, w4, Pi, Po, ol, wl
 
         # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
         # every layer with its own activations and gradients (12.3 GB in total, so nothing is served from

@@ -150,6 +150,23 @@ grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_lay
                               uint32_t k, uint32_t s, uint64_t seed, uint64_t ldo,
                               void* ws, size_t ws_bytes, grass_stream stream);
 
+/* ---------------------------------------------------------- LoGra baseline
+ * Sec. 3.3.2 "Recap on LoGra", Eq. (3): the factorised dense projection
+ * Gauss_{k_in (x) k_out} FactGraSS is compared with,
+ *     out_i[a*k_out + b] = sum_t (P_in x_t)[a] * (P_out g_t)[b].
+ * x: (n, T, d_in) bf16, gout: (n, T, d_out) bf16, P_in: k_in x d_in bf16,
+ * P_out: k_out x d_out bf16 (all contiguous; e.g. grass_gauss_matrix followed by
+ * grass_to_bf16).  out: n x (k_in*k_out) fp32, ldo >= k_in*k_out.  bf16 products
+ * are exact in fp32; both contractions accumulate in fp32.
+ * k_in, k_out <= 64; d_in, d_out multiples of 8 (GRASS_EUNSUPPORTED otherwise). */
+grass_status logra_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t k_in, uint32_t k_out,
+                                          size_t* host_bytes);
+grass_status logra_linear(const void* x, const void* gout,
+                          uint64_t n, uint64_t T, uint32_t d_in, uint32_t d_out,
+                          const void* P_in, uint32_t k_in, const void* P_out, uint32_t k_out,
+                          float* out, uint64_t ldo,
+                          void* ws, size_t ws_bytes, grass_stream stream);
+
 /* ---------------------------------------------------------------------- score
  * Sec. 2.1, attribute stage: scores[m, i] = <test_m, train_i> for all pairs of
  * compressed gradients (no preconditioner).

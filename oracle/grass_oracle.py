@@ -212,6 +212,25 @@ def factgrass_linear(x, gout, idx_in, idx_out, k: int, s: int, seed: int, stream
 
 
 # ----------------------------------------------------------------------------
+# LoGra baseline (Sec. 3.3.2, "Recap on LoGra"; Eq. (3)): the factorised dense
+# projection Gauss_{k_in (x) k_out} that FactGraSS is compared with.
+# ----------------------------------------------------------------------------
+def logra_linear(x: np.ndarray, gout: np.ndarray, P_in: np.ndarray, P_out: np.ndarray) -> np.ndarray:
+    """out_i = sum_t (P_in x_t) (x) (P_out g_t) = (P_in (x) P_out) vec(DW_i), flat index a*k_out + b.
+    x is (n, T, d_in), gout is (n, T, d_out), P_in is k_in x d_in, P_out is k_out x d_out (handed in as data)."""
+    xs = np.asarray(x, dtype=np.float64)
+    gs = np.asarray(gout, dtype=np.float64)
+    Pi = np.asarray(P_in, dtype=np.float64)
+    Po = np.asarray(P_out, dtype=np.float64)
+    n, T, _ = xs.shape
+    out = np.zeros((n, Pi.shape[0] * Po.shape[0]), dtype=np.float64)
+    for i in range(n):
+        for t in range(T):
+            out[i] += np.kron(Pi @ xs[i, t], Po @ gs[i, t])
+    return out
+
+
+# ----------------------------------------------------------------------------
 # Attribute stage (Sec. 2.1): all-pair inner products of compressed gradients,
 # without a preconditioner (GradDot).
 # ----------------------------------------------------------------------------

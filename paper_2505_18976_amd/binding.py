@@ -45,6 +45,8 @@ SIGNATURES = {
     "factgrass_layers_workspace_bytes": (_int, [_u32, _u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
     "factgrass_layers": (_int, [ctypes.POINTER(FactgrassLayer), _u32, _u64, _u64, _u32, _u32, _u32, _u32, _u64, _u64,
                                 _vp, _sz, _vp]),
+    "logra_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
+    "logra_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
     "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_to_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_score_bf16": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
@@ -226,6 +228,31 @@ def factgrass_layers(layers, k: int, s: int, seed: int, out: torch.Tensor, ws: t
         ws = _workspace(factgrass_layers_workspace_bytes(len(layers), n, T, kin_p, kout_p, k, s), out.device)
     _check(load_library().factgrass_layers(table, len(layers), n, T, kin_p, kout_p, k, s, seed, _ld(out), _ptr(ws),
                                            0 if ws is None else ws.numel(), _stream()), "factgrass_layers")
+    return out
+
+
+def logra_linear_workspace_bytes(n: int, T: int, k_in: int, k_out: int) -> int:
+    out = _sz(0)
+    _check(load_library().logra_linear_workspace_bytes(n, T, k_in, k_out, ctypes.byref(out)),
+           "logra_linear_workspace_bytes")
+    return out.value
+
+
+def logra_linear(x: torch.Tensor, gout: torch.Tensor, P_in: torch.Tensor, P_out: torch.Tensor,
+                 out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    for t in (x, gout, P_in, P_out):
+        assert t.dtype == torch.bfloat16 and t.is_contiguous()
+    n, T, d_in = x.shape
+    d_out = gout.shape[2]
+    k_in, k_out = P_in.shape[0], P_out.shape[0]
+    assert P_in.shape[1] == d_in and P_out.shape[1] == d_out and gout.shape[:2] == (n, T)
+    if out is None:
+        out = torch.empty((n, k_in * k_out), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(logra_linear_workspace_bytes(n, T, k_in, k_out), x.device)
+    _check(load_library().logra_linear(_ptr(x), _ptr(gout), n, T, d_in, d_out, _ptr(P_in), k_in, _ptr(P_out), k_out,
+                                       _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "logra_linear")
     return out
 
 

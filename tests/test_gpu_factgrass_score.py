@@ -135,6 +135,46 @@ def test_factgrass_many_layers_in_one_launch(grass, tokens):
     assert np.all(got[:, k_l * len(shapes):] == -1.0)          # columns beyond the last block are untouched
 
 
+# ------------------------------------------------------------------- LoGra
+TOL_LOGRA = 1e-4      # two chained fp32 accumulations (over d and over T) of exact bf16 products
+
+LOGRA_CASES = [
+    # n, T, d_in, d_out, k_in, k_out
+    (1, 1, 8, 8, 1, 1),
+    (2, 5, 40, 24, 7, 3),
+    (3, 70, 128, 256, 16, 16),
+    (2, 130, 264, 200, 32, 64),
+    (2, 300, 512, 384, 64, 64),
+    (8, 64, 2048, 2048, 64, 64),
+]
+
+
+@pytest.mark.parametrize("n,T,d_in,d_out,ki,ko", LOGRA_CASES)
+def test_logra_parity(grass, n, T, d_in, d_out, ki, ko):
+    x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=95, device=_dev())
+    Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(0, 40, d_in, ki, 0, d_in, device=_dev()))
+    Po = grass.grass_to_bf16(grass.grass_gauss_matrix(0, 41, d_out, ko, 0, d_out, device=_dev()))
+    out = grass.logra_linear(x, g, Pi, Po)
+    torch.cuda.synchronize()
+    ref = orc.logra_linear(_np(x), _np(g), _np(Pi), _np(Po))
+    assert out.shape == (n, ki * ko)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_LOGRA
+
+
+def test_logra_with_selection_matrices_matches_factgrass_mask_stage(grass):
+    """Mask_{k_in (x) k_out}: LoGra's kernel fed selection matrices reproduces FactGraSS's sparsified gradient."""
+    n, T, d_in, d_out, kf = 2, 96, 256, 128, 32
+    x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=96, device=_dev())
+    ii = grass.grass_mask_indices(0, 16, d_in, kf, device=_dev())
+    io = grass.grass_mask_indices(0, 17, d_out, kf, device=_dev())
+    Mi = torch.zeros((kf, d_in), dtype=torch.bfloat16, device=_dev()); Mi[torch.arange(kf), ii.long()] = 1
+    Mo = torch.zeros((kf, d_out), dtype=torch.bfloat16, device=_dev()); Mo[torch.arange(kf), io.long()] = 1
+    out = grass.logra_linear(x, g, Mi, Mo)
+    torch.cuda.synchronize()
+    ref = orc.factgrass_sparsified_gradient(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy())
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_LOGRA
+
+
 # ------------------------------------------------------------------- score
 SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70)]
 

@@ -115,6 +115,42 @@ def test_swapping_factors_changes_the_order():
     assert np.flatnonzero(v).tolist() == [2 * 3 + 1]
 
 
+# ------------------------------------------------------------------- LoGra
+def test_logra_equals_kronecker_projection_of_the_layer_gradient():
+    """Eq. (3): (P_in (x) P_out) vec(DW) with vec(DW) = sum_t x_t (x) g_t (column-major vec of g x^T)."""
+    rng = np.random.default_rng(20)
+    n, T, d_in, d_out, ki, ko = 2, 5, 7, 6, 3, 4
+    x, g = _factors(rng, n, T, d_in, d_out)
+    Pi = rng.standard_normal((ki, d_in)); Po = rng.standard_normal((ko, d_out))
+    got = orc.logra_linear(x, g, Pi, Po)
+    for i in range(n):
+        DW = sum(np.outer(g[i, t], x[i, t]) for t in range(T))
+        want = np.kron(Pi, Po) @ DW.flatten(order="F")
+        assert np.allclose(got[i], want, rtol=0, atol=1e-11)
+
+
+def test_logra_with_selection_matrices_is_factorised_masking():
+    """Swapping the Gaussian factors for selection matrices gives Mask_{k_in (x) k_out},
+    i.e. FactGraSS's stages 1 and 2 (Sec. 3.3.2, 'Bottlenecks of integrating GraSS with LoGra')."""
+    rng = np.random.default_rng(21)
+    x, g = _factors(rng, 2, 4, 9, 8)
+    ii, io = np.array([1, 5, 8]), np.array([0, 2, 3, 7])
+    Mi = np.zeros((3, 9)); Mi[np.arange(3), ii] = 1
+    Mo = np.zeros((4, 8)); Mo[np.arange(4), io] = 1
+    assert np.allclose(orc.logra_linear(x, g, Mi, Mo), orc.factgrass_sparsified_gradient(x, g, ii, io),
+                       rtol=0, atol=1e-13)
+
+
+def test_logra_is_bilinear_and_token_additive():
+    rng = np.random.default_rng(22)
+    x, g = _factors(rng, 1, 6, 5, 4)
+    Pi = rng.standard_normal((2, 5)); Po = rng.standard_normal((3, 4))
+    whole = orc.logra_linear(x, g, Pi, Po)
+    parts = orc.logra_linear(x[:, :2], g[:, :2], Pi, Po) + orc.logra_linear(x[:, 2:], g[:, 2:], Pi, Po)
+    assert np.allclose(whole, parts, rtol=0, atol=1e-12)
+    assert np.allclose(orc.logra_linear(3 * x, g, Pi, Po), 3 * whole, rtol=0, atol=1e-12)
+
+
 # ------------------------------------------------------------------- score
 def test_score_definition_and_symmetry():
     rng = np.random.default_rng(7)
