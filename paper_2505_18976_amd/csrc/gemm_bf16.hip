@@ -1,6 +1,7 @@
-// Score GEMM on bf16 operands (Sec. 2.1, attribute stage: all-pair inner
-// products of compressed gradients), for callers that keep the compressed
-// gradients in bf16, plus the fp32 -> bf16 conversion they need.
+// Score GEMM (Sec. 2.1, attribute stage: all-pair inner products of compressed
+// gradients) on the direct-to-LDS pipeline: bf16 operands for callers that keep
+// the compressed gradients in bf16 (plus the fp32 -> bf16 conversion they need),
+// and fp32 operands (also used by the dense Gaussian baseline of Sec. 2.2).
 //
 // C[M x N] = A[M x K] * B[N x K]^T, A and B row-major bf16 with K contiguous,
 // fp32 accumulation.  One workgroup of 8 wavefronts (2 x 4) owns a 256 x 256 tile
@@ -188,8 +189,26 @@ __device__ __forceinline__ void bare_barrier() {
     asm volatile("" ::: "memory");
 }
 
-__global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Args a) {
+// F32 = false: bf16 operands, v_mfma_f32_32x32x16_bf16, a slice is 32 elements.
+// F32 = true:  fp32 operands, v_mfma_f32_32x32x2_f32, a slice is 16 elements.  The
+//   LDS image is the same (64-byte rows of four 16-byte chunks); a lane's chunk
+//   holds 4 consecutive k, and MFMA step e of a chunk pair uses element e of the
+//   lower lanes' chunk (k = 4c + e) and of the upper lanes' chunk (k = 4c + 4 + e),
+//   the same pairing for both operands.
+struct GemmDmaArgs {
+    const void* A;        // M x K
+    const void* B;        // N x K
+    float* C;             // M x N
+    uint64_t M, N, K, lda, ldb, ldc;
+    uint32_t tiles_m, tiles_n;
+    int accumulate;       // C += instead of C =
+};
+
+template <bool F32>
+__global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int ESZ = F32 ? 4 : 2;                 // bytes per element
+    constexpr int SK = 64 / ESZ;                     // elements per slice (64-byte rows)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
 
@@ -202,25 +221,26 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Arg
 
     // DMA map: the stage is 512 rows (A then B) = 32 groups of 16 rows; wavefront w moves groups 4w..4w+3,
     // lane i moves row 16*group + i/4, LDS chunk position i%4, i.e. global chunk (i%4) ^ swizzle(row).
-    const uint16_t* gsrc[4];
+    const unsigned char* gsrc[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int grp = wave * 4 + j;
         const int r = grp * 16 + (lane >> 2);                      // 0..511
         const int kc = (lane & 3) ^ ((r >> 1) & 3);
         if (r < TM) {
-            const uint64_t row = m0 + r;
-            gsrc[j] = a.A + (row < a.M ? row : a.M - 1) * a.lda + kc * 8;     // rows past the edge re-read the last row;
-        } else {                                                              // their products are never stored
+            const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
+            gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16;
+        } else {                                                    // their products are never stored
             const uint64_t row = n0 + (r - TM);
-            gsrc[j] = a.B + (row < a.N ? row : a.N - 1) * a.ldb + kc * 8;
+            gsrc[j] = static_cast<const unsigned char*>(a.B) + ((row < a.N ? row : a.N - 1) * a.ldb) * ESZ + kc * 16;
         }
     }
     auto dma = [&](uint64_t slice, int stage) {
         unsigned char* base = smem + stage * kDmaStageBytes + wave * 4096;
 #pragma unroll
         for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds(gsrc[j] + slice * TK, reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + slice * 64),
+                                             reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
     };
 
     // fragment addresses: row*64 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
@@ -228,12 +248,13 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Arg
     const int koff0 = (((lane >> 5)) ^ fl) * 16, koff1 = ((2 + (lane >> 5)) ^ fl) * 16;
     const int a_row = (wm * 128 + (lane & 31)) * 64;
     const int b_row = (TM + wn * 64 + (lane & 31)) * 64;
-    auto load_frags = [&](Frags& f, int stage, int ks) {
+    struct RawFrags { u32x4 a[4], b[2]; };
+    auto load_frags = [&](RawFrags& f, int stage, int ks) {
         const unsigned char* base = smem + stage * kDmaStageBytes + (ks ? koff1 : koff0);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const bf16x8*>(base + a_row + i * 32 * 64);
+        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 64);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const bf16x8*>(base + b_row + j * 32 * 64);
+        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 64);
     };
 
     f32x16 acc[4][2];
@@ -243,22 +264,32 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Arg
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    auto mma_half = [&](const Frags& f, int half) {       // rows 64*half .. 64*half+63 of the wavefront tile
+    auto mma_half = [&](const RawFrags& f, int half) {       // rows 64*half .. 64*half+63 of the wavefront tile
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
-                acc[2 * half + i][j] =
-                    __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.a[2 * half + i], f.b[j], acc[2 * half + i][j], 0, 0, 0);
+            for (int j = 0; j < 2; ++j) {
+                const int ii = 2 * half + i;
+                if constexpr (F32) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(f.a[ii][e]),
+                                                                          __uint_as_float(f.b[j][e]), acc[ii][j], 0, 0, 0);
+                } else {
+                    acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[ii]),
+                                                                         __builtin_bit_cast(bf16x8, f.b[j]), acc[ii][j],
+                                                                         0, 0, 0);
+                }
+            }
     };
 
-    const uint64_t nkt = a.K / TK;            // K is a multiple of 32 here
+    const uint64_t nkt = a.K / SK;            // K is a multiple of the slice width here
     // invariant at the top of iteration kt: slices <= kt+1 are in LDS and visible, slice kt+2 is in flight
     dma(0, 0);
     if (nkt > 1) dma(1, 1);
     if (nkt > 2) { dma(2, 2); wait_vmcnt_le4(); } else { wait_vmcnt_0(); }
     bare_barrier();
-    Frags f0, f1;
+    RawFrags f0, f1;
     load_frags(f0, 0, 0);
     for (uint64_t kt = 0; kt < nkt; ++kt) {
         const int cur = (int)(kt & 3), nxt = (int)((kt + 1) & 3);
@@ -281,7 +312,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Arg
         for (int j = 0; j < 2; ++j) {
             const uint64_t col = n0 + wn * 64 + j * 32 + (lane & 31);
             const uint64_t rbase = m0 + wm * 128 + i * 32 + 4 * (lane >> 5);
-            if (interior) {
+            if (interior && !a.accumulate) {
                 float* c = a.C + rbase * a.ldc + col;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) c[(uint64_t)(8 * (e >> 2) + (e & 3)) * a.ldc] = acc[i][j][e];
@@ -289,10 +320,44 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_dma_kernel(GemmBf16Arg
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     const uint64_t row = rbase + 8 * (e >> 2) + (e & 3);
-                    if (row < a.M && col < a.N) a.C[row * a.ldc + col] = acc[i][j][e];
+                    if (row < a.M && col < a.N) {
+                        float* c = a.C + row * a.ldc + col;
+                        *c = a.accumulate ? *c + acc[i][j][e] : acc[i][j][e];
+                    }
                 }
             }
         }
+}
+
+// Host-side launch shared by the score GEMMs and the Gaussian baseline.  Returns
+// false when the operands do not qualify (K not a multiple of the slice width,
+// leading dimensions or bases not 16-byte aligned); the caller then falls back.
+bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
+                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err) {
+    const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
+    if (K % sk != 0 || (lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
+    GemmDmaArgs a;
+    a.A = A; a.B = B; a.C = C; a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.accumulate = accumulate;
+    a.tiles_m = (uint32_t)ceil_div(M, TM);
+    a.tiles_n = (uint32_t)ceil_div(N, TN);
+    const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n;
+    if (total == 0 || total > 0x7FFFFFFFull) return false;
+    static bool attr_done[2] = {false, false};
+    const void* fn = f32 ? reinterpret_cast<const void*>(gemm_dma_kernel<true>)
+                         : reinterpret_cast<const void*>(gemm_dma_kernel<false>);
+    if (!attr_done[f32]) {
+        *err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (*err != hipSuccess) return true;
+        attr_done[f32] = true;
+    }
+    const size_t lds = (size_t)kDmaStages * kDmaStageBytes;
+    if (f32)
+        hipLaunchKernelGGL(gemm_dma_kernel<true>, dim3((uint32_t)total), dim3(kBf16Threads), lds, st, a);
+    else
+        hipLaunchKernelGGL(gemm_dma_kernel<false>, dim3((uint32_t)total), dim3(kBf16Threads), lds, st, a);
+    *err = hipGetLastError();
+    return true;
 }
 
 // fp32 -> bf16, round to nearest even; 4 elements per thread.
@@ -356,17 +421,9 @@ extern "C" grass_status grass_score_bf16(const void* train, const void* test, ui
             return GRASS_EHIP;
         attr_done = true;
     }
-    static bool attr_dma_done = false;
-    if (!attr_dma_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_dma_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
-            return GRASS_EHIP;
-        attr_dma_done = true;
-    }
-    if (K % TK == 0)
-        hipLaunchKernelGGL(gemm_bf16_dma_kernel, dim3((uint32_t)total), dim3(kBf16Threads),
-                           (size_t)kDmaStages * kDmaStageBytes, as_stream(stream), a);
-    else
-        hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((uint32_t)total), dim3(kBf16Threads), lds_bytes, as_stream(stream), a);
+    hipError_t derr = hipSuccess;
+    if (launch_gemm_dma(false, test, train, scores, M, N, K, ld_test, ld_train, ld_scores, 0, as_stream(stream), &derr))
+        return derr == hipSuccess ? GRASS_OK : GRASS_EHIP;
+    hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((uint32_t)total), dim3(kBf16Threads), lds_bytes, as_stream(stream), a);
     return launch_status();
 }

@@ -202,7 +202,15 @@ static int vec_width(const float* p, uint64_t ld) {
     return 1;
 }
 
+// defined in gemm_bf16.hip: 256 x 256 tiles fed by direct-to-LDS loads
+bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
+                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err);
+
 static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st) {
+    if (mode == 0 && a.M >= 128 && a.N >= 128) {       // large fp32 problems: the direct-to-LDS pipeline
+        hipError_t derr = hipSuccess;
+        if (launch_gemm_dma(true, a.A, a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc, a.accumulate, st, &derr)) return derr;
+    }
     GemmArgs g = a;
     g.tiles_m = (uint32_t)ceil_div(a.M, BM);
     g.tiles_n = (uint32_t)ceil_div(a.N, BN);
