@@ -12,7 +12,9 @@ orders are resolved, normalisation) the choice is stated in the docstring as a
 Pins (see tests/test_oracle_*.py): published splitmix64 outputs; brute force
 on tiny inputs; an explicitly materialised dense projection matrix; linearity;
 the Kronecker/vec identity of Eq. (2)/(3); closed-form first and second
-moments of the count-sketch norm; limits k'=p and k'=k of Sec. 3.3.1.
+moments of the count-sketch norm; limits k'=p and k'=k of Sec. 3.3.1; the
+Gaussian matrix against the normal distribution (Kolmogorov-Smirnov, moments)
+and the norm-preservation property of Sec. 2.2.
 Parity unpinned: absolute output values (the paper prints no worked example).
 """
 from __future__ import annotations
@@ -240,10 +242,28 @@ def score(train: np.ndarray, test: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
-# Dense random projection baseline (Sec. 2.2): g_hat = P g with P handed in as
-# data (k x p), so that no transcendental function has to agree bit for bit.
+# Dense random projection baseline (Sec. 2.2): g_hat = P g with P (k x p),
+# P_ab ~ N(0, 1/k) i.i.d.
+#
+# Reading (the paper says "Gaussian" and leaves out both the generator and the
+# 1/sqrt(k) that makes E||Pg||^2 = ||g||^2): entry (a, b) is one Box-Muller
+# normal from the hash of the flat index a*p + b.  Bits 63..41 of the hash give
+# u1 = (x + 1/2) / 2^23 in (0, 1) and bits 39..16 give u2 = y / 2^24 in [0, 1),
+# both exactly representable in fp32, and z = sqrt(-2 ln u1) cos(2 pi u2).
 # ----------------------------------------------------------------------------
+def gauss_matrix(seed: int, stream: int, p: int, k: int, p0: int = 0, pc: int | None = None, rows=None) -> np.ndarray:
+    """Columns [p0, p0+pc) of P as a k x pc float64 matrix (only the listed rows if `rows` is given)."""
+    pc = p - p0 if pc is None else pc
+    rows = (np.arange(k, dtype=np.uint64) if rows is None else np.asarray(rows, dtype=np.uint64))[:, None]
+    cols = (np.uint64(p0) + np.arange(pc, dtype=np.uint64))[None, :]
+    h = stream_hash(seed, stream, rows * np.uint64(p) + cols)
+    u1 = ((h >> _U64(41)).astype(np.float64) + 0.5) / 8388608.0
+    u2 = ((h >> _U64(16)) & _U64(0xFFFFFF)).astype(np.float64) / 16777216.0
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2) / np.sqrt(float(k))
+
+
 def gauss_project(g: np.ndarray, P: np.ndarray) -> np.ndarray:
+    """g_hat = g P^T for a materialised P (k x p)."""
     return np.asarray(g, dtype=np.float64) @ np.asarray(P, dtype=np.float64).T
 
 

@@ -202,6 +202,8 @@ struct GemmDmaArgs {
     uint64_t M, N, K, lda, ldb, ldc;
     uint32_t tiles_m, tiles_n;
     int accumulate;       // C += instead of C =
+    uint32_t slices_per_split;   // split-K: workgroup (split, tile) contracts slices [split*sps, (split+1)*sps)
+    uint64_t split_stride_c;     //          into C + split*split_stride_c
 };
 
 template <bool F32>
@@ -213,11 +215,14 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     const int wm = wave >> 2, wn = wave & 3;
 
     const uint32_t total = a.tiles_m * a.tiles_n;
-    const uint32_t bid = blockIdx.x;
+    const uint32_t split = blockIdx.x / total;
+    const uint32_t bid = blockIdx.x - split * total;
     uint32_t logical = bid;
     if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;
     const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
     const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
+    const uint64_t slice0 = (uint64_t)split * a.slices_per_split;
+    a.C += split * a.split_stride_c;
 
     // DMA map: the stage is 512 rows (A then B) = 32 groups of 16 rows; wavefront w moves groups 4w..4w+3,
     // lane i moves row 16*group + i/4, LDS chunk position i%4, i.e. global chunk (i%4) ^ swizzle(row).
@@ -229,10 +234,12 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         const int kc = (lane & 3) ^ ((r >> 1) & 3);
         if (r < TM) {
             const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
-            gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16;
+            gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16 +
+                      slice0 * 64;
         } else {                                                    // their products are never stored
             const uint64_t row = n0 + (r - TM);
-            gsrc[j] = static_cast<const unsigned char*>(a.B) + ((row < a.N ? row : a.N - 1) * a.ldb) * ESZ + kc * 16;
+            gsrc[j] = static_cast<const unsigned char*>(a.B) + ((row < a.N ? row : a.N - 1) * a.ldb) * ESZ + kc * 16 +
+                      slice0 * 64;
         }
     }
     auto dma = [&](uint64_t slice, int stage) {
@@ -283,7 +290,8 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
             }
     };
 
-    const uint64_t nkt = a.K / SK;            // K is a multiple of the slice width here
+    const uint64_t nk_all = a.K / SK;         // K is a multiple of the slice width here
+    const uint64_t nkt = nk_all - slice0 < a.slices_per_split ? nk_all - slice0 : a.slices_per_split;   // >= 1
     // invariant at the top of iteration kt: slices <= kt+1 are in LDS and visible, slice kt+2 is in flight
     dma(0, 0);
     if (nkt > 1) dma(1, 1);
@@ -329,11 +337,26 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         }
 }
 
+// Split-K factor that fills the chip when there are few output tiles: the number
+// of K ranges (at most max_splits) such that tiles*splits reaches the CU count.
+uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits) {
+    const uint64_t tiles = ceil_div(M, TM) * ceil_div(N, TN), slices = K / (f32 ? 16 : 32);
+    if (tiles == 0 || tiles >= kNumCU || slices < 64) return 1;
+    uint64_t s = ceil_div(kNumCU, tiles);
+    if (s > max_splits) s = max_splits;
+    if (s > slices / 32) s = slices / 32;                         // at least 32 slices per range
+    const uint64_t sps = ceil_div(slices, s);
+    return (uint32_t)ceil_div(slices, sps);                        // no empty range
+}
+
 // Host-side launch shared by the score GEMMs and the Gaussian baseline.  Returns
 // false when the operands do not qualify (K not a multiple of the slice width,
 // leading dimensions or bases not 16-byte aligned); the caller then falls back.
+// splits > 1 (a value from gemm_dma_splits) writes the partial product of K range
+// s to partials + s*M*N (dense M x N, accumulate applies to it) instead of C.
 bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
-                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err) {
+                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
+                     float* partials) {
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
     if (K % sk != 0 || (lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
     GemmDmaArgs a;
@@ -341,7 +364,14 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     a.accumulate = accumulate;
     a.tiles_m = (uint32_t)ceil_div(M, TM);
     a.tiles_n = (uint32_t)ceil_div(N, TN);
-    const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n;
+    const uint64_t slices = K / sk;
+    if (splits < 1 || !partials) splits = 1;
+    if (slices == 0 || splits > slices) return false;
+    a.slices_per_split = (uint32_t)ceil_div(slices, splits);
+    if (ceil_div(slices, a.slices_per_split) != splits) return false;      // every K range non-empty
+    a.split_stride_c = 0;
+    if (splits > 1) { a.C = partials; a.ldc = N; a.split_stride_c = M * N; }
+    const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return false;
     static bool attr_done[2] = {false, false};
     const void* fn = f32 ? reinterpret_cast<const void*>(gemm_dma_kernel<true>)
@@ -422,7 +452,8 @@ extern "C" grass_status grass_score_bf16(const void* train, const void* test, ui
         attr_done = true;
     }
     hipError_t derr = hipSuccess;
-    if (launch_gemm_dma(false, test, train, scores, M, N, K, ld_test, ld_train, ld_scores, 0, as_stream(stream), &derr))
+    if (launch_gemm_dma(false, test, train, scores, M, N, K, ld_test, ld_train, ld_scores, 0, as_stream(stream), &derr, 1,
+                        nullptr))
         return derr == hipSuccess ? GRASS_OK : GRASS_EHIP;
     hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((uint32_t)total), dim3(kBf16Threads), lds_bytes, as_stream(stream), a);
     return launch_status();

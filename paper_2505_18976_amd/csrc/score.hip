@@ -204,13 +204,20 @@ static int vec_width(const float* p, uint64_t ld) {
 
 // defined in gemm_bf16.hip: 256 x 256 tiles fed by direct-to-LDS loads
 bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
-                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err);
+                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
+                     float* partials);
+uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits);
 
-static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st) {
+// splits > 1 (fp32 mode only): K-range partial products go to `partials`, see launch_gemm_dma.
+static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint32_t splits = 1,
+                              float* partials = nullptr) {
     if (mode == 0 && a.M >= 128 && a.N >= 128) {       // large fp32 problems: the direct-to-LDS pipeline
         hipError_t derr = hipSuccess;
-        if (launch_gemm_dma(true, a.A, a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc, a.accumulate, st, &derr)) return derr;
+        if (launch_gemm_dma(true, a.A, a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc, a.accumulate, st, &derr, splits,
+                            partials))
+            return derr;
     }
+    if (splits > 1) return hipErrorInvalidValue;
     GemmArgs g = a;
     g.tiles_m = (uint32_t)ceil_div(a.M, BM);
     g.tiles_n = (uint32_t)ceil_div(a.N, BN);
@@ -232,19 +239,28 @@ static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st) {
 }
 
 // P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.
+// blockIdx.x: a run of 256 columns, blockIdx.y (+ stride): rows.
 __global__ void __launch_bounds__(256) gauss_matrix_kernel(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0,
                                                            uint64_t pc, float* P, uint64_t ldP, float inv_sqrt_k) {
-    const uint64_t total = (uint64_t)k * pc;
-    uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
-    for (; t < total; t += stride) {
-        const uint64_t row = t / pc, col = t - row * pc;
-        const uint64_t h = sm(sub, row * p + p0 + col);
-        const float u1 = ((float)(uint32_t)(h >> 40) + 0.5f) * (1.0f / 16777216.0f);          // (0, 1)
+    const uint64_t col = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (col >= pc) return;
+    for (uint32_t row = blockIdx.y; row < k; row += gridDim.y) {
+        const uint64_t h = sm(sub, (uint64_t)row * p + p0 + col);
+        const float u1 = ((float)(uint32_t)(h >> 41) + 0.5f) * (1.0f / 8388608.0f);           // (0, 1), exact
         const float u2 = (float)(uint32_t)((h >> 16) & 0xFFFFFFu) * (1.0f / 16777216.0f);      // [0, 1)
         const float rad = sqrtf(-2.0f * logf(u1));
-        P[row * ldP + col] = rad * cospif(2.0f * u2) * inv_sqrt_k;
+        P[(uint64_t)row * ldP + col] = rad * cospif(2.0f * u2) * inv_sqrt_k;
     }
+}
+
+static void launch_gauss_matrix(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0, uint64_t pc, float* P, uint64_t ldP,
+                                hipStream_t hs) {
+    const uint32_t gx = (uint32_t)ceil_div(pc, 256);
+    uint32_t gy = k;                                   // about 16K workgroups keep every CU busy
+    if ((uint64_t)gx * gy > 16384) gy = (uint32_t)(16384 / gx > 0 ? 16384 / gx : 1);
+    if (gy > 65535) gy = 65535;
+    hipLaunchKernelGGL(gauss_matrix_kernel, dim3(gx, gy), dim3(256), 0, hs, sub, p, k, p0, pc, P, ldP,
+                       1.0f / sqrtf((float)k));
 }
 
 }  // namespace grass
@@ -267,10 +283,8 @@ extern "C" grass_status grass_score(const float* train, const float* test, int c
 extern "C" grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t k, uint64_t p0,
                                            uint64_t pc, float* P, uint64_t ldP, grass_stream stream) {
     if (p == 0 || k == 0 || pc == 0 || p0 + pc > p || !P || ldP < pc) return GRASS_EINVAL;
-    const uint64_t total = (uint64_t)k * pc;
-    const uint32_t blocks = (uint32_t)(ceil_div(total, 256) > 16384 ? 16384 : ceil_div(total, 256));
-    hipLaunchKernelGGL(gauss_matrix_kernel, dim3(blocks), dim3(256), 0, as_stream(stream),
-                       substream(seed, stream_id), p, k, p0, pc, P, ldP, 1.0f / sqrtf((float)k));
+    if (ceil_div(pc, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    launch_gauss_matrix(substream(seed, stream_id), p, k, p0, pc, P, ldP, as_stream(stream));
     return launch_status();
 }
 
@@ -280,11 +294,20 @@ static uint64_t gauss_chunk(uint64_t p, uint64_t p_chunk) {
     return pc > p ? (p + 3) / 4 * 4 : pc;
 }
 
+// K ranges of the first (largest) chunk's product; later chunks never use more.
+static uint32_t gauss_splits(uint64_t n, uint64_t p, uint32_t k, uint64_t pc, int compute_mode) {
+    if (compute_mode != 0 || n < 128 || k < 128) return 1;
+    return gemm_dma_splits(n, k, pc < p ? pc : p, true, 8);
+}
+
+static size_t gauss_p_bytes(uint32_t k, uint64_t pc) { return ((size_t)k * pc * sizeof(float) + 255) / 256 * 256; }
+
 extern "C" grass_status grass_gauss_project_workspace_bytes(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk,
                                                             size_t* host_bytes) {
-    (void)n;
     if (!host_bytes || p == 0 || k == 0) return GRASS_EINVAL;
-    *host_bytes = (size_t)k * gauss_chunk(p, p_chunk) * sizeof(float);
+    const uint64_t pc = gauss_chunk(p, p_chunk);
+    const uint32_t splits = gauss_splits(n, p, k, pc, 0);          // the larger of the two modes' needs
+    *host_bytes = gauss_p_bytes(k, pc) + (splits > 1 ? (size_t)splits * n * k * sizeof(float) : 0);
     return GRASS_OK;
 }
 
@@ -296,22 +319,44 @@ extern "C" grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t
     if (n == 0) return GRASS_OK;
     if (!g || !out || ldg < p || ldo < k) return GRASS_EINVAL;
     const uint64_t pc = gauss_chunk(p, p_chunk);
-    if (!ws || ws_bytes < (size_t)k * pc * sizeof(float) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    if (ceil_div(pc, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    uint32_t splits = gauss_splits(n, p, k, pc, compute_mode);
+    // the split path needs every chunk to qualify for the direct-to-LDS kernel
+    if (splits > 1 && (!aligned(g, 16) || ldg % 4 != 0 || pc % 16 != 0 || (pc < p ? pc : p) % 16 != 0)) splits = 1;
+    const size_t need = gauss_p_bytes(k, pc) + (splits > 1 ? (size_t)splits * n * k * sizeof(float) : 0);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return GRASS_EWORKSPACE;
     float* P = static_cast<float*>(ws);
+    float* partials = splits > 1 ? reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + gauss_p_bytes(k, pc)) : nullptr;
     hipStream_t hs = as_stream(stream);
     const uint64_t sub = substream(seed, stream_id);
-    const float inv_sqrt_k = 1.0f / sqrtf((float)k);
     for (uint64_t p0 = 0; p0 < p; p0 += pc) {
         const uint64_t cur = p0 + pc <= p ? pc : p - p0;
-        const uint64_t total = (uint64_t)k * cur;
-        const uint32_t blocks = (uint32_t)(ceil_div(total, 256) > 16384 ? 16384 : ceil_div(total, 256));
-        hipLaunchKernelGGL(gauss_matrix_kernel, dim3(blocks), dim3(256), 0, hs, sub, p, k, p0, cur, P, pc,
-                           inv_sqrt_k);
+        launch_gauss_matrix(sub, p, k, p0, cur, P, pc, hs);
         GemmArgs a;
         a.A = g + p0; a.B = P; a.C = out;
         a.M = n; a.N = k; a.K = cur; a.lda = ldg; a.ldb = pc; a.ldc = ldo;
         a.accumulate = p0 != 0;
-        if (launch_gemm(a, compute_mode, hs) != hipSuccess) return GRASS_EHIP;
+        if (splits > 1 && cur % 16 == 0) {
+            uint32_t s_cur = gemm_dma_splits(n, k, cur, true, splits);
+            if (s_cur > splits) s_cur = splits;
+            if (s_cur == 1) {                              // short tail: a one-range product into partial 0
+                a.C = partials; a.ldc = k;
+                if (launch_gemm(a, 0, hs) != hipSuccess) return GRASS_EHIP;
+            } else if (launch_gemm(a, 0, hs, s_cur, partials) != hipSuccess) {
+                return GRASS_EHIP;
+            }
+        } else if (splits > 1) {                           // ragged tail (cur not a multiple of the slice width)
+            a.C = partials; a.ldc = k;
+            if (launch_gemm(a, 0, hs) != hipSuccess) return GRASS_EHIP;
+        } else if (launch_gemm(a, compute_mode, hs) != hipSuccess) {
+            return GRASS_EHIP;
+        }
+    }
+    if (splits > 1) {
+        const uint64_t total = n * (uint64_t)k;
+        if (ceil_div(total, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, hs, partials, n, k,
+                           splits, 1.0f, out, ldo);
     }
     return launch_status();
 }

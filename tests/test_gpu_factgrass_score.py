@@ -260,15 +260,30 @@ def test_gauss_matrix_moments_and_chunk_consistency(grass):
     assert abs(np.corrcoef(z[:-1], z[1:])[0, 1]) < 4 / np.sqrt(nz)
 
 
+@pytest.mark.parametrize("seed,stream,p,k,p0,pc", [(1, 2, 5001, 130, 0, 5001), (7, 40, 300, 257, 0, 300),
+                                                   (3, 2, 11173962, 70, 11173000, 962), (0, 2, 1, 1, 0, 1)])
+def test_gauss_matrix_parity(grass, seed, stream, p, k, p0, pc):
+    """Box-Muller in fp32 against the fp64 oracle: both start from the same exactly representable uniforms, so the
+    only difference is the rounding of logf, sqrtf and cospif (a few ulp of a value of magnitude <= 5.8/sqrt(k))."""
+    P = grass.grass_gauss_matrix(seed, stream, p, k, p0, pc, device=_dev())
+    torch.cuda.synchronize()
+    ref = orc.gauss_matrix(seed, stream, p, k, p0, pc)
+    assert P.shape == ref.shape
+    assert np.abs(P.cpu().numpy().astype(np.float64) - ref).max() * np.sqrt(k) <= 4e-6
+
+
 @pytest.mark.parametrize("n,p,k,chunk,mode", [(3, 100, 8, 0, 0), (70, 5001, 130, 1024, 0), (70, 5001, 130, 1024, 1),
-                                              (256, 16384, 256, 4096, 1), (33, 4098, 64, 4096, 0)])
+                                              (256, 16384, 256, 4096, 1), (33, 4098, 64, 4096, 0),
+                                              # few output tiles: the contraction is split over K ranges
+                                              (256, 16384, 256, 4096, 0), (130, 20000, 300, 8192, 0),
+                                              (128, 9000, 128, 4104, 0), (200, 2048, 128, 0, 0)])
 def test_gauss_project_parity(grass, n, p, k, chunk, mode):
     g = synth.laplace_sparse(n, p, 0.3, 1e-3, seed=80, device=_dev())
     out = grass.grass_gauss_project(g, k, seed=1, stream_id=2, p_chunk=chunk, compute_mode=mode)
-    P = grass.grass_gauss_matrix(1, 2, p, k, 0, p, device=_dev())
     torch.cuda.synchronize()
-    ref = orc.gauss_project(g.cpu().numpy(), P.cpu().numpy())
+    P = orc.gauss_matrix(1, 2, p, k)
+    ref = orc.gauss_project(g.cpu().numpy(), P)
     if mode == 0:
         assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_F32
     else:
-        _check_bf16_mode(out.cpu().numpy(), g.cpu().numpy(), P.cpu().numpy())
+        _check_bf16_mode(out.cpu().numpy(), g.cpu().numpy(), P.astype(np.float32))

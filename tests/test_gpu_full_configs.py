@@ -81,8 +81,7 @@ def test_resnet_scale_sjlt_and_gaussian_slice(grass):
         og = grass.grass_gauss_project(gs, k, seed=0, stream_id=2, p_chunk=chunk, compute_mode=mode)
         torch.cuda.synchronize()
         buckets = [0, 1, 4095, 8191]
-        Prows = np.concatenate([grass.grass_gauss_matrix(0, 2, pc, k, c0, chunk, device=_dev())[buckets].cpu().numpy()
-                                for c0 in range(0, pc, chunk)], axis=1).astype(np.float64)
+        Prows = orc.gauss_matrix(0, 2, pc, k, rows=buckets)
         gr = g_rows[:, :pc].astype(np.float64)
         exact = gr @ Prows.T
         got = og[rows][:, buckets].cpu().numpy()

@@ -184,3 +184,44 @@ def test_gauss_project_definition():
     for i in range(3):
         for a in range(5):
             assert np.isclose(out[i, a], sum(P[a, j] * g[i, j] for j in range(20)), rtol=1e-12)
+
+
+def test_gauss_matrix_is_standard_normal_scaled():
+    """Sec. 2.2: P_ab ~ N(0, 1/k) i.i.d.  Checked against scipy's normal CDF and the closed-form moments."""
+    from scipy import stats
+    p, k = 4000, 50
+    P = orc.gauss_matrix(5, 2, p, k)
+    z = P.ravel() * np.sqrt(k)
+    nz = z.size
+    assert stats.kstest(z, "norm").pvalue > 1e-3
+    assert abs(z.mean()) < 4 / np.sqrt(nz)
+    assert abs(z.var() - 1) < 4 * np.sqrt(2 / nz)
+    assert abs((z ** 3).mean()) < 4 * np.sqrt(15 / nz)
+    assert abs((z ** 4).mean() - 3) < 4 * np.sqrt(96 / nz)
+    # independence along both axes and between the two uniform fields
+    assert abs(np.corrcoef(P[:, :-1].ravel(), P[:, 1:].ravel())[0, 1]) < 4 / np.sqrt(nz)
+    assert abs(np.corrcoef(P[:-1].ravel(), P[1:].ravel())[0, 1]) < 4 / np.sqrt(nz)
+    assert abs(np.corrcoef(np.abs(P[:, :-1]).ravel(), np.abs(P[:, 1:]).ravel())[0, 1]) < 4 / np.sqrt(nz)
+
+
+def test_gauss_matrix_windows_seeds_and_streams():
+    p, k = 300, 7
+    P = orc.gauss_matrix(1, 2, p, k)
+    assert np.array_equal(orc.gauss_matrix(1, 2, p, k, 100, 50), P[:, 100:150])    # a window is a slice
+    assert np.array_equal(orc.gauss_matrix(1, 2, p, k, rows=[6, 0]), P[[6, 0]])
+    assert not np.allclose(orc.gauss_matrix(2, 2, p, k), P)
+    assert not np.allclose(orc.gauss_matrix(1, 3, p, k), P)
+    # entry (a, b) depends on the flat index a*p + b: with p' = 2p row a of the narrow matrix is not row a of the wide
+    assert not np.allclose(orc.gauss_matrix(1, 2, 2 * p, k)[1:, :p], P[1:])
+    assert np.array_equal(orc.gauss_matrix(1, 2, 2 * p, k)[0, :p], P[0] )
+
+
+def test_gauss_projection_preserves_norms_in_expectation():
+    """Sec. 2.2 (Johnson-Lindenstrauss): E||P g||^2 = ||g||^2 and Var = 2||g||^4/k for Gaussian P."""
+    rng = np.random.default_rng(3)
+    p, k, trials = 60, 16, 1500
+    g = rng.standard_normal((1, p))
+    vals = np.array([np.sum(orc.gauss_project(g, orc.gauss_matrix(seed, 2, p, k)) ** 2) for seed in range(trials)])
+    n2 = float(np.sum(g ** 2))
+    assert abs(vals.mean() - n2) < 4.5 * np.sqrt(2 * n2 ** 2 / k / trials)
+    assert abs(vals.var() / (2 * n2 ** 2 / k) - 1) < 0.25
