@@ -242,6 +242,35 @@ def score(train: np.ndarray, test: np.ndarray) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# Cache stage after compression (Sec. 2.1 steps 2 and 3, applied to compressed
+# gradients as in Sec. 2.2 / Sec. 3.3.2): the projected FIM of a block of k
+# compressed coordinates and the inverse-FIM-vector product with the damping
+# term of App. B ("damping lambda used for the Hessian/FIM inverse").
+#
+# Reading: the damped inverse is (F + lambda*I)^{-1} with lambda an absolute
+# number (the grid of App. B lists absolute values); the paper prints F^{-1}
+# only.  A block-diagonal FIM (Sec. 3.3.2) is this function applied to each
+# layer's k_l columns separately.
+# ----------------------------------------------------------------------------
+def fim(G: np.ndarray) -> np.ndarray:
+    """F = (1/n) sum_i g_i g_i^T for the rows g_i of G (n x k)."""
+    G = np.asarray(G, dtype=np.float64)
+    return G.T @ G / G.shape[0]
+
+
+def ifvp(G: np.ndarray, F: np.ndarray, lam: float) -> np.ndarray:
+    """Row i of the result is (F + lam*I)^{-1} g_i."""
+    G = np.asarray(G, dtype=np.float64)
+    F = np.asarray(F, dtype=np.float64)
+    return np.linalg.solve(F + lam * np.eye(F.shape[0]), G.T).T
+
+
+def influence(train: np.ndarray, test: np.ndarray, lam: float) -> np.ndarray:
+    """I[m, i] = <test_m, (F + lam*I)^{-1} train_i> with F the FIM of the train rows (Sec. 2.1)."""
+    return score(ifvp(train, fim(train), lam), test)
+
+
+# ----------------------------------------------------------------------------
 # Dense random projection baseline (Sec. 2.2): g_hat = P g with P (k x p),
 # P_ab ~ N(0, 1/k) i.i.d.
 #

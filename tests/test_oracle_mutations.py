@@ -22,6 +22,7 @@ def _load(name):
 pins_sjlt = _load("test_oracle_sjlt")
 pins_mask = _load("test_oracle_hash_mask")
 pins_fact = _load("test_oracle_factgrass_score")
+pins_fim = _load("test_oracle_fim")
 
 _U64 = np.uint64
 
@@ -139,3 +140,38 @@ def test_mask_with_rescaling_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "mask", lambda g, idx: real(g, idx) * np.sqrt(np.asarray(g).shape[-1] / len(idx)))
     with pytest.raises(AssertionError):
         pins_mask.test_mask_norm_expectation()
+
+
+def test_fim_without_the_sample_average_is_caught(monkeypatch):
+    monkeypatch.setattr(orc, "fim", lambda G: np.asarray(G, np.float64).T @ np.asarray(G, np.float64))
+    with pytest.raises(AssertionError):
+        pins_fim.test_fim_is_the_average_outer_product()
+    with pytest.raises(AssertionError):
+        pins_fim.test_ifvp_woodbury_when_fewer_rows_than_columns()
+
+
+def test_fim_of_the_transposed_matrix_is_caught(monkeypatch):
+    monkeypatch.setattr(orc, "fim", lambda G: np.asarray(G, np.float64) @ np.asarray(G, np.float64).T / G.shape[0])
+    with pytest.raises((AssertionError, ValueError)):
+        pins_fim.test_fim_is_the_average_outer_product()
+
+
+def test_ifvp_with_damping_dropped_or_scaled_is_caught(monkeypatch):
+    def no_damping(G, F, lam):
+        return np.linalg.solve(np.asarray(F, np.float64) + 1e-300 * np.eye(F.shape[0]), np.asarray(G, np.float64).T).T
+    monkeypatch.setattr(orc, "ifvp", no_damping)
+    with pytest.raises(AssertionError):
+        pins_fim.test_ifvp_diagonal_fim_is_an_elementwise_division()
+
+    def damping_times_k(G, F, lam):
+        k = F.shape[0]
+        return np.linalg.solve(np.asarray(F, np.float64) + lam * k * np.eye(k), np.asarray(G, np.float64).T).T
+    monkeypatch.setattr(orc, "ifvp", damping_times_k)
+    with pytest.raises(AssertionError):
+        pins_fim.test_ifvp_rank_one_fim_sherman_morrison()
+
+
+def test_ifvp_multiplying_instead_of_solving_is_caught(monkeypatch):
+    monkeypatch.setattr(orc, "ifvp", lambda G, F, lam: np.asarray(G, np.float64) @ (F + lam * np.eye(F.shape[0])))
+    with pytest.raises(AssertionError):
+        pins_fim.test_ifvp_solves_the_damped_system()
