@@ -208,6 +208,41 @@ grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t p, uint64_
                                  float* out, uint64_t ldo,
                                  void* ws, size_t ws_bytes, grass_stream stream);
 
+/* ------------------------------------------- projected FIM and iFVP (cache stage)
+ * Sec. 2.1, cache stage steps 2 and 3, applied to compressed gradients (the
+ * "projected FIM" of Sec. 2.2; per layer block for the block-diagonal FIM of
+ * Sec. 3.3.2), with the damping term of App. B.
+ *
+ * grass_fim: F = (1/N) sum_i g_i g_i^T for the rows of G (N x k fp32 device,
+ * ldg >= k).  F is k x k fp32 (ldf >= k), written in full and exactly
+ * symmetric.  fp32 MFMA, accumulated over row chunks of G in a fixed order
+ * (bit-reproducible).  Workspace from grass_fim_workspace_bytes(N, k), 256-byte
+ * aligned.
+ *
+ * grass_fim_inverse: W = (F + lambda I)^{-1}, k x k fp32 (ldw >= k), lambda >= 0
+ * absolute.  Only the lower triangle of F is read.  The factorisation runs in
+ * fp64 (blocked Cholesky, triangular inverse, W = L^{-T} L^{-1}) and is rounded
+ * to fp32 once at the end.  info (device int32, may be NULL) receives 0, or the
+ * 1-based index of the first non-positive pivot (F + lambda I not positive
+ * definite in fp64; W is then meaningless).  k <= 32768.  Workspace
+ * 2 * kp^2 * 8 bytes with kp = k rounded up to 64.
+ *
+ * grass_ifvp: out (N x k fp32, ldo >= k), row i = W g_i for the rows g_i of G
+ * (N x k).  W must be symmetric (as grass_fim_inverse writes it).  fp32 MFMA.
+ * Scores with the preconditioner are then grass_score(out_train, test) =
+ * <g_test, (F + lambda I)^{-1} g_i>.
+ * Errors: GRASS_EINVAL for null pointers, k = 0, N = 0 in grass_fim, short
+ * leading dimensions, negative or NaN lambda; GRASS_EWORKSPACE; GRASS_EHIP.   */
+grass_status grass_fim_workspace_bytes(uint64_t N, uint32_t k, size_t* host_bytes);
+grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64_t ldg, float* F, uint64_t ldf,
+                       void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_fim_inverse_workspace_bytes(uint32_t k, size_t* host_bytes);
+grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t ldf, double lambda,
+                               float* W, uint64_t ldw, int32_t* info,
+                               void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint64_t ldg,
+                        const float* W, uint64_t ldw, float* out, uint64_t ldo, grass_stream stream);
+
 /* ------------------------------------------------------------------- tuning
  * Overrides the launch heuristics of grass_sjlt for experiments: rows per
  * block (1,2,4,8), column chunks per row group, threads per block

@@ -53,6 +53,11 @@ SIGNATURES = {
     "grass_gauss_matrix": (_int, [_u64, _u64, _u64, _u32, _u64, _u64, _vp, _u64, _vp]),
     "grass_gauss_project_workspace_bytes": (_int, [_u64, _u64, _u32, _u64, ctypes.POINTER(_sz)]),
     "grass_gauss_project": (_int, [_vp, _u64, _u64, _u64, _u32, _u64, _u64, _u64, _int, _vp, _u64, _vp, _sz, _vp]),
+    "grass_fim_workspace_bytes": (_int, [_u64, _u32, ctypes.POINTER(_sz)]),
+    "grass_fim": (_int, [_vp, _u64, _u32, _u64, _vp, _u64, _vp, _sz, _vp]),
+    "grass_fim_inverse_workspace_bytes": (_int, [_u32, ctypes.POINTER(_sz)]),
+    "grass_fim_inverse": (_int, [_vp, _u32, _u64, ctypes.c_double, _vp, _u64, _vp, _vp, _sz, _vp]),
+    "grass_ifvp": (_int, [_vp, _u64, _u32, _u64, _vp, _u64, _vp, _u64, _vp]),
     "grass_set_sjlt_tuning": (None, [_int, _int, _int, _int]),
     "grass_set_factgrass_tuning": (None, [_int]),
 }
@@ -316,6 +321,58 @@ def grass_gauss_project(g: torch.Tensor, k: int, seed: int, stream_id: int, p_ch
     _check(load_library().grass_gauss_project(_ptr(g), n, p, _ld(g), k, seed, stream_id, p_chunk, compute_mode,
                                               _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(),
                                               _stream()), "grass_gauss_project")
+    return out
+
+
+def grass_fim_workspace_bytes(N: int, k: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_fim_workspace_bytes(N, k, ctypes.byref(out)), "grass_fim_workspace_bytes")
+    return out.value
+
+
+def grass_fim(G: torch.Tensor, out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """F = (1/N) G^T G for the rows of G (N x k fp32)."""
+    assert G.dtype == torch.float32
+    N, k = G.shape
+    if out is None:
+        out = torch.empty((k, k), dtype=torch.float32, device=G.device)
+    if ws is None:
+        ws = _workspace(grass_fim_workspace_bytes(N, k), G.device)
+    _check(load_library().grass_fim(_ptr(G), N, k, _ld(G), _ptr(out), _ld(out), _ptr(ws),
+                                    0 if ws is None else ws.numel(), _stream()), "grass_fim")
+    return out
+
+
+def grass_fim_inverse_workspace_bytes(k: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_fim_inverse_workspace_bytes(k, ctypes.byref(out)), "grass_fim_inverse_workspace_bytes")
+    return out.value
+
+
+def grass_fim_inverse(F: torch.Tensor, lam: float, out: torch.Tensor | None = None, info: torch.Tensor | None = None,
+                      ws: torch.Tensor | None = None) -> torch.Tensor:
+    """W = (F + lam*I)^{-1}; `info` (int32 device tensor of one element) receives the pivot status if given."""
+    assert F.dtype == torch.float32 and F.shape[0] == F.shape[1]
+    k = F.shape[0]
+    if out is None:
+        out = torch.empty((k, k), dtype=torch.float32, device=F.device)
+    if ws is None:
+        ws = _workspace(grass_fim_inverse_workspace_bytes(k), F.device)
+    assert info is None or (info.dtype == torch.int32 and info.numel() >= 1)
+    _check(load_library().grass_fim_inverse(_ptr(F), k, _ld(F), float(lam), _ptr(out), _ld(out), _ptr(info), _ptr(ws),
+                                            0 if ws is None else ws.numel(), _stream()), "grass_fim_inverse")
+    return out
+
+
+def grass_ifvp(G: torch.Tensor, W: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Row i of the result is W g_i (W symmetric, from grass_fim_inverse)."""
+    assert G.dtype == torch.float32 and W.dtype == torch.float32
+    N, k = G.shape
+    assert W.shape == (k, k)
+    if out is None:
+        out = torch.empty((N, k), dtype=torch.float32, device=G.device)
+    _check(load_library().grass_ifvp(_ptr(G), N, k, _ld(G), _ptr(W), _ld(W), _ptr(out), _ld(out), _stream()),
+           "grass_ifvp")
     return out
 
 

@@ -1,0 +1,376 @@
+// Cache stage after compression (Sec. 2.1 steps 2 and 3 on compressed gradients, Sec. 2.2 "projected FIM",
+// damping of App. B):
+//   grass_fim          F = (1/N) G^T G                      fp32 MFMA (transpose + NT GEMM, lower tiles only)
+//   grass_fim_inverse  W = (F + lambda I)^{-1}              fp64: blocked Cholesky, recursive triangular inverse,
+//                                                           W = L^{-T} L^{-1}; fp64 MFMA for every product
+//   grass_ifvp         out = G W  (row i = W g_i)           fp32 MFMA NT GEMM (W is symmetric)
+#include <hip/hip_runtime.h>
+
+#include "grass.h"
+#include "grass_device.h"
+
+namespace grass {
+
+hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
+                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st);
+
+// ------------------------------------------------------------------------------------------------ FIM (fp32)
+// dst (k x ld_dst) = transpose of rows [r0, r0+rc) of src (N x k); columns rc..rc_pad of dst are zero-filled.
+__global__ void __launch_bounds__(256) transpose_rows_kernel(const float* src, uint64_t ld_src, uint64_t r0, uint32_t rc,
+                                                            uint32_t rc_pad, uint32_t k, float* dst, uint64_t ld_dst) {
+    __shared__ float tile[64][65];
+    const uint32_t c0 = blockIdx.x * 64;      // column of src = row of dst
+    const uint32_t q0 = blockIdx.y * 64;      // row of the chunk = column of dst
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const uint32_t q = q0 + r, c = c0 + tx;
+        tile[r][tx] = (q < rc && c < k) ? src[(r0 + q) * ld_src + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const uint32_t c = c0 + r, q = q0 + tx;
+        if (c < k && q < rc_pad) dst[(uint64_t)c * ld_dst + q] = tile[tx][r];
+    }
+}
+
+// F[a][b] = F[b][a] = scale * F[a][b] for a >= b: applies 1/N and mirrors the computed lower triangle.
+__global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf, uint32_t k, float scale) {
+    const uint32_t b = blockIdx.x * 64 + (threadIdx.x & 63);
+    const uint32_t a0 = blockIdx.y * 64;
+    if (blockIdx.x > blockIdx.y || b >= k) return;
+    for (uint32_t a = a0 + (threadIdx.x >> 6); a < a0 + 64 && a < k; a += 4) {
+        if (a < b) continue;
+        const float v = F[(uint64_t)a * ldf + b] * scale;
+        F[(uint64_t)a * ldf + b] = v;
+        F[(uint64_t)b * ldf + a] = v;
+    }
+}
+
+// ------------------------------------------------------------------------------------- fp64 building blocks
+constexpr int NB = 64;                        // block size of the factorisation
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// A64 (kp x kp): lower triangle of F + lambda I, identity on the padding rows; X64 = 0.
+__global__ void __launch_bounds__(256) fim_load_kernel(const float* F, uint64_t ldf, uint32_t k, double lambda,
+                                                      double* A64, double* X64, uint32_t kp) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (uint64_t)kp * kp) return;
+    const uint32_t a = (uint32_t)(t / kp), b = (uint32_t)(t - (uint64_t)a * kp);
+    double v = 0.0;
+    if (a < k && b <= a) v = (double)F[(uint64_t)a * ldf + b] + (a == b ? lambda : 0.0);
+    else if (a >= k && a == b) v = 1.0;
+    A64[t] = v;
+    X64[t] = 0.0;
+}
+
+// Cholesky factor of the NB x NB diagonal block j (lower, in place) and its inverse D = L_jj^{-1} into the
+// same block of X64 (zeros above the diagonal).  One workgroup.  A non-positive pivot records its 1-based
+// index in *info (first one wins) and is replaced by 1 so that the run stays finite.
+__global__ void __launch_bounds__(256) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
+    __shared__ double a[NB][NB + 1];
+    __shared__ double x[NB][NB + 1];
+    const int tid = threadIdx.x;
+    double* Ab = A64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
+    double* Xb = X64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
+    for (int e = tid; e < NB * NB; e += 256) a[e / NB][e % NB] = Ab[(uint64_t)(e / NB) * kp + e % NB];
+    __syncthreads();
+    for (int c = 0; c < NB; ++c) {
+        const double piv = a[c][c];
+        const bool ok = piv > 0.0;                                   // false for NaN too
+        const double d = ok ? sqrt(piv) : 1.0;
+        __syncthreads();                                             // everyone has read the pivot
+        if (tid == 0) {
+            a[c][c] = d;
+            if (!ok && info) atomicCAS(info, 0, (int)(j * NB + c + 1));
+        }
+        if (tid > c && tid < NB) a[tid][c] /= d;
+        __syncthreads();
+        // trailing update of the lower triangle: a[r][q] -= a[r][c] * a[q][c] for c < q <= r
+        for (int e = tid; e < NB * NB; e += 256) {
+            const int r = e / NB, q = e % NB;
+            if (q > c && r >= q) a[r][q] -= a[r][c] * a[q][c];
+        }
+        __syncthreads();
+    }
+    // inverse by forward substitution, thread t owns column t of D
+    if (tid < NB) {
+        const int t = tid;
+        for (int r = 0; r < NB; ++r) {
+            double v;
+            if (r < t) v = 0.0;
+            else {
+                double acc = (r == t) ? 1.0 : 0.0;
+                for (int m = t; m < r; ++m) acc -= a[r][m] * x[m][t];
+                v = acc / a[r][r];
+            }
+            x[r][t] = v;
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < NB * NB; e += 256) {
+        const int r = e / NB, q = e % NB;
+        Ab[(uint64_t)r * kp + q] = q <= r ? a[r][q] : 0.0;
+        Xb[(uint64_t)r * kp + q] = x[r][q];
+    }
+}
+
+// C = alpha * A B + beta * C in fp64 with v_mfma_f64_16x16x4_f64.  A is M x K, B is K x N, C is M x N, each given
+// by element strides (rs = row stride, cs = column stride), so transposed operands need no copy.  M, N, K are
+// multiples of 64.  64 x 64 tile per workgroup, 4 wavefronts of 32 x 32 (2 x 2 MFMA blocks), K steps of 16 through
+// LDS stored k-major with a row stride of 80 doubles (operand reads of one half-wavefront cover all 64 banks).
+// Structure flags restrict the contraction range of a tile at (m0, n0) when an operand is triangular:
+//   K_FROM_ROW: k >= m0      K_FROM_COL: k >= n0      K_TO_ROW: k < m0 + 64
+// LOWER_TILES computes only tiles with m0 >= n0; MIRROR (fp32 output only) also writes the transposed element of
+// off-diagonal tiles.  blockIdx.z is a batch index with strides bsA/bsB/bsC.
+enum : int { K_FROM_ROW = 1, K_FROM_COL = 2, K_TO_ROW = 4, LOWER_TILES = 8, MIRROR = 16 };
+struct DgemmArgs {
+    const double* A; const double* B; double* C; float* Cf;
+    int64_t rsA, csA, rsB, csB, rsC, csC;
+    int64_t bsA, bsB, bsC;
+    uint32_t M, N, K;
+    double alpha, beta;
+    int flags;
+};
+constexpr int kDLd = 80;
+
+__global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
+    __shared__ double As[16][kDLd];
+    __shared__ double Bs[16][kDLd];
+    const uint32_t m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    if ((g.flags & LOWER_TILES) && n0 > m0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const double* A = g.A + (int64_t)blockIdx.z * g.bsA;
+    const double* B = g.B + (int64_t)blockIdx.z * g.bsB;
+
+    uint32_t kb = 0, ke = g.K;
+    if ((g.flags & K_FROM_ROW) && m0 > kb) kb = m0;
+    if ((g.flags & K_FROM_COL) && n0 > kb) kb = n0;
+    if ((g.flags & K_TO_ROW) && m0 + 64 < ke) ke = m0 + 64;
+
+    // staging map: the contiguous direction of each operand goes to adjacent lanes, 4 doubles per thread
+    const bool a_k_contig = g.csA == 1, b_k_contig = g.rsB == 1;
+    int ai, ak, bi, bk;                       // first (i, k) element of this thread, 4 elements along the contiguous dimension
+    if (a_k_contig) { ai = tid >> 2; ak = (tid & 3) * 4; } else { ak = tid >> 4; ai = (tid & 15) * 4; }
+    if (b_k_contig) { bi = tid >> 2; bk = (tid & 3) * 4; } else { bk = tid >> 4; bi = (tid & 15) * 4; }
+    const double* ap = A + (int64_t)(m0 + ai) * g.rsA + (int64_t)ak * g.csA;
+    const double* bp = B + (int64_t)bk * g.rsB + (int64_t)(n0 + bi) * g.csB;
+    const int64_t a_step = a_k_contig ? g.csA : g.rsA, b_step = b_k_contig ? g.rsB : g.csB;
+
+    f64x4 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+    double ra[4], rb[4];
+    auto fetch = [&](uint32_t k0) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            ra[q] = ap[(int64_t)k0 * g.csA + q * a_step];
+            rb[q] = bp[(int64_t)k0 * g.rsB + q * b_step];
+        }
+    };
+    if (kb < ke) fetch(kb);
+    for (uint32_t k0 = kb; k0 < ke; k0 += 16) {
+        __syncthreads();                                   // previous step's reads are done
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (a_k_contig) As[ak + q][ai] = ra[q]; else As[ak][ai + q] = ra[q];
+            if (b_k_contig) Bs[bk + q][bi] = rb[q]; else Bs[bk][bi + q] = rb[q];
+        }
+        __syncthreads();
+        if (k0 + 16 < ke) fetch(k0 + 16);
+#pragma unroll
+        for (int kk = 0; kk < 16; kk += 4) {
+            const int kr = kk + (lane >> 4);
+            double fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = As[kr][wm * 32 + i * 16 + (lane & 15)];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[j] = Bs[kr][wn * 32 + j * 16 + (lane & 15)];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+
+    // accumulator element e of a lane: row 4*e + lane/16, column lane%16 of the 16 x 16 block
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t row = m0 + wm * 32 + i * 16 + 4 * e + (lane >> 4);
+                const uint32_t col = n0 + wn * 32 + j * 16 + (lane & 15);
+                double v = g.alpha * acc[i][j][e];
+                if (g.Cf) {
+                    float* c = g.Cf + (int64_t)blockIdx.z * g.bsC;
+                    c[(int64_t)row * g.rsC + (int64_t)col * g.csC] = (float)v;
+                    if ((g.flags & MIRROR) && m0 != n0) c[(int64_t)col * g.rsC + (int64_t)row * g.csC] = (float)v;
+                } else {
+                    double* c = g.C + (int64_t)blockIdx.z * g.bsC + (int64_t)row * g.rsC + (int64_t)col * g.csC;
+                    if (g.beta != 0.0) v += g.beta * *c;
+                    *c = v;
+                }
+            }
+}
+
+// W[a][b] = (float) S[max(a,b)][min(a,b)] for the leading k x k part of a kp x kp matrix whose lower triangle is valid.
+__global__ void __launch_bounds__(256) fim_store_kernel(const double* S, uint32_t kp, uint32_t k, float* W, uint64_t ldw) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (uint64_t)k * k) return;
+    const uint32_t a = (uint32_t)(t / k), b = (uint32_t)(t - (uint64_t)a * k);
+    const uint32_t hi = a > b ? a : b, lo = a > b ? b : a;
+    W[(uint64_t)a * ldw + b] = (float)S[(uint64_t)hi * kp + lo];
+}
+
+__global__ void fill_i32_kernel(int* p, int count, int value) {
+    if ((int)threadIdx.x < count) p[threadIdx.x] = value;
+}
+
+static hipError_t dgemm(const DgemmArgs& g, uint32_t batch, hipStream_t st) {
+    if (g.M == 0 || g.N == 0 || batch == 0) return hipSuccess;
+    if (g.M % 64 || g.N % 64 || g.K % 64) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(dgemm_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
+    return hipGetLastError();
+}
+
+static uint32_t padded(uint32_t k) { return (k + NB - 1) / NB * NB; }
+
+}  // namespace grass
+
+using namespace grass;
+
+// --------------------------------------------------------------------------------------------------- C ABI
+static uint64_t fim_chunk_rows(uint64_t N) { return N < 8192 ? (N + 15) / 16 * 16 : 8192; }
+
+extern "C" grass_status grass_fim_workspace_bytes(uint64_t N, uint32_t k, size_t* host_bytes) {
+    if (!host_bytes || k == 0) return GRASS_EINVAL;
+    *host_bytes = (size_t)k * fim_chunk_rows(N ? N : 1) * sizeof(float);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64_t ldg, float* F, uint64_t ldf, void* ws,
+                                  size_t ws_bytes, grass_stream stream) {
+    if (k == 0 || N == 0) return GRASS_EINVAL;
+    if (!G || !F || ldg < k || ldf < k) return GRASS_EINVAL;
+    const uint64_t rows = fim_chunk_rows(N);
+    if (!ws || ws_bytes < (size_t)k * rows * sizeof(float) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    float* Gt = static_cast<float*>(ws);
+    hipStream_t hs = as_stream(stream);
+    for (uint64_t r0 = 0; r0 < N; r0 += rows) {
+        const uint32_t rc = (uint32_t)(r0 + rows <= N ? rows : N - r0);
+        const uint32_t rc_pad = (rc + 15) / 16 * 16;                 // the GEMM contracts over whole 64-byte slices
+        hipLaunchKernelGGL(transpose_rows_kernel, dim3((k + 63) / 64, (rc_pad + 63) / 64), dim3(256), 0, hs, G, ldg, r0, rc,
+                           rc_pad, k, Gt, rows);
+        if (gemm_nt_f32(Gt, Gt, F, k, k, rc_pad, rows, rows, ldf, r0 != 0, 1, hs) != hipSuccess) return GRASS_EHIP;
+    }
+    hipLaunchKernelGGL(fim_finish_kernel, dim3((k + 63) / 64, (k + 63) / 64), dim3(256), 0, hs, F, ldf, k,
+                       (float)(1.0 / (double)N));
+    return launch_status();
+}
+
+extern "C" grass_status grass_fim_inverse_workspace_bytes(uint32_t k, size_t* host_bytes) {
+    if (!host_bytes || k == 0) return GRASS_EINVAL;
+    const size_t kp = padded(k);
+    *host_bytes = 2 * kp * kp * sizeof(double);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t ldf, double lambda, float* W, uint64_t ldw,
+                                          int32_t* info, void* ws, size_t ws_bytes, grass_stream stream) {
+    if (k == 0 || !(lambda >= 0.0)) return GRASS_EINVAL;
+    if (!F || !W || ldf < k || ldw < k) return GRASS_EINVAL;
+    if (k > 32768) return GRASS_EUNSUPPORTED;
+    const uint32_t kp = padded(k), nblk = kp / NB;
+    const size_t mat = (size_t)kp * kp * sizeof(double);
+    if (!ws || ws_bytes < 2 * mat || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    double* A64 = static_cast<double*>(ws);
+    double* X64 = A64 + (size_t)kp * kp;
+    hipStream_t hs = as_stream(stream);
+    const int64_t ld = kp;
+
+    if (info) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, hs, info, 1, 0);
+    hipLaunchKernelGGL(fim_load_kernel, dim3((uint32_t)ceil_div((uint64_t)kp * kp, 256)), dim3(256), 0, hs, F, ldf, k, lambda,
+                       A64, X64, kp);
+
+    // right-looking blocked Cholesky: A = L L^T, L overwrites the lower triangle of A64
+    for (uint32_t j = 0; j < nblk; ++j) {
+        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(256), 0, hs, A64, X64, kp, j, info);
+        const uint32_t below = kp - (j + 1) * NB;
+        if (below == 0) break;
+        double* panel = A64 + (size_t)(j + 1) * NB * kp + (size_t)j * NB;
+        const double* D = X64 + (size_t)j * NB * kp + (size_t)j * NB;
+        DgemmArgs p{};                                     // panel <- panel * D^T   (in place: one tile per 64 rows)
+        p.A = panel; p.rsA = ld; p.csA = 1;
+        p.B = D; p.rsB = 1; p.csB = ld;                     // B[kk][n] = D[n][kk]
+        p.C = panel; p.rsC = ld; p.csC = 1;
+        p.M = below; p.N = NB; p.K = NB; p.alpha = 1.0; p.beta = 0.0; p.flags = 0;
+        if (dgemm(p, 1, hs) != hipSuccess) return GRASS_EHIP;
+        DgemmArgs u{};                                     // trailing lower triangle -= panel * panel^T
+        u.A = panel; u.rsA = ld; u.csA = 1;
+        u.B = panel; u.rsB = 1; u.csB = ld;
+        u.C = A64 + (size_t)(j + 1) * NB * kp + (size_t)(j + 1) * NB; u.rsC = ld; u.csC = 1;
+        u.M = below; u.N = below; u.K = NB; u.alpha = -1.0; u.beta = 1.0; u.flags = LOWER_TILES;
+        if (dgemm(u, 1, hs) != hipSuccess) return GRASS_EHIP;
+    }
+
+    // X = L^{-1} by doubling: with the inverses X11, X22 of two adjacent diagonal blocks of size b in place,
+    // X21 = -X22 (L21 X11).  T = L21 X11 is parked transposed in the unused upper triangle of A64.
+    for (uint32_t b = NB; b < kp; b *= 2) {
+        const uint32_t full = kp / (2 * b);                // pairs with a complete second block
+        const uint32_t rest = kp - full * 2 * b;           // a last pair with a shorter second block if rest > b
+        for (int pass = 0; pass < 2; ++pass) {
+            const uint32_t batch = pass == 0 ? full : (rest > b ? 1 : 0);
+            if (batch == 0) continue;
+            const uint32_t M2 = pass == 0 ? b : rest - b;
+            const size_t o = pass == 0 ? 0 : (size_t)full * 2 * b;
+            const int64_t bs = (int64_t)2 * b * (ld + 1);  // next pair: 2b down the diagonal
+            DgemmArgs t{};                                 // T (M2 x b) = L21 * X11, X11 lower: k >= n0
+            t.A = A64 + (o + b) * kp + o; t.rsA = ld; t.csA = 1; t.bsA = bs;
+            t.B = X64 + o * kp + o; t.rsB = ld; t.csB = 1; t.bsB = bs;
+            t.C = A64 + o * kp + (o + b); t.rsC = 1; t.csC = ld; t.bsC = bs;      // T[r][c] at A64[o+c][o+b+r]
+            t.M = M2; t.N = b; t.K = b; t.alpha = 1.0; t.beta = 0.0; t.flags = K_FROM_COL;
+            if (dgemm(t, batch, hs) != hipSuccess) return GRASS_EHIP;
+            DgemmArgs x{};                                 // X21 (M2 x b) = -X22 * T, X22 lower: k < m0 + 64
+            x.A = X64 + (o + b) * kp + (o + b); x.rsA = ld; x.csA = 1; x.bsA = bs;
+            x.B = A64 + o * kp + (o + b); x.rsB = 1; x.csB = ld; x.bsB = bs;      // B[kk][n] = T[kk][n]
+            x.C = X64 + (o + b) * kp + o; x.rsC = ld; x.csC = 1; x.bsC = bs;
+            x.M = M2; x.N = b; x.K = M2; x.alpha = -1.0; x.beta = 0.0; x.flags = K_TO_ROW;
+            if (dgemm(x, batch, hs) != hipSuccess) return GRASS_EHIP;
+        }
+    }
+
+    // W = X^T X (lower tiles, mirrored), written as fp32; only the leading k x k part leaves the workspace
+    if (kp == k) {
+        DgemmArgs w{};
+        w.A = X64; w.rsA = 1; w.csA = ld;                   // A[i][kk] = X[kk][i]
+        w.B = X64; w.rsB = ld; w.csB = 1;
+        w.Cf = W; w.rsC = (int64_t)ldw; w.csC = 1;
+        w.M = kp; w.N = kp; w.K = kp; w.alpha = 1.0; w.beta = 0.0; w.flags = K_FROM_ROW | LOWER_TILES | MIRROR;
+        if (dgemm(w, 1, hs) != hipSuccess) return GRASS_EHIP;
+    } else {                                                // padded: go through A64 (free now), then copy k x k
+        DgemmArgs w{};
+        w.A = X64; w.rsA = 1; w.csA = ld;
+        w.B = X64; w.rsB = ld; w.csB = 1;
+        w.C = A64; w.rsC = ld; w.csC = 1;
+        w.M = kp; w.N = kp; w.K = kp; w.alpha = 1.0; w.beta = 0.0; w.flags = K_FROM_ROW | LOWER_TILES;
+        if (dgemm(w, 1, hs) != hipSuccess) return GRASS_EHIP;
+        hipLaunchKernelGGL(fim_store_kernel, dim3((uint32_t)ceil_div((uint64_t)k * k, 256)), dim3(256), 0, hs, A64, kp, k, W,
+                           ldw);
+    }
+    return launch_status();
+}
+
+extern "C" grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint64_t ldg, const float* W, uint64_t ldw,
+                                   float* out, uint64_t ldo, grass_stream stream) {
+    if (k == 0) return GRASS_EINVAL;
+    if (N == 0) return GRASS_OK;
+    if (!G || !W || !out || ldg < k || ldw < k || ldo < k) return GRASS_EINVAL;
+    // out[i][a] = sum_c G[i][c] W[a][c]  (W symmetric)
+    return gemm_nt_f32(G, W, out, N, k, k, ldg, ldw, ldo, 0, 0, as_stream(stream)) == hipSuccess ? GRASS_OK : GRASS_EHIP;
+}

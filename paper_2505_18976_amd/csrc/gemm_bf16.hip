@@ -204,6 +204,7 @@ struct GemmDmaArgs {
     int accumulate;       // C += instead of C =
     uint32_t slices_per_split;   // split-K: workgroup (split, tile) contracts slices [split*sps, (split+1)*sps)
     uint64_t split_stride_c;     //          into C + split*split_stride_c
+    int lower_only;              // symmetric product: tiles strictly above the diagonal are skipped
 };
 
 template <bool F32>
@@ -220,6 +221,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     uint32_t logical = bid;
     if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;
     const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
+    if (a.lower_only && tn > tm) return;                       // uniform over the workgroup
     const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
     const uint64_t slice0 = (uint64_t)split * a.slices_per_split;
     a.C += split * a.split_stride_c;
@@ -354,14 +356,16 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
 // leading dimensions or bases not 16-byte aligned); the caller then falls back.
 // splits > 1 (a value from gemm_dma_splits) writes the partial product of K range
 // s to partials + s*M*N (dense M x N, accumulate applies to it) instead of C.
+// lower_only (A == B, M == N): only tiles on or below the diagonal are computed.
 bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                      uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
-                     float* partials) {
+                     float* partials, int lower_only) {
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
     if (K % sk != 0 || (lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
     GemmDmaArgs a;
     a.A = A; a.B = B; a.C = C; a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.accumulate = accumulate;
+    a.lower_only = lower_only;
     a.tiles_m = (uint32_t)ceil_div(M, TM);
     a.tiles_n = (uint32_t)ceil_div(N, TN);
     const uint64_t slices = K / sk;
@@ -453,7 +457,7 @@ extern "C" grass_status grass_score_bf16(const void* train, const void* test, ui
     }
     hipError_t derr = hipSuccess;
     if (launch_gemm_dma(false, test, train, scores, M, N, K, ld_test, ld_train, ld_scores, 0, as_stream(stream), &derr, 1,
-                        nullptr))
+                        nullptr, 0))
         return derr == hipSuccess ? GRASS_OK : GRASS_EHIP;
     hipLaunchKernelGGL(gemm_bf16_nt_kernel, dim3((uint32_t)total), dim3(kBf16Threads), lds_bytes, as_stream(stream), a);
     return launch_status();

@@ -205,16 +205,16 @@ static int vec_width(const float* p, uint64_t ld) {
 // defined in gemm_bf16.hip: 256 x 256 tiles fed by direct-to-LDS loads
 bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                      uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
-                     float* partials);
+                     float* partials, int lower_only);
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits);
 
 // splits > 1 (fp32 mode only): K-range partial products go to `partials`, see launch_gemm_dma.
 static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint32_t splits = 1,
-                              float* partials = nullptr) {
+                              float* partials = nullptr, int lower_only = 0) {
     if (mode == 0 && a.M >= 128 && a.N >= 128) {       // large fp32 problems: the direct-to-LDS pipeline
         hipError_t derr = hipSuccess;
         if (launch_gemm_dma(true, a.A, a.B, a.C, a.M, a.N, a.K, a.lda, a.ldb, a.ldc, a.accumulate, st, &derr, splits,
-                            partials))
+                            partials, lower_only))
             return derr;
     }
     if (splits > 1) return hipErrorInvalidValue;
@@ -236,6 +236,17 @@ static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint3
     }
 #undef GRASS_GEMM
     return hipGetLastError();
+}
+
+// C (M x N) = or += A (M x K) B^T (N x K), fp32 MFMA; used by the FIM and the inverse-FIM-vector product.
+// lower_only: A == B and the caller reads only the tiles on or below the diagonal (the others may be left unwritten).
+hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
+                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st) {
+    GemmArgs a;
+    a.A = A; a.B = B; a.C = C;
+    a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.accumulate = accumulate;
+    return launch_gemm(a, 0, st, 1, nullptr, lower_only);
 }
 
 // P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.

@@ -110,3 +110,12 @@ LLAMA_BLOCK_LINEARS = (
     ("q", 2048, 2048), ("k", 2048, 2048), ("v", 2048, 2048), ("o", 2048, 2048),
     ("gate", 2048, 8192), ("up", 2048, 8192), ("down", 8192, 2048),
 )
+
+
+def compressed_gradients(rows: int, k: int, seed: int, device="cpu", decay: float = 0.5) -> torch.Tensor:
+    """rows x k fp32 stand-in for compressed per-sample gradients with a decaying spectrum: column c is
+    N(0, (1+c)^(-2*decay)), so the FIM has eigenvalues spread over k^(2*decay) instead of a flat identity."""
+    gen = _gen(seed, device)
+    out = torch.empty((rows, k), dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=gen)
+    scale = (1.0 + torch.arange(k, dtype=torch.float32, device=device)) ** (-decay)
+    return out * scale[None, :]
