@@ -261,6 +261,25 @@ def main() -> int:
                                             "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4)}
         t, _, _ = _timed(lambda: grass.grass_to_bf16(tr, out=trb), 5, 1, torch)
         extras["to_bf16_train_rows"] = {"ms": round(t / 5, 4)}
+        del trb, teb, te, sc
+
+        # cache stage after compression on the same block: FIM, damped inverse, iFVP of all train rows
+        Fm = torch.empty((K5, K5), dtype=torch.float32, device=dev)
+        Wm = torch.empty((K5, K5), dtype=torch.float32, device=dev)
+        wf = torch.empty(grass.grass_fim_workspace_bytes(N5, K5), dtype=torch.uint8, device=dev)
+        wi = torch.empty(grass.grass_fim_inverse_workspace_bytes(K5), dtype=torch.uint8, device=dev)
+        pre = torch.empty((N5, K5), dtype=torch.float32, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_fim(tr, out=Fm, ws=wf), 3, 1, torch)
+        tf = 2.0 * N5 * K5 * K5 / (t / 3 * 1e-3) / 1e12
+        extras["fim_65536x4096"] = {"ms": round(t / 3, 3), "TFLOPs_full_product": round(tf, 2),
+                                    "note": "only tiles on or below the diagonal are computed"}
+        t, _, _ = _timed(lambda: grass.grass_fim_inverse(Fm, 1e-3, out=Wm, ws=wi), 3, 1, torch)
+        extras["fim_inverse_4096"] = {"ms": round(t / 3, 3), "fp64_GFLOPs_at_k3": round(K5 ** 3 / (t / 3 * 1e-3) / 1e9, 1)}
+        t, _, _ = _timed(lambda: grass.grass_ifvp(tr, Wm, out=pre), 3, 1, torch)
+        tf = 2.0 * N5 * K5 * K5 / (t / 3 * 1e-3) / 1e12
+        extras["ifvp_65536x4096"] = {"ms": round(t / 3, 3), "TFLOPs": round(tf, 2),
+                                     "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4)}
+        del Fm, Wm, wf, wi, pre, tr
         result["extras"] = extras
 
     print(json.dumps(result))

@@ -12,7 +12,8 @@
 namespace grass {
 
 hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
-                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st);
+                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st, uint32_t splits,
+                       float* partials);
 
 // ------------------------------------------------------------------------------------------------ FIM (fp32)
 // dst (k x ld_dst) = transpose of rows [r0, r0+rc) of src (N x k); columns rc..rc_pad of dst are zero-filled.
@@ -33,14 +34,22 @@ __global__ void __launch_bounds__(256) transpose_rows_kernel(const float* src, u
     }
 }
 
-// F[a][b] = F[b][a] = scale * F[a][b] for a >= b: applies 1/N and mirrors the computed lower triangle.
-__global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf, uint32_t k, float scale) {
+// F[a][b] = F[b][a] = scale * S[a][b] for a >= b: applies 1/N and mirrors the computed lower triangle.  S is F itself
+// (splits == 0) or the sum, in ascending order, of `splits` dense k x k partial products.
+__global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf, uint32_t k, float scale,
+                                                        const float* partials, uint32_t splits) {
     const uint32_t b = blockIdx.x * 64 + (threadIdx.x & 63);
     const uint32_t a0 = blockIdx.y * 64;
     if (blockIdx.x > blockIdx.y || b >= k) return;
     for (uint32_t a = a0 + (threadIdx.x >> 6); a < a0 + 64 && a < k; a += 4) {
         if (a < b) continue;
-        const float v = F[(uint64_t)a * ldf + b] * scale;
+        float v;
+        if (splits == 0) v = F[(uint64_t)a * ldf + b];
+        else {
+            v = 0.0f;
+            for (uint32_t s = 0; s < splits; ++s) v += partials[((uint64_t)s * k + a) * k + b];
+        }
+        v *= scale;
         F[(uint64_t)a * ldf + b] = v;
         F[(uint64_t)b * ldf + a] = v;
     }
@@ -66,51 +75,54 @@ __global__ void __launch_bounds__(256) fim_load_kernel(const float* F, uint64_t 
 // Cholesky factor of the NB x NB diagonal block j (lower, in place) and its inverse D = L_jj^{-1} into the
 // same block of X64 (zeros above the diagonal).  One workgroup.  A non-positive pivot records its 1-based
 // index in *info (first one wins) and is replaced by 1 so that the run stays finite.
+// Factor: one barrier per column; column c of L goes to a second array, so the rank-one update of step c can
+// read the unscaled column (a[r][q] -= a[r][c] a[q][c] / pivot) while it is written.  Lane = column q, the four
+// wavefronts take rows r = w, w+4, ...  Inverse: lane t of wavefront 0 solves L x = e_t with x in registers.
 __global__ void __launch_bounds__(256) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
     __shared__ double a[NB][NB + 1];
-    __shared__ double x[NB][NB + 1];
-    const int tid = threadIdx.x;
+    __shared__ double l[NB][NB + 1];
+    __shared__ double rinv[NB];
+    const int tid = threadIdx.x, q = tid & 63, w = tid >> 6;
     double* Ab = A64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
     double* Xb = X64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
-    for (int e = tid; e < NB * NB; e += 256) a[e / NB][e % NB] = Ab[(uint64_t)(e / NB) * kp + e % NB];
+    for (int r = w; r < NB; r += 4) a[r][q] = Ab[(uint64_t)r * kp + q];
     __syncthreads();
     for (int c = 0; c < NB; ++c) {
         const double piv = a[c][c];
         const bool ok = piv > 0.0;                                   // false for NaN too
-        const double d = ok ? sqrt(piv) : 1.0;
-        __syncthreads();                                             // everyone has read the pivot
-        if (tid == 0) {
-            a[c][c] = d;
-            if (!ok && info) atomicCAS(info, 0, (int)(j * NB + c + 1));
+        const double pv = ok ? piv : 1.0;
+        // y = pivot^(-1/2): hardware estimate refined by two Newton steps (fp64 sqrt and divide cost hundreds of
+        // cycles each and sit on the critical path of every column)
+        double y = __builtin_amdgcn_rsq(pv);
+        y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
+        y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
+        const double d = pv * y, inv = y * y;
+        if (tid == 0 && !ok && info) atomicCAS(info, 0, (int)(j * NB + c + 1));
+        if (w == 0 && q >= c) {
+            l[q][c] = q == c ? d : a[q][c] * y;
+            if (q == c) rinv[c] = y;
         }
-        if (tid > c && tid < NB) a[tid][c] /= d;
-        __syncthreads();
-        // trailing update of the lower triangle: a[r][q] -= a[r][c] * a[q][c] for c < q <= r
-        for (int e = tid; e < NB * NB; e += 256) {
-            const int r = e / NB, q = e % NB;
-            if (q > c && r >= q) a[r][q] -= a[r][c] * a[q][c];
+        if (q > c) {
+            const double aqc = a[q][c] * inv;
+            int r0 = q > c + 1 ? q : c + 1;                          // rows r >= max(q, c+1), r = w mod 4
+            r0 += (w - r0) & 3;
+            for (int r = r0; r < NB; r += 4) a[r][q] -= a[r][c] * aqc;
         }
         __syncthreads();
     }
-    // inverse by forward substitution, thread t owns column t of D
-    if (tid < NB) {
-        const int t = tid;
+    for (int r = w; r < NB; r += 4) Ab[(uint64_t)r * kp + q] = q <= r ? l[r][q] : 0.0;
+    if (w == 0) {
+        double x[NB];
+#pragma unroll
         for (int r = 0; r < NB; ++r) {
-            double v;
-            if (r < t) v = 0.0;
-            else {
-                double acc = (r == t) ? 1.0 : 0.0;
-                for (int m = t; m < r; ++m) acc -= a[r][m] * x[m][t];
-                v = acc / a[r][r];
-            }
-            x[r][t] = v;
+            double acc[4] = {r == q ? 1.0 : 0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int m = 0; m < r; ++m) acc[m & 3] -= l[r][m] * x[m];
+            const double v = ((acc[0] + acc[1]) + (acc[2] + acc[3])) * rinv[r];
+            x[r] = r >= q ? v : 0.0;
         }
-    }
-    __syncthreads();
-    for (int e = tid; e < NB * NB; e += 256) {
-        const int r = e / NB, q = e % NB;
-        Ab[(uint64_t)r * kp + q] = q <= r ? a[r][q] : 0.0;
-        Xb[(uint64_t)r * kp + q] = x[r][q];
+#pragma unroll
+        for (int r = 0; r < NB; ++r) Xb[(uint64_t)r * kp + q] = x[r];
     }
 }
 
@@ -246,11 +258,28 @@ static uint32_t padded(uint32_t k) { return (k + NB - 1) / NB * NB; }
 using namespace grass;
 
 // --------------------------------------------------------------------------------------------------- C ABI
-static uint64_t fim_chunk_rows(uint64_t N) { return N < 8192 ? (N + 15) / 16 * 16 : 8192; }
+// rows of G per transposed chunk: long enough that each K range of a chunk product amortises its pipeline fill
+static uint64_t fim_chunk_rows(uint64_t N) { return N < 16384 ? (N + 15) / 16 * 16 : 16384; }
+
+// K ranges per chunk product.  The lower-triangle tiles of a 256 x 256 tiling are few (136 for k = 4,096 on 256
+// CUs), so each chunk's contraction is cut into up to 8 ranges that accumulate separate partial sums.
+static uint32_t fim_splits(uint64_t N, uint32_t k) {
+    if (k < 128) return 1;
+    const uint64_t t = ((uint64_t)k + 255) / 256, lower = t * (t + 1) / 2;
+    uint64_t s = ceil_div(1024, lower);
+    if (s > 8) s = 8;
+    const uint64_t slices = fim_chunk_rows(N) / 16;        // of the first (largest) chunk
+    if (s > slices / 32) s = slices / 32;
+    return s < 2 ? 1 : (uint32_t)s;
+}
+
+static size_t fim_gt_bytes(uint64_t N, uint32_t k) { return ((size_t)k * fim_chunk_rows(N) * sizeof(float) + 255) / 256 * 256; }
 
 extern "C" grass_status grass_fim_workspace_bytes(uint64_t N, uint32_t k, size_t* host_bytes) {
     if (!host_bytes || k == 0) return GRASS_EINVAL;
-    *host_bytes = (size_t)k * fim_chunk_rows(N ? N : 1) * sizeof(float);
+    if (N == 0) N = 1;
+    const uint32_t splits = fim_splits(N, k);
+    *host_bytes = fim_gt_bytes(N, k) + (splits > 1 ? (size_t)splits * k * k * sizeof(float) : 0);
     return GRASS_OK;
 }
 
@@ -259,18 +288,33 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
     if (k == 0 || N == 0) return GRASS_EINVAL;
     if (!G || !F || ldg < k || ldf < k) return GRASS_EINVAL;
     const uint64_t rows = fim_chunk_rows(N);
-    if (!ws || ws_bytes < (size_t)k * rows * sizeof(float) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    const uint32_t splits = fim_splits(N, k);
+    const size_t need = fim_gt_bytes(N, k) + (splits > 1 ? (size_t)splits * k * k * sizeof(float) : 0);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return GRASS_EWORKSPACE;
     float* Gt = static_cast<float*>(ws);
+    float* partials = splits > 1 ? reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + fim_gt_bytes(N, k)) : nullptr;
     hipStream_t hs = as_stream(stream);
     for (uint64_t r0 = 0; r0 < N; r0 += rows) {
         const uint32_t rc = (uint32_t)(r0 + rows <= N ? rows : N - r0);
         const uint32_t rc_pad = (rc + 15) / 16 * 16;                 // the GEMM contracts over whole 64-byte slices
         hipLaunchKernelGGL(transpose_rows_kernel, dim3((k + 63) / 64, (rc_pad + 63) / 64), dim3(256), 0, hs, G, ldg, r0, rc,
                            rc_pad, k, Gt, rows);
-        if (gemm_nt_f32(Gt, Gt, F, k, k, rc_pad, rows, rows, ldf, r0 != 0, 1, hs) != hipSuccess) return GRASS_EHIP;
+        hipError_t e;
+        if (splits > 1) {
+            // a short last chunk uses fewer ranges; the first chunk (accumulate = 0) initialises all of them
+            uint32_t s_cur = splits;
+            if ((uint64_t)rc_pad / 16 < (uint64_t)s_cur * 32) s_cur = rc_pad / 16 / 32;
+            if (s_cur >= 2)
+                e = gemm_nt_f32(Gt, Gt, nullptr, k, k, rc_pad, rows, rows, k, r0 != 0, 1, hs, s_cur, partials);
+            else
+                e = gemm_nt_f32(Gt, Gt, partials, k, k, rc_pad, rows, rows, k, r0 != 0, 1, hs, 1, nullptr);
+        } else {
+            e = gemm_nt_f32(Gt, Gt, F, k, k, rc_pad, rows, rows, ldf, r0 != 0, 1, hs, 1, nullptr);
+        }
+        if (e != hipSuccess) return GRASS_EHIP;
     }
     hipLaunchKernelGGL(fim_finish_kernel, dim3((k + 63) / 64, (k + 63) / 64), dim3(256), 0, hs, F, ldf, k,
-                       (float)(1.0 / (double)N));
+                       (float)(1.0 / (double)N), partials, splits > 1 ? splits : 0);
     return launch_status();
 }
 
@@ -372,5 +416,6 @@ extern "C" grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint6
     if (N == 0) return GRASS_OK;
     if (!G || !W || !out || ldg < k || ldw < k || ldo < k) return GRASS_EINVAL;
     // out[i][a] = sum_c G[i][c] W[a][c]  (W symmetric)
-    return gemm_nt_f32(G, W, out, N, k, k, ldg, ldw, ldo, 0, 0, as_stream(stream)) == hipSuccess ? GRASS_OK : GRASS_EHIP;
+    return gemm_nt_f32(G, W, out, N, k, k, ldg, ldw, ldo, 0, 0, as_stream(stream), 1, nullptr) == hipSuccess ? GRASS_OK
+                                                                                                             : GRASS_EHIP;
 }

@@ -215,13 +215,22 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
 
-    const uint32_t total = a.tiles_m * a.tiles_n;
+    // lower_only: only the tiles_m*(tiles_m+1)/2 tiles on or below the diagonal are launched, numbered row by row
+    const uint32_t total = a.lower_only ? a.tiles_m * (a.tiles_m + 1) / 2 : a.tiles_m * a.tiles_n;
     const uint32_t split = blockIdx.x / total;
     const uint32_t bid = blockIdx.x - split * total;
     uint32_t logical = bid;
-    if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;
-    const uint32_t tn = logical / a.tiles_m, tm = logical % a.tiles_m;
-    if (a.lower_only && tn > tm) return;                       // uniform over the workgroup
+    if (total % 8 == 0) logical = (bid % 8) * (total / 8) + bid / 8;      // consecutive tiles stay on one XCD
+    uint32_t tn, tm;
+    if (a.lower_only) {
+        tm = (uint32_t)((sqrtf(8.0f * (float)logical + 1.0f) - 1.0f) * 0.5f);
+        while (tm * (tm + 1) / 2 > logical) --tm;
+        while ((tm + 1) * (tm + 2) / 2 <= logical) ++tm;
+        tn = logical - tm * (tm + 1) / 2;
+    } else {
+        tn = logical / a.tiles_m;
+        tm = logical % a.tiles_m;
+    }
     const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
     const uint64_t slice0 = (uint64_t)split * a.slices_per_split;
     a.C += split * a.split_stride_c;
@@ -375,7 +384,8 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     if (ceil_div(slices, a.slices_per_split) != splits) return false;      // every K range non-empty
     a.split_stride_c = 0;
     if (splits > 1) { a.C = partials; a.ldc = N; a.split_stride_c = M * N; }
-    const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n * splits;
+    if (lower_only && a.tiles_m != a.tiles_n) return false;
+    const uint64_t total = (lower_only ? (uint64_t)a.tiles_m * (a.tiles_m + 1) / 2 : (uint64_t)a.tiles_m * a.tiles_n) * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return false;
     static bool attr_done[2] = {false, false};
     const void* fn = f32 ? reinterpret_cast<const void*>(gemm_dma_kernel<true>)

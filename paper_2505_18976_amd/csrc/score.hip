@@ -240,13 +240,16 @@ static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint3
 
 // C (M x N) = or += A (M x K) B^T (N x K), fp32 MFMA; used by the FIM and the inverse-FIM-vector product.
 // lower_only: A == B and the caller reads only the tiles on or below the diagonal (the others may be left unwritten).
+// splits > 1: the partial product of K range s goes to partials + s*M*N (dense) instead of C; needs M, N >= 128,
+// K a multiple of 16 with at least `splits` slices of 16, 16-byte aligned operands.
 hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
-                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st) {
+                       uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st, uint32_t splits,
+                       float* partials) {
     GemmArgs a;
     a.A = A; a.B = B; a.C = C;
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.accumulate = accumulate;
-    return launch_gemm(a, 0, st, 1, nullptr, lower_only);
+    return launch_gemm(a, 0, st, splits, partials, lower_only);
 }
 
 // P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.

@@ -27,7 +27,8 @@ def _dev():
     return torch.device("cuda:0")
 
 
-@pytest.mark.parametrize("N,k", [(50, 7), (300, 130), (1000, 256), (9000, 300), (20000, 512), (17, 64), (8192, 128)])
+@pytest.mark.parametrize("N,k", [(50, 7), (300, 130), (1000, 256), (9000, 300), (20000, 512), (17, 64), (8192, 128),
+                                 (40000, 384), (2100, 640)])
 def test_fim_parity(grass, N, k):
     G = synth.compressed_gradients(N, k, seed=2000 + k, device=_dev())
     F = grass.grass_fim(G)
