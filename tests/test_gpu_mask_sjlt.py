@@ -112,6 +112,33 @@ def test_sjlt_parity(grass, n, d, k, s, pad):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
+# Unmasked rows are grouped so that all rows of a workgroup start at the same offset inside a 128-byte line
+# (row period P = 32 / gcd(ld mod 32, 32)) and the vector loop starts on a line; the cases below walk through
+# P = 32, 16, 8, 1, a ragged last block of rows, a misaligned base pointer and inputs shorter than the lead-in.
+ALIGNED_CASES = [
+    # n, d, pad (ld = off + d + pad), off (first column of the view), k, s
+    (1100, 1001, 0, 0, 64, 1),           # ld mod 32 = 9: P = 32, 8 rows per group, last block ragged
+    (520, 2050, 0, 0, 2048, 2),          # ld mod 32 = 2: P = 16
+    (70, 4100, 0, 0, 8192, 1),           # ld mod 32 = 4: P = 8, 2 rows per group
+    (40, 3000, 5, 3, 512, 4),            # ld = 3008: P = 1, base 12 bytes into a line (29 leading positions)
+    (9, 64, 0, 0, 16, 1),                # one line per row
+    (4, 10, 51, 3, 8, 1),                # fewer positions than the lead-in
+    (5, 20, 12, 7, 8, 1),                # too few rows to group: consecutive rows, scalar loads
+    (33, 70001, 31, 0, 1024, 1),         # ld = 70032 (mod 32 = 16): P = 2, several chunks
+]
+
+
+@pytest.mark.parametrize("n,d,pad,off,k,s", ALIGNED_CASES)
+def test_sjlt_line_aligned_row_groups(grass, n, d, pad, off, k, s):
+    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
+    full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=23, device=_dev())
+    g = full[:, off:off + d]
+    out = grass.grass_sjlt(g, k, s, seed=3, stream_id=1)
+    torch.cuda.synchronize()
+    ref = orc.sjlt(g.cpu().numpy(), k, s, 3, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+
+
 @pytest.mark.parametrize("rows,chunks,threads,acc", [(1, 1, 256, 0), (2, 3, 512, 1), (4, 7, 1024, 2), (8, 2, 256, 3),
                                                      (8, 1, 1024, 2), (4, 1, 512, 1), (2, 5, 1024, 3)])
 def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
