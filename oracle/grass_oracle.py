@@ -271,6 +271,70 @@ def influence(train: np.ndarray, test: np.ndarray, lam: float) -> np.ndarray:
 
 
 # ----------------------------------------------------------------------------
+# Selective Mask (Sec. 3.2, Eq. (1); practical notes in App. B.4 "Selective
+# Mask"): the mask logits S in R^p maximise the average, over test points, of
+# the Pearson correlation between the exact GradDot scores <g_i, g_test> and
+# the soft-masked ones <sigma(S) * g_i, sigma(S) * g_test>, minus
+# lambda * ||sigma(S)||_1.  App. B.4 replaces S by S / T (inverse temperature).
+#
+# Readings: the expectation over test points is the mean over the rows handed
+# in; corr is the Pearson correlation over the n training points with
+# population (1/n) moments; ||sigma||_1 is the plain sum (sigma > 0).  The paper
+# names no optimiser, step size or schedule: the oracle (and the library) stop
+# at the objective and its gradient, the update rule is the caller's.
+# ----------------------------------------------------------------------------
+def _sigmoid(x):
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+def selective_mask_objective(S, G, Gt, lam: float, temperature: float = 1.0) -> float:
+    """Eq. (1) for train rows G (n x p), test rows Gt (m x p) and logits S (p)."""
+    S = np.asarray(S, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    Gt = np.asarray(Gt, dtype=np.float64)
+    sig = _sigmoid(S / temperature)
+    total = 0.0
+    for t in range(Gt.shape[0]):
+        exact = G @ Gt[t]                                  # <g_i, g_test>, i = 1..n
+        masked = (G * sig) @ (Gt[t] * sig)                 # <sigma*g_i, sigma*g_test>
+        da, db = exact - exact.mean(), masked - masked.mean()
+        total += (da @ db) / np.sqrt((da @ da) * (db @ db))
+    return total / Gt.shape[0] - lam * sig.sum()
+
+
+def selective_mask_gradient(S, G, Gt, lam: float, temperature: float = 1.0) -> np.ndarray:
+    """Gradient of selective_mask_objective with respect to S, by the chain rule:
+    d corr / d masked_i = (da_i / (|da||db|) - corr * db_i / |db|^2), masked_i = sum_j sigma_j^2 G_ij Gt_j,
+    d sigma_j / d S_j = sigma_j (1 - sigma_j) / T."""
+    S = np.asarray(S, dtype=np.float64)
+    G = np.asarray(G, dtype=np.float64)
+    Gt = np.asarray(Gt, dtype=np.float64)
+    sig = _sigmoid(S / temperature)
+    dsig = sig * (1.0 - sig) / temperature
+    grad_w = np.zeros_like(S)                              # with respect to w_j = sigma_j^2
+    for t in range(Gt.shape[0]):
+        exact = G @ Gt[t]
+        masked = (G * sig) @ (Gt[t] * sig)
+        da, db = exact - exact.mean(), masked - masked.mean()
+        na, nb = np.sqrt(da @ da), np.sqrt(db @ db)
+        corr = (da @ db) / (na * nb)
+        c = da / (na * nb) - corr * db / (nb * nb)         # sums to zero, so centring needs no extra term
+        grad_w += (c @ G) * Gt[t]
+    grad_w /= Gt.shape[0]
+    return grad_w * 2.0 * sig * dsig - lam * dsig
+
+
+def selective_mask_indices(S, k: int | None = None) -> np.ndarray:
+    """Index extraction (Sec. 3.2): all j with sigma(S_j) >= 1/2, i.e. S_j >= 0, ascending.  With k given, the
+    'ensuring exact k' rule of App. B.4: the k largest logits (ties towards the smaller index), ascending."""
+    S = np.asarray(S, dtype=np.float64)
+    if k is None:
+        return np.nonzero(S >= 0.0)[0].astype(np.int32)
+    order = np.lexsort((np.arange(S.size), -S))            # by -S, then by index
+    return np.sort(order[:k]).astype(np.int32)
+
+
+# ----------------------------------------------------------------------------
 # Dense random projection baseline (Sec. 2.2): g_hat = P g with P (k x p),
 # P_ab ~ N(0, 1/k) i.i.d.
 #

@@ -170,8 +170,9 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_nt_kernel(GemmBf16Args
 // LDS base + 16*i), so no registers are spent on staging and four LDS stages of
 // 32 KB keep two slices in flight behind the one being multiplied.  Rows are
 // stored unpadded (64 bytes); the 16-byte chunk kc of row r sits at position
-// kc ^ ((r >> 1) & 3), which makes the fragment reads of 8 consecutive rows hit
-// 8 distinct 16-byte bank groups.
+// kc ^ ((r >> 2) & 3), which makes the fragment reads of 16 consecutive rows hit
+// the 16 distinct 16-byte bank groups (with (r >> 1) the bank-conflict counter
+// showed every second LDS cycle of the kernel stalled).
 constexpr int kDmaStages = 4;
 constexpr int kDmaStageBytes = (TM + TN) * TK * 2;     // 32 KB
 
@@ -242,7 +243,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     for (int j = 0; j < 4; ++j) {
         const int grp = wave * 4 + j;
         const int r = grp * 16 + (lane >> 2);                      // 0..511
-        const int kc = (lane & 3) ^ ((r >> 1) & 3);
+        const int kc = (lane & 3) ^ ((r >> 2) & 3);
         if (r < TM) {
             const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
             gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16 +
@@ -262,7 +263,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     };
 
     // fragment addresses: row*64 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
-    const int fl = (lane >> 1) & 3;
+    const int fl = (lane >> 2) & 3;
     const int koff0 = (((lane >> 5)) ^ fl) * 16, koff1 = ((2 + (lane >> 5)) ^ fl) * 16;
     const int a_row = (wm * 128 + (lane & 31)) * 64;
     const int b_row = (TM + wn * 64 + (lane & 31)) * 64;

@@ -23,6 +23,7 @@ pins_sjlt = _load("test_oracle_sjlt")
 pins_mask = _load("test_oracle_hash_mask")
 pins_fact = _load("test_oracle_factgrass_score")
 pins_fim = _load("test_oracle_fim")
+pins_sm = _load("test_oracle_selective_mask")
 
 _U64 = np.uint64
 
@@ -175,3 +176,53 @@ def test_ifvp_multiplying_instead_of_solving_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "ifvp", lambda G, F, lam: np.asarray(G, np.float64) @ (F + lam * np.eye(F.shape[0])))
     with pytest.raises(AssertionError):
         pins_fim.test_ifvp_solves_the_damped_system()
+
+
+def _sm_objective_variant(single_sigma=False, plus_penalty=False, no_centering=False):
+    def objective(S, G, Gt, lam, temperature=1.0):
+        S = np.asarray(S, np.float64); G = np.asarray(G, np.float64); Gt = np.asarray(Gt, np.float64)
+        sig = 1.0 / (1.0 + np.exp(-S / temperature))
+        w = sig if single_sigma else sig * sig
+        total = 0.0
+        for t in range(Gt.shape[0]):
+            a = G @ Gt[t]; b = (G * w) @ Gt[t]
+            da, db = (a, b) if no_centering else (a - a.mean(), b - b.mean())
+            total += (da @ db) / np.sqrt((da @ da) * (db @ db))
+        pen = lam * sig.sum()
+        return total / Gt.shape[0] + (pen if plus_penalty else -pen)
+    return objective
+
+
+@pytest.mark.parametrize("kwargs", [dict(single_sigma=True), dict(plus_penalty=True), dict(no_centering=True)])
+def test_selective_mask_objective_mistakes_are_caught(monkeypatch, kwargs):
+    monkeypatch.setattr(orc, "selective_mask_objective", _sm_objective_variant(**kwargs))
+    failed = 0
+    for pin in (pins_sm.test_objective_matches_scipy_pearson_written_out,
+                pins_sm.test_constant_logits_give_perfect_correlation,
+                lambda: pins_sm.test_gradient_matches_central_differences(1.0, 0.07, 4)):
+        try:
+            pin()
+        except AssertionError:
+            failed += 1
+    assert failed >= 1
+
+
+def test_selective_mask_gradient_mistakes_are_caught(monkeypatch):
+    good = orc.selective_mask_gradient
+    monkeypatch.setattr(orc, "selective_mask_gradient", lambda S, G, Gt, lam, temperature=1.0: good(S, G, Gt, lam, 1.0))
+    with pytest.raises(AssertionError):                     # temperature ignored
+        pins_sm.test_gradient_matches_central_differences(0.5, 0.02, 5)
+    monkeypatch.setattr(orc, "selective_mask_gradient", lambda S, G, Gt, lam, temperature=1.0: good(S, G, Gt, 0.0, temperature))
+    with pytest.raises(AssertionError):                     # penalty term dropped
+        pins_sm.test_gradient_matches_central_differences(1.0, 0.07, 4)
+    monkeypatch.setattr(orc, "selective_mask_gradient",
+                        lambda S, G, Gt, lam, temperature=1.0: 0.5 * (good(S, G, Gt, lam, temperature) - lam * 0) )
+    with pytest.raises(AssertionError):                     # factor 2 of d(sigma^2) lost
+        pins_sm.test_gradient_matches_central_differences(1.0, 0.0, 3)
+
+
+def test_selective_mask_threshold_mistake_is_caught(monkeypatch):
+    monkeypatch.setattr(orc, "selective_mask_indices",
+                        lambda S, k=None: np.nonzero(np.asarray(S) > 0.5)[0].astype(np.int32))   # thresholds S, not sigma(S)
+    with pytest.raises(AssertionError):
+        pins_sm.test_index_extraction()

@@ -1,0 +1,92 @@
+"""Pins for the oracle's Selective Mask objective, gradient and index extraction (Sec. 3.2 Eq. (1), App. B.4)."""
+import numpy as np
+import pytest
+from scipy import stats
+
+from oracle import grass_oracle as orc
+
+
+def _problem(n=9, m=3, p=7, seed=0):
+    rng = np.random.default_rng(seed)
+    return rng.standard_normal(p), rng.standard_normal((n, p)), rng.standard_normal((m, p))
+
+
+def test_objective_matches_scipy_pearson_written_out():
+    S, G, Gt = _problem()
+    lam = 0.03
+    sig = 1 / (1 + np.exp(-S))
+    want = 0.0
+    for t in range(Gt.shape[0]):
+        exact = [sum(G[i, j] * Gt[t, j] for j in range(7)) for i in range(9)]
+        masked = [sum(sig[j] * G[i, j] * sig[j] * Gt[t, j] for j in range(7)) for i in range(9)]
+        want += stats.pearsonr(exact, masked)[0]
+    want = want / Gt.shape[0] - lam * sum(sig)
+    assert np.isclose(orc.selective_mask_objective(S, G, Gt, lam), want, rtol=1e-12)
+
+
+def test_constant_logits_give_perfect_correlation():
+    """sigma constant: the masked scores are a positive multiple of the exact ones, corr = 1 for every test point."""
+    _, G, Gt = _problem(seed=1)
+    for s0 in (-2.0, 0.0, 3.0):
+        S = np.full(7, s0)
+        sig = 1 / (1 + np.exp(-s0))
+        assert np.isclose(orc.selective_mask_objective(S, G, Gt, 0.1), 1.0 - 0.1 * 7 * sig, rtol=1e-12)
+
+
+def test_objective_invariances():
+    S, G, Gt = _problem(seed=2)
+    base = orc.selective_mask_objective(S, G, Gt, 0.05)
+    # correlation ignores positive rescaling of a test gradient and of all training gradients
+    Gt2 = Gt * np.array([[2.0], [0.5], [7.0]])
+    assert np.isclose(orc.selective_mask_objective(S, G, Gt2, 0.05), base, rtol=1e-12)
+    assert np.isclose(orc.selective_mask_objective(S, 3.0 * G, Gt, 0.05), base, rtol=1e-12)
+    # temperature: S / T with T = 2 equals logits S / 2 at T = 1
+    assert np.isclose(orc.selective_mask_objective(S, G, Gt, 0.05, temperature=2.0),
+                      orc.selective_mask_objective(S / 2.0, G, Gt, 0.05), rtol=1e-12)
+    # a coordinate that is zero in every gradient only pays the penalty
+    G0, Gt0 = np.hstack([G, np.zeros((9, 1))]), np.hstack([Gt, np.zeros((3, 1))])
+    S0 = np.append(S, 1.3)
+    assert np.isclose(orc.selective_mask_objective(S0, G0, Gt0, 0.05), base - 0.05 / (1 + np.exp(-1.3)), rtol=1e-12)
+
+
+@pytest.mark.parametrize("temperature,lam,seed", [(1.0, 0.0, 3), (1.0, 0.07, 4), (0.5, 0.02, 5), (3.0, 0.3, 6)])
+def test_gradient_matches_central_differences(temperature, lam, seed):
+    S, G, Gt = _problem(n=11, m=4, p=9, seed=seed)
+    g = orc.selective_mask_gradient(S, G, Gt, lam, temperature)
+    h = 1e-6
+    for j in range(S.size):
+        e = np.zeros_like(S); e[j] = h
+        fd = (orc.selective_mask_objective(S + e, G, Gt, lam, temperature)
+              - orc.selective_mask_objective(S - e, G, Gt, lam, temperature)) / (2 * h)
+        assert np.isclose(g[j], fd, rtol=2e-6, atol=1e-9)
+
+
+def test_gradient_of_the_penalty_alone_at_perfect_correlation():
+    """At constant logits the correlation term is flat along the all-ones direction (scale invariance):
+    the directional derivative there is the penalty's alone."""
+    _, G, Gt = _problem(seed=7)
+    S = np.full(7, 0.4)
+    sig = 1 / (1 + np.exp(-0.4))
+    g = orc.selective_mask_gradient(S, G, Gt, 0.2)
+    assert np.isclose(g.sum(), -0.2 * 7 * sig * (1 - sig), rtol=1e-9)
+
+
+def test_gradient_ascent_increases_the_objective():
+    S, G, Gt = _problem(n=20, m=5, p=12, seed=8)
+    f0 = orc.selective_mask_objective(S, G, Gt, 0.01)
+    S1 = S + 0.05 * orc.selective_mask_gradient(S, G, Gt, 0.01)
+    assert orc.selective_mask_objective(S1, G, Gt, 0.01) > f0
+
+
+def test_index_extraction():
+    S = np.array([0.3, -0.1, 0.0, 2.0, -5.0, 0.3])
+    assert orc.selective_mask_indices(S).tolist() == [0, 2, 3, 5]            # sigma(S) >= 1/2  <=>  S >= 0
+    assert orc.selective_mask_indices(S, k=2).tolist() == [0, 3]             # 2.0, then the first of the two 0.3
+    assert orc.selective_mask_indices(S, k=3).tolist() == [0, 3, 5]
+    assert orc.selective_mask_indices(S, k=6).tolist() == [0, 1, 2, 3, 4, 5]
+    assert orc.selective_mask_indices(S, k=1).dtype == np.int32
+    # brute force
+    rng = np.random.default_rng(9)
+    S = rng.standard_normal(50)
+    want = sorted(sorted(range(50), key=lambda j: (-S[j], j))[:13])
+    assert orc.selective_mask_indices(S, k=13).tolist() == want
