@@ -152,7 +152,23 @@ def main() -> int:
         # mask index generation (one-time set-up)
         t, _, _ = _timed(lambda: grass.grass_mask_indices(seed, 0, p, kp, device=dev), 5, 1, torch)
         extras["mask_indices_p1863690"] = {"ms": round(t / 5, 4)}
-        del g, gm, out, ws, ws4
+        del gm, out, ws, ws4
+        torch.cuda.empty_cache()
+        # one Selective Mask training step (objective + gradient) on the same batch of gradients, 256 test rows
+        msm = 256
+        gt_sm = synth.mlp_relu_gradients(msm, seed=1012, device=dev)
+        s_sm = synth.dense_normal(1, p, seed=1013, device=dev).reshape(-1).contiguous()
+        a_sm = grass.grass_score(g, gt_sm, compute_mode=0)
+        w_sm = torch.empty(grass.grass_selective_mask_grad_workspace_bytes(n, msm, p), dtype=torch.uint8, device=dev)
+        gr_sm = torch.empty(p, dtype=torch.float32, device=dev)
+        ob_sm = torch.empty(1, dtype=torch.float64, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_selective_mask_grad(g, gt_sm, a_sm, s_sm, 1e-6, 1.0, grad=gr_sm, objective=ob_sm,
+                                                                 ws=w_sm), 2, 1, torch)
+        tf = 2 * 2.0 * n * msm * p / (t / 2 * 1e-3) / 1e12
+        extras["selective_mask_grad_mlp"] = {"ms": round(t / 2, 2), "TFLOPs": round(tf, 1), "train_rows": n, "test_rows": msm}
+        t, _, _ = _timed(lambda: grass.grass_selective_mask_indices(s_sm, kp), 3, 1, torch)
+        extras["selective_mask_indices_top_k"] = {"ms": round(t / 3, 3)}
+        del g, gt_sm, s_sm, a_sm, w_sm, gr_sm, ob_sm
         torch.cuda.empty_cache()
 
         # ResNet-scale unmasked SJLT

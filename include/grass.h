@@ -243,6 +243,41 @@ grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t ldf, double 
 grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint64_t ldg,
                         const float* W, uint64_t ldw, float* out, uint64_t ldo, grass_stream stream);
 
+/* ------------------------------------------------------------- Selective Mask
+ * Sec. 3.2 "Selective Mask", Eq. (1), with the practical notes of App. B.4:
+ * logits S in R^p are trained to maximise
+ *   mean over test rows t of corr_i( <g_i, gt_t>, <sigma*g_i, sigma*gt_t> )  -  lambda * sum_j sigma_j,
+ * sigma = sigmoid(S / temperature), corr the Pearson correlation over the n train
+ * rows.  The paper fixes no optimiser; the library provides the two pieces every
+ * first-order method needs, the caller owns the update rule.
+ *
+ * grass_selective_mask_grad: objective value and gradient with respect to S.
+ *   G  (n x p fp32, ldg)  train gradients;  Gt (m x p fp32, ldgt) test gradients;
+ *   A  (m x n fp32, lda)  exact scores A[t][i] = <gt_t, g_i>, i.e.
+ *                         grass_score(train = G, test = Gt), computed once;
+ *   S  (p fp32) logits;  grad (p fp32) receives d objective / d S;
+ *   objective (device double, may be NULL) receives the objective value.
+ *   n >= 2, m >= 1.  A test row whose exact or masked scores are constant over i
+ *   has no correlation: it contributes 0 to the value and to the gradient.
+ *   Two fp32 MFMA GEMMs of 2*m*n*p flops each; reductions in fp64, fixed order.
+ *
+ * grass_selective_mask_indices: index extraction.  k == 0: every j with
+ *   sigma(S_j) >= 1/2 (S_j >= 0), ascending; their number goes to *count (device
+ *   uint32, required) and idx must hold p entries.  k > 0 ("ensuring exact k"):
+ *   the k largest logits, ties towards the smaller index, ascending; count (may
+ *   be NULL) receives k.  S must not contain NaN.  p < 2^31.
+ * All pointers device; workspaces from the *_workspace_bytes queries.           */
+grass_status grass_selective_mask_grad_workspace_bytes(uint64_t n, uint64_t m, uint64_t p, size_t* host_bytes);
+grass_status grass_selective_mask_grad(const float* G, uint64_t n, uint64_t ldg,
+                                       const float* Gt, uint64_t m, uint64_t ldgt, uint64_t p,
+                                       const float* A, uint64_t lda, const float* S,
+                                       double lambda, double temperature,
+                                       float* grad, double* objective,
+                                       void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* host_bytes);
+grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
+                                          uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream);
+
 /* ------------------------------------------------------------------- tuning
  * Overrides the launch heuristics of grass_sjlt for experiments: rows per
  * block (1,2,4,8), column chunks per row group, threads per block

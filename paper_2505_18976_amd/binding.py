@@ -58,6 +58,11 @@ SIGNATURES = {
     "grass_fim_inverse_workspace_bytes": (_int, [_u32, ctypes.POINTER(_sz)]),
     "grass_fim_inverse": (_int, [_vp, _u32, _u64, ctypes.c_double, _vp, _u64, _vp, _vp, _sz, _vp]),
     "grass_ifvp": (_int, [_vp, _u64, _u32, _u64, _vp, _u64, _vp, _u64, _vp]),
+    "grass_selective_mask_grad_workspace_bytes": (_int, [_u64, _u64, _u64, ctypes.POINTER(_sz)]),
+    "grass_selective_mask_grad": (_int, [_vp, _u64, _u64, _vp, _u64, _u64, _u64, _vp, _u64, _vp, ctypes.c_double,
+                                         ctypes.c_double, _vp, _vp, _vp, _sz, _vp]),
+    "grass_selective_mask_indices_workspace_bytes": (_int, [_u64, ctypes.POINTER(_sz)]),
+    "grass_selective_mask_indices": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _sz, _vp]),
     "grass_set_sjlt_tuning": (None, [_int, _int, _int, _int]),
     "grass_set_factgrass_tuning": (None, [_int]),
 }
@@ -374,6 +379,55 @@ def grass_ifvp(G: torch.Tensor, W: torch.Tensor, out: torch.Tensor | None = None
     _check(load_library().grass_ifvp(_ptr(G), N, k, _ld(G), _ptr(W), _ld(W), _ptr(out), _ld(out), _stream()),
            "grass_ifvp")
     return out
+
+
+def grass_selective_mask_grad_workspace_bytes(n: int, m: int, p: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_selective_mask_grad_workspace_bytes(n, m, p, ctypes.byref(out)),
+           "grass_selective_mask_grad_workspace_bytes")
+    return out.value
+
+
+def grass_selective_mask_grad(G: torch.Tensor, Gt: torch.Tensor, A: torch.Tensor, S: torch.Tensor, lam: float,
+                              temperature: float = 1.0, grad: torch.Tensor | None = None,
+                              objective: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+    """Objective of the Selective Mask problem and its gradient with respect to the logits S.
+    A = grass_score(G, Gt) holds the exact scores.  Returns (grad fp32 [p], objective float64 [1])."""
+    assert G.dtype == Gt.dtype == A.dtype == S.dtype == torch.float32 and S.is_contiguous()
+    n, p = G.shape
+    m = Gt.shape[0]
+    assert Gt.shape[1] == p and A.shape == (m, n) and S.numel() == p
+    if grad is None:
+        grad = torch.empty(p, dtype=torch.float32, device=G.device)
+    if objective is None:
+        objective = torch.empty(1, dtype=torch.float64, device=G.device)
+    if ws is None:
+        ws = _workspace(grass_selective_mask_grad_workspace_bytes(n, m, p), G.device)
+    _check(load_library().grass_selective_mask_grad(_ptr(G), n, _ld(G), _ptr(Gt), m, _ld(Gt), p, _ptr(A), _ld(A), _ptr(S),
+                                                    float(lam), float(temperature), _ptr(grad), _ptr(objective), _ptr(ws),
+                                                    0 if ws is None else ws.numel(), _stream()),
+           "grass_selective_mask_grad")
+    return grad, objective
+
+
+def grass_selective_mask_indices_workspace_bytes(p: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_selective_mask_indices_workspace_bytes(p, ctypes.byref(out)),
+           "grass_selective_mask_indices_workspace_bytes")
+    return out.value
+
+
+def grass_selective_mask_indices(S: torch.Tensor, k: int = 0) -> torch.Tensor:
+    """k == 0: every j with sigmoid(S_j) >= 1/2, ascending (reads the count back, which synchronises);
+    k > 0: the k largest logits, ascending."""
+    assert S.dtype == torch.float32 and S.is_contiguous()
+    p = S.numel()
+    idx = torch.empty(p if k == 0 else k, dtype=torch.int32, device=S.device)
+    count = torch.zeros(1, dtype=torch.int32, device=S.device)
+    ws = _workspace(grass_selective_mask_indices_workspace_bytes(p), S.device)
+    _check(load_library().grass_selective_mask_indices(_ptr(S), p, k, _ptr(idx), _ptr(count), _ptr(ws), ws.numel(),
+                                                       _stream()), "grass_selective_mask_indices")
+    return idx[: int(count.item())] if k == 0 else idx
 
 
 def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0,

@@ -16,24 +16,6 @@ hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uin
                        float* partials);
 
 // ------------------------------------------------------------------------------------------------ FIM (fp32)
-// dst (k x ld_dst) = transpose of rows [r0, r0+rc) of src (N x k); columns rc..rc_pad of dst are zero-filled.
-__global__ void __launch_bounds__(256) transpose_rows_kernel(const float* src, uint64_t ld_src, uint64_t r0, uint32_t rc,
-                                                            uint32_t rc_pad, uint32_t k, float* dst, uint64_t ld_dst) {
-    __shared__ float tile[64][65];
-    const uint32_t c0 = blockIdx.x * 64;      // column of src = row of dst
-    const uint32_t q0 = blockIdx.y * 64;      // row of the chunk = column of dst
-    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
-    for (int r = ty; r < 64; r += 4) {
-        const uint32_t q = q0 + r, c = c0 + tx;
-        tile[r][tx] = (q < rc && c < k) ? src[(r0 + q) * ld_src + c] : 0.0f;
-    }
-    __syncthreads();
-    for (int r = ty; r < 64; r += 4) {
-        const uint32_t c = c0 + r, q = q0 + tx;
-        if (c < k && q < rc_pad) dst[(uint64_t)c * ld_dst + q] = tile[tx][r];
-    }
-}
-
 // F[a][b] = F[b][a] = scale * S[a][b] for a >= b: applies 1/N and mirrors the computed lower triangle.  S is F itself
 // (splits == 0) or the sum, in ascending order, of `splits` dense k x k partial products.
 __global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf, uint32_t k, float scale,

@@ -349,6 +349,12 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         }
 }
 
+// Operands the direct-to-LDS kernel can take: whole 64-byte K slices, 16-byte aligned rows.
+bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint64_t lda, uint64_t ldb) {
+    const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
+    return K % sk == 0 && (lda * esz) % 16 == 0 && (ldb * esz) % 16 == 0 && aligned(A, 16) && aligned(B, 16);
+}
+
 // Split-K factor that fills the chip when there are few output tiles: the number
 // of K ranges (at most max_splits) such that tiles*splits reaches the CU count.
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits) {
@@ -370,8 +376,8 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
 bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                      uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
                      float* partials, int lower_only) {
+    if (!gemm_dma_eligible(f32, A, B, K, lda, ldb)) return false;
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
-    if (K % sk != 0 || (lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
     GemmDmaArgs a;
     a.A = A; a.B = B; a.C = C; a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.accumulate = accumulate;

@@ -61,6 +61,24 @@ static __global__ void __launch_bounds__(256) reduce_partials_kernel(const float
     out[i * ldo + b] = sum * scale;
 }
 
+// dst (k x ld_dst) = transpose of rows [r0, r0+rc) of src (N x k); columns rc..rc_pad of dst are zero-filled.
+static __global__ void __launch_bounds__(256) transpose_rows_kernel(const float* src, uint64_t ld_src, uint64_t r0, uint32_t rc,
+                                                            uint32_t rc_pad, uint32_t k, float* dst, uint64_t ld_dst) {
+    __shared__ float tile[64][65];
+    const uint32_t c0 = blockIdx.x * 64;      // column of src = row of dst
+    const uint32_t q0 = blockIdx.y * 64;      // row of the chunk = column of dst
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    for (int r = ty; r < 64; r += 4) {
+        const uint32_t q = q0 + r, c = c0 + tx;
+        tile[r][tx] = (q < rc && c < k) ? src[(r0 + q) * ld_src + c] : 0.0f;
+    }
+    __syncthreads();
+    for (int r = ty; r < 64; r += 4) {
+        const uint32_t c = c0 + r, q = q0 + tx;
+        if (c < k && q < rc_pad) dst[(uint64_t)c * ld_dst + q] = tile[tx][r];
+    }
+}
+
 constexpr int kNumCU = 256;                 // MI355X
 constexpr size_t kLdsBytes = 160 * 1024;    // per CU and per workgroup on gfx950
 

@@ -1,4 +1,4 @@
-// Random Mask index generation, mask gather, SJLT table dump, index check.
+// Random Mask index generation, Selective Mask index extraction, mask gather, SJLT table dump, index check.
 //
 // Sec. 3.2: Random Mask keeps a random subset of k' of the p coordinates; as a
 // matrix it is a binary selection matrix with one non-repeating non-zero per
@@ -24,28 +24,46 @@ struct SelectState {
     uint32_t pad;
 };
 
+// Key sources of the select kernels.  HashKeys: Random Mask, key_j = H(seed, stream, j), never stored.
+// LogitKeys: Selective Mask with an exact count (App. B.4 "ensuring exact k"): the largest logits first, so the key
+// is the bitwise complement of the order-preserving integer image of S_j (-0 is folded into +0), in the upper word.
+struct HashKeys {
+    uint64_t sub;
+    __device__ __forceinline__ uint64_t operator()(uint64_t j) const { return sm(sub, j); }
+};
+__device__ __forceinline__ uint64_t logit_key(float v) {
+    uint32_t u = __float_as_uint(v + 0.0f);
+    u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);          // ascending in v
+    return (uint64_t)(~u) << 32;                                // ascending key = descending logit
+}
+struct LogitKeys {
+    const float* S;
+    __device__ __forceinline__ uint64_t operator()(uint64_t j) const { return logit_key(S[j]); }
+};
+
 __global__ void fill_u32_kernel(uint32_t* p, uint64_t count, uint32_t v) {
     uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (; t < count; t += stride) p[t] = v;
 }
 
-__global__ void select_init_kernel(SelectState* st, uint32_t kprime) {
-    st->prefix = 0ull;
-    st->need = kprime;
+__global__ void select_init_kernel(SelectState* st, unsigned long long prefix, uint32_t need) {
+    st->prefix = prefix;
+    st->need = need;
     st->pad = 0;
 }
 
 // pass = 0..3: histogram of bits [48-16*pass, 64-16*pass) among keys whose
 // higher bits equal the prefix.
-__global__ void __launch_bounds__(256) select_hist_kernel(uint64_t sub, uint64_t p, int pass,
+template <class KeyFn>
+__global__ void __launch_bounds__(256) select_hist_kernel(KeyFn kf, uint64_t p, int pass,
                                                           const SelectState* st, uint32_t* hist) {
     const unsigned long long prefix = st->prefix;
     const int shift = 48 - 16 * pass;
     uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (; j < p; j += stride) {
-        const uint64_t key = sm(sub, j);
+        const uint64_t key = kf(j);
         const bool in_class = pass == 0 ? true : ((key >> (shift + 16)) == prefix);
         if (in_class) atomicAdd(&hist[(key >> shift) & 0xFFFFull], 1u);
     }
@@ -108,7 +126,8 @@ __device__ __forceinline__ void block_scan2(uint32_t a, uint32_t b, uint32_t* ea
 }
 
 // Per tile of kSelTile coordinates: how many keys are below T, how many equal T.
-__global__ void __launch_bounds__(kSelThreads) select_count_kernel(uint64_t sub, uint64_t p,
+template <class KeyFn>
+__global__ void __launch_bounds__(kSelThreads) select_count_kernel(KeyFn kf, uint64_t p,
                                                                    const SelectState* st, uint32_t* tile_less,
                                                                    uint32_t* tile_eq) {
     const unsigned long long T = st->prefix;
@@ -118,7 +137,7 @@ __global__ void __launch_bounds__(kSelThreads) select_count_kernel(uint64_t sub,
     for (int i = 0; i < kSelItems; ++i) {
         const uint64_t j = j0 + i;
         if (j < p) {
-            const uint64_t key = sm(sub, j);
+            const uint64_t key = kf(j);
             less += key < T;
             eq += key == T;
         }
@@ -129,8 +148,9 @@ __global__ void __launch_bounds__(kSelThreads) select_count_kernel(uint64_t sub,
 }
 
 // One workgroup: exclusive scan of the per-tile counts, in place.
+// total_less (may be null) receives the number of keys below T.
 __global__ void __launch_bounds__(1024) select_scan_tiles_kernel(uint32_t* tile_less, uint32_t* tile_eq,
-                                                                 uint64_t tiles) {
+                                                                 uint64_t tiles, uint32_t* total_less) {
     __shared__ uint32_t sa[1024], sb[1024];
     const int t = threadIdx.x;
     const uint64_t per = (tiles + 1023) / 1024;
@@ -147,6 +167,7 @@ __global__ void __launch_bounds__(1024) select_scan_tiles_kernel(uint32_t* tile_
         sa[t] += va; sb[t] += vb;
         __syncthreads();
     }
+    if (t == 1023 && total_less) *total_less = sa[1023];
     uint32_t ra = sa[t] - a, rb = sb[t] - b;
     for (uint64_t i = lo; i < hi; ++i) {
         const uint32_t ca = tile_less[i], cb = tile_eq[i];
@@ -158,7 +179,8 @@ __global__ void __launch_bounds__(1024) select_scan_tiles_kernel(uint32_t* tile_
 // Ordered compaction: coordinate j is kept iff key_j < T, or key_j == T and
 // fewer than `need` equal keys precede it; its output slot is the number of
 // kept coordinates before it.
-__global__ void __launch_bounds__(kSelThreads) select_compact_kernel(uint64_t sub, uint64_t p,
+template <class KeyFn>
+__global__ void __launch_bounds__(kSelThreads) select_compact_kernel(KeyFn kf, uint64_t p,
                                                                      const SelectState* st,
                                                                      const uint32_t* tile_less,
                                                                      const uint32_t* tile_eq, int32_t* idx,
@@ -172,7 +194,7 @@ __global__ void __launch_bounds__(kSelThreads) select_compact_kernel(uint64_t su
     for (int i = 0; i < kSelItems; ++i) {
         const uint64_t j = j0 + i;
         if (j < p) {
-            const uint64_t key = sm(sub, j);
+            const uint64_t key = kf(j);
             if (key < T) { ++less; flag_less |= 1u << i; }
             if (key == T) { ++eq; flag_eq |= 1u << i; }
         }
@@ -265,34 +287,70 @@ extern "C" grass_status grass_mask_indices_workspace_bytes(uint64_t p, uint32_t 
     return GRASS_OK;
 }
 
-extern "C" grass_status grass_mask_indices(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t kprime,
-                                           int32_t* idx, void* ws, size_t ws_bytes, grass_stream stream) {
-    if (p == 0 || p >= (1ull << 31) || kprime == 0 || kprime > p || !idx) return GRASS_EINVAL;
+// k smallest (key, j) pairs in ascending j.  radix = false skips the search for the threshold key: the state is
+// preset to (T, 0) and every j with key_j < T is emitted (their number goes to *count).
+template <class KeyFn>
+static grass_status run_select(KeyFn kf, uint64_t p, uint32_t k, bool radix, unsigned long long preset_T, int32_t* idx,
+                               uint32_t capacity, uint32_t* count, void* ws, hipStream_t hs) {
     const SelectLayout L = select_layout(p);
-    if (!ws || ws_bytes < L.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
     char* base = static_cast<char*>(ws);
     SelectState* st = reinterpret_cast<SelectState*>(base + L.off_state);
     uint32_t* hist = reinterpret_cast<uint32_t*>(base + L.off_hist);
     uint32_t* tile_less = reinterpret_cast<uint32_t*>(base + L.off_less);
     uint32_t* tile_eq = reinterpret_cast<uint32_t*>(base + L.off_eq);
-    hipStream_t hs = as_stream(stream);
-    const uint64_t sub = substream(seed, stream_id);
-
-    hipLaunchKernelGGL(fill_u32_kernel, dim3(256), dim3(256), 0, hs, hist, (uint64_t)4 * kHistBins, 0u);
-    hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(1), 0, hs, st, kprime);
-    uint32_t hist_blocks = (uint32_t)ceil_div(p, 256);
-    if (hist_blocks > 4096) hist_blocks = 4096;
-    for (int pass = 0; pass < 4; ++pass) {
-        uint32_t* h = hist + (size_t)pass * kHistBins;
-        hipLaunchKernelGGL(select_hist_kernel, dim3(hist_blocks), dim3(256), 0, hs, sub, p, pass, st, h);
-        hipLaunchKernelGGL(select_pick_kernel, dim3(1), dim3(1024), 0, hs, st, h);
+    if (radix) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(256), dim3(256), 0, hs, hist, (uint64_t)4 * kHistBins, 0u);
+        hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(1), 0, hs, st, 0ull, k);
+        uint32_t hist_blocks = (uint32_t)ceil_div(p, 256);
+        if (hist_blocks > 4096) hist_blocks = 4096;
+        for (int pass = 0; pass < 4; ++pass) {
+            uint32_t* h = hist + (size_t)pass * kHistBins;
+            hipLaunchKernelGGL(select_hist_kernel<KeyFn>, dim3(hist_blocks), dim3(256), 0, hs, kf, p, pass, st, h);
+            hipLaunchKernelGGL(select_pick_kernel, dim3(1), dim3(1024), 0, hs, st, h);
+        }
+    } else {
+        hipLaunchKernelGGL(select_init_kernel, dim3(1), dim3(1), 0, hs, st, preset_T, 0u);
     }
-    hipLaunchKernelGGL(select_count_kernel, dim3((uint32_t)L.tiles), dim3(kSelThreads), 0, hs, sub, p, st,
+    hipLaunchKernelGGL(select_count_kernel<KeyFn>, dim3((uint32_t)L.tiles), dim3(kSelThreads), 0, hs, kf, p, st,
                        tile_less, tile_eq);
-    hipLaunchKernelGGL(select_scan_tiles_kernel, dim3(1), dim3(1024), 0, hs, tile_less, tile_eq, L.tiles);
-    hipLaunchKernelGGL(select_compact_kernel, dim3((uint32_t)L.tiles), dim3(kSelThreads), 0, hs, sub, p, st,
-                       tile_less, tile_eq, idx, kprime);
+    hipLaunchKernelGGL(select_scan_tiles_kernel, dim3(1), dim3(1024), 0, hs, tile_less, tile_eq, L.tiles, count);
+    hipLaunchKernelGGL(select_compact_kernel<KeyFn>, dim3((uint32_t)L.tiles), dim3(kSelThreads), 0, hs, kf, p, st,
+                       tile_less, tile_eq, idx, capacity);
     return launch_status();
+}
+
+extern "C" grass_status grass_mask_indices(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t kprime,
+                                           int32_t* idx, void* ws, size_t ws_bytes, grass_stream stream) {
+    if (p == 0 || p >= (1ull << 31) || kprime == 0 || kprime > p || !idx) return GRASS_EINVAL;
+    if (!ws || ws_bytes < select_layout(p).total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    return run_select(HashKeys{substream(seed, stream_id)}, p, kprime, true, 0ull, idx, kprime, nullptr, ws,
+                      as_stream(stream));
+}
+
+extern "C" grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* host_bytes) {
+    if (!host_bytes || p == 0 || p >= (1ull << 31)) return GRASS_EINVAL;
+    *host_bytes = select_layout(p).total;
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
+                                                     uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream) {
+    if (p == 0 || p >= (1ull << 31) || k > p || !S || !idx) return GRASS_EINVAL;
+    if (k == 0 && !count) return GRASS_EINVAL;
+    if (!ws || ws_bytes < select_layout(p).total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    hipStream_t hs = as_stream(stream);
+    if (k == 0) {
+        // sigma(S_j) >= 1/2  <=>  S_j >= 0  <=>  key_j <= key(+0)  <=>  key_j < key(+0) + 2^32 (low word is zero)
+        const uint32_t zero_image = 0x80000000u;                                // order-preserving image of +0.0f
+        const unsigned long long thr = ((unsigned long long)(~zero_image) << 32) + (1ull << 32);
+        return run_select(LogitKeys{S}, p, 0, false, thr, idx, (uint32_t)p, count, ws, hs);
+    }
+    grass_status st = run_select(LogitKeys{S}, p, k, true, 0ull, idx, k, nullptr, ws, hs);
+    if (st == GRASS_OK && count) {
+        hipLaunchKernelGGL(fill_u32_kernel, dim3(1), dim3(1), 0, hs, count, (uint64_t)1, k);
+        st = launch_status();
+    }
+    return st;
 }
 
 extern "C" grass_status grass_check_indices(const int32_t* idx, uint32_t kprime, uint64_t p, int* host_ok,

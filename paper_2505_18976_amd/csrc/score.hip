@@ -31,6 +31,8 @@ struct GemmArgs {
     uint64_t M, N, K, lda, ldb, ldc;
     uint32_t tiles_m, tiles_n;
     int accumulate;   // C += instead of C =
+    uint64_t kt_per_split;     // split-K: workgroup (split, tile) contracts K slices [split*kps, (split+1)*kps)
+    uint64_t split_stride_c;   //          into C + split*split_stride_c
 };
 
 __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
@@ -75,7 +77,9 @@ __global__ void __launch_bounds__(kGemmThreads) gemm_nt_kernel(GemmArgs a) {
 
     // XCD-aware tile order: consecutive logical tiles share the same B (train) tile.
     const uint32_t total = a.tiles_m * a.tiles_n;
-    const uint32_t bid = blockIdx.x;
+    const uint32_t split = blockIdx.x / total;
+    const uint32_t bid = blockIdx.x - split * total;
+    a.C += split * a.split_stride_c;
     const uint32_t per_xcd = (total + 7) / 8;
     uint32_t logical = (bid % 8) * per_xcd + bid / 8;
     if (total % 8 != 0) logical = bid;              // ragged grids keep the plain order
@@ -104,9 +108,11 @@ __global__ void __launch_bounds__(kGemmThreads) gemm_nt_kernel(GemmArgs a) {
         }
     };
 
-    const uint64_t nkt = (a.K + BK - 1) / BK;
-    fetch(0);
-    for (uint64_t kt = 0; kt < nkt; ++kt) {
+    const uint64_t nkt_all = (a.K + BK - 1) / BK;
+    const uint64_t kt_begin = (uint64_t)split * a.kt_per_split;
+    const uint64_t nkt = kt_begin + a.kt_per_split < nkt_all ? kt_begin + a.kt_per_split : nkt_all;
+    fetch(kt_begin * BK);
+    for (uint64_t kt = kt_begin; kt < nkt; ++kt) {
         __syncthreads();    // everyone is done reading the previous slice
         if constexpr (MODE == 0) {
             float* As = reinterpret_cast<float*>(smem);            // [BK][kLdF32]
@@ -207,6 +213,7 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
                      uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
                      float* partials, int lower_only);
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits);
+bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint64_t lda, uint64_t ldb);
 
 // splits > 1 (fp32 mode only): K-range partial products go to `partials`, see launch_gemm_dma.
 static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint32_t splits = 1,
@@ -217,11 +224,17 @@ static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint3
                             partials, lower_only))
             return derr;
     }
-    if (splits > 1) return hipErrorInvalidValue;
     GemmArgs g = a;
     g.tiles_m = (uint32_t)ceil_div(a.M, BM);
     g.tiles_n = (uint32_t)ceil_div(a.N, BN);
-    const uint64_t total = (uint64_t)g.tiles_m * g.tiles_n;
+    const uint64_t nkt = ceil_div(a.K, BK);
+    if (splits < 1 || !partials) splits = 1;
+    if (splits > nkt) return hipErrorInvalidValue;
+    g.kt_per_split = ceil_div(nkt, splits);
+    if (ceil_div(nkt, g.kt_per_split) != splits) return hipErrorInvalidValue;      // every K range non-empty
+    g.split_stride_c = 0;
+    if (splits > 1) { g.C = partials; g.ldc = a.N; g.split_stride_c = a.M * a.N; }
+    const uint64_t total = (uint64_t)g.tiles_m * g.tiles_n * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return hipErrorInvalidValue;
     int v = vec_width(a.A, a.lda);
     const int vb = vec_width(a.B, a.ldb);
@@ -250,6 +263,20 @@ hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uin
     a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
     a.accumulate = accumulate;
     return launch_gemm(a, 0, st, splits, partials, lower_only);
+}
+
+// Number of K ranges gemm_nt_f32 should be given (with a partials buffer of that many M x N matrices) so that a product
+// with few output tiles still fills the chip; 1 = no split.
+uint32_t gemm_nt_f32_splits(const float* A, const float* B, uint64_t M, uint64_t N, uint64_t K, uint64_t lda, uint64_t ldb,
+                            uint32_t max_splits) {
+    if (M >= 128 && N >= 128 && gemm_dma_eligible(true, A, B, K, lda, ldb)) return gemm_dma_splits(M, N, K, true, max_splits);
+    const uint64_t tiles = ceil_div(M, BM) * ceil_div(N, BN), slices = ceil_div(K, BK);
+    if (tiles == 0 || tiles >= 2 * kNumCU || slices < 128) return 1;
+    uint64_t s = ceil_div(2 * kNumCU, tiles);
+    if (s > max_splits) s = max_splits;
+    if (s > slices / 64) s = slices / 64;
+    if (s < 2) return 1;
+    return (uint32_t)ceil_div(slices, ceil_div(slices, s));
 }
 
 // P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.

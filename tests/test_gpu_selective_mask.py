@@ -1,0 +1,126 @@
+"""GPU parity of the Selective Mask objective, gradient and index extraction against the CPU oracle.
+
+Tolerance of the gradient: both contractions are fp32 MFMA products and the row c_t is a difference of two nearly
+parallel vectors when the correlation is high (relative amplification about 1 / (1 - corr^2)); the test problems
+keep the correlations away from 1 and the bar is 2e-4 of the largest gradient entry (observed up to 5e-6).  The objective
+is a mean of correlations of order 1: absolute 1e-5.  Index extraction is bit-exact.
+"""
+import numpy as np
+import pytest
+import torch
+
+import synth
+from oracle import grass_oracle as orc
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def grass():
+    import paper_2505_18976_amd as g
+    g.load_library()
+    return g
+
+
+def _dev():
+    return torch.device("cuda:0")
+
+
+def _problem(n, m, p, seed, pad=0):
+    G = synth.bernoulli_sparse_normal(n, p + pad, 0.4, 1.0, seed=seed, device=_dev())[:, :p]
+    Gt = synth.bernoulli_sparse_normal(m, p + pad, 0.4, 1.0, seed=seed + 1, device=_dev())[:, :p]
+    S = synth.dense_normal(1, p, seed=seed + 2, device=_dev(), std=1.5).reshape(-1).contiguous()
+    return G, Gt, S
+
+
+@pytest.mark.parametrize("n,m,p,lam,temp,pad", [(9, 3, 7, 0.03, 1.0, 0), (50, 5, 333, 0.01, 1.0, 1),
+                                                (200, 130, 4096, 1e-3, 0.5, 0), (300, 140, 5002, 1e-4, 2.0, 2),
+                                                (130, 129, 70000, 1e-5, 1.0, 0)])
+def test_selective_mask_grad_parity(grass, n, m, p, lam, temp, pad):
+    G, Gt, S = _problem(n, m, p, seed=3000 + p, pad=pad)
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    grad, obj = grass.grass_selective_mask_grad(G, Gt, A, S, lam, temp)
+    torch.cuda.synchronize()
+    Gh, Gth, Sh = G.cpu().numpy(), Gt.cpu().numpy(), S.cpu().numpy()
+    want_obj = orc.selective_mask_objective(Sh, Gh, Gth, lam, temp)
+    want_grad = orc.selective_mask_gradient(Sh, Gh, Gth, lam, temp)
+    assert abs(float(obj.item()) - want_obj) <= 1e-5 * max(1.0, abs(want_obj))
+    got = grad.cpu().numpy().astype(np.float64)
+    assert np.abs(got - want_grad).max() <= 2e-4 * np.abs(want_grad).max()
+
+
+def test_selective_mask_grad_constant_logits_and_degenerate_rows(grass):
+    """Constant logits: corr = 1 for every test row, the objective is 1 - lambda p sigma.  A test row of zeros has
+    constant scores: it contributes nothing (the oracle would divide by zero, the library defines it as 0)."""
+    n, m, p, lam = 40, 6, 500, 0.002
+    G, Gt, _ = _problem(n, m, p, seed=3100)
+    S = torch.full((p,), 0.7, dtype=torch.float32, device=_dev())
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    _, obj = grass.grass_selective_mask_grad(G, Gt, A, S, lam)
+    torch.cuda.synchronize()
+    sig = 1 / (1 + np.exp(-0.7))
+    assert abs(float(obj.item()) - (1.0 - lam * p * sig)) <= 1e-5
+    Gt2 = Gt.clone(); Gt2[2] = 0.0
+    S2 = synth.dense_normal(1, p, seed=3101, device=_dev()).reshape(-1).contiguous()
+    A2 = grass.grass_score(G, Gt2, compute_mode=0)
+    grad, obj = grass.grass_selective_mask_grad(G, Gt2, A2, S2, lam)
+    torch.cuda.synchronize()
+    keep = [0, 1, 3, 4, 5]
+    Gh, Gth, Sh = G.cpu().numpy(), Gt2.cpu().numpy()[keep], S2.cpu().numpy()
+    # mean over 6 rows with one zero contribution = 5/6 of the mean over the 5 proper rows (penalty unchanged)
+    pen = lam * (1 / (1 + np.exp(-Sh.astype(np.float64)))).sum()
+    want_obj = (orc.selective_mask_objective(Sh, Gh, Gth, 0.0) * 5 / 6) - pen
+    assert abs(float(obj.item()) - want_obj) <= 1e-5
+    want_grad = orc.selective_mask_gradient(Sh, Gh, Gth, 0.0) * 5 / 6 + orc.selective_mask_gradient(Sh, Gh, Gth, lam) \
+        - orc.selective_mask_gradient(Sh, Gh, Gth, 0.0)
+    assert np.abs(grad.cpu().numpy() - want_grad).max() <= 2e-3 * np.abs(want_grad).max()
+    assert torch.isfinite(grad).all()
+
+
+def test_selective_mask_ascent_step_improves_the_objective(grass):
+    n, m, p, lam = 64, 16, 2048, 1e-4
+    G, Gt, S = _problem(n, m, p, seed=3200)
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    grad, obj0 = grass.grass_selective_mask_grad(G, Gt, A, S, lam)
+    step = 0.5 / float(grad.abs().max().item())
+    _, obj1 = grass.grass_selective_mask_grad(G, Gt, A, (S + step * grad).contiguous(), lam)
+    torch.cuda.synchronize()
+    assert float(obj1.item()) > float(obj0.item())
+
+
+@pytest.mark.parametrize("p,k", [(1, 0), (1, 1), (10, 0), (10, 3), (5000, 0), (5000, 1234), (100003, 0), (100003, 4096),
+                                 (100003, 100003)])
+def test_selective_mask_indices_bit_exact(grass, p, k):
+    S = synth.dense_normal(1, p, seed=3300 + p, device=_dev()).reshape(-1).contiguous()
+    S[::7] = 0.25                                   # ties
+    S[3::11] = 0.0
+    S[5::13] = -0.0
+    idx = grass.grass_selective_mask_indices(S, k)
+    torch.cuda.synchronize()
+    want = orc.selective_mask_indices(S.cpu().numpy(), None if k == 0 else k)
+    assert idx.dtype == torch.int32
+    assert np.array_equal(idx.cpu().numpy(), want)
+
+
+def test_selective_mask_indices_feed_the_fused_kernel(grass):
+    """The extracted indices are a mask like any other: GraSS with them equals the oracle's."""
+    n, p, k = 6, 20000, 256
+    G, _, S = _problem(n, 1, p, seed=3400)
+    idx = grass.grass_selective_mask_indices(S, 2048)
+    out = grass.grass_sjlt(G, k, 1, seed=0, stream_id=1, idx=idx)
+    torch.cuda.synchronize()
+    ref = orc.grass(G.cpu().numpy(), orc.selective_mask_indices(S.cpu().numpy(), 2048), k, 1, 0)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= 1e-5
+
+
+def test_selective_mask_argument_checks(grass):
+    G, Gt, S = _problem(8, 2, 16, seed=3500)
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_grad(G, Gt, A, S, -1.0)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_grad(G, Gt, A, S, 0.1, temperature=0.0)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_grad(G[:1], Gt, A[:, :1], S, 0.1)      # n = 1: no correlation
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_indices(S, 17)
