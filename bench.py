@@ -29,7 +29,7 @@ MFMA_PEAK_BF16_TFLOPS = 2500.0
 # HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a plain copy of known
 # size; see profiles/sjlt_fused_mlp_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": 21084114739}
+MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": 21088634880}
 
 
 def _timed(fn, steps, warmup, torch):
@@ -56,6 +56,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-extras", action="store_true", help="time the headline workload only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="SJLT (s = 1) against the dense Gaussian projection at p = 131,072 over target dimensions and "
+                         "input sparsity levels (the setting of the paper's SJLT benchmark figure); prints one JSON object")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -83,6 +86,35 @@ def main() -> int:
         t, _, _ = _timed(lambda: b.copy_(a), 5, 2, torch)
         print(json.dumps({"copy_reference_bytes_read": nbytes, "copy_reference_bytes_written": nbytes,
                           "ms": round(t / 5, 4), "GBps_read_plus_write": round(2 * nbytes / (t / 5 * 1e-3) / 1e9, 1)}))
+        return 0
+
+    if args.sweep:
+        ns, ps, seed = 1024, 131072, 0
+        rows = []
+        for zero_frac in (0.0, 0.5, 0.9, 0.99):
+            gs = synth.bernoulli_sparse_normal(ns, ps, zero_frac, 1.0, seed=1300, device=dev)
+            sub = gs[:256]
+            d_exact = torch.cdist(sub.double(), sub.double())
+            mask = ~torch.eye(256, dtype=torch.bool, device=dev)
+            for ks in (64, 256, 1024, 4096, 16384):
+                o = torch.empty((ns, ks), dtype=torch.float32, device=dev)
+                w = torch.empty(max(grass.grass_sjlt_workspace_bytes(ns, ps, 0, ks, 1), 1), dtype=torch.uint8, device=dev)
+                t, _, _ = _timed(lambda: grass.grass_sjlt(gs, ks, 1, seed, 1, out=o, ws=w), 20, 3, torch)
+                d = torch.cdist(o[:256].double(), o[:256].double())
+                err_s = float(((d[mask] / d_exact[mask]) - 1).abs().mean().item())
+                wg = torch.empty(grass.grass_gauss_project_workspace_bytes(ns, ps, ks, 32768), dtype=torch.uint8, device=dev)
+                tg, _, _ = _timed(lambda: grass.grass_gauss_project(gs, ks, seed, 2, 32768, compute_mode=0, out=o, ws=wg),
+                                  3, 1, torch)
+                d = torch.cdist(o[:256].double(), o[:256].double())
+                err_g = float(((d[mask] / d_exact[mask]) - 1).abs().mean().item())
+                rows.append({"zero_frac": zero_frac, "k": ks, "sjlt_ms": round(t / 20, 4), "gauss_fp32_ms": round(tg / 3, 3),
+                             "sjlt_rel_dist_err": round(err_s, 4), "gauss_rel_dist_err": round(err_g, 4)})
+                del o, w, wg
+            del gs
+            torch.cuda.empty_cache()
+        print(json.dumps({"sweep": "sjlt_vs_gaussian", "n": ns, "p": ps, "s": 1,
+                          "note": "Gaussian time includes generating P chunk by chunk; errors are the mean relative "
+                                  "pairwise-distance error over the first 256 rows", "rows": rows}))
         return 0
 
     # ------------------------------------------------------------ headline
@@ -259,6 +291,32 @@ def main() -> int:
         w1 = torch.empty(max(grass.grass_sjlt_workspace_bytes(64, 65536, 8192, 1024, 1), 1), dtype=torch.uint8, device=dev)
         t, _, _ = _timed(lambda: grass.grass_sjlt(g1, 1024, 1, seed, 1, idx=i1, out=o1, ws=w1), 50, 5, torch)
         extras["tiny_mask_sjlt"] = {"ms": round(t / 50, 4), "samples_per_s": round(64 / (t / 50 * 1e-3), 1)}
+        # the same call over a rotating set of 40 input buffers (671 MB > the 256 MB last-level cache), so that the
+        # 16.8 MB input does not stay cache-resident between launches
+        ring = [synth.bernoulli_sparse_normal(64, 65536, 0.8, 1.0, seed=1100 + i, device=dev) for i in range(40)]
+        turn = [0]
+
+        def tiny_rotating():
+            grass.grass_sjlt(ring[turn[0] % 40], 1024, 1, seed, 1, idx=i1, out=o1, ws=w1)
+            turn[0] += 1
+        t, _, _ = _timed(tiny_rotating, 80, 40, torch)
+        extras["tiny_mask_sjlt_rotating_inputs"] = {"ms": round(t / 80, 4), "samples_per_s": round(64 / (t / 80 * 1e-3), 1),
+                                                    "buffers": 40}
+        del ring
+
+        # reference points measured in the same process: a plain 1 GiB device copy and a square bf16 GEMM from the
+        # vendor library (context for the roofline fractions, not part of the library)
+        ca = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        cb = torch.empty_like(ca)
+        t, _, _ = _timed(lambda: cb.copy_(ca), 5, 2, torch)
+        extras["reference_device_copy"] = {"GBps_read_plus_write": round(2 * (1 << 30) / (t / 5 * 1e-3) / 1e9, 1)}
+        del ca, cb
+        ma = synth.dense_normal(8192, 8192, seed=1200, device=dev).to(torch.bfloat16)
+        mb = synth.dense_normal(8192, 8192, seed=1201, device=dev).to(torch.bfloat16)
+        t, _, _ = _timed(lambda: torch.matmul(ma, mb.t()), 5, 2, torch)
+        extras["reference_vendor_bf16_gemm_8192"] = {"TFLOPs": round(2.0 * 8192 ** 3 / (t / 5 * 1e-3) / 1e12, 1)}
+        del ma, mb
+        torch.cuda.empty_cache()
 
         # score GEMM, one layer block of compressed gradients
         N5, M5, K5 = 65536, 1024, 4096
