@@ -177,6 +177,11 @@ def main() -> int:
         ws4 = torch.empty(max(grass.grass_sjlt_workspace_bytes(n, p, kp, k, 4), 1), dtype=torch.uint8, device=dev)
         t, _, _ = _timed(lambda: grass.grass_sjlt(g, k, 4, seed, 1, idx=idx, out=out, ws=ws4), st, 2, torch)
         extras["mlp_mask_sjlt_s4"] = {"ms": round(t / st, 4), "samples_per_s": round(n / (t / st * 1e-3), 1)}
+        # the same batch stored as bf16 (half the lines: 64 columns per 128-byte line)
+        g16 = g.to(torch.bfloat16)
+        t, _, _ = _timed(lambda: grass.grass_sjlt_bf16(g16, k, s, seed, 1, idx=idx, out=out, ws=ws), st, 2, torch)
+        extras["mlp_mask_sjlt_s1_bf16_input"] = {"ms": round(t / st, 4), "samples_per_s": round(n / (t / st * 1e-3), 1)}
+        del g16
         # plain gather
         gm = torch.empty((n, kp), dtype=torch.float32, device=dev)
         t, _, _ = _timed(lambda: grass.grass_mask(g, idx, out=gm), st, 2, torch)
@@ -212,7 +217,13 @@ def main() -> int:
         gbps = n3 * (4 * p3 + 4 * k3) / (t / 10 * 1e-3) / 1e9
         extras["resnet_sjlt_s1"] = {"ms": round(t / 10, 4), "samples_per_s": round(n3 / (t / 10 * 1e-3), 1),
                                     "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
-        del g3, o3, w3
+        g3h = g3.to(torch.bfloat16)
+        del g3
+        t, _, _ = _timed(lambda: grass.grass_sjlt_bf16(g3h, k3, 1, seed, 1, out=o3, ws=w3), 10, 2, torch)
+        gbps = n3 * (2 * p3 + 4 * k3) / (t / 10 * 1e-3) / 1e9
+        extras["resnet_sjlt_s1_bf16_input"] = {"ms": round(t / 10, 4), "samples_per_s": round(n3 / (t / 10 * 1e-3), 1),
+                                               "algorithmic_GBps": round(gbps, 1)}
+        del g3h, o3, w3
         torch.cuda.empty_cache()
 
         # FactGraSS on one 4096 x 4096 linear layer

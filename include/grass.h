@@ -107,6 +107,16 @@ grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
                         uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
                         float* out, uint64_t ldo,
                         void* ws, size_t ws_bytes, grass_stream stream);
+/* The same operation on gradients stored as bf16 (n x p 16-bit words, ldg in
+ * elements, 2-byte aligned): every value is used exactly (a bf16 is the upper
+ * half of an fp32), accumulation and output are as in grass_sjlt.  Workspace:
+ * grass_sjlt_workspace_bytes.  Fastest when rows are 16-byte aligned
+ * (ldg % 8 == 0) or the batch has enough rows to be grouped by alignment.     */
+grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg,
+                             const int32_t* idx, uint32_t kprime,
+                             uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                             float* out, uint64_t ldo,
+                             void* ws, size_t ws_bytes, grass_stream stream);
 
 /* ------------------------------------------------------------------ FactGraSS
  * Sec. 3.3.2 "Factorized GraSS" for one linear layer, using Eq. (2)/(3):

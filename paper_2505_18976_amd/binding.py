@@ -39,6 +39,7 @@ SIGNATURES = {
     "grass_sjlt_tables": (_int, [_u64, _u64, _u64, _u32, _u32, _vp, _vp, _vp]),
     "grass_sjlt_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
     "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
+    "grass_sjlt_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
     "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
                                 _vp, _u64, _vp, _sz, _vp]),
@@ -187,6 +188,22 @@ def grass_sjlt(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, i
     _check(load_library().grass_sjlt(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
                                      _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
            "grass_sjlt")
+    return out
+
+
+def grass_sjlt_bf16(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, idx: torch.Tensor | None = None,
+                    out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """grass_sjlt on gradients stored as bf16 (fp32 accumulation and output)."""
+    assert g.dtype == torch.bfloat16
+    n, p = g.shape
+    kprime = 0 if idx is None else idx.numel()
+    if out is None:
+        out = torch.empty((n, k), dtype=torch.float32, device=g.device)
+    if ws is None:
+        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s), g.device)
+    _check(load_library().grass_sjlt_bf16(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
+                                          _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "grass_sjlt_bf16")
     return out
 
 

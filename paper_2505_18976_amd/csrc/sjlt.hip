@@ -41,7 +41,7 @@ template <int ACC> struct AccT { using type = float; };
 template <> struct AccT<ACC_F64> { using type = double; };
 
 struct SjltArgs {
-    const float* g;
+    const void* g;        // fp32 or bf16 words, see the kernel's element type
     const int32_t* idx;   // nullptr: positions are columns
     float* dst;           // out (direct) or partial workspace
     uint64_t ldg;
@@ -105,19 +105,27 @@ __device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, 
     }
 }
 
-typedef float f32x2 __attribute__((ext_vector_type(2)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-template <int V> struct VecT;
-template <> struct VecT<1> { using type = float; };
-template <> struct VecT<2> { using type = f32x2; };
-template <> struct VecT<4> { using type = f32x4; };
+// Input element types: fp32, or bf16 handed over as raw 16-bit words (exact in fp32: the word is the upper half).
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr uint32_t per_line = 32;                       // elements per 128-byte line
+    static __device__ __forceinline__ float f(float v) { return v; }
+};
+template <> struct Elem<uint16_t> {
+    static constexpr uint32_t per_line = 64;
+    static __device__ __forceinline__ float f(uint16_t v) { return __uint_as_float((uint32_t)v << 16); }
+};
+template <typename T, int V> struct VecT { typedef T type __attribute__((ext_vector_type(V))); };
+template <typename T> struct VecT<T, 1> { using type = T; };
 
-template <int V>
-__device__ __forceinline__ void unpack(const typename VecT<V>::type& x, float* o);
-template <> __device__ __forceinline__ void unpack<1>(const float& x, float* o) { o[0] = x; }
-template <> __device__ __forceinline__ void unpack<2>(const f32x2& x, float* o) { o[0] = x.x; o[1] = x.y; }
-template <> __device__ __forceinline__ void unpack<4>(const f32x4& x, float* o) {
-    o[0] = x.x; o[1] = x.y; o[2] = x.z; o[3] = x.w;
+template <typename T, int V>
+__device__ __forceinline__ void unpack(const typename VecT<T, V>::type& x, float* o) {
+    if constexpr (V == 1) {
+        o[0] = Elem<T>::f(x);
+    } else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) o[i] = Elem<T>::f(x[i]);
+    }
 }
 
 // The gradient matrix is read exactly once: non-temporal loads keep it from
@@ -127,7 +135,7 @@ __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontempo
 
 // R rows per workgroup, V positions per load (unmasked only), U loads in flight
 // per row and thread.
-template <int R, int V, int U, bool MASKED, int ACC, bool FAST>
+template <typename T, int R, int V, int U, bool MASKED, int ACC, bool FAST>
 __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
     using acc_t = typename AccT<ACC>::type;
     extern __shared__ __align__(16) unsigned char smem[];
@@ -145,9 +153,10 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
 
     const uint64_t begin = (uint64_t)blockIdx.y * a.pos_per_chunk;
     const uint64_t end = (begin + a.pos_per_chunk < a.d) ? begin + a.pos_per_chunk : a.d;
-    const float* rowp[R];
+    const T* rowp[R];
 #pragma unroll
-    for (int r = 0; r < R; ++r) rowp[r] = a.g + (row0 + (r < nrows ? (uint64_t)r * P : 0)) * a.ldg;
+    for (int r = 0; r < R; ++r)
+        rowp[r] = static_cast<const T*>(a.g) + (row0 + (r < nrows ? (uint64_t)r * P : 0)) * a.ldg;
 
     const uint64_t zpos = (uint64_t)a.s * kGamma;             // generator-state distance between positions
 
@@ -168,22 +177,23 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             for (int u = 0; u < U; ++u) {
 #pragma unroll
                 for (int r = 0; r < R; ++r)
-                    v[u][r] = (col[u] >= 0 && r < nrows) ? stream_load(rowp[r] + col[u]) : 0.0f;
+                    v[u][r] = (col[u] >= 0 && r < nrows) ? Elem<T>::f(stream_load(rowp[r] + col[u])) : 0.0f;
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) scatter_position<R, ACC, FAST>(acc, v[u], z + zstep * u, a);
         }
     } else {
-        using VT = typename VecT<V>::type;
+        using VT = typename VecT<T, V>::type;
+        constexpr uint32_t E = Elem<T>::per_line;
         // vector range [vbeg, vend): the chunk shifted to the first 128-byte line of these rows
         uint64_t lead = 0;
-        if (a.align_lines) lead = (32 - (uint32_t)((reinterpret_cast<uintptr_t>(rowp[0]) >> 2) & 31)) & 31;
+        if (a.align_lines) lead = (E - (uint32_t)((reinterpret_cast<uintptr_t>(rowp[0]) / sizeof(T)) & (E - 1))) & (E - 1);
         const uint64_t vbeg = begin + lead < a.d ? begin + lead : a.d;
         const uint64_t vend = end + lead < a.d ? end + lead : a.d;          // the last chunk has end == d
-        if (blockIdx.y == 0 && threadIdx.x < lead && threadIdx.x < a.d) {   // fewer than 32 leading positions
+        if (blockIdx.y == 0 && threadIdx.x < lead && threadIdx.x < a.d) {   // fewer than a line of leading positions
             float v[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) v[r] = r < nrows ? rowp[r][threadIdx.x] : 0.0f;
+            for (int r = 0; r < R; ++r) v[r] = r < nrows ? Elem<T>::f(rowp[r][threadIdx.x]) : 0.0f;
             scatter_position<R, ACC, FAST>(acc, v, a.sub + ((uint64_t)threadIdx.x * a.s + 1) * kGamma, a);
         }
         const uint64_t nvec = (vend - vbeg) / V;
@@ -200,14 +210,14 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     if (vi < nvec && r < nrows)
                         x[u][r] = stream_load(reinterpret_cast<const VT*>(rowp[r] + vbeg + vi * V));
                     else
-                        x[u][r] = VT(0.0f);
+                        x[u][r] = VT{};
                 }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 float e[R][V];
 #pragma unroll
-                for (int r = 0; r < R; ++r) unpack<V>(x[u][r], e[r]);
+                for (int r = 0; r < R; ++r) unpack<T, V>(x[u][r], e[r]);
 #pragma unroll
                 for (int c = 0; c < V; ++c) {
                     float v[R];
@@ -222,7 +232,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
         if (tail < vend) {
             float v[R];
 #pragma unroll
-            for (int r = 0; r < R; ++r) v[r] = r < nrows ? rowp[r][tail] : 0.0f;
+            for (int r = 0; r < R; ++r) v[r] = r < nrows ? Elem<T>::f(rowp[r][tail]) : 0.0f;
             scatter_position<R, ACC, FAST>(acc, v, a.sub + (tail * a.s + 1) * kGamma, a);
         }
     }
@@ -247,8 +257,9 @@ struct SjltPlan {
 
 // force_v != 0 (workspace query, where the alignment of g is unknown): consecutive rows and that vector width;
 // consecutive rows give the fewest row groups and so the most chunks, an upper bound for every layout.
-static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const float* g, uint64_t ldg,
-                      SjltPlan* pl, int force_v = 0) {
+// in_bytes: 4 (fp32 input) or 2 (bf16 input).
+static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const void* g, uint64_t ldg,
+                      SjltPlan* pl, int force_v = 0, uint32_t in_bytes = 4) {
     if ((size_t)k * 4 > 128 * 1024) return false;
     int acc = ACC_F64;
     if ((size_t)k * 8 > 128 * 1024) acc = ACC_CAS;            // fp64 buckets of one row no longer fit
@@ -272,13 +283,14 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const flo
         V = force_v;
     } else if (!masked) {
         // rows P apart start at the same offset inside a 128-byte line; group them if there are enough rows
-        uint32_t r32 = (uint32_t)(ldg % 32), gcd = 32;
-        while (r32 % gcd != 0) gcd >>= 1;                     // gcd(ld mod 32, 32); 32 when ld mod 32 == 0
-        const uint32_t period = 32 / gcd;
+        const uint32_t E = 128 / in_bytes, vmax = 16 / in_bytes;   // elements per line, per 16-byte load
+        uint32_t rem = (uint32_t)(ldg % E), gcd = E;
+        while (rem % gcd != 0) gcd >>= 1;                     // gcd(ld mod E, E); E when ld mod E == 0
+        const uint32_t period = E / gcd;
         if (period == 1 || n >= 4ull * period * R) {
-            P = period; V = 4; align_lines = true;
-        } else if (aligned(g, 16) && ldg % 4 == 0) V = 4;
-        else if (aligned(g, 8) && ldg % 2 == 0) V = 2;
+            P = period; V = (int)vmax; align_lines = true;
+        } else if (aligned(g, 16) && ldg % vmax == 0) V = (int)vmax;
+        else if (in_bytes == 4 && aligned(g, 8) && ldg % 2 == 0) V = 2;
     }
     const uint64_t row_groups = ceil_div(n, (uint64_t)P * R) * P;
     // chunks: enough workgroups to fill the chip, but keep the partial-sum
@@ -306,9 +318,9 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const flo
     return true;
 }
 
-template <int R, int V, int U, bool MASKED, int ACC, bool FAST>
+template <typename T, int R, int V, int U, bool MASKED, int ACC, bool FAST>
 static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
-    auto kern = sjlt_kernel<R, V, U, MASKED, ACC, FAST>;
+    auto kern = sjlt_kernel<T, R, V, U, MASKED, ACC, FAST>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -321,21 +333,36 @@ static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t 
     return hipGetLastError();
 }
 
-template <int R, int ACC, bool FAST>
+template <typename T, int R, int ACC, bool FAST>
 static hipError_t launch_raf(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
-    if (masked) return launch_one<R, 1, (R >= 8 ? 2 : 4), true, ACC, FAST>(a, pl, st);
-    switch (pl.V) {
-        case 4: return launch_one<R, 4, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
-        case 2: return launch_one<R, 2, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
-        default: return launch_one<R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
+    if (masked) return launch_one<T, R, 1, (R >= 8 ? 2 : 4), true, ACC, FAST>(a, pl, st);
+    if constexpr (sizeof(T) == 4) {
+        switch (pl.V) {
+            case 4: return launch_one<T, R, 4, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
+            case 2: return launch_one<T, R, 2, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
+            default: return launch_one<T, R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
+        }
+    } else {
+        if (pl.V == 8) return launch_one<T, R, 8, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
+        return launch_one<T, R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
     }
 }
 
-template <int R>
+template <typename T, int R>
 static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, bool fast, hipStream_t st) {
     if (pl.acc == ACC_CAS)
-        return fast ? launch_raf<R, ACC_CAS, true>(a, pl, masked, st) : launch_raf<R, ACC_CAS, false>(a, pl, masked, st);
-    return fast ? launch_raf<R, ACC_F64, true>(a, pl, masked, st) : launch_raf<R, ACC_F64, false>(a, pl, masked, st);
+        return fast ? launch_raf<T, R, ACC_CAS, true>(a, pl, masked, st) : launch_raf<T, R, ACC_CAS, false>(a, pl, masked, st);
+    return fast ? launch_raf<T, R, ACC_F64, true>(a, pl, masked, st) : launch_raf<T, R, ACC_F64, false>(a, pl, masked, st);
+}
+
+template <typename T>
+static hipError_t launch_t(const SjltArgs& a, const SjltPlan& pl, bool masked, bool fast, hipStream_t st) {
+    switch (pl.R) {
+        case 8: return launch_r<T, 8>(a, pl, masked, fast, st);
+        case 4: return launch_r<T, 4>(a, pl, masked, fast, st);
+        case 2: return launch_r<T, 2>(a, pl, masked, fast, st);
+        default: return launch_r<T, 1>(a, pl, masked, fast, st);
+    }
 }
 
 }  // namespace grass
@@ -377,18 +404,18 @@ extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint3
     return GRASS_OK;
 }
 
-extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
-                                   uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
-                                   float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
+                             uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id, float* out,
+                             uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
     const bool masked = idx != nullptr;
     grass_status st = check_sjlt_dims(n, p, masked, kprime, k, s);
     if (st != GRASS_OK) return st;
     if (n == 0) return GRASS_OK;
-    if (!g || !out || ldg < p || ldo < k || !aligned(g, 4) || !aligned(out, 4)) return GRASS_EINVAL;
+    if (!g || !out || ldg < p || ldo < k || !aligned(g, in_bytes) || !aligned(out, 4)) return GRASS_EINVAL;
     if (n * ldg >= (1ull << 62)) return GRASS_EINVAL;
     const uint64_t d = masked ? kprime : p;
     SjltPlan pl;
-    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl, 0, in_bytes)) return GRASS_EUNSUPPORTED;
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
 
     SjltArgs a;
@@ -413,13 +440,7 @@ extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint6
         a.dst = static_cast<float*>(ws); a.ld_dst = k; a.chunk_stride = n * k; a.scale = 1.0f;
     }
     hipStream_t hs = as_stream(stream);
-    hipError_t e;
-    switch (pl.R) {
-        case 8: e = launch_r<8>(a, pl, masked, fast, hs); break;
-        case 4: e = launch_r<4>(a, pl, masked, fast, hs); break;
-        case 2: e = launch_r<2>(a, pl, masked, fast, hs); break;
-        default: e = launch_r<1>(a, pl, masked, fast, hs); break;
-    }
+    const hipError_t e = in_bytes == 4 ? launch_t<float>(a, pl, masked, fast, hs) : launch_t<uint16_t>(a, pl, masked, fast, hs);
     if (e != hipSuccess) return GRASS_EHIP;
     if (pl.chunks > 1) {
         const uint64_t total = n * k;
@@ -428,4 +449,16 @@ extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint6
         if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
     }
     return GRASS_OK;
+}
+
+extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
+                                   uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                                   float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+    return run_sjlt(g, 4, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, stream);
+}
+
+extern "C" grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
+                                        uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                                        float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+    return run_sjlt(g, 2, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, stream);
 }

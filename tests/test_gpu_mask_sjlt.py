@@ -139,6 +139,42 @@ def test_sjlt_line_aligned_row_groups(grass, n, d, pad, off, k, s):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
+# bf16 gradients: 64 elements per 128-byte line, 8 per 16-byte load; row periods 64 ... 1, consecutive-row fallbacks
+BF16_CASES = [
+    # n, d, pad, off, k, s, k' (0 = unmasked)
+    (3, 5, 0, 0, 8, 2, 0),
+    (2100, 1001, 0, 0, 64, 1, 0),         # ld mod 64 = 41: P = 64, 8 rows per group
+    (600, 2050, 0, 0, 2048, 2, 0),        # ld mod 64 = 2: P = 32
+    (70, 4104, 0, 0, 8192, 1, 0),         # ld mod 64 = 8: P = 8, 2 rows per group
+    (40, 3000, 69, 3, 512, 4, 0),         # ld = 3072: P = 1, base 6 bytes into a line
+    (9, 128, 0, 0, 16, 1, 0),
+    (4, 10, 115, 3, 8, 1, 0),             # fewer positions than the lead-in
+    (5, 24, 0, 0, 8, 1, 0),               # too few rows to group, rows 16-byte aligned: 8-element loads
+    (5, 21, 0, 0, 8, 1, 0),               # ... and not aligned: scalar loads
+    (33, 70001, 31, 0, 1024, 1, 0),
+    (7, 3000, 0, 0, 64, 2, 500),          # fused mask
+    (64, 65536, 0, 0, 1024, 1, 8192),
+    (10, 100003, 0, 0, 4096, 4, 9973),
+]
+
+
+@pytest.mark.parametrize("n,d,pad,off,k,s,kp", BF16_CASES)
+def test_sjlt_bf16_inputs(grass, n, d, pad, off, k, s, kp):
+    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
+    full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=24, device=_dev()).to(torch.bfloat16)
+    g = full[:, off:off + d]
+    exact = g.float().cpu().numpy()                              # bf16 values are exact in fp32
+    if kp:
+        idx = grass.grass_mask_indices(2, 0, d, kp, device=_dev())
+        out = grass.grass_sjlt_bf16(g, k, s, seed=3, stream_id=1, idx=idx)
+        ref = orc.grass(exact, orc.mask_indices(2, 0, d, kp), k, s, 3)
+    else:
+        out = grass.grass_sjlt_bf16(g, k, s, seed=3, stream_id=1)
+        ref = orc.sjlt(exact, k, s, 3, 1)
+    torch.cuda.synchronize()
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+
+
 @pytest.mark.parametrize("rows,chunks,threads,acc", [(1, 1, 256, 0), (2, 3, 512, 1), (4, 7, 1024, 2), (8, 2, 256, 3),
                                                      (8, 1, 1024, 2), (4, 1, 512, 1), (2, 5, 1024, 3)])
 def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
