@@ -74,6 +74,26 @@ def test_factgrass_parity(grass, n, T, d_in, d_out, ka, kb, k, s, layer):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_FACT
 
 
+def test_factgrass_random_shapes(grass):
+    """30 seeded random layers: tokens, widths, mask sizes (1..128), k and s vary, including non-multiples of every tile."""
+    grass.grass_set_factgrass_tuning(0)
+    rng = np.random.default_rng(777)
+    for case in range(30):
+        n, T = int(rng.integers(1, 6)), int(rng.integers(1, 300))
+        d_in, d_out = int(rng.integers(1, 700)), int(rng.integers(1, 700))
+        ka, kb = int(rng.integers(1, min(d_in, 128) + 1)), int(rng.integers(1, min(d_out, 128) + 1))
+        s = int(rng.choice([1, 1, 2, 4]))
+        k = s * int(rng.choice([1, 5, 64, 1000, 4096]))
+        x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=7000 + case, device=_dev())
+        ii = grass.grass_mask_indices(case, 16, d_in, ka, device=_dev())
+        io = grass.grass_mask_indices(case, 17, d_out, kb, device=_dev())
+        out = grass.factgrass_linear(x, g, ii, io, k, s, case, 18)
+        torch.cuda.synchronize()
+        ref = orc.factgrass_linear(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy(), k, s, case, 18)
+        err = orc.max_rel_err(out.cpu().numpy(), ref)
+        assert err <= TOL_FACT, (case, n, T, d_in, d_out, ka, kb, k, s, err)
+
+
 @pytest.mark.parametrize("tokens", [32, 64, 4096])
 def test_factgrass_token_chunking(grass, tokens):
     n, T, d_in, d_out, ka, kb, k = 3, 150, 256, 256, 64, 64, 1024

@@ -175,6 +175,39 @@ def test_sjlt_bf16_inputs(grass, n, d, pad, off, k, s, kp):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
+def test_sjlt_random_shapes_and_alignments(grass):
+    """60 seeded random problems: shape, leading dimension, view offset, element type, mask, k and s all vary, so that
+    every row period, lead-in length, vector width and chunk count of the planner is hit by something."""
+    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
+    rng = np.random.default_rng(12345)
+    for case in range(60):
+        bf16 = bool(rng.integers(2))
+        n = int(rng.choice([1, 2, 7, 33, 150, 700, 2200]))
+        d = int(rng.integers(1, 6000)) if n > 100 else int(rng.integers(1, 90000))
+        off, pad = int(rng.integers(0, 9)), int(rng.integers(0, 70))
+        s = int(rng.choice([1, 1, 2, 4]))
+        k = s * int(rng.choice([1, 3, 16, 250, 1024, 4096]))
+        masked = bool(rng.integers(3) == 0)
+        full = synth.bernoulli_sparse_normal(n, off + d + pad, float(rng.choice([0.0, 0.5, 0.95])), 1.0,
+                                             seed=5000 + case, device=_dev())
+        if bf16:
+            full = full.to(torch.bfloat16)
+        g = full[:, off:off + d]
+        exact = g.float().cpu().numpy()
+        fn = grass.grass_sjlt_bf16 if bf16 else grass.grass_sjlt
+        if masked:
+            kp = int(rng.integers(1, d + 1))
+            idx = grass.grass_mask_indices(case, 0, d, kp, device=_dev())
+            out = fn(g, k, s, seed=case, stream_id=1, idx=idx)
+            ref = orc.grass(exact, orc.mask_indices(case, 0, d, kp), k, s, case)
+        else:
+            out = fn(g, k, s, seed=case, stream_id=1)
+            ref = orc.sjlt(exact, k, s, case, 1)
+        torch.cuda.synchronize()
+        err = orc.max_rel_err(out.cpu().numpy(), ref)
+        assert err <= TOL_SJLT, (case, bf16, n, d, off, pad, k, s, masked, err)
+
+
 @pytest.mark.parametrize("rows,chunks,threads,acc", [(1, 1, 256, 0), (2, 3, 512, 1), (4, 7, 1024, 2), (8, 2, 256, 3),
                                                      (8, 1, 1024, 2), (4, 1, 512, 1), (2, 5, 1024, 3)])
 def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
