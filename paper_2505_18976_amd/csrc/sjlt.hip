@@ -270,11 +270,16 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     while (R > 1 && (size_t)R * k * esz > 128 * 1024) R >>= 1;
     // no point holding more rows than there are samples
     while (R > 1 && (uint64_t)R > n) R >>= 1;
+    // short rows (a few iterations of one workgroup): the launch is latency-bound, so one chunk (no second
+    // kernel for the partial sums) and fewer rows per workgroup until there are 32 workgroups
+    const bool short_rows = d <= 32768;
+    if (short_rows) while (R > 1 && ceil_div(n, R) < 32) R >>= 1;
     if (g_tune_rows == 1 || g_tune_rows == 2 || g_tune_rows == 4 || g_tune_rows == 8) {
         if ((size_t)g_tune_rows * k * esz <= kLdsBytes) R = g_tune_rows;
     }
     int threads = 1024;
     if ((size_t)R * k * esz <= 64 * 1024) threads = 512;      // two or more groups per CU anyway
+    if (short_rows && ceil_div(n, R) <= (uint64_t)kNumCU) threads = 1024;   // one workgroup per CU at most: widest
     if (g_tune_threads == 256 || g_tune_threads == 512 || g_tune_threads == 1024) threads = g_tune_threads;
     int V = 1;
     uint32_t P = 1;
@@ -303,6 +308,7 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     uint64_t chunks = ceil_div(2 * kNumCU, row_groups);
     if (chunks > max_chunks_work) chunks = max_chunks_work;
     if (chunks > max_chunks_traffic) chunks = max_chunks_traffic;
+    if (short_rows) chunks = 1;
     if (g_tune_chunks > 0) chunks = g_tune_chunks;
     if (chunks > 65535) chunks = 65535;
     uint64_t ppc = ceil_div(d, chunks);
