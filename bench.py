@@ -247,7 +247,16 @@ def main() -> int:
         extras["logra_linear_4096"] = {"ms": round(tl / 20, 4), "tokens_per_s": round(n4 * T4 / (tl / 20 * 1e-3), 1),
                                        "algorithmic_GBps": round(2 * n4 * T4 * d4 * 2 / (tl / 20 * 1e-3) / 1e9, 1),
                                        "factgrass_speedup": round((tl / 20) / extras["factgrass_linear_4096"]["ms"], 2)}
-        del x4, go4, o4, w4, Pi, Po, ol, wl
+        # the other factorised compressors of the paper's Table 2 on the same layer (64 x 64 -> 4,096 outputs)
+        wm = torch.empty(max(grass.factmask_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
+        tm, _, _ = _timed(lambda: grass.factmask_linear(x4, go4, ii, io, out=ol, ws=wm), 20, 3, torch)
+        Si = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 40, d4, kf, 1, device=dev))
+        So = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 41, d4, kf, 1, device=dev))
+        ts, _, _ = _timed(lambda: grass.logra_linear(x4, go4, Si, So, out=ol, ws=wl), 20, 3, torch)
+        extras["table2_style_4096_layer_ms"] = {"mask_kin_x_kout": round(tm / 20, 4), "sjlt_kin_x_kout": round(ts / 20, 4),
+                                                "factgrass": extras["factgrass_linear_4096"]["ms"],
+                                                "logra_gauss_kin_x_kout": round(tl / 20, 4)}
+        del x4, go4, o4, w4, Pi, Po, ol, wl, wm, Si, So
 
         # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
         # every layer with its own activations and gradients (12.3 GB in total, so nothing is served from

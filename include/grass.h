@@ -288,6 +288,36 @@ grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* ho
 grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
                                           uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream);
 
+/* ------------------------------------------- factorised baselines of Table 2
+ * Sec. 3.3.2 ("Bottlenecks of integrating GraSS with LoGra"): the dense factor
+ * projections of LoGra can be replaced by other compressors, giving
+ * Mask_{k_in x k_out}, SJLT_{k_in x k_out} and GraSS_{k_in x k_out}.
+ *
+ * factmask_linear: Mask_{k_in x k_out}, i.e. stages 1 and 2 of factgrass_linear
+ * without the sparse projection: out_i[a*k_out' + b] = sum_t x_t[idx_in[a]] *
+ * g_t[idx_out[b]]; out is n x (k_in'*k_out') fp32, ldo >= k_in'*k_out'.  Arguments
+ * as in factgrass_linear.
+ *
+ * grass_projection_matrix: the compressor as an explicit dense matrix P (k x p
+ * fp32, ldP >= p, fully overwritten): idx == NULL -> the SJLT matrix of
+ * grass_sjlt (s non-zeros +-1/sqrt(s) per column); idx != NULL -> the GraSS
+ * matrix SJLT_k * Mask_k' (non-zeros only in the kept columns).  Handing two such
+ * matrices (converted with grass_to_bf16; exact for s = 1, 4, 16) to
+ * logra_linear gives SJLT_{k_in x k_out} or GraSS_{k_in x k_out}: at factor sizes
+ * k_in, k_out <= 64 the dense matrix-core product is the fast way to apply a
+ * sparse projection on this chip.  Also a debugging aid (P g == grass_sjlt(g)). */
+grass_status factmask_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
+                                             size_t* host_bytes);
+grass_status factmask_linear(const void* x, const void* gout,
+                             uint64_t n, uint64_t T, uint32_t d_in, uint32_t d_out,
+                             const int32_t* idx_in, uint32_t kin_p,
+                             const int32_t* idx_out, uint32_t kout_p,
+                             float* out, uint64_t ldo,
+                             void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_id, uint64_t p,
+                                     const int32_t* idx, uint32_t kprime,
+                                     uint32_t k, uint32_t s, float* P, uint64_t ldP, grass_stream stream);
+
 /* ------------------------------------------------------------------- tuning
  * Overrides the launch heuristics of grass_sjlt for experiments: rows per
  * block (1,2,4,8), column chunks per row group, threads per block

@@ -186,6 +186,23 @@ def grass(g: np.ndarray, idx: np.ndarray, k: int, s: int, seed: int,
 
 
 # ----------------------------------------------------------------------------
+# The compressors as explicit matrices (Sec. 3.1: P has s non-zeros +-1/sqrt(s)
+# per column; Sec. 3.3.1: GraSS is the product of that matrix and the binary
+# selection matrix of the mask).  Used for the factorised baselines of
+# Sec. 3.3.2, where P_in and P_out of Eq. (3) may be any compressor.
+# ----------------------------------------------------------------------------
+def projection_matrix(seed: int, stream: int, p: int, k: int, s: int, idx=None) -> np.ndarray:
+    """k x p matrix P with P g = sjlt(g) (idx None) or P g = grass(g, idx)."""
+    cols = np.arange(p) if idx is None else np.asarray(idx, dtype=np.int64)
+    bucket, sign = sjlt_tables(seed, stream, cols.size, k, s)
+    P = np.zeros((k, p), dtype=np.float64)
+    for jp in range(cols.size):
+        for r in range(s):
+            P[int(bucket[jp, r]), int(cols[jp])] += float(sign[jp, r]) / np.sqrt(float(s))
+    return P
+
+
+# ----------------------------------------------------------------------------
 # FactGraSS (Sec. 3.3.2, "Factorized GraSS"; Eq. (2), Eq. (3)).
 # ----------------------------------------------------------------------------
 def factgrass_sparsified_gradient(x: np.ndarray, gout: np.ndarray,

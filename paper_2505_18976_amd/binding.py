@@ -64,6 +64,9 @@ SIGNATURES = {
                                          ctypes.c_double, _vp, _vp, _vp, _sz, _vp]),
     "grass_selective_mask_indices_workspace_bytes": (_int, [_u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_indices": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _sz, _vp]),
+    "factmask_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
+    "factmask_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
+    "grass_projection_matrix": (_int, [_u64, _u64, _u64, _vp, _u32, _u32, _u32, _vp, _u64, _vp]),
     "grass_set_sjlt_tuning": (None, [_int, _int, _int, _int]),
     "grass_set_factgrass_tuning": (None, [_int]),
 }
@@ -445,6 +448,41 @@ def grass_selective_mask_indices(S: torch.Tensor, k: int = 0) -> torch.Tensor:
     _check(load_library().grass_selective_mask_indices(_ptr(S), p, k, _ptr(idx), _ptr(count), _ptr(ws), ws.numel(),
                                                        _stream()), "grass_selective_mask_indices")
     return idx[: int(count.item())] if k == 0 else idx
+
+
+def factmask_linear_workspace_bytes(n: int, T: int, kin_p: int, kout_p: int) -> int:
+    out = _sz(0)
+    _check(load_library().factmask_linear_workspace_bytes(n, T, kin_p, kout_p, ctypes.byref(out)),
+           "factmask_linear_workspace_bytes")
+    return out.value
+
+
+def factmask_linear(x: torch.Tensor, gout: torch.Tensor, idx_in: torch.Tensor, idx_out: torch.Tensor,
+                    out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+    """Mask_{k_in x k_out}: sum_t x_t[idx_in] (x) g_t[idx_out], flat index a*k_out' + b."""
+    assert x.dtype == torch.bfloat16 and gout.dtype == torch.bfloat16
+    assert x.is_contiguous() and gout.is_contiguous()
+    n, T, d_in = x.shape
+    d_out = gout.shape[2]
+    ka, kb = idx_in.numel(), idx_out.numel()
+    if out is None:
+        out = torch.empty((n, ka * kb), dtype=torch.float32, device=x.device)
+    if ws is None:
+        ws = _workspace(factmask_linear_workspace_bytes(n, T, ka, kb), x.device)
+    _check(load_library().factmask_linear(_ptr(x), _ptr(gout), n, T, d_in, d_out, _ptr(idx_in), ka, _ptr(idx_out), kb,
+                                          _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "factmask_linear")
+    return out
+
+
+def grass_projection_matrix(seed: int, stream_id: int, p: int, k: int, s: int, idx: torch.Tensor | None = None,
+                            device="cuda") -> torch.Tensor:
+    """The SJLT (idx None) or GraSS (idx given) compressor as a dense k x p fp32 matrix."""
+    P = torch.empty((k, p), dtype=torch.float32, device=device)
+    kprime = 0 if idx is None else idx.numel()
+    _check(load_library().grass_projection_matrix(seed, stream_id, p, _ptr(idx), kprime, k, s, _ptr(P), _ld(P), _stream()),
+           "grass_projection_matrix")
+    return P
 
 
 def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0,

@@ -56,6 +56,7 @@ struct FgArgs {
     uint32_t k, s, m;
     uint32_t tokens_per_block, chunks;
     float scale;
+    uint32_t identity;      // 1: no SJLT, out[a*kb + b] = v[a*kb + b] (the factorised mask Mask_{k_in x k_out})
 };
 
 // TA, TB: number of 32-wide tiles covering k_in' and k_out'.
@@ -141,7 +142,9 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
             for (int e = 0; e < 16; ++e) {
                 const uint32_t aq = ta * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
                 const float val = acc[i][e];
-                if (aq < a.ka && bq < a.kb && val != 0.0f) {
+                if (a.identity) {                                  // every (a', b') belongs to exactly one lane
+                    if (aq < a.ka && bq < a.kb) sk[aq * a.kb + bq] = (bucket_t)val;
+                } else if (aq < a.ka && bq < a.kb && val != 0.0f) {
                     uint64_t c = ((uint64_t)aq * a.kb + bq) * a.s;
                     for (uint32_t rr = 0; rr < a.s; ++rr, ++c) {
                         const uint64_t h = sm(L.sub, c);
@@ -297,6 +300,7 @@ static void fill_common(FgArgs& a, const FgPlan& pl, uint64_t n, uint64_t T, uin
     a.k = k; a.s = s; a.m = k / s;
     a.tokens_per_block = pl.tokens_per_block; a.chunks = pl.chunks;
     a.scale = 1.0f / sqrtf((float)s);
+    a.identity = 0;
 }
 
 extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64_t n, uint64_t T, uint32_t d_in,
@@ -378,4 +382,39 @@ extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uin
     a.many = static_cast<const FgLayer*>(ws);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + table);
     return run_fg(a, pl, n_layers, hs);
+}
+
+// Mask_{k_in x k_out} (Sec. 3.3.2, the factorised mask used as a baseline in Table 2 and as stage 1-2 of FactGraSS):
+// out_i[a*k_out' + b] = sum_t x_t[idx_in[a]] * g_t[idx_out[b]], no sparse projection afterwards.
+extern "C" grass_status factmask_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
+                                                        size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    if (kin_p == 0 || kout_p == 0 || kin_p > GRASS_MAX_FACTOR || kout_p > GRASS_MAX_FACTOR) return GRASS_EINVAL;
+    return factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, kin_p * kout_p, 1, host_bytes);
+}
+
+extern "C" grass_status factmask_linear(const void* x, const void* gout, uint64_t n, uint64_t T, uint32_t d_in,
+                                        uint32_t d_out, const int32_t* idx_in, uint32_t kin_p, const int32_t* idx_out,
+                                        uint32_t kout_p, float* out, uint64_t ldo, void* ws, size_t ws_bytes,
+                                        grass_stream stream) {
+    if (kin_p == 0 || kout_p == 0 || kin_p > GRASS_MAX_FACTOR || kout_p > GRASS_MAX_FACTOR) return GRASS_EINVAL;
+    const uint32_t k = kin_p * kout_p;
+    grass_status st = check_fg(n, T, kin_p, kout_p, k, 1);
+    if (st != GRASS_OK) return st;
+    if (kin_p > d_in || kout_p > d_out) return GRASS_EINVAL;
+    if (n == 0) return GRASS_OK;
+    if (!x || !gout || !idx_in || !idx_out || !out || ldo < k) return GRASS_EINVAL;
+    FgPlan pl;
+    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
+    FgArgs a;
+    fill_common(a, pl, n, T, kin_p, kout_p, k, 1, ldo);
+    a.identity = 1;
+    a.one.x = static_cast<const uint16_t*>(x);
+    a.one.g = static_cast<const uint16_t*>(gout);
+    a.one.idx_in = idx_in; a.one.idx_out = idx_out; a.one.out = out;
+    a.one.sub = 0;
+    a.one.d_in = d_in; a.one.d_out = d_out;
+    a.partial = static_cast<float*>(ws);
+    return run_fg(a, pl, 1, as_stream(stream));
 }

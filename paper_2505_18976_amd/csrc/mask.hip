@@ -249,6 +249,29 @@ __global__ void __launch_bounds__(256) sjlt_tables_kernel(uint64_t sub, uint64_t
     }
 }
 
+// P[row(j', r)][col(j')] = sign(j', r) / sqrt(s) for the SJLT positions j' in [0, d): col(j') = idx[j'] for the fused
+// mask (P is then the product of the SJLT matrix and the selection matrix), j' itself otherwise.  P is zero-filled first.
+__global__ void __launch_bounds__(256) projection_matrix_kernel(uint64_t sub, uint64_t d, const int32_t* idx, uint32_t s,
+                                                               uint32_t m, float value, float* P, uint64_t ldP) {
+    const uint64_t total = d * s;
+    uint64_t c = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (; c < total; c += stride) {
+        const uint64_t jp = c / s;
+        const uint32_t r = (uint32_t)(c - jp * s);
+        const uint64_t h = sm(sub, c);
+        const uint64_t col = idx ? (uint64_t)idx[jp] : jp;
+        P[(uint64_t)(r * m + bucket_of(h, m)) * ldP + col] = signbit_of(h) ? -value : value;
+    }
+}
+
+__global__ void __launch_bounds__(256) zero_rows_kernel(float* P, uint64_t rows, uint64_t cols, uint64_t ld) {
+    const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= rows * cols) return;
+    const uint64_t r = t / cols;
+    P[r * ld + (t - r * cols)] = 0.0f;
+}
+
 __global__ void __launch_bounds__(256) check_indices_kernel(const int32_t* idx, uint32_t kprime, uint64_t p,
                                                             uint32_t* bad) {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
@@ -351,6 +374,23 @@ extern "C" grass_status grass_selective_mask_indices(const float* S, uint64_t p,
         st = launch_status();
     }
     return st;
+}
+
+extern "C" grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, const int32_t* idx,
+                                                uint32_t kprime, uint32_t k, uint32_t s, float* P, uint64_t ldP,
+                                                grass_stream stream) {
+    if (p == 0 || p >= (1ull << 31) || k == 0 || s == 0 || k % s != 0 || !P || ldP < p) return GRASS_EINVAL;
+    if (idx && (kprime == 0 || kprime > p)) return GRASS_EINVAL;
+    if (ceil_div((uint64_t)k * p, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    const uint64_t d = idx ? kprime : p;
+    hipStream_t hs = as_stream(stream);
+    hipLaunchKernelGGL(zero_rows_kernel, dim3((uint32_t)ceil_div((uint64_t)k * p, 256)), dim3(256), 0, hs, P, (uint64_t)k, p,
+                       ldP);
+    const uint64_t total = d * s;
+    const uint32_t blocks = (uint32_t)(ceil_div(total, 256) > 8192 ? 8192 : ceil_div(total, 256));
+    hipLaunchKernelGGL(projection_matrix_kernel, dim3(blocks), dim3(256), 0, hs, substream(seed, stream_id), d, idx, s, k / s,
+                       1.0f / sqrtf((float)s), P, ldP);
+    return launch_status();
 }
 
 extern "C" grass_status grass_check_indices(const int32_t* idx, uint32_t kprime, uint64_t p, int* host_ok,

@@ -94,6 +94,55 @@ def test_factgrass_random_shapes(grass):
         assert err <= TOL_FACT, (case, n, T, d_in, d_out, ka, kb, k, s, err)
 
 
+@pytest.mark.parametrize("n,T,d_in,d_out,ka,kb", [(1, 1, 8, 8, 1, 1), (3, 150, 256, 384, 64, 64), (2, 70, 128, 96, 33, 17),
+                                                  (4, 300, 512, 512, 128, 128), (5, 40, 64, 700, 7, 100)])
+def test_factmask_parity(grass, n, T, d_in, d_out, ka, kb):
+    """Mask_{k_in x k_out} (Sec. 3.3.2): the sparsified gradient itself, flat index a*k_out' + b."""
+    x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=45, device=_dev())
+    ii = grass.grass_mask_indices(0, 16, d_in, ka, device=_dev())
+    io = grass.grass_mask_indices(0, 17, d_out, kb, device=_dev())
+    wide = torch.full((n, ka * kb + 5), 3.0, dtype=torch.float32, device=_dev())
+    grass.factmask_linear(x, g, ii, io, out=wide[:, :ka * kb])
+    torch.cuda.synchronize()
+    ref = orc.factgrass_sparsified_gradient(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy())
+    assert orc.max_rel_err(wide[:, :ka * kb].cpu().numpy(), ref) <= TOL_FACT
+    assert torch.all(wide[:, ka * kb:] == 3.0)
+
+
+@pytest.mark.parametrize("p,k,s,kp", [(1, 1, 1, 0), (300, 16, 1, 0), (4099, 64, 4, 0), (5000, 48, 3, 0), (5000, 64, 1, 700),
+                                      (65536, 1024, 2, 8192)])
+def test_projection_matrix_bit_exact(grass, p, k, s, kp):
+    idx = grass.grass_mask_indices(2, 0, p, kp, device=_dev()) if kp else None
+    P = grass.grass_projection_matrix(4, 1, p, k, s, idx=idx, device=_dev())
+    torch.cuda.synchronize()
+    if p * k <= 400000:
+        ref = orc.projection_matrix(4, 1, p, k, s, None if idx is None else orc.mask_indices(2, 0, p, kp))
+        assert np.array_equal(P.cpu().numpy(), ref.astype(np.float32))
+    # P g equals the scan on the GPU as well
+    g = synth.dense_normal(3, p, seed=46, device=_dev())
+    via_matrix = (g.double() @ P.double().T).cpu().numpy()
+    direct = grass.grass_sjlt(g, k, s, seed=4, stream_id=1, idx=idx)
+    torch.cuda.synchronize()
+    assert orc.max_rel_err(direct.cpu().numpy(), via_matrix) <= 1e-5
+
+
+@pytest.mark.parametrize("n,T,d,k_in,k_out,masked", [(2, 100, 256, 16, 32, False), (3, 130, 512, 64, 64, False),
+                                                     (2, 64, 1024, 64, 64, True)])
+def test_factorised_sjlt_and_grass_baselines_through_the_dense_kernel(grass, n, T, d, k_in, k_out, masked):
+    """SJLT_{k_in x k_out} / GraSS_{k_in x k_out}: logra_linear with the compressors' dense matrices (s = 1, exact in bf16)."""
+    x, g = synth.linear_layer_factors(n, T, d, d, seed=47, device=_dev())
+    ii = grass.grass_mask_indices(0, 16, d, d // 4, device=_dev()) if masked else None
+    io = grass.grass_mask_indices(0, 17, d, d // 4, device=_dev()) if masked else None
+    Pi = grass.grass_projection_matrix(0, 40, d, k_in, 1, idx=ii, device=_dev())
+    Po = grass.grass_projection_matrix(0, 41, d, k_out, 1, idx=io, device=_dev())
+    out = grass.logra_linear(x, g, grass.grass_to_bf16(Pi), grass.grass_to_bf16(Po))
+    torch.cuda.synchronize()
+    Pih = orc.projection_matrix(0, 40, d, k_in, 1, None if ii is None else ii.cpu().numpy())
+    Poh = orc.projection_matrix(0, 41, d, k_out, 1, None if io is None else io.cpu().numpy())
+    ref = orc.logra_linear(_np(x), _np(g), Pih, Poh)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= 1e-4
+
+
 @pytest.mark.parametrize("tokens", [32, 64, 4096])
 def test_factgrass_token_chunking(grass, tokens):
     n, T, d_in, d_out, ka, kb, k = 3, 150, 256, 256, 64, 64, 1024

@@ -225,3 +225,42 @@ def test_gauss_projection_preserves_norms_in_expectation():
     n2 = float(np.sum(g ** 2))
     assert abs(vals.mean() - n2) < 4.5 * np.sqrt(2 * n2 ** 2 / k / trials)
     assert abs(vals.var() / (2 * n2 ** 2 / k) - 1) < 0.25
+
+
+def test_projection_matrix_is_the_compressor():
+    """Sec. 3.1 / 3.3.1: the dense matrix applied to g equals the scan; s non-zeros per kept column, none elsewhere."""
+    rng = np.random.default_rng(21)
+    p, k, s = 90, 12, 3
+    g = rng.standard_normal((4, p))
+    P = orc.projection_matrix(6, 1, p, k, s)
+    assert np.allclose(g @ P.T, orc.sjlt(g, k, s, 6, 1), rtol=1e-12, atol=1e-14)
+    assert np.all((P != 0).sum(axis=0) == s) and np.allclose(np.abs(P[P != 0]), 1 / np.sqrt(s))
+    idx = orc.mask_indices(6, 0, p, 20)
+    Pm = orc.projection_matrix(6, 1, p, k, s, idx)
+    assert np.allclose(g @ Pm.T, orc.grass(g, idx, k, s, 6, 1), rtol=1e-12, atol=1e-14)
+    kept = np.zeros(p, bool); kept[idx] = True
+    assert np.all((Pm != 0).sum(axis=0)[kept] == s) and not Pm[:, ~kept].any()
+
+
+def test_factorised_sjlt_baseline_is_per_token_sjlt_then_kronecker():
+    """SJLT_{k_in x k_out} of Sec. 3.3.2 = Eq. (3) with SJLT matrices: sum_t SJLT(x_t) (x) SJLT(g_t)."""
+    rng = np.random.default_rng(22)
+    n, T, d_in, d_out, k_in, k_out = 2, 5, 30, 24, 4, 6
+    x, g = rng.standard_normal((n, T, d_in)), rng.standard_normal((n, T, d_out))
+    P_in, P_out = orc.projection_matrix(3, 40, d_in, k_in, 1), orc.projection_matrix(3, 41, d_out, k_out, 1)
+    got = orc.logra_linear(x, g, P_in, P_out)
+    for i in range(n):
+        want = sum(np.kron(orc.sjlt(x[i, t:t + 1], k_in, 1, 3, 40)[0], orc.sjlt(g[i, t:t + 1], k_out, 1, 3, 41)[0])
+                   for t in range(T))
+        assert np.allclose(got[i], want, rtol=1e-12, atol=1e-14)
+
+
+def test_factorised_mask_baseline_is_logra_with_selection_matrices():
+    """Mask_{k_in x k_out} = Eq. (3) with binary selection matrices = the sparsified gradient of FactGraSS."""
+    rng = np.random.default_rng(23)
+    n, T, d_in, d_out = 2, 4, 20, 16
+    x, g = rng.standard_normal((n, T, d_in)), rng.standard_normal((n, T, d_out))
+    ii, io = orc.mask_indices(1, 16, d_in, 5), orc.mask_indices(1, 17, d_out, 3)
+    M_in = np.zeros((5, d_in)); M_in[np.arange(5), ii] = 1
+    M_out = np.zeros((3, d_out)); M_out[np.arange(3), io] = 1
+    assert np.allclose(orc.factgrass_sparsified_gradient(x, g, ii, io), orc.logra_linear(x, g, M_in, M_out), rtol=1e-13)
