@@ -133,6 +133,25 @@ def test_influence_scores_end_to_end(grass):
     assert orc.max_rel_err(scores.cpu().numpy(), ref) <= 1e-4
 
 
+def test_attribution_pass_from_raw_gradients(grass):
+    """The README pipeline: Random Mask + SJLT (fused), FIM, damped inverse, iFVP, scores -- against the oracle chain."""
+    n, m, p, kp, k, lam = 300, 20, 20000, 4000, 128, 1e-2
+    g_train = synth.bernoulli_sparse_normal(n, p, 0.5, 1.0, seed=2600, device=_dev())
+    g_test = synth.bernoulli_sparse_normal(m, p, 0.5, 1.0, seed=2601, device=_dev())
+    idx = grass.grass_mask_indices(seed=0, stream_id=0, p=p, kprime=kp, device=_dev())
+    train = grass.grass_sjlt(g_train, k, 1, seed=0, stream_id=1, idx=idx)
+    test = grass.grass_sjlt(g_test, k, 1, seed=0, stream_id=1, idx=idx)
+    W = grass.grass_fim_inverse(grass.grass_fim(train), lam)
+    score = grass.grass_score(grass.grass_ifvp(train, W), test)
+    torch.cuda.synchronize()
+    idx_h = orc.mask_indices(0, 0, p, kp)
+    tr = orc.grass(g_train.cpu().numpy(), idx_h, k, 1, 0)
+    te = orc.grass(g_test.cpu().numpy(), idx_h, k, 1, 0)
+    ref = orc.influence(tr, te, lam)
+    assert score.shape == (m, n)
+    assert orc.max_rel_err(score.cpu().numpy(), ref) <= 1e-4
+
+
 def test_fim_and_ifvp_argument_checks(grass):
     G = synth.compressed_gradients(8, 16, seed=1, device=_dev())
     F = grass.grass_fim(G)
