@@ -305,7 +305,7 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     if (max_chunks_work < 1) max_chunks_work = 1;
     uint64_t max_chunks_traffic = (d * (masked ? 8 : 1)) / (8ull * k);
     if (max_chunks_traffic < 1) max_chunks_traffic = 1;
-    uint64_t chunks = ceil_div(2 * kNumCU, row_groups);
+    uint64_t chunks = ceil_div(4 * kNumCU, row_groups);       // four rounds of workgroups even out the tail
     if (chunks > max_chunks_work) chunks = max_chunks_work;
     if (chunks > max_chunks_traffic) chunks = max_chunks_traffic;
     if (short_rows) chunks = 1;
