@@ -92,8 +92,10 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
-    for (uint64_t t0 = t_begin; t0 < t_end; t0 += kTokTile) {
-        uint16_t xv[kTokTile / XSTEP], gv[kTokTile / GSTEP];
+    // The gather of a token tile is pure latency (every 2-byte pick is its own 128-byte line), so the loads of
+    // tile t+1 are issued before the matrix products of tile t.
+    uint16_t xv[kTokTile / XSTEP], gv[kTokTile / GSTEP];
+    auto gather = [&](uint64_t t0) {
 #pragma unroll
         for (int i = 0; i < kTokTile / XSTEP; ++i) {
             const uint64_t t = t0 + xt0 + i * XSTEP;
@@ -104,12 +106,16 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
             const uint64_t t = t0 + gt0 + i * GSTEP;
             gv[i] = (gcol >= 0 && t < t_end) ? grow[t * L.d_out + gcol] : (uint16_t)0;
         }
+    };
+    if (t_begin < t_end) gather(t_begin);
+    for (uint64_t t0 = t_begin; t0 < t_end; t0 += kTokTile) {
         __syncthreads();   // previous tile's MFMA reads are done
 #pragma unroll
         for (int i = 0; i < kTokTile / XSTEP; ++i) xs[xa * kTokStride + xt0 + i * XSTEP] = xv[i];
 #pragma unroll
         for (int i = 0; i < kTokTile / GSTEP; ++i) gs[gb * kTokStride + gt0 + i * GSTEP] = gv[i];
         __syncthreads();
+        if (t0 + kTokTile < t_end) gather(t0 + kTokTile);
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int tile = wave + 4 * i;
