@@ -344,10 +344,15 @@ def main() -> int:
         te = synth.dense_normal(M5, K5, seed=1006, device=dev)
         sc = torch.empty((M5, N5), dtype=torch.float32, device=dev)
         for mode, peak in ((0, MFMA_PEAK_F32_TFLOPS), (1, MFMA_PEAK_BF16_TFLOPS)):
-            t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=mode, out=sc), 5, 1, torch)
+            wsc = torch.empty(max(grass.grass_score_workspace_bytes(N5, M5, K5, mode), 1), dtype=torch.uint8, device=dev)
+            t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=mode, out=sc, ws=wsc), 5, 1, torch)
             tf = 2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12
             extras[f"score_gemm_mode{mode}"] = {"ms": round(t / 5, 4), "TFLOPs": round(tf, 2),
                                                 "frac_of_mfma_peak": round(tf / peak, 4)}
+            del wsc
+        t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=1, out=sc, ws=None), 5, 1, torch)
+        extras["score_gemm_mode1_no_workspace"] = {"ms": round(t / 5, 4),
+                                                   "TFLOPs": round(2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12, 2)}
         trb, teb = grass.grass_to_bf16(tr), grass.grass_to_bf16(te)
         t, _, _ = _timed(lambda: grass.grass_score_bf16(trb, teb, out=sc), 10, 2, torch)
         tf = 2.0 * N5 * M5 * K5 / (t / 10 * 1e-3) / 1e12

@@ -181,12 +181,22 @@ grass_status logra_linear(const void* x, const void* gout,
  * Sec. 2.1, attribute stage: scores[m, i] = <test_m, train_i> for all pairs of
  * compressed gradients (no preconditioner).
  * train: N x K fp32 (ld_train >= K), test: M x K fp32, scores: M x N fp32.
- * compute_mode 0: fp32 MFMA.  1: inputs rounded to bf16 (nearest-even) on
- * load, bf16 MFMA with fp32 accumulation.                                    */
+ * compute_mode 0: fp32 MFMA.  1: inputs rounded to bf16 (nearest-even), bf16
+ * MFMA with fp32 accumulation.
+ * Workspace (optional, from grass_score_workspace_bytes): with it, mode 1
+ * rounds both operands once into the workspace and runs the direct-to-LDS bf16
+ * kernel (about twice as fast as rounding on the fly), and products whose M x N
+ * output has few tiles but a long K are split over K ranges with fixed-order
+ * partial sums.  ws == NULL selects the paths that need no scratch memory; a
+ * non-NULL workspace that is too small or not 256-byte aligned is
+ * GRASS_EWORKSPACE.                                                           */
+grass_status grass_score_workspace_bytes(uint64_t N, uint64_t M, uint64_t K, int compute_mode,
+                                         size_t* host_bytes);
 grass_status grass_score(const float* train, const float* test, int compute_mode,
                          uint64_t N, uint64_t M, uint64_t K,
                          uint64_t ld_train, uint64_t ld_test,
-                         float* scores, uint64_t ld_scores, grass_stream stream);
+                         float* scores, uint64_t ld_scores,
+                         void* ws, size_t ws_bytes, grass_stream stream);
 
 /* The same scores for callers that keep compressed gradients in bf16 (Sec. 2.1;
  * halves the bytes of the attribute stage): train N x K and test M x K are bf16
@@ -207,7 +217,8 @@ grass_status grass_score_bf16(const void* train, const void* test,
  * grass_gauss_matrix writes columns [p0, p0+pc) of P as a k x pc fp32 matrix
  * (ldP >= pc); grass_gauss_project computes out = g P^T (n x k fp32) in
  * p-chunks of at most p_chunk columns, regenerating P chunk by chunk in the
- * workspace.  compute_mode as in grass_score.                                */
+ * workspace.  compute_mode 0: fp32 MFMA.  1: both the chunk of P and the chunk
+ * of g are rounded to bf16 (nearest-even), bf16 MFMA, fp32 accumulation.      */
 grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t k,
                                 uint64_t p0, uint64_t pc, float* P, uint64_t ldP, grass_stream stream);
 grass_status grass_gauss_project_workspace_bytes(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk,

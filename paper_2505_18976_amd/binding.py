@@ -48,7 +48,8 @@ SIGNATURES = {
                                 _vp, _sz, _vp]),
     "logra_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
     "logra_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
-    "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
+    "grass_score_workspace_bytes": (_int, [_u64, _u64, _u64, _int, ctypes.POINTER(_sz)]),
+    "grass_score": (_int, [_vp, _vp, _int, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
     "grass_to_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_score_bf16": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _u64, _vp, _u64, _vp]),
     "grass_gauss_matrix": (_int, [_u64, _u64, _u64, _u32, _u64, _u64, _vp, _u64, _vp]),
@@ -286,16 +287,27 @@ def logra_linear(x: torch.Tensor, gout: torch.Tensor, P_in: torch.Tensor, P_out:
     return out
 
 
+def grass_score_workspace_bytes(N: int, M: int, K: int, compute_mode: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_score_workspace_bytes(N, M, K, compute_mode, ctypes.byref(out)),
+           "grass_score_workspace_bytes")
+    return out.value
+
+
 def grass_score(train: torch.Tensor, test: torch.Tensor, compute_mode: int = 0,
-                out: torch.Tensor | None = None) -> torch.Tensor:
+                out: torch.Tensor | None = None, ws: torch.Tensor | None | bool = True) -> torch.Tensor:
+    """scores[m, i] = <test_m, train_i>.  ws: True allocates the optional workspace, None runs without one."""
     assert train.dtype == torch.float32 and test.dtype == torch.float32
     N, K = train.shape
     M = test.shape[0]
     assert test.shape[1] == K
     if out is None:
         out = torch.empty((M, N), dtype=torch.float32, device=train.device)
+    if ws is True:
+        ws = _workspace(grass_score_workspace_bytes(N, M, K, compute_mode), train.device)
     _check(load_library().grass_score(_ptr(train), _ptr(test), compute_mode, N, M, K, _ld(train), _ld(test),
-                                      _ptr(out), _ld(out), _stream()), "grass_score")
+                                      _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+           "grass_score")
     return out
 
 

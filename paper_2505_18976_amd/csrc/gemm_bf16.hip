@@ -411,10 +411,10 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     return true;
 }
 
-// fp32 -> bf16, round to nearest even; 4 elements per thread.
-__global__ void __launch_bounds__(256) to_bf16_kernel(const float* src, uint64_t rows, uint64_t cols, uint64_t ld_src,
-                                                      uint16_t* dst, uint64_t ld_dst) {
-    const uint64_t quads = (cols + 3) / 4;
+// fp32 -> bf16, round to nearest even; 4 elements per thread.  Columns cols..cols_pad of dst are zero-filled.
+__global__ void __launch_bounds__(256) to_bf16_kernel(const float* src, uint64_t rows, uint64_t cols, uint64_t cols_pad,
+                                                      uint64_t ld_src, uint16_t* dst, uint64_t ld_dst) {
+    const uint64_t quads = (cols_pad + 3) / 4;
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= rows * quads) return;
     const uint64_t r = t / quads, c0 = (t - r * quads) * 4;
@@ -426,8 +426,21 @@ __global__ void __launch_bounds__(256) to_bf16_kernel(const float* src, uint64_t
             if ((u & 0x7FFFFFFFu) > 0x7F800000u) h = (uint16_t)((u >> 16) | 0x40u);
             else { u += 0x7FFFu + ((u >> 16) & 1u); h = (uint16_t)(u >> 16); }
             dst[r * ld_dst + c0 + j] = h;
+        } else if (c0 + j < cols_pad) {
+            dst[r * ld_dst + c0 + j] = 0;
         }
     }
+}
+
+// dst (rows x ld_dst bf16) = src rounded to nearest even, zero-padded up to cols_pad columns.
+hipError_t convert_to_bf16(const float* src, uint64_t rows, uint64_t cols, uint64_t cols_pad, uint64_t ld_src, uint16_t* dst,
+                           uint64_t ld_dst, hipStream_t st) {
+    const uint64_t total = rows * ((cols_pad + 3) / 4);
+    if (total == 0) return hipSuccess;
+    if (ceil_div(total, 256) > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(to_bf16_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, st, src, rows, cols, cols_pad,
+                       ld_src, dst, ld_dst);
+    return hipGetLastError();
 }
 
 }  // namespace grass
@@ -439,11 +452,9 @@ extern "C" grass_status grass_to_bf16(const float* src, uint64_t rows, uint64_t 
     if (cols == 0) return GRASS_EINVAL;
     if (rows == 0) return GRASS_OK;
     if (!src || !dst || ld_src < cols || ld_dst < cols) return GRASS_EINVAL;
-    const uint64_t total = rows * ((cols + 3) / 4);
-    if (ceil_div(total, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
-    hipLaunchKernelGGL(to_bf16_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, as_stream(stream), src, rows,
-                       cols, ld_src, static_cast<uint16_t*>(dst), ld_dst);
-    return launch_status();
+    if (ceil_div(rows * ((cols + 3) / 4), 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
+    return convert_to_bf16(src, rows, cols, cols, ld_src, static_cast<uint16_t*>(dst), ld_dst, as_stream(stream)) == hipSuccess
+               ? GRASS_OK : GRASS_EHIP;
 }
 
 extern "C" grass_status grass_score_bf16(const void* train, const void* test, uint64_t N, uint64_t M, uint64_t K,

@@ -214,6 +214,8 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
                      float* partials, int lower_only);
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits);
 bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint64_t lda, uint64_t ldb);
+hipError_t convert_to_bf16(const float* src, uint64_t rows, uint64_t cols, uint64_t cols_pad, uint64_t ld_src, uint16_t* dst,
+                           uint64_t ld_dst, hipStream_t st);
 
 // splits > 1 (fp32 mode only): K-range partial products go to `partials`, see launch_gemm_dma.
 static hipError_t launch_gemm(const GemmArgs& a, int mode, hipStream_t st, uint32_t splits = 1,
@@ -281,74 +283,161 @@ uint32_t gemm_nt_f32_splits(const float* A, const float* B, uint64_t M, uint64_t
 
 // P[a, b] for b in [p0, p0+pc): one Box-Muller normal per hash, scaled to variance 1/k.
 // blockIdx.x: a run of 256 columns, blockIdx.y (+ stride): rows.
+// BF16: the value is rounded to bf16 (nearest even) and columns pc..pc_pad are zero-filled (whole K slices for the
+// bf16 GEMM); otherwise pc_pad == pc.
+template <bool BF16>
 __global__ void __launch_bounds__(256) gauss_matrix_kernel(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0,
-                                                           uint64_t pc, float* P, uint64_t ldP, float inv_sqrt_k) {
+                                                           uint64_t pc, uint64_t pc_pad, void* Pv, uint64_t ldP,
+                                                           float inv_sqrt_k) {
     const uint64_t col = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (col >= pc) return;
+    if (col >= pc_pad) return;
     for (uint32_t row = blockIdx.y; row < k; row += gridDim.y) {
-        const uint64_t h = sm(sub, (uint64_t)row * p + p0 + col);
-        const float u1 = ((float)(uint32_t)(h >> 41) + 0.5f) * (1.0f / 8388608.0f);           // (0, 1), exact
-        const float u2 = (float)(uint32_t)((h >> 16) & 0xFFFFFFu) * (1.0f / 16777216.0f);      // [0, 1)
-        const float rad = sqrtf(-2.0f * logf(u1));
-        P[(uint64_t)row * ldP + col] = rad * cospif(2.0f * u2) * inv_sqrt_k;
+        float v = 0.0f;
+        if (col < pc) {
+            const uint64_t h = sm(sub, (uint64_t)row * p + p0 + col);
+            const float u1 = ((float)(uint32_t)(h >> 41) + 0.5f) * (1.0f / 8388608.0f);           // (0, 1), exact
+            const float u2 = (float)(uint32_t)((h >> 16) & 0xFFFFFFu) * (1.0f / 16777216.0f);      // [0, 1)
+            v = sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2) * inv_sqrt_k;
+        }
+        if constexpr (BF16) static_cast<uint16_t*>(Pv)[(uint64_t)row * ldP + col] = f32_to_bf16_rne(v);
+        else static_cast<float*>(Pv)[(uint64_t)row * ldP + col] = v;
     }
 }
 
-static void launch_gauss_matrix(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0, uint64_t pc, float* P, uint64_t ldP,
-                                hipStream_t hs) {
-    const uint32_t gx = (uint32_t)ceil_div(pc, 256);
+static void launch_gauss_matrix(uint64_t sub, uint64_t p, uint32_t k, uint64_t p0, uint64_t pc, uint64_t pc_pad, bool bf16,
+                                void* P, uint64_t ldP, hipStream_t hs) {
+    const uint32_t gx = (uint32_t)ceil_div(pc_pad, 256);
     uint32_t gy = k;                                   // about 16K workgroups keep every CU busy
     if ((uint64_t)gx * gy > 16384) gy = (uint32_t)(16384 / gx > 0 ? 16384 / gx : 1);
     if (gy > 65535) gy = 65535;
-    hipLaunchKernelGGL(gauss_matrix_kernel, dim3(gx, gy), dim3(256), 0, hs, sub, p, k, p0, pc, P, ldP,
-                       1.0f / sqrtf((float)k));
+    const float scale = 1.0f / sqrtf((float)k);
+    if (bf16)
+        hipLaunchKernelGGL(gauss_matrix_kernel<true>, dim3(gx, gy), dim3(256), 0, hs, sub, p, k, p0, pc, pc_pad, P, ldP, scale);
+    else
+        hipLaunchKernelGGL(gauss_matrix_kernel<false>, dim3(gx, gy), dim3(256), 0, hs, sub, p, k, p0, pc, pc_pad, P, ldP, scale);
 }
 
 }  // namespace grass
 
 using namespace grass;
 
+// Workspace plan of grass_score: bf16 copies of both operands (mode 1) and K-range partial sums when the M x N
+// output has too few tiles to fill the chip.
+struct ScorePlan {
+    uint64_t kp;               // K rounded up to whole 64-byte bf16 slices
+    size_t off_test, off_train, off_part, total;
+    bool may_split;
+};
+static size_t up256s(size_t x) { return (x + 255) / 256 * 256; }
+static ScorePlan score_plan(uint64_t N, uint64_t M, uint64_t K, int mode) {
+    ScorePlan P;
+    P.kp = (K + 31) / 32 * 32;
+    size_t o = 0;
+    P.off_test = o;  if (mode == 1) o += up256s((size_t)M * P.kp * 2);
+    P.off_train = o; if (mode == 1) o += up256s((size_t)N * P.kp * 2);
+    P.may_split = ceil_div(M, 128) * ceil_div(N, 128) < 1024 && K >= 4096;
+    P.off_part = o;  if (P.may_split) o += up256s((size_t)8 * M * N * 4);
+    P.total = o;
+    return P;
+}
+
+extern "C" grass_status grass_score_workspace_bytes(uint64_t N, uint64_t M, uint64_t K, int compute_mode,
+                                                    size_t* host_bytes) {
+    if (!host_bytes || K == 0 || (compute_mode != 0 && compute_mode != 1)) return GRASS_EINVAL;
+    *host_bytes = (N == 0 || M == 0) ? 0 : score_plan(N, M, K, compute_mode).total;
+    return GRASS_OK;
+}
+
 extern "C" grass_status grass_score(const float* train, const float* test, int compute_mode, uint64_t N, uint64_t M,
                                     uint64_t K, uint64_t ld_train, uint64_t ld_test, float* scores,
-                                    uint64_t ld_scores, grass_stream stream) {
+                                    uint64_t ld_scores, void* ws, size_t ws_bytes, grass_stream stream) {
     if (K == 0 || (compute_mode != 0 && compute_mode != 1)) return GRASS_EINVAL;
     if (N == 0 || M == 0) return GRASS_OK;
     if (!train || !test || !scores || ld_train < K || ld_test < K || ld_scores < N) return GRASS_EINVAL;
+    hipStream_t hs = as_stream(stream);
+    const ScorePlan P = score_plan(N, M, K, compute_mode);
+    const bool have_ws = ws != nullptr && ws_bytes >= P.total && P.total > 0;
+    if (ws != nullptr && P.total > 0 && (ws_bytes < P.total || !aligned(ws, 256))) return GRASS_EWORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(ws);
     GemmArgs a;
     a.A = test; a.B = train; a.C = scores;
     a.M = M; a.N = N; a.K = K; a.lda = ld_test; a.ldb = ld_train; a.ldc = ld_scores;
     a.accumulate = 0;
-    return launch_gemm(a, compute_mode, as_stream(stream)) == hipSuccess ? GRASS_OK : GRASS_EHIP;
+    if (compute_mode == 1 && have_ws) {
+        // round both operands once, then the bf16 direct-to-LDS kernel (zero-padded to whole K slices)
+        uint16_t* te = reinterpret_cast<uint16_t*>(base + P.off_test);
+        uint16_t* tr = reinterpret_cast<uint16_t*>(base + P.off_train);
+        if (convert_to_bf16(test, M, K, P.kp, ld_test, te, P.kp, hs) != hipSuccess) return GRASS_EHIP;
+        if (convert_to_bf16(train, N, K, P.kp, ld_train, tr, P.kp, hs) != hipSuccess) return GRASS_EHIP;
+        uint32_t splits = P.may_split ? gemm_dma_splits(M, N, P.kp, false, 8) : 1;
+        float* partials = reinterpret_cast<float*>(base + P.off_part);
+        hipError_t derr = hipSuccess;
+        if (launch_gemm_dma(false, te, tr, scores, M, N, P.kp, P.kp, P.kp, ld_scores, 0, hs, &derr, splits,
+                            splits > 1 ? partials : nullptr, 0)) {
+            if (derr != hipSuccess) return GRASS_EHIP;
+            if (splits > 1)
+                hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(M * N, 256)), dim3(256), 0, hs, partials, M,
+                                   (uint32_t)N, splits, 1.0f, scores, ld_scores);
+            return launch_status();
+        }
+        // not reachable with the padded copies; fall through to the on-the-fly kernel
+    }
+    if (compute_mode == 0 && have_ws && P.may_split) {
+        const uint32_t splits = gemm_nt_f32_splits(test, train, M, N, K, ld_test, ld_train, 8);
+        if (splits > 1) {
+            float* partials = reinterpret_cast<float*>(base + P.off_part);
+            if (launch_gemm(a, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
+            hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(M * N, 256)), dim3(256), 0, hs, partials, M,
+                               (uint32_t)N, splits, 1.0f, scores, ld_scores);
+            return launch_status();
+        }
+    }
+    return launch_gemm(a, compute_mode, hs) == hipSuccess ? GRASS_OK : GRASS_EHIP;
 }
 
 extern "C" grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, uint64_t p, uint32_t k, uint64_t p0,
                                            uint64_t pc, float* P, uint64_t ldP, grass_stream stream) {
     if (p == 0 || k == 0 || pc == 0 || p0 + pc > p || !P || ldP < pc) return GRASS_EINVAL;
     if (ceil_div(pc, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
-    launch_gauss_matrix(substream(seed, stream_id), p, k, p0, pc, P, ldP, as_stream(stream));
+    launch_gauss_matrix(substream(seed, stream_id), p, k, p0, pc, pc, false, P, ldP, as_stream(stream));
     return launch_status();
 }
 
 static uint64_t gauss_chunk(uint64_t p, uint64_t p_chunk) {
     uint64_t pc = p_chunk == 0 ? 8192 : p_chunk;
-    pc = (pc + 3) / 4 * 4;                 // keeps every chunk of P 16-byte aligned
-    return pc > p ? (p + 3) / 4 * 4 : pc;
+    pc = (pc + 31) / 32 * 32;              // whole 64-byte K slices of fp32 and of bf16
+    return pc > p ? (p + 31) / 32 * 32 : pc;
 }
 
-// K ranges of the first (largest) chunk's product; later chunks never use more.
-static uint32_t gauss_splits(uint64_t n, uint64_t p, uint32_t k, uint64_t pc, int compute_mode) {
-    if (compute_mode != 0 || n < 128 || k < 128) return 1;
-    return gemm_dma_splits(n, k, pc < p ? pc : p, true, 8);
+// Workspace plan of grass_gauss_project.  mode 0: the fp32 chunk of P.  mode 1 (n, k >= 128): bf16 chunks of P and
+// of g.  Both: K-range partial sums when the n x k output has too few tiles to fill the chip.
+struct GaussPlan {
+    uint64_t pc;
+    uint32_t splits;           // K ranges of the first (largest) chunk's product; later chunks never use more
+    bool bf16_path;
+    size_t off_p, off_g, off_part, total;
+};
+static GaussPlan gauss_plan(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk, int mode) {
+    GaussPlan G;
+    G.pc = gauss_chunk(p, p_chunk);
+    const bool big = n >= 128 && k >= 128;
+    G.bf16_path = mode == 1 && big;
+    const uint64_t first = G.pc < p ? G.pc : p;
+    G.splits = 1;
+    if (big && (mode == 0 || G.bf16_path) && first % 32 == 0) G.splits = gemm_dma_splits(n, k, first, mode == 0, 8);
+    size_t o = 0;
+    G.off_p = o; o += up256s((size_t)k * G.pc * (G.bf16_path ? 2 : 4));
+    G.off_g = o; if (G.bf16_path) o += up256s((size_t)n * G.pc * 2);
+    G.off_part = o; if (G.splits > 1) o += up256s((size_t)G.splits * n * k * 4);
+    G.total = o;
+    return G;
 }
-
-static size_t gauss_p_bytes(uint32_t k, uint64_t pc) { return ((size_t)k * pc * sizeof(float) + 255) / 256 * 256; }
 
 extern "C" grass_status grass_gauss_project_workspace_bytes(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk,
                                                             size_t* host_bytes) {
     if (!host_bytes || p == 0 || k == 0) return GRASS_EINVAL;
-    const uint64_t pc = gauss_chunk(p, p_chunk);
-    const uint32_t splits = gauss_splits(n, p, k, pc, 0);          // the larger of the two modes' needs
-    *host_bytes = gauss_p_bytes(k, pc) + (splits > 1 ? (size_t)splits * n * k * sizeof(float) : 0);
+    const size_t a = gauss_plan(n, p, k, p_chunk, 0).total, b = gauss_plan(n, p, k, p_chunk, 1).total;
+    *host_bytes = a > b ? a : b;           // the mode is not an argument of the query: enough for either
     return GRASS_OK;
 }
 
@@ -359,45 +448,60 @@ extern "C" grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t
     if (p == 0 || k == 0 || (compute_mode != 0 && compute_mode != 1)) return GRASS_EINVAL;
     if (n == 0) return GRASS_OK;
     if (!g || !out || ldg < p || ldo < k) return GRASS_EINVAL;
-    const uint64_t pc = gauss_chunk(p, p_chunk);
+    GaussPlan G = gauss_plan(n, p, k, p_chunk, compute_mode);
+    const uint64_t pc = G.pc;
     if (ceil_div(pc, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
-    uint32_t splits = gauss_splits(n, p, k, pc, compute_mode);
-    // the split path needs every chunk to qualify for the direct-to-LDS kernel
-    if (splits > 1 && (!aligned(g, 16) || ldg % 4 != 0 || pc % 16 != 0 || (pc < p ? pc : p) % 16 != 0)) splits = 1;
-    const size_t need = gauss_p_bytes(k, pc) + (splits > 1 ? (size_t)splits * n * k * sizeof(float) : 0);
-    if (!ws || ws_bytes < need || !aligned(ws, 256)) return GRASS_EWORKSPACE;
-    float* P = static_cast<float*>(ws);
-    float* partials = splits > 1 ? reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + gauss_p_bytes(k, pc)) : nullptr;
+    if (!ws || ws_bytes < G.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    // the split fp32 path needs every chunk of g to qualify for the direct-to-LDS kernel
+    if (G.splits > 1 && compute_mode == 0 && (!aligned(g, 16) || ldg % 4 != 0)) G.splits = 1;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* partials = G.splits > 1 ? reinterpret_cast<float*>(base + G.off_part) : nullptr;
     hipStream_t hs = as_stream(stream);
     const uint64_t sub = substream(seed, stream_id);
     for (uint64_t p0 = 0; p0 < p; p0 += pc) {
         const uint64_t cur = p0 + pc <= p ? pc : p - p0;
-        launch_gauss_matrix(sub, p, k, p0, cur, P, pc, hs);
+        const int accumulate = p0 != 0;
+        if (G.bf16_path) {
+            // P and g chunks rounded to bf16 once (zero-padded to whole K slices), bf16 matrix cores, fp32 accumulation
+            const uint64_t cur_pad = (cur + 31) / 32 * 32;
+            uint16_t* Pb = reinterpret_cast<uint16_t*>(base + G.off_p);
+            uint16_t* gb = reinterpret_cast<uint16_t*>(base + G.off_g);
+            launch_gauss_matrix(sub, p, k, p0, cur, cur_pad, true, Pb, pc, hs);
+            if (convert_to_bf16(g + p0, n, cur, cur_pad, ldg, gb, pc, hs) != hipSuccess) return GRASS_EHIP;
+            uint32_t s_cur = G.splits > 1 ? gemm_dma_splits(n, k, cur_pad, false, G.splits) : 1;
+            if (s_cur > G.splits) s_cur = G.splits;
+            float* C = G.splits > 1 ? partials : out;
+            const uint64_t ldc = G.splits > 1 ? k : ldo;
+            hipError_t derr = hipSuccess;
+            if (!launch_gemm_dma(false, gb, Pb, C, n, k, cur_pad, pc, pc, ldc, accumulate, hs, &derr, s_cur,
+                                 s_cur > 1 ? partials : nullptr, 0) || derr != hipSuccess)
+                return GRASS_EHIP;
+            continue;
+        }
+        float* P = reinterpret_cast<float*>(base + G.off_p);
+        launch_gauss_matrix(sub, p, k, p0, cur, cur, false, P, pc, hs);
         GemmArgs a;
         a.A = g + p0; a.B = P; a.C = out;
         a.M = n; a.N = k; a.K = cur; a.lda = ldg; a.ldb = pc; a.ldc = ldo;
-        a.accumulate = p0 != 0;
-        if (splits > 1 && cur % 16 == 0) {
-            uint32_t s_cur = gemm_dma_splits(n, k, cur, true, splits);
-            if (s_cur > splits) s_cur = splits;
-            if (s_cur == 1) {                              // short tail: a one-range product into partial 0
+        a.accumulate = accumulate;
+        if (G.splits > 1) {
+            uint32_t s_cur = cur % 16 == 0 ? gemm_dma_splits(n, k, cur, true, G.splits) : 1;
+            if (s_cur > G.splits) s_cur = G.splits;
+            if (s_cur == 1) {                              // short or ragged tail: a one-range product into partial 0
                 a.C = partials; a.ldc = k;
                 if (launch_gemm(a, 0, hs) != hipSuccess) return GRASS_EHIP;
             } else if (launch_gemm(a, 0, hs, s_cur, partials) != hipSuccess) {
                 return GRASS_EHIP;
             }
-        } else if (splits > 1) {                           // ragged tail (cur not a multiple of the slice width)
-            a.C = partials; a.ldc = k;
-            if (launch_gemm(a, 0, hs) != hipSuccess) return GRASS_EHIP;
         } else if (launch_gemm(a, compute_mode, hs) != hipSuccess) {
             return GRASS_EHIP;
         }
     }
-    if (splits > 1) {
+    if (G.splits > 1) {
         const uint64_t total = n * (uint64_t)k;
         if (ceil_div(total, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, hs, partials, n, k,
-                           splits, 1.0f, out, ldo);
+                           G.splits, 1.0f, out, ldo);
     }
     return launch_status();
 }

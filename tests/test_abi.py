@@ -84,8 +84,8 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     # workspace required but missing: many chunks for a single long row
     assert lib.grass_sjlt(fake, 1, 1 << 22, 1 << 22, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EWORKSPACE
     assert lib.grass_mask_indices(0, 0, 1000, 10, fake, null, 0, null) == b.GRASS_EWORKSPACE
-    assert lib.grass_score(fake, fake, 2, 8, 8, 8, 8, 8, fake, 8, null) == b.GRASS_EINVAL
-    assert lib.grass_score(fake, fake, 0, 8, 8, 8, 7, 8, fake, 8, null) == b.GRASS_EINVAL
+    assert lib.grass_score(fake, fake, 2, 8, 8, 8, 8, 8, fake, 8, null, 0, null) == b.GRASS_EINVAL
+    assert lib.grass_score(fake, fake, 0, 8, 8, 8, 7, 8, fake, 8, null, 0, null) == b.GRASS_EINVAL
     assert lib.factgrass_linear(fake, fake, 2, 16, 64, 64, fake, 65, fake, 8, 32, 1, 0, 18, fake, 32, null, 0,
                                 null) == b.GRASS_EINVAL                                                  # k_in' > d_in
     assert lib.grass_gauss_project(fake, 2, 64, 64, 8, 0, 2, 0, 0, fake, 8, null, 0, null) == b.GRASS_EWORKSPACE

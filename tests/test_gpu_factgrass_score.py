@@ -245,15 +245,19 @@ def test_logra_with_selection_matrices_matches_factgrass_mask_stage(grass):
 
 
 # ------------------------------------------------------------------- score
-SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70)]
+SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70),
+               (200, 130, 8192), (130, 129, 12304), (129, 3, 5000)]      # few tiles, long K: split over K ranges
 
 
 @pytest.mark.parametrize("N,M,K", SCORE_CASES)
 @pytest.mark.parametrize("mode", [0, 1])
-def test_score_parity(grass, N, M, K, mode):
+@pytest.mark.parametrize("with_ws", [True, False])
+def test_score_parity(grass, N, M, K, mode, with_ws):
+    """with_ws: the optional workspace (operands rounded once for mode 1, K-range partial sums); without it the
+    on-the-fly paths.  Both must meet the same bars."""
     train = synth.dense_normal(N, K, seed=70, device=_dev())
     test = synth.dense_normal(M, K, seed=71, device=_dev())
-    sc = grass.grass_score(train, test, compute_mode=mode)
+    sc = grass.grass_score(train, test, compute_mode=mode, ws=True if with_ws else None)
     torch.cuda.synchronize()
     ref = orc.score(train.cpu().numpy(), test.cpu().numpy())
     assert sc.shape == (M, N)
@@ -344,7 +348,7 @@ def test_gauss_matrix_parity(grass, seed, stream, p, k, p0, pc):
 @pytest.mark.parametrize("n,p,k,chunk,mode", [(3, 100, 8, 0, 0), (70, 5001, 130, 1024, 0), (70, 5001, 130, 1024, 1),
                                               (256, 16384, 256, 4096, 1), (33, 4098, 64, 4096, 0),
                                               # few output tiles: the contraction is split over K ranges
-                                              (256, 16384, 256, 4096, 0), (130, 20000, 300, 8192, 0),
+                                              (256, 16384, 256, 4096, 0), (130, 20000, 300, 8192, 1), (200, 5001, 128, 1024, 1), (130, 20000, 300, 8192, 0),
                                               (128, 9000, 128, 4104, 0), (200, 2048, 128, 0, 0)])
 def test_gauss_project_parity(grass, n, p, k, chunk, mode):
     g = synth.laplace_sparse(n, p, 0.3, 1e-3, seed=80, device=_dev())
