@@ -8,9 +8,9 @@
 // One workgroup (4 wavefronts) owns one sample and one chunk of its tokens.
 //   Stage 1: a = X_chunk P_in^T and b = G_chunk P_out^T, 64 tokens at a time, bf16
 //            MFMA with fp32 accumulation; K (= d_in, d_out) is streamed in slices
-//            of 128 through two LDS stages, the next slice prefetched in registers
-//            (64 KB per workgroup in flight: one workgroup per CU has to cover the
-//            HBM latency by itself).
+//            of 128 through two LDS stages with the next two slices prefetched in
+//            registers (128 KB per workgroup in flight: one workgroup per CU has to
+//            cover the HBM latency by itself).
 //            Wavefronts 0,1 compute a (token halves), wavefronts 2,3 compute b.
 //   Stage 2: acc[a][b] += sum_t a_t[a] * b_t[b] on the fp32 matrix cores from LDS.
 // Per-chunk partial k_in x k_out blocks are added in a fixed order by
@@ -65,31 +65,31 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
     for (int v = 0; v < 16; ++v) acc2[v] = 0.0f;
     const int ta = wave >> 1, tb = wave & 1;
 
+    struct RegSet { u32x4 rx[NI], rg[NI], rpi[NI], rpo[NI]; };
     for (uint64_t t0 = t_begin; t0 < t_end; t0 += LT) {
-        u32x4 rx[NI], rg[NI], rpi[NI], rpo[NI];
-        auto fetch = [&](uint32_t k0) {
+        auto fetch = [&](RegSet& r, uint32_t k0) {
             const uint32_t kk = k0 + skc * 8;           // d_in, d_out are multiples of 8: a chunk is all in or all out
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
                 const int row = srow + RSTEP * i;
                 const uint64_t t = t0 + row;
-                rx[i] = (t < t_end && kk < a.d_in) ? *reinterpret_cast<const u32x4*>(xs + t * a.d_in + kk) : u32x4(0u);
-                rg[i] = (t < t_end && kk < a.d_out) ? *reinterpret_cast<const u32x4*>(gs + t * a.d_out + kk) : u32x4(0u);
-                rpi[i] = ((uint32_t)row < a.k_in && kk < a.d_in)
-                             ? *reinterpret_cast<const u32x4*>(a.pin + (uint64_t)row * a.d_in + kk) : u32x4(0u);
-                rpo[i] = ((uint32_t)row < a.k_out && kk < a.d_out)
-                             ? *reinterpret_cast<const u32x4*>(a.pout + (uint64_t)row * a.d_out + kk) : u32x4(0u);
+                r.rx[i] = (t < t_end && kk < a.d_in) ? *reinterpret_cast<const u32x4*>(xs + t * a.d_in + kk) : u32x4(0u);
+                r.rg[i] = (t < t_end && kk < a.d_out) ? *reinterpret_cast<const u32x4*>(gs + t * a.d_out + kk) : u32x4(0u);
+                r.rpi[i] = ((uint32_t)row < a.k_in && kk < a.d_in)
+                               ? *reinterpret_cast<const u32x4*>(a.pin + (uint64_t)row * a.d_in + kk) : u32x4(0u);
+                r.rpo[i] = ((uint32_t)row < a.k_out && kk < a.d_out)
+                               ? *reinterpret_cast<const u32x4*>(a.pout + (uint64_t)row * a.d_out + kk) : u32x4(0u);
             }
         };
-        auto stash = [&](int stage) {
+        auto stash = [&](const RegSet& r, int stage) {
             uint16_t* base = lds + stage * kLograStage;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
                 const int off = (srow + RSTEP * i) * LRS + skc * 8;
-                *reinterpret_cast<u32x4*>(base + off) = rx[i];
-                *reinterpret_cast<u32x4*>(base + kTileElems + off) = rg[i];
-                *reinterpret_cast<u32x4*>(base + 2 * kTileElems + off) = rpi[i];
-                *reinterpret_cast<u32x4*>(base + 3 * kTileElems + off) = rpo[i];
+                *reinterpret_cast<u32x4*>(base + off) = r.rx[i];
+                *reinterpret_cast<u32x4*>(base + kTileElems + off) = r.rg[i];
+                *reinterpret_cast<u32x4*>(base + 2 * kTileElems + off) = r.rpi[i];
+                *reinterpret_cast<u32x4*>(base + 3 * kTileElems + off) = r.rpo[i];
             }
         };
 
@@ -98,14 +98,7 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc1[j][v] = 0.0f;
-
-        __syncthreads();                                // stage-2 reads of the previous token tile are done
-        fetch(0);
-        stash(0);
-        __syncthreads();
-        for (uint32_t sl = 0; sl < nslices; ++sl) {
-            const int cur = sl & 1;
-            if (sl + 1 < nslices) fetch((sl + 1) * LK);
+        auto multiply = [&](int cur, uint32_t sl) {
             // operand tiles of this wavefront: tokens (X or G) and projection rows (P_in or P_out)
             const uint16_t* tok = lds + cur * kLograStage + wg * kTileElems + (wh * 32 + (lane & 31)) * LRS + (lane >> 5) * 8;
             const uint16_t* prj = lds + cur * kLograStage + (2 + wg) * kTileElems + (lane & 31) * LRS + (lane >> 5) * 8;
@@ -121,7 +114,26 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
                     }
                 }
             }
-            if (sl + 1 < nslices) stash(cur ^ 1);
+        };
+
+        // Two K slices are in flight in registers behind the one being multiplied (set B holds the odd slices, set A
+        // the even ones); loads complete in order, so storing slice s+1 to LDS waits for that slice only.
+        RegSet A, B;
+        __syncthreads();                                // stage-2 reads of the previous token tile are done
+        fetch(A, 0);
+        stash(A, 0);
+        if (nslices > 1) fetch(B, LK);
+        if (nslices > 2) fetch(A, 2 * LK);
+        __syncthreads();
+        for (uint32_t sl = 0; sl < nslices; sl += 2) {
+            multiply(0, sl);                            // stage 0: slice sl
+            if (sl + 1 < nslices) stash(B, 1);
+            if (sl + 3 < nslices) fetch(B, (sl + 3) * LK);
+            __syncthreads();
+            if (sl + 1 >= nslices) break;
+            multiply(1, sl + 1);                        // stage 1: slice sl + 1
+            if (sl + 2 < nslices) stash(A, 0);
+            if (sl + 4 < nslices) fetch(A, (sl + 4) * LK);
             __syncthreads();
         }
 
