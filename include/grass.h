@@ -295,6 +295,25 @@ grass_status grass_selective_mask_grad(const float* G, uint64_t n, uint64_t ldg,
                                        double lambda, double temperature,
                                        float* grad, double* objective,
                                        void* ws, size_t ws_bytes, grass_stream stream);
+/* Factorised form for one linear layer (App. B.4 "Linear Layer", one token per
+ * sample as in the paper's formula): per-sample gradients are z_in (x) z_out,
+ * the mask is sigma(S_in) (x) sigma(S_out), the penalty lambda * (|sigma(S_in)|_1
+ * + |sigma(S_out)|_1).  Z_in n x d_in, Z_out n x d_out (train), Zt_in m x d_in,
+ * Zt_out m x d_out (test), A[t][i] = <zt_in_t, z_in_i> * <zt_out_t, z_out_i>
+ * (two grass_score calls and a product).  grad_in (d_in) and grad_out (d_out)
+ * receive d objective / d S_in and d S_out.  The layer gradient is never formed. */
+grass_status grass_selective_mask_grad_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
+                                                                  uint64_t d_out, size_t* host_bytes);
+grass_status grass_selective_mask_grad_factorized(const float* Z_in, const float* Z_out, uint64_t n,
+                                                  uint64_t ld_zin, uint64_t ld_zout,
+                                                  const float* Zt_in, const float* Zt_out, uint64_t m,
+                                                  uint64_t ld_ztin, uint64_t ld_ztout,
+                                                  uint64_t d_in, uint64_t d_out,
+                                                  const float* A, uint64_t lda,
+                                                  const float* S_in, const float* S_out,
+                                                  double lambda, double temperature,
+                                                  float* grad_in, float* grad_out, double* objective,
+                                                  void* ws, size_t ws_bytes, grass_stream stream);
 grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* host_bytes);
 grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
                                           uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream);

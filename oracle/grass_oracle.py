@@ -341,6 +341,34 @@ def selective_mask_gradient(S, G, Gt, lam: float, temperature: float = 1.0) -> n
     return grad_w * 2.0 * sig * dsig - lam * dsig
 
 
+def selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam: float, temperature: float = 1.0):
+    """Factorised Selective Mask of a linear layer (App. B.4 "Linear Layer"): gradients are z_in (x) z_out, the mask is
+    sigma(S_in) (x) sigma(S_out), the penalty lam * (|sigma(S_in)|_1 + |sigma(S_out)|_1), and every inner product of
+    Kronecker products factorises, <a (x) b, c (x) d> = <a, c> <b, d>.  One token per sample, as in the paper's formula.
+    Returns (objective, d objective / d S_in, d objective / d S_out)."""
+    S_in, S_out = np.asarray(S_in, np.float64), np.asarray(S_out, np.float64)
+    Z_in, Z_out = np.asarray(Z_in, np.float64), np.asarray(Z_out, np.float64)
+    Zt_in, Zt_out = np.asarray(Zt_in, np.float64), np.asarray(Zt_out, np.float64)
+    si, so = _sigmoid(S_in / temperature), _sigmoid(S_out / temperature)
+    dsi, dso = si * (1 - si) / temperature, so * (1 - so) / temperature
+    m = Zt_in.shape[0]
+    total, gi, go = 0.0, np.zeros_like(S_in), np.zeros_like(S_out)
+    for t in range(m):
+        exact = (Z_in @ Zt_in[t]) * (Z_out @ Zt_out[t])
+        b_in = (Z_in * si) @ (Zt_in[t] * si)
+        b_out = (Z_out * so) @ (Zt_out[t] * so)
+        masked = b_in * b_out
+        da, db = exact - exact.mean(), masked - masked.mean()
+        na, nb = np.sqrt(da @ da), np.sqrt(db @ db)
+        corr = (da @ db) / (na * nb)
+        total += corr
+        c = da / (na * nb) - corr * db / (nb * nb)
+        gi += ((c * b_out) @ Z_in) * Zt_in[t]              # d masked_i / d w_in_j = b_out_i Z_in[i, j] Zt_in[t, j]
+        go += ((c * b_in) @ Z_out) * Zt_out[t]
+    obj = total / m - lam * (si.sum() + so.sum())
+    return obj, gi / m * 2 * si * dsi - lam * dsi, go / m * 2 * so * dso - lam * dso
+
+
 def selective_mask_indices(S, k: int | None = None) -> np.ndarray:
     """Index extraction (Sec. 3.2): all j with sigma(S_j) >= 1/2, i.e. S_j >= 0, ascending.  With k given, the
     'ensuring exact k' rule of App. B.4: the k largest logits (ties towards the smaller index), ascending."""

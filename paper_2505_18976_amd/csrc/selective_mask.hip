@@ -96,13 +96,25 @@ __global__ void __launch_bounds__(256) sm_grad_kernel(const float* Gt, uint64_t 
     grad[j] = (float)(2.0 * (double)sig * (double)dsig * acc - (double)lambda * (double)dsig);
 }
 
+// out[t][i] = x[t][i] * y[t][i] for i < n_valid and 0 for n_valid <= i < n (row distance ld for all three): the
+// padding columns of the workspace matrices may hold anything, the product must not.
+__global__ void __launch_bounds__(256) sm_hadamard_kernel(const float* x, const float* y, float* out, uint64_t m, uint64_t n,
+                                                         uint64_t n_valid, uint64_t ld) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= m * n) return;
+    const uint64_t r = t / n, c = t - r * n;
+    out[r * ld + c] = c < n_valid ? x[r * ld + c] * y[r * ld + c] : 0.0f;
+}
+
 // objective = mean of corr - lambda * sum of the sigma partial sums; one workgroup, fixed order.
 __global__ void __launch_bounds__(256) sm_objective_kernel(const double* corr, uint64_t m, const double* sig_part,
-                                                          uint64_t parts, double lambda, double* objective) {
+                                                          uint64_t parts, const double* sig_part2, uint64_t parts2,
+                                                          double lambda, double* objective) {
     __shared__ double red[256];
     double c = 0.0, s = 0.0;
     for (uint64_t i = threadIdx.x; i < m; i += 256) c += corr[i];
     for (uint64_t i = threadIdx.x; i < parts; i += 256) s += sig_part[i];
+    for (uint64_t i = threadIdx.x; i < parts2; i += 256) s += sig_part2[i];
     c = block_sum(c, red);
     s = block_sum(s, red);
     if (threadIdx.x == 0) *objective = c / (double)m - lambda * s;
@@ -113,6 +125,7 @@ struct SmLayout {
     size_t off_gtw, off_b, off_c, off_corr, off_sig, off_gt, off_r, off_part, total;
 };
 static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
+// p: the widest factor the workspace has to serve.
 static SmLayout sm_layout(uint64_t n, uint64_t m, uint64_t p) {
     SmLayout L;
     L.ld_w = (p + 3) / 4 * 4;
@@ -137,6 +150,46 @@ static SmLayout sm_layout(uint64_t n, uint64_t m, uint64_t p) {
     if (ceil_div(m, 128) * ceil_div(n, 128) < 1024) o += up256((size_t)kSmMaxSplits * m * n * 4);
     L.total = o;
     return L;
+}
+
+// B (m x n, row distance n_pad) = (Gt * sigma^2) G^T; sig_part receives the per-block sums of sigma.
+static grass_status sm_masked_scores(const SmLayout& L, unsigned char* base, const float* G, uint64_t n, uint64_t ldg,
+                                     const float* Gt, uint64_t m, uint64_t ldgt, uint64_t p, const float* S, float inv_temp,
+                                     float* B, double* sig_part, hipStream_t hs) {
+    float* Gtw = reinterpret_cast<float*>(base + L.off_gtw);
+    const uint64_t ld_w = (p + 3) / 4 * 4;
+    hipLaunchKernelGGL(sm_weight_kernel, dim3((uint32_t)ceil_div(ld_w, 256)), dim3(256), 0, hs, Gt, ldgt, m, p, S, inv_temp, Gtw,
+                       ld_w, sig_part);
+    uint32_t splits = 1;
+    if (ceil_div(m, 128) * ceil_div(n, 128) < 1024) splits = gemm_nt_f32_splits(Gtw, G, m, n, p, ld_w, ldg, kSmMaxSplits);
+    if (splits > 1) {
+        float* partials = reinterpret_cast<float*>(base + L.off_part);
+        if (gemm_nt_f32(Gtw, G, nullptr, m, n, p, ld_w, ldg, n, 0, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
+        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(m * n, 256)), dim3(256), 0, hs, partials, m,
+                           (uint32_t)n, splits, 1.0f, B, L.n_pad);
+    } else if (gemm_nt_f32(Gtw, G, B, m, n, p, ld_w, ldg, L.n_pad, 0, 0, hs, 1, nullptr) != hipSuccess) {
+        return GRASS_EHIP;
+    }
+    return GRASS_OK;
+}
+
+// grad[j] = 2 sigma_j sigma_j' sum_t Gt[t][j] (C G)[t][j] - lambda sigma_j' for all p columns, G transposed in chunks.
+static grass_status sm_backward(const SmLayout& L, unsigned char* base, const float* G, uint64_t n, uint64_t ldg,
+                                const float* Gt, uint64_t m, uint64_t ldgt, uint64_t p, const float* S, float inv_temp,
+                                float lambda, const float* C, float* grad, hipStream_t hs) {
+    float* GTc = reinterpret_cast<float*>(base + L.off_gt);
+    float* Rc = reinterpret_cast<float*>(base + L.off_r);
+    for (uint64_t j0 = 0; j0 < p; j0 += L.pc) {
+        const uint64_t pc = j0 + L.pc <= p ? L.pc : p - j0;
+        // GTc (pc x n_pad) = transpose of the column block [j0, j0 + pc) of G
+        hipLaunchKernelGGL(transpose_rows_kernel, dim3((uint32_t)ceil_div(pc, 64), (uint32_t)ceil_div(L.n_pad, 64)), dim3(256), 0,
+                           hs, G + j0, ldg, (uint64_t)0, (uint32_t)n, (uint32_t)L.n_pad, (uint32_t)pc, GTc, L.n_pad);
+        if (gemm_nt_f32(C, GTc, Rc, m, pc, L.n_pad, L.n_pad, L.n_pad, L.pc, 0, 0, hs, 1, nullptr) != hipSuccess)
+            return GRASS_EHIP;
+        hipLaunchKernelGGL(sm_grad_kernel, dim3((uint32_t)ceil_div(pc, 256)), dim3(256), 0, hs, Gt, ldgt, m, Rc, L.pc, j0, pc,
+                           S, inv_temp, lambda, grad);
+    }
+    return GRASS_OK;
 }
 
 }  // namespace grass
@@ -169,41 +222,85 @@ extern "C" grass_status grass_selective_mask_grad(const float* G, uint64_t n, ui
     const SmLayout L = sm_layout(n, m, p);
     if (!ws || ws_bytes < L.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
     unsigned char* base = static_cast<unsigned char*>(ws);
-    float* Gtw = reinterpret_cast<float*>(base + L.off_gtw);
     float* B = reinterpret_cast<float*>(base + L.off_b);
     float* C = reinterpret_cast<float*>(base + L.off_c);
     double* corr = reinterpret_cast<double*>(base + L.off_corr);
     double* sig_part = reinterpret_cast<double*>(base + L.off_sig);
-    float* GTc = reinterpret_cast<float*>(base + L.off_gt);
-    float* Rc = reinterpret_cast<float*>(base + L.off_r);
     hipStream_t hs = as_stream(stream);
     const float inv_temp = (float)(1.0 / temperature);
 
-    hipLaunchKernelGGL(sm_weight_kernel, dim3((uint32_t)L.parts), dim3(256), 0, hs, Gt, ldgt, m, p, S, inv_temp, Gtw, L.ld_w,
-                       sig_part);
-    uint32_t splits = 1;
-    if (ceil_div(m, 128) * ceil_div(n, 128) < 1024) splits = gemm_nt_f32_splits(Gtw, G, m, n, p, L.ld_w, ldg, kSmMaxSplits);
-    if (splits > 1) {
-        float* partials = reinterpret_cast<float*>(base + L.off_part);
-        if (gemm_nt_f32(Gtw, G, nullptr, m, n, p, L.ld_w, ldg, n, 0, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
-        hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(m * n, 256)), dim3(256), 0, hs, partials, m,
-                           (uint32_t)n, splits, 1.0f, B, L.n_pad);
-    } else if (gemm_nt_f32(Gtw, G, B, m, n, p, L.ld_w, ldg, L.n_pad, 0, 0, hs, 1, nullptr) != hipSuccess) {
-        return GRASS_EHIP;
-    }
+    st = sm_masked_scores(L, base, G, n, ldg, Gt, m, ldgt, p, S, inv_temp, B, sig_part, hs);
+    if (st != GRASS_OK) return st;
     hipLaunchKernelGGL(sm_corr_kernel, dim3((uint32_t)m), dim3(256), 0, hs, A, lda, B, L.n_pad, n, m, C, L.n_pad, corr);
-    for (uint64_t j0 = 0; j0 < p; j0 += L.pc) {
-        const uint64_t pc = j0 + L.pc <= p ? L.pc : p - j0;
-        // GTc (pc x n_pad) = transpose of the column block [j0, j0 + pc) of G
-        hipLaunchKernelGGL(transpose_rows_kernel, dim3((uint32_t)ceil_div(pc, 64), (uint32_t)(L.n_pad / 64 + (L.n_pad % 64 != 0))),
-                           dim3(256), 0, hs, G + j0, ldg, (uint64_t)0, (uint32_t)n, (uint32_t)L.n_pad, (uint32_t)pc, GTc,
-                           L.n_pad);
-        if (gemm_nt_f32(C, GTc, Rc, m, pc, L.n_pad, L.n_pad, L.n_pad, L.pc, 0, 0, hs, 1, nullptr) != hipSuccess)
-            return GRASS_EHIP;
-        hipLaunchKernelGGL(sm_grad_kernel, dim3((uint32_t)ceil_div(pc, 256)), dim3(256), 0, hs, Gt, ldgt, m, Rc, L.pc, j0, pc,
-                           S, inv_temp, (float)lambda, grad);
-    }
+    st = sm_backward(L, base, G, n, ldg, Gt, m, ldgt, p, S, inv_temp, (float)lambda, C, grad, hs);
+    if (st != GRASS_OK) return st;
     if (objective)
-        hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_part, L.parts, lambda, objective);
+        hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_part, ceil_div((p + 3) / 4 * 4, 256),
+                           (const double*)nullptr, (uint64_t)0, lambda, objective);
+    return launch_status();
+}
+
+// Factorised form for a linear layer (App. B.4 "Linear Layer"): gradients z_in (x) z_out, mask sigma(S_in) (x) sigma(S_out),
+// <a (x) b, c (x) d> = <a, c><b, d>, so the masked scores are the elementwise product of the two factors' masked scores
+// and each factor's gradient is the plain backward pass with C multiplied by the other factor's masked scores.
+extern "C" grass_status grass_selective_mask_grad_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
+                                                                             uint64_t d_out, size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    const uint64_t p = d_in > d_out ? d_in : d_out;
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK || d_in == 0 || d_out == 0) return st != GRASS_OK ? st : GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, p);
+    // + B_out, C_in / C_out scratch and the second factor's sigma partial sums
+    *host_bytes = L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_selective_mask_grad_factorized(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
+    uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature, float* grad_in, float* grad_out,
+    double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
+    const uint64_t p = d_in > d_out ? d_in : d_out;
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK) return st;
+    if (d_in == 0 || d_out == 0 || !Z_in || !Z_out || !Zt_in || !Zt_out || !A || !S_in || !S_out || !grad_in || !grad_out)
+        return GRASS_EINVAL;
+    if (ld_zin < d_in || ld_ztin < d_in || ld_zout < d_out || ld_ztout < d_out || lda < n) return GRASS_EINVAL;
+    if (!(temperature > 0.0) || !(lambda >= 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, p);
+    const size_t extra_b = up256((size_t)m * L.n_pad * 4);
+    const size_t need = L.total + 2 * extra_b + up256((size_t)L.parts * 8);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* B_in = reinterpret_cast<float*>(base + L.off_b);
+    float* C = reinterpret_cast<float*>(base + L.off_c);
+    double* corr = reinterpret_cast<double*>(base + L.off_corr);
+    double* sig_in = reinterpret_cast<double*>(base + L.off_sig);
+    float* B_out = reinterpret_cast<float*>(base + L.total);
+    float* Cx = reinterpret_cast<float*>(base + L.total + extra_b);
+    double* sig_out = reinterpret_cast<double*>(base + L.total + 2 * extra_b);
+    hipStream_t hs = as_stream(stream);
+    const float inv_temp = (float)(1.0 / temperature);
+    const uint32_t eb = (uint32_t)ceil_div(m * n, 256);
+
+    st = sm_masked_scores(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, B_in, sig_in, hs);
+    if (st != GRASS_OK) return st;
+    st = sm_masked_scores(L, base, Z_out, n, ld_zout, Zt_out, m, ld_ztout, d_out, S_out, inv_temp, B_out, sig_out, hs);
+    if (st != GRASS_OK) return st;
+    // masked scores of the Kronecker gradients, their correlation with A and the row c
+    hipLaunchKernelGGL(sm_hadamard_kernel, dim3(eb), dim3(256), 0, hs, B_in, B_out, Cx, m, n, n, L.n_pad);
+    hipLaunchKernelGGL(sm_corr_kernel, dim3((uint32_t)m), dim3(256), 0, hs, A, lda, Cx, L.n_pad, n, m, C, L.n_pad, corr);
+    // input factor: C * B_out (padding columns of C are zero and stay zero)
+    hipLaunchKernelGGL(sm_hadamard_kernel, dim3((uint32_t)ceil_div(m * L.n_pad, 256)), dim3(256), 0, hs, C, B_out, Cx, m,
+                       L.n_pad, n, L.n_pad);
+    st = sm_backward(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, (float)lambda, Cx, grad_in, hs);
+    if (st != GRASS_OK) return st;
+    hipLaunchKernelGGL(sm_hadamard_kernel, dim3((uint32_t)ceil_div(m * L.n_pad, 256)), dim3(256), 0, hs, C, B_in, Cx, m,
+                       L.n_pad, n, L.n_pad);
+    st = sm_backward(L, base, Z_out, n, ld_zout, Zt_out, m, ld_ztout, d_out, S_out, inv_temp, (float)lambda, Cx, grad_out, hs);
+    if (st != GRASS_OK) return st;
+    if (objective)
+        hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_in, ceil_div((d_in + 3) / 4 * 4, 256),
+                           (const double*)sig_out, ceil_div((d_out + 3) / 4 * 4, 256), lambda, objective);
     return launch_status();
 }

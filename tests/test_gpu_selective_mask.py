@@ -88,6 +88,28 @@ def test_selective_mask_ascent_step_improves_the_objective(grass):
     assert float(obj1.item()) > float(obj0.item())
 
 
+@pytest.mark.parametrize("n,m,d_in,d_out,lam,temp", [(8, 3, 5, 4, 0.05, 1.0), (60, 7, 300, 129, 0.01, 0.7),
+                                                      (200, 130, 1024, 4096, 1e-3, 1.0), (150, 129, 2050, 513, 1e-4, 2.0)])
+def test_selective_mask_factorized_parity(grass, n, m, d_in, d_out, lam, temp):
+    """App. B.4 "Linear Layer": Kronecker gradients, factor masks; the layer gradient (d_in * d_out wide) is never formed."""
+    Z_in = synth.dense_normal(n, d_in, seed=3600, device=_dev())
+    Z_out = synth.dense_normal(n, d_out, seed=3601, device=_dev())
+    Zt_in = synth.dense_normal(m, d_in, seed=3602, device=_dev())
+    Zt_out = synth.dense_normal(m, d_out, seed=3603, device=_dev())
+    S_in = synth.dense_normal(1, d_in, seed=3604, device=_dev(), std=1.5).reshape(-1).contiguous()
+    S_out = synth.dense_normal(1, d_out, seed=3605, device=_dev(), std=1.5).reshape(-1).contiguous()
+    A = (grass.grass_score(Z_in, Zt_in) * grass.grass_score(Z_out, Zt_out)).contiguous()
+    gi, go, obj = grass.grass_selective_mask_grad_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam, temp)
+    torch.cuda.synchronize()
+    h = lambda t: t.cpu().numpy()
+    want_obj, want_gi, want_go = orc.selective_mask_factorized(h(S_in), h(S_out), h(Z_in), h(Z_out), h(Zt_in), h(Zt_out),
+                                                               lam, temp)
+    assert abs(float(obj.item()) - want_obj) <= 1e-5 * max(1.0, abs(want_obj))
+    assert np.abs(h(gi) - want_gi).max() <= 2e-4 * np.abs(want_gi).max()
+    assert np.abs(h(go) - want_go).max() <= 2e-4 * np.abs(want_go).max()
+    assert torch.isfinite(gi).all() and torch.isfinite(go).all()
+
+
 @pytest.mark.parametrize("p,k", [(1, 0), (1, 1), (10, 0), (10, 3), (5000, 0), (5000, 1234), (100003, 0), (100003, 4096),
                                  (100003, 100003)])
 def test_selective_mask_indices_bit_exact(grass, p, k):

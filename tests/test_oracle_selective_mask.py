@@ -90,3 +90,38 @@ def test_index_extraction():
     S = rng.standard_normal(50)
     want = sorted(sorted(range(50), key=lambda j: (-S[j], j))[:13])
     assert orc.selective_mask_indices(S, k=13).tolist() == want
+
+
+def _fact_problem(seed=0, n=8, m=3, d_in=5, d_out=4):
+    rng = np.random.default_rng(seed)
+    return (rng.standard_normal(d_in), rng.standard_normal(d_out), rng.standard_normal((n, d_in)),
+            rng.standard_normal((n, d_out)), rng.standard_normal((m, d_in)), rng.standard_normal((m, d_out)))
+
+
+def test_factorized_objective_equals_the_plain_one_on_kronecker_gradients():
+    """App. B.4: with g_i = z_in (x) z_out and mask sigma_in (x) sigma_out the correlation term is Eq. (1) itself."""
+    S_in, S_out, Z_in, Z_out, Zt_in, Zt_out = _fact_problem(1)
+    G = np.stack([np.kron(Z_in[i], Z_out[i]) for i in range(Z_in.shape[0])])
+    Gt = np.stack([np.kron(Zt_in[t], Zt_out[t]) for t in range(Zt_in.shape[0])])
+    sig = np.kron(1 / (1 + np.exp(-S_in)), 1 / (1 + np.exp(-S_out)))
+    S_full = np.log(sig / (1 - sig))                         # logits whose sigmoid is the Kronecker mask
+    plain = orc.selective_mask_objective(S_full, G, Gt, 0.0)
+    obj, _, _ = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, 0.0)
+    assert np.isclose(obj, plain, rtol=1e-11)
+    lam = 0.07
+    pen = lam * ((1 / (1 + np.exp(-S_in))).sum() + (1 / (1 + np.exp(-S_out))).sum())
+    assert np.isclose(orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam)[0], plain - pen, rtol=1e-11)
+
+
+@pytest.mark.parametrize("temperature,lam,seed", [(1.0, 0.0, 2), (0.7, 0.05, 3), (2.0, 0.2, 4)])
+def test_factorized_gradients_match_central_differences(temperature, lam, seed):
+    S_in, S_out, Z_in, Z_out, Zt_in, Zt_out = _fact_problem(seed, n=10, m=4, d_in=6, d_out=5)
+    _, gi, go = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, temperature)
+    f = lambda a, b: orc.selective_mask_factorized(a, b, Z_in, Z_out, Zt_in, Zt_out, lam, temperature)[0]
+    h = 1e-6
+    for j in range(S_in.size):
+        e = np.zeros_like(S_in); e[j] = h
+        assert np.isclose(gi[j], (f(S_in + e, S_out) - f(S_in - e, S_out)) / (2 * h), rtol=2e-6, atol=1e-9)
+    for j in range(S_out.size):
+        e = np.zeros_like(S_out); e[j] = h
+        assert np.isclose(go[j], (f(S_in, S_out + e) - f(S_in, S_out - e)) / (2 * h), rtol=2e-6, atol=1e-9)
