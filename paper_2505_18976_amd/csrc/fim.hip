@@ -54,58 +54,65 @@ __global__ void __launch_bounds__(256) fim_load_kernel(const float* F, uint64_t 
     X64[t] = 0.0;
 }
 
+// Value of lane `src` (a compile-time constant) of a double, as a wavefront-uniform scalar.
+__device__ __forceinline__ double lane_bcast(double v, int src) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), src);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), src);
+    return __hiloint2double(hi, lo);
+}
+
 // Cholesky factor of the NB x NB diagonal block j (lower, in place) and its inverse D = L_jj^{-1} into the
-// same block of X64 (zeros above the diagonal).  One workgroup.  A non-positive pivot records its 1-based
-// index in *info (first one wins) and is replaced by 1 so that the run stays finite.
-// Factor: one barrier per column; column c of L goes to a second array, so the rank-one update of step c can
-// read the unscaled column (a[r][q] -= a[r][c] a[q][c] / pivot) while it is written.  Lane = column q, the four
-// wavefronts take rows r = w, w+4, ...  Inverse: lane t of wavefront 0 solves L x = e_t with x in registers.
-__global__ void __launch_bounds__(256) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
-    __shared__ double a[NB][NB + 1];
-    __shared__ double l[NB][NB + 1];
-    __shared__ double rinv[NB];
-    const int tid = threadIdx.x, q = tid & 63, w = tid >> 6;
+// same block of X64 (zeros above the diagonal).  A non-positive pivot records its 1-based index in *info
+// (first one wins) and is replaced by 1 so that the run stays finite.
+// One wavefront, no LDS and no barriers: the column recurrence is a chain of dependent fp64 operations (32 cycles
+// each on this chip), so what matters is the length of that chain, not parallel width.  Lane r keeps row r of the
+// block in registers; in step c the pivot and the entries l[q][c] reach the other lanes through readlane, and the
+// trailing update a[r][q] -= l[r][c] l[q][c] is 63-c independent FMAs per lane.  The inverse is computed the same
+// way: lane t solves L x = e_t, the entries L[r][m] arriving by readlane from lane r.
+__global__ void __launch_bounds__(64) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
+    const int r = threadIdx.x;
     double* Ab = A64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
     double* Xb = X64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
-    for (int r = w; r < NB; r += 4) a[r][q] = Ab[(uint64_t)r * kp + q];
-    __syncthreads();
+    double a[NB], yv[NB];
+#pragma unroll
+    for (int q = 0; q < NB; ++q) a[q] = Ab[(uint64_t)r * kp + q];
+    int bad = 0;
+#pragma unroll
     for (int c = 0; c < NB; ++c) {
-        const double piv = a[c][c];
+        const double piv = lane_bcast(a[c], c);
         const bool ok = piv > 0.0;                                   // false for NaN too
+        if (!ok && bad == 0) bad = c + 1;
         const double pv = ok ? piv : 1.0;
-        // y = pivot^(-1/2): hardware estimate refined by two Newton steps (fp64 sqrt and divide cost hundreds of
-        // cycles each and sit on the critical path of every column)
-        double y = __builtin_amdgcn_rsq(pv);
+        double y = __builtin_amdgcn_rsq(pv);                         // pivot^(-1/2): estimate + two Newton steps
         y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
         y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
-        const double d = pv * y, inv = y * y;
-        if (tid == 0 && !ok && info) atomicCAS(info, 0, (int)(j * NB + c + 1));
-        if (w == 0 && q >= c) {
-            l[q][c] = q == c ? d : a[q][c] * y;
-            if (q == c) rinv[c] = y;
-        }
-        if (q > c) {
-            const double aqc = a[q][c] * inv;
-            int r0 = q > c + 1 ? q : c + 1;                          // rows r >= max(q, c+1), r = w mod 4
-            r0 += (w - r0) & 3;
-            for (int r = r0; r < NB; r += 4) a[r][q] -= a[r][c] * aqc;
-        }
-        __syncthreads();
+        yv[c] = y;
+        const double lc = r == c ? pv * y : (r > c ? a[c] * y : 0.0);
+        a[c] = lc;
+#pragma unroll
+        for (int q = c + 1; q < NB; ++q) a[q] = fma(-lc, lane_bcast(lc, q), a[q]);    // only rows r >= q are used later
     }
-    for (int r = w; r < NB; r += 4) Ab[(uint64_t)r * kp + q] = q <= r ? l[r][q] : 0.0;
-    if (w == 0) {
-        double x[NB];
+    if (r == 0 && bad != 0 && info) atomicCAS(info, 0, (int)(j * NB) + bad);
 #pragma unroll
-        for (int r = 0; r < NB; ++r) {
-            double acc[4] = {r == q ? 1.0 : 0.0, 0.0, 0.0, 0.0};
+    for (int q = 0; q < NB; ++q) Ab[(uint64_t)r * kp + q] = q <= r ? a[q] : 0.0;
+    // lane t = r: column t of the inverse
+    double x[NB];
 #pragma unroll
-            for (int m = 0; m < r; ++m) acc[m & 3] -= l[r][m] * x[m];
-            const double v = ((acc[0] + acc[1]) + (acc[2] + acc[3])) * rinv[r];
-            x[r] = r >= q ? v : 0.0;
+    for (int i = 0; i < NB; ++i) {
+        double acc0 = i == r ? 1.0 : 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+#pragma unroll
+        for (int m = 0; m < i; ++m) {
+            const double lim = lane_bcast(a[m], i);                  // L[i][m]
+            if ((m & 3) == 0) acc0 = fma(-lim, x[m], acc0);
+            else if ((m & 3) == 1) acc1 = fma(-lim, x[m], acc1);
+            else if ((m & 3) == 2) acc2 = fma(-lim, x[m], acc2);
+            else acc3 = fma(-lim, x[m], acc3);
         }
-#pragma unroll
-        for (int r = 0; r < NB; ++r) Xb[(uint64_t)r * kp + q] = x[r];
+        const double v = ((acc0 + acc1) + (acc2 + acc3)) * yv[i];
+        x[i] = i >= r ? v : 0.0;
     }
+#pragma unroll
+    for (int i = 0; i < NB; ++i) Xb[(uint64_t)i * kp + r] = x[i];
 }
 
 // C = alpha * A B + beta * C in fp64 with v_mfma_f64_16x16x4_f64.  A is M x K, B is K x N, C is M x N, each given
@@ -326,7 +333,7 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
 
     // right-looking blocked Cholesky: A = L L^T, L overwrites the lower triangle of A64
     for (uint32_t j = 0; j < nblk; ++j) {
-        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(256), 0, hs, A64, X64, kp, j, info);
+        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(64), 0, hs, A64, X64, kp, j, info);
         const uint32_t below = kp - (j + 1) * NB;
         if (below == 0) break;
         double* panel = A64 + (size_t)(j + 1) * NB * kp + (size_t)j * NB;
