@@ -152,3 +152,35 @@ def test_factgrass_llama_style_layers_and_score(grass):
     a = np.abs(test[te_rows].cpu().numpy().astype(np.float64))
     b = np.abs(train[tr_rows].cpu().numpy().astype(np.float64))
     assert np.all(np.abs(got - exact) <= (2.0 ** -8 + 2.0 ** -17 + 2.0 ** -20) * (a @ b.T))
+
+
+def test_calls_follow_the_callers_stream(grass):
+    """Every entry point enqueues on the stream it is given (torch's current stream in the binding): run a chain on a
+    side stream while the default stream is kept busy, and compare with the same chain on the default stream."""
+    n, p, kp, k = 64, 30000, 4000, 256
+    g = synth.bernoulli_sparse_normal(n, p, 0.5, 1.0, seed=1400, device=_dev())
+    x, go = synth.linear_layer_factors(4, 96, 256, 256, seed=1401, device=_dev())
+
+    def chain():
+        idx = grass.grass_mask_indices(1, 0, p, kp, device=_dev())
+        c = grass.grass_sjlt(g, k, 1, seed=1, stream_id=1, idx=idx)
+        W = grass.grass_fim_inverse(grass.grass_fim(c), 0.1)
+        s = grass.grass_score(grass.grass_ifvp(c, W), c)
+        ii = grass.grass_mask_indices(1, 16, 256, 64, device=_dev())
+        io = grass.grass_mask_indices(1, 17, 256, 64, device=_dev())
+        f = grass.factgrass_linear(x, go, ii, io, 512, 1, 1, 18)
+        return s, f
+
+    ref_s, ref_f = chain()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    busy = torch.empty(1 << 26, dtype=torch.float32, device=_dev())
+    with torch.cuda.stream(side):
+        side.wait_stream(torch.cuda.current_stream())
+    for _ in range(3):
+        busy.normal_()                                # default stream has work queued
+    with torch.cuda.stream(side):
+        s, f = chain()
+    side.synchronize()
+    assert torch.equal(s, ref_s) and torch.equal(f, ref_f)
+    torch.cuda.synchronize()
