@@ -99,7 +99,12 @@ grass_status grass_sjlt_tables(uint64_t seed, uint64_t stream_id, uint64_t d, ui
  * g: n x p fp32, ldg >= p.  kprime is ignored when idx == NULL.
  * out: n x k fp32, ldo >= k.  k <= GRASS_MAX_K.
  * Fastest when g and ldg are 16-byte aligned (ldg % 4 == 0); any alignment
- * of at least 4 bytes works.                                                 */
+ * of at least 4 bytes works.
+ * Workspace: partial sums of the column chunks, and for long unmasked inputs
+ * with s == 1 room for a per-call table of 16-bit (bucket, sign) entries.  A
+ * workspace that is too small for the partial sums is GRASS_EWORKSPACE; one
+ * that holds them but not the table is accepted and the call hashes every
+ * position instead (same result bit for bit, a few per cent slower).         */
 grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint32_t kprime_or_0,
                                         uint32_t k, uint32_t s, size_t* host_bytes);
 grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg,

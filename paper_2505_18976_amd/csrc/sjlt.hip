@@ -54,6 +54,7 @@ struct SjltArgs {
     uint32_t k, s, m;
     uint32_t shift;       // 32 - log2(m) when m is a power of two >= 2
     float scale;          // applied when writing directly
+    const uint16_t* table;  // MODE_TABLE: bucket | sign << 15 of every position (s == 1)
     uint32_t row_period;  // P: the rows of a workgroup are first + q*P (1 = consecutive rows)
     uint32_t align_lines; // unmasked, V == 4: start the vector loop on a 128-byte line
 };
@@ -74,15 +75,22 @@ __device__ __forceinline__ void lds_add(typename AccT<ACC>::type* addr, float v)
 
 // Adds the R values of one input position to their buckets.  z is the generator
 // state of the position's first non-zero, i.e. sub + (pos*s + 1)*gamma.
-// FAST: s == 1 and m a power of two >= 2 (bucket by shift, no loop over s).
-template <int R, int ACC, bool FAST>
+// How bucket and sign of a position are obtained:
+//   MODE_GENERAL  hash per non-zero, bucket by multiply-high (any s, any m);
+//   MODE_FAST     s == 1 and m a power of two >= 2: bucket by shift, no loop over s;
+//   MODE_TABLE    s == 1, unmasked, line-aligned rows: read from a table of 16-bit entries that the call builds first
+//                 (11 million positions cost 22 MB and a few microseconds).  Every row group re-evaluates the same p
+//                 hashes otherwise, and with 8 quarter-rate integer multiplies each they were 12 % of the launch
+//                 on the ResNet-scale input; the table is shared through L2 by the workgroups of an XCD.
+enum { MODE_GENERAL = 0, MODE_FAST = 1, MODE_TABLE = 2 };
+template <int R, int ACC, int MODE>
 __device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, const float (&v)[R], uint64_t z,
                                                  const SjltArgs& a) {
     bool any = false;
 #pragma unroll
     for (int r = 0; r < R; ++r) any |= (v[r] != 0.0f);
     if (!any) return;
-    if constexpr (FAST) {
+    if constexpr (MODE == MODE_FAST) {
         const uint64_t h = finalise(z);
         const uint32_t b = (uint32_t)(h >> 32) >> a.shift;
         const uint32_t sg = signbit_of(h);
@@ -102,6 +110,18 @@ __device__ __forceinline__ void scatter_position(typename AccT<ACC>::type* acc, 
                 if (v[r] != 0.0f) lds_add<ACC>(slot + (uint32_t)r * a.k, __uint_as_float(__float_as_uint(v[r]) ^ sg));
             }
         }
+    }
+}
+
+// The same with bucket and sign taken from a table entry.
+template <int R, int ACC>
+__device__ __forceinline__ void scatter_entry(typename AccT<ACC>::type* acc, const float (&v)[R], uint32_t e,
+                                              const SjltArgs& a) {
+    typename AccT<ACC>::type* slot = acc + (e & 0x7FFFu);
+    const uint32_t sg = (e >> 15) << 31;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (v[r] != 0.0f) lds_add<ACC>(slot + (uint32_t)r * a.k, __uint_as_float(__float_as_uint(v[r]) ^ sg));
     }
 }
 
@@ -135,8 +155,9 @@ __device__ __forceinline__ T stream_load(const T* p) { return __builtin_nontempo
 
 // R rows per workgroup, V positions per load (unmasked only), U loads in flight
 // per row and thread.
-template <typename T, int R, int V, int U, bool MASKED, int ACC, bool FAST>
+template <typename T, int R, int V, int U, bool MASKED, int ACC, int MODE>
 __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
+    constexpr int HMODE = MODE == MODE_TABLE ? MODE_GENERAL : MODE;   // hash path of the few scalar positions
     using acc_t = typename AccT<ACC>::type;
     extern __shared__ __align__(16) unsigned char smem[];
     acc_t* acc = reinterpret_cast<acc_t*>(smem);
@@ -180,7 +201,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     v[u][r] = (col[u] >= 0 && r < nrows) ? Elem<T>::f(stream_load(rowp[r] + col[u])) : 0.0f;
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) scatter_position<R, ACC, FAST>(acc, v[u], z + zstep * u, a);
+            for (int u = 0; u < U; ++u) scatter_position<R, ACC, HMODE>(acc, v[u], z + zstep * u, a);
         }
     } else {
         using VT = typename VecT<T, V>::type;
@@ -194,7 +215,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             float v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) v[r] = r < nrows ? Elem<T>::f(rowp[r][threadIdx.x]) : 0.0f;
-            scatter_position<R, ACC, FAST>(acc, v, a.sub + ((uint64_t)threadIdx.x * a.s + 1) * kGamma, a);
+            scatter_position<R, ACC, HMODE>(acc, v, a.sub + ((uint64_t)threadIdx.x * a.s + 1) * kGamma, a);
         }
         const uint64_t nvec = (vend - vbeg) / V;
         const uint64_t zstep = zpos * V * nt;
@@ -202,6 +223,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
         uint64_t z = a.sub + ((vbeg + vb * V) * a.s + 1) * kGamma;
         for (; vb < nvec; vb += (uint64_t)nt * U, z += zstep * U) {
             VT x[U][R];
+            typename VecT<uint16_t, V>::type te[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint64_t vi = vb + (uint64_t)u * nt;
@@ -211,6 +233,10 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                         x[u][r] = stream_load(reinterpret_cast<const VT*>(rowp[r] + vbeg + vi * V));
                     else
                         x[u][r] = VT{};
+                }
+                if constexpr (MODE == MODE_TABLE) {
+                    using TE = typename VecT<uint16_t, V>::type;
+                    te[u] = vi < nvec ? *reinterpret_cast<const TE*>(a.table + vbeg + vi * V) : TE{};
                 }
             }
 #pragma unroll
@@ -223,7 +249,13 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                     float v[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) v[r] = e[r][c];
-                    scatter_position<R, ACC, FAST>(acc, v, z + zstep * u + zpos * c, a);   // all-zero past nvec: skipped
+                    if constexpr (MODE == MODE_TABLE) {
+                        uint32_t e;
+                        if constexpr (V == 1) e = te[u]; else e = te[u][c];
+                        scatter_entry<R, ACC>(acc, v, e, a);
+                    } else {
+                        scatter_position<R, ACC, MODE>(acc, v, z + zstep * u + zpos * c, a);   // all-zero past nvec: skipped
+                    }
                 }
             }
         }
@@ -233,7 +265,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
             float v[R];
 #pragma unroll
             for (int r = 0; r < R; ++r) v[r] = r < nrows ? Elem<T>::f(rowp[r][tail]) : 0.0f;
-            scatter_position<R, ACC, FAST>(acc, v, a.sub + (tail * a.s + 1) * kGamma, a);
+            scatter_position<R, ACC, HMODE>(acc, v, a.sub + (tail * a.s + 1) * kGamma, a);
         }
     }
     __syncthreads();
@@ -245,10 +277,20 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
     }
 }
 
+// table[j] = bucket | sign << 15 of position j (s == 1, m = k <= 32768).
+__global__ void __launch_bounds__(256) sjlt_table_kernel(uint64_t sub, uint64_t d, uint32_t m, uint16_t* table) {
+    const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j >= d) return;
+    const uint64_t h = sm(sub, j);
+    table[j] = (uint16_t)(bucket_of(h, m) | (signbit_of(h) ? 0x8000u : 0u));
+}
+
 struct SjltPlan {
     int R, V, threads, acc;
     uint32_t row_period;      // P of the kernel's row mapping
     bool align_lines;
+    bool table;               // bucket/sign table in the workspace behind the partial sums (optional)
+    size_t table_offset, table_bytes;
     uint32_t chunks;
     uint64_t pos_per_chunk;
     size_t lds_bytes;
@@ -259,7 +301,7 @@ struct SjltPlan {
 // consecutive rows give the fewest row groups and so the most chunks, an upper bound for every layout.
 // in_bytes: 4 (fp32 input) or 2 (bf16 input).
 static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const void* g, uint64_t ldg,
-                      SjltPlan* pl, int force_v = 0, uint32_t in_bytes = 4) {
+                      SjltPlan* pl, int force_v = 0, uint32_t in_bytes = 4, uint32_t s = 1) {
     if ((size_t)k * 4 > 128 * 1024) return false;
     int acc = ACC_F64;
     if ((size_t)k * 8 > 128 * 1024) acc = ACC_CAS;            // fp64 buckets of one row no longer fit
@@ -321,12 +363,19 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     pl->pos_per_chunk = ppc;
     pl->lds_bytes = (size_t)R * k * esz;
     pl->ws_bytes = chunks > 1 ? (size_t)chunks * n * k * 4 : 0;
+    // the table pays when many row groups would repeat the same hashes over a long row.  Its conditions do not depend
+    // on the alignment of g, so that the workspace query (which does not know it) reserves the room; a call whose
+    // rows are not grouped by line offset, or whose workspace has no room for it, hashes as before.
+    pl->table = !masked && s == 1 && acc == ACC_F64 && k <= 32768 && d >= 65536 && ceil_div(n, R) >= 16;
+    pl->table_offset = (pl->ws_bytes + 255) / 256 * 256;
+    pl->table_bytes = pl->table ? d * sizeof(uint16_t) : 0;
+    if (!align_lines && force_v == 0) pl->table = false;
     return true;
 }
 
-template <typename T, int R, int V, int U, bool MASKED, int ACC, bool FAST>
+template <typename T, int R, int V, int U, bool MASKED, int ACC, int MODE>
 static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
-    auto kern = sjlt_kernel<T, R, V, U, MASKED, ACC, FAST>;
+    auto kern = sjlt_kernel<T, R, V, U, MASKED, ACC, MODE>;
     static bool attr_done = false;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -339,35 +388,38 @@ static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t 
     return hipGetLastError();
 }
 
-template <typename T, int R, int ACC, bool FAST>
+template <typename T, int R, int ACC, int MODE>
 static hipError_t launch_raf(const SjltArgs& a, const SjltPlan& pl, bool masked, hipStream_t st) {
-    if (masked) return launch_one<T, R, 1, (R >= 8 ? 2 : 4), true, ACC, FAST>(a, pl, st);
-    if constexpr (sizeof(T) == 4) {
-        switch (pl.V) {
-            case 4: return launch_one<T, R, 4, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
-            case 2: return launch_one<T, R, 2, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
-            default: return launch_one<T, R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
-        }
+    constexpr int VMAX = 16 / sizeof(T);
+    if constexpr (MODE == MODE_TABLE) {
+        return launch_one<T, R, VMAX, (R >= 8 ? 1 : 2), false, ACC, MODE>(a, pl, st);   // the plan guarantees V == VMAX
     } else {
-        if (pl.V == 8) return launch_one<T, R, 8, (R >= 8 ? 1 : 2), false, ACC, FAST>(a, pl, st);
-        return launch_one<T, R, 1, (R >= 8 ? 2 : 4), false, ACC, FAST>(a, pl, st);
+        if (masked) return launch_one<T, R, 1, (R >= 8 ? 2 : 4), true, ACC, MODE>(a, pl, st);
+        if (pl.V == VMAX) return launch_one<T, R, VMAX, (R >= 8 ? 1 : 2), false, ACC, MODE>(a, pl, st);
+        if constexpr (sizeof(T) == 4) {
+            if (pl.V == 2) return launch_one<T, R, 2, (R >= 8 ? 2 : 4), false, ACC, MODE>(a, pl, st);
+        }
+        return launch_one<T, R, 1, (R >= 8 ? 2 : 4), false, ACC, MODE>(a, pl, st);
     }
 }
 
 template <typename T, int R>
-static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, bool fast, hipStream_t st) {
+static hipError_t launch_r(const SjltArgs& a, const SjltPlan& pl, bool masked, int mode, hipStream_t st) {
+    if (mode == MODE_TABLE) return launch_raf<T, R, ACC_F64, MODE_TABLE>(a, pl, masked, st);
     if (pl.acc == ACC_CAS)
-        return fast ? launch_raf<T, R, ACC_CAS, true>(a, pl, masked, st) : launch_raf<T, R, ACC_CAS, false>(a, pl, masked, st);
-    return fast ? launch_raf<T, R, ACC_F64, true>(a, pl, masked, st) : launch_raf<T, R, ACC_F64, false>(a, pl, masked, st);
+        return mode == MODE_FAST ? launch_raf<T, R, ACC_CAS, MODE_FAST>(a, pl, masked, st)
+                                 : launch_raf<T, R, ACC_CAS, MODE_GENERAL>(a, pl, masked, st);
+    return mode == MODE_FAST ? launch_raf<T, R, ACC_F64, MODE_FAST>(a, pl, masked, st)
+                             : launch_raf<T, R, ACC_F64, MODE_GENERAL>(a, pl, masked, st);
 }
 
 template <typename T>
-static hipError_t launch_t(const SjltArgs& a, const SjltPlan& pl, bool masked, bool fast, hipStream_t st) {
+static hipError_t launch_t(const SjltArgs& a, const SjltPlan& pl, bool masked, int mode, hipStream_t st) {
     switch (pl.R) {
-        case 8: return launch_r<T, 8>(a, pl, masked, fast, st);
-        case 4: return launch_r<T, 4>(a, pl, masked, fast, st);
-        case 2: return launch_r<T, 2>(a, pl, masked, fast, st);
-        default: return launch_r<T, 1>(a, pl, masked, fast, st);
+        case 8: return launch_r<T, 8>(a, pl, masked, mode, st);
+        case 4: return launch_r<T, 4>(a, pl, masked, mode, st);
+        case 2: return launch_r<T, 2>(a, pl, masked, mode, st);
+        default: return launch_r<T, 1>(a, pl, masked, mode, st);
     }
 }
 
@@ -403,8 +455,9 @@ extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint3
     size_t worst = 0;
     for (int v = 1; v <= 4; v *= 2) {
         SjltPlan pl;
-        if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, nullptr, 0, &pl, v)) return GRASS_EUNSUPPORTED;
-        if (pl.ws_bytes > worst) worst = pl.ws_bytes;
+        if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, nullptr, 0, &pl, v, 4, s)) return GRASS_EUNSUPPORTED;
+        const size_t need = pl.table ? pl.table_offset + pl.table_bytes : pl.ws_bytes;
+        if (need > worst) worst = need;
     }
     *host_bytes = worst;
     return GRASS_OK;
@@ -421,21 +474,30 @@ static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint6
     if (n * ldg >= (1ull << 62)) return GRASS_EINVAL;
     const uint64_t d = masked ? kprime : p;
     SjltPlan pl;
-    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl, 0, in_bytes)) return GRASS_EUNSUPPORTED;
+    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl, 0, in_bytes, s)) return GRASS_EUNSUPPORTED;
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
 
     SjltArgs a;
     a.g = g; a.idx = idx; a.ldg = ldg; a.n = n; a.d = d;
     a.k = k; a.s = s; a.m = k / s;
     a.shift = 0;
-    bool fast = false;
+    int mode = MODE_GENERAL;
     if (s == 1 && a.m >= 2 && (a.m & (a.m - 1)) == 0) {
         uint32_t lg = 0;
         while ((1u << lg) < a.m) ++lg;
         a.shift = 32 - lg;
-        fast = true;
+        mode = MODE_FAST;
     }
     a.sub = substream(seed, stream_id);
+    a.table = nullptr;
+    hipStream_t hs = as_stream(stream);
+    if (pl.table && ws && aligned(ws, 256) && ws_bytes >= pl.table_offset + pl.table_bytes) {
+        uint16_t* table = reinterpret_cast<uint16_t*>(static_cast<char*>(ws) + pl.table_offset);
+        hipLaunchKernelGGL(sjlt_table_kernel, dim3((uint32_t)ceil_div(d, 256)), dim3(256), 0, hs, a.sub, d, a.m, table);
+        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+        a.table = table;
+        mode = MODE_TABLE;
+    }
     a.pos_per_chunk = pl.pos_per_chunk;
     a.row_period = pl.row_period;
     a.align_lines = pl.align_lines ? 1u : 0u;
@@ -445,8 +507,7 @@ static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint6
     } else {
         a.dst = static_cast<float*>(ws); a.ld_dst = k; a.chunk_stride = n * k; a.scale = 1.0f;
     }
-    hipStream_t hs = as_stream(stream);
-    const hipError_t e = in_bytes == 4 ? launch_t<float>(a, pl, masked, fast, hs) : launch_t<uint16_t>(a, pl, masked, fast, hs);
+    const hipError_t e = in_bytes == 4 ? launch_t<float>(a, pl, masked, mode, hs) : launch_t<uint16_t>(a, pl, masked, mode, hs);
     if (e != hipSuccess) return GRASS_EHIP;
     if (pl.chunks > 1) {
         const uint64_t total = n * k;

@@ -175,6 +175,41 @@ def test_sjlt_bf16_inputs(grass, n, d, pad, off, k, s, kp):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
+# Long unmasked rows with s = 1 and at least 16 groups of rows read bucket and sign from a 16-bit table that the call
+# builds in its workspace; the same call with a workspace that only holds the partial sums hashes per position.
+# Both must match the oracle, and each other bit for bit (same values added in the same order).
+TABLE_CASES = [
+    # n, d, pad, off, k, bf16
+    (130, 70001, 15, 0, 512, False),      # ld = 70016: P = 1, ragged tail of positions, 17 groups of 8 rows
+    (140, 66001, 31, 0, 1000, False),     # m not a power of two
+    (1100, 65537, 0, 0, 256, False),      # ld mod 32 = 1: P = 32
+    (70, 70001, 15, 3, 8192, False),      # 4 rows per group, lead-in of 29 positions, k of the headline
+    (40, 66000, 16, 0, 16384, False),     # 2 rows per group
+    (130, 70001, 15, 0, 512, True),
+    (150, 65600, 0, 5, 4096, True),       # bf16, lead-in of 59 positions
+]
+
+
+@pytest.mark.parametrize("n,d,pad,off,k,bf16", TABLE_CASES)
+def test_sjlt_bucket_table_path(grass, n, d, pad, off, k, bf16):
+    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
+    full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=29, device=_dev())
+    if bf16:
+        full = full.to(torch.bfloat16)
+    g = full[:, off:off + d]
+    fn = grass.grass_sjlt_bf16 if bf16 else grass.grass_sjlt
+    nbytes = grass.grass_sjlt_workspace_bytes(n, d, 0, k, 1)
+    assert nbytes >= 2 * d                                        # the query reserves the table
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=_dev())
+    out = fn(g, k, 1, seed=9, stream_id=1, ws=ws)
+    small = ws[:max(256, nbytes - 2 * d)]                         # partial sums only: no room for the table
+    plain = fn(g, k, 1, seed=9, stream_id=1, ws=small)
+    torch.cuda.synchronize()
+    ref = orc.sjlt(g.float().cpu().numpy(), k, 1, 9, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
+    assert torch.equal(out, plain)
+
+
 def test_sjlt_random_shapes_and_alignments(grass):
     """60 seeded random problems: shape, leading dimension, view offset, element type, mask, k and s all vary, so that
     every row period, lead-in length, vector width and chunk count of the planner is hit by something."""
