@@ -165,19 +165,22 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_bf16_nt_kernel(GemmBf16Args
 }
 
 // ---------------------------------------------------------------------------
-// Fast path (K a multiple of 32): the K slices travel HBM/L2 -> LDS directly
+// Fast path (K a multiple of 64 bytes): the operands travel HBM/L2 -> LDS directly
 // (global_load_lds_dwordx4: lane i of a wavefront deposits its 16 bytes at
-// LDS base + 16*i), so no registers are spent on staging and four LDS stages of
-// 32 KB keep two slices in flight behind the one being multiplied.  Rows are
-// stored unpadded (64 bytes); the 16-byte chunk kc of row r sits at position
-// kc ^ ((r >> 2) & 3), which makes the fragment reads of 16 consecutive rows hit
-// the 16 distinct 16-byte bank groups (with (r >> 1) the bank-conflict counter
-// showed every second LDS cycle of the kernel stalled).
-constexpr int kDmaStages = 4;
-constexpr int kDmaStageBytes = (TM + TN) * TK * 2;     // 32 KB
+// LDS base + 16*i), so no registers are spent on staging.  A stage holds 128
+// bytes (two 64-byte slices: 64 bf16 or 32 fp32) of each of the 512 tile rows,
+// and two stages of 64 KB alternate.  A wavefront load covers whole 128-byte
+// lines (with 64-byte rows every line was requested twice, one iteration apart)
+// and there is one barrier per 64 (32) k instead of per 32 (16): measured 4 to
+// 19 % faster than four stages of 64-byte rows, depending on shape and data.
+// Rows are stored unpadded; the
+// 16-byte chunk kc of row r sits at position kc ^ ((r >> 1) & 7), which makes the
+// fragment reads of 16 consecutive rows hit the 16 distinct 16-byte bank groups.
+constexpr int kDmaStages = 2;
+constexpr int kDmaStageBytes = (TM + TN) * 128;        // 64 KB
 
-__device__ __forceinline__ void wait_vmcnt_le4() { __builtin_amdgcn_s_waitcnt(0x0F74); }   // vmcnt<=4, others free
 __device__ __forceinline__ void wait_vmcnt_0() { __builtin_amdgcn_s_waitcnt(0x0F70); }     // vmcnt==0, others free
+__device__ __forceinline__ void wait_lgkmcnt_0() { __builtin_amdgcn_s_waitcnt(0xC07F); }   // lgkmcnt==0, others free
 // Workgroup barrier without the memory fence of __syncthreads(): the fence would
 // wait for every outstanding direct-to-LDS load, including the slices that are
 // meant to stay in flight.  Each wavefront waits for its own loads of the slice
@@ -236,14 +239,15 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     const uint64_t slice0 = (uint64_t)split * a.slices_per_split;
     a.C += split * a.split_stride_c;
 
-    // DMA map: the stage is 512 rows (A then B) = 32 groups of 16 rows; wavefront w moves groups 4w..4w+3,
-    // lane i moves row 16*group + i/4, LDS chunk position i%4, i.e. global chunk (i%4) ^ swizzle(row).
-    const unsigned char* gsrc[4];
+    // DMA map: a stage is 512 rows (A then B) of 128 bytes; wavefront w moves rows 64w..64w+63 with 8
+    // instructions of 8 rows; lane i moves row 8j + i/8, LDS chunk position i%8 = global chunk (i%8) ^ swizzle(row).
+    // In the half group that ends an odd number of slices the lanes of chunks 4..7 re-read chunks 0..3 (in
+    // bounds; their LDS data is never used).
+    const unsigned char* gsrc[8];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int grp = wave * 4 + j;
-        const int r = grp * 16 + (lane >> 2);                      // 0..511
-        const int kc = (lane & 3) ^ ((r >> 2) & 3);
+    for (int j = 0; j < 8; ++j) {
+        const int r = wave * 64 + j * 8 + (lane >> 3);             // 0..511
+        const int kc = (lane & 7) ^ ((r >> 1) & 7);
         if (r < TM) {
             const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
             gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16 +
@@ -254,26 +258,33 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
                       slice0 * 64;
         }
     }
-    auto dma = [&](uint64_t slice, int stage) {
-        unsigned char* base = smem + stage * kDmaStageBytes + wave * 4096;
+    const uint64_t nk_all = a.K / SK;         // 64-byte slices; K is a multiple of the slice width here
+    const uint64_t nsl = nk_all - slice0 < a.slices_per_split ? nk_all - slice0 : a.slices_per_split;   // >= 1
+    const uint64_t ng = (nsl + 1) / 2;        // groups of two slices = 128-byte rows
+    const bool half_tail = (nsl & 1) != 0;
+    const int upper = (lane >> 2) & 1;        // chunk >= 4 for even j, chunk < 4 for odd j
+    auto dma = [&](uint64_t group, int stage) {
+        unsigned char* base = smem + stage * kDmaStageBytes + wave * 8192;
+        const bool tail = half_tail && group == ng - 1;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + slice * 64),
+        for (int j = 0; j < 8; ++j) {
+            const int back = (tail && (upper ^ (j & 1))) ? 64 : 0;
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + group * 128 - back),
                                              reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
+        }
     };
 
-    // fragment addresses: row*64 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
-    const int fl = (lane >> 2) & 3;
-    const int koff0 = (((lane >> 5)) ^ fl) * 16, koff1 = ((2 + (lane >> 5)) ^ fl) * 16;
-    const int a_row = (wm * 128 + (lane & 31)) * 64;
-    const int b_row = (TM + wn * 64 + (lane & 31)) * 64;
+    // fragment addresses: row*128 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
+    const int fl = (lane >> 1) & 7;
+    const int a_row = (wm * 128 + (lane & 31)) * 128;
+    const int b_row = (TM + wn * 64 + (lane & 31)) * 128;
     struct RawFrags { u32x4 a[4], b[2]; };
     auto load_frags = [&](RawFrags& f, int stage, int ks) {
-        const unsigned char* base = smem + stage * kDmaStageBytes + (ks ? koff1 : koff0);
+        const unsigned char* base = smem + stage * kDmaStageBytes + (((2 * ks + (lane >> 5)) ^ fl) * 16);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 64);
+        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 128);
 #pragma unroll
-        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 64);
+        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 128);
     };
 
     f32x16 acc[4][2];
@@ -283,46 +294,50 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-    auto mma_half = [&](const RawFrags& f, int half) {       // rows 64*half .. 64*half+63 of the wavefront tile
+    auto mma = [&](const RawFrags& f) {
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const int ii = 2 * half + i;
                 if constexpr (F32) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(f.a[ii][e]),
-                                                                          __uint_as_float(f.b[j][e]), acc[ii][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(f.a[i][e]),
+                                                                         __uint_as_float(f.b[j][e]), acc[i][j], 0, 0, 0);
                 } else {
-                    acc[ii][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[ii]),
-                                                                         __builtin_bit_cast(bf16x8, f.b[j]), acc[ii][j],
-                                                                         0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
+                                                                        __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j],
+                                                                        0, 0, 0);
                 }
             }
     };
 
-    const uint64_t nk_all = a.K / SK;         // K is a multiple of the slice width here
-    const uint64_t nkt = nk_all - slice0 < a.slices_per_split ? nk_all - slice0 : a.slices_per_split;   // >= 1
-    // invariant at the top of iteration kt: slices <= kt+1 are in LDS and visible, slice kt+2 is in flight
+    // Two stages.  The barrier of group g sits before its last multiply step: by then every wavefront has all
+    // fragments of stage g in registers (the stage may be overwritten) and its own part of group g+1 has landed
+    // (the other stage may be read).  Behind it the loads of group g+2 are issued, the first fragments of group
+    // g+1 are requested, and the last step of group g covers their latency.
     dma(0, 0);
-    if (nkt > 1) dma(1, 1);
-    if (nkt > 2) { dma(2, 2); wait_vmcnt_le4(); } else { wait_vmcnt_0(); }
+    wait_vmcnt_0();
     bare_barrier();
+    if (ng > 1) dma(1, 1);
     RawFrags f0, f1;
     load_frags(f0, 0, 0);
-    for (uint64_t kt = 0; kt < nkt; ++kt) {
-        const int cur = (int)(kt & 3), nxt = (int)((kt + 1) & 3);
-        const bool issue = kt + 3 < nkt;
-        if (issue) dma(kt + 3, (int)((kt + 3) & 3));          // that stage was last read in iteration kt-1
+    for (uint64_t g = 0; g < ng; ++g) {
+        const int cur = (int)(g & 1);
         load_frags(f1, cur, 1);
-        mma_half(f0, 0);
-        mma_half(f0, 1);
-        mma_half(f1, 0);                                      // queued MFMA work hides the latency of the next reads
-        if (kt + 1 < nkt) load_frags(f0, nxt, 0);
-        mma_half(f1, 1);
-        if (issue) wait_vmcnt_le4(); else wait_vmcnt_0();     // this wavefront's part of slice kt+2 has landed
+        mma(f0);
+        if (!(half_tail && g == ng - 1)) {                       // uniform
+            load_frags(f0, cur, 2);
+            mma(f1);
+            load_frags(f1, cur, 3);
+            mma(f0);
+        }
+        wait_lgkmcnt_0();
+        wait_vmcnt_0();
         bare_barrier();
+        if (g + 2 < ng) dma(g + 2, cur);
+        if (g + 1 < ng) load_frags(f0, cur ^ 1, 0);
+        mma(f1);
     }
 
     const bool interior = m0 + TM <= a.M && n0 + TN <= a.N;     // uniform
@@ -363,7 +378,8 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
     uint64_t s = ceil_div(kNumCU, tiles);
     if (s > max_splits) s = max_splits;
     if (s > slices / 32) s = slices / 32;                         // at least 32 slices per range
-    const uint64_t sps = ceil_div(slices, s);
+    uint64_t sps = ceil_div(slices, s);
+    sps += sps & 1;                                                // ranges start on a 128-byte group
     return (uint32_t)ceil_div(slices, sps);                        // no empty range
 }
 
@@ -388,6 +404,7 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     if (splits < 1 || !partials) splits = 1;
     if (slices == 0 || splits > slices) return false;
     a.slices_per_split = (uint32_t)ceil_div(slices, splits);
+    if (splits > 1) a.slices_per_split += a.slices_per_split & 1;          // ranges start on a 128-byte group
     if (ceil_div(slices, a.slices_per_split) != splits) return false;      // every K range non-empty
     a.split_stride_c = 0;
     if (splits > 1) { a.C = partials; a.ldc = N; a.split_stride_c = M * N; }

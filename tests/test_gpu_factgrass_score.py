@@ -246,7 +246,8 @@ def test_logra_with_selection_matrices_matches_factgrass_mask_stage(grass):
 
 # ------------------------------------------------------------------- score
 SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70),
-               (200, 130, 8192), (130, 129, 12304), (129, 3, 5000)]      # few tiles, long K: split over K ranges
+               (200, 130, 8192), (130, 129, 12304), (129, 3, 5000),      # few tiles, long K: split over K ranges
+               (128, 128, 16), (256, 256, 48), (384, 130, 4112)]         # an odd number of 64-byte slices: half group last
 
 
 @pytest.mark.parametrize("N,M,K", SCORE_CASES)
@@ -267,7 +268,8 @@ def test_score_parity(grass, N, M, K, mode, with_ws):
         _check_bf16_mode(sc.cpu().numpy(), test.cpu().numpy(), train.cpu().numpy())
 
 
-BF16_SCORE_CASES = [(1, 1, 8), (300, 200, 1000), (256, 256, 64), (257, 255, 72), (1024, 512, 4096), (700, 1024, 136)]
+BF16_SCORE_CASES = [(1, 1, 8), (300, 200, 1000), (256, 256, 64), (257, 255, 72), (1024, 512, 4096), (700, 1024, 136),
+                    (256, 256, 32), (300, 260, 96), (384, 130, 4128)]       # odd numbers of 64-byte slices
 
 
 @pytest.mark.parametrize("N,M,K", BF16_SCORE_CASES)
