@@ -134,11 +134,18 @@ def sjlt_tables(seed: int, stream: int, d: int, k: int, s: int):
         sign   = +1 if the lowest bit of h is 0, else -1
     so that every column has exactly s non-zeros in distinct rows.
     """
+    return sjlt_entries(seed, stream, np.arange(d, dtype=np.uint64), k, s)
+
+
+def sjlt_entries(seed: int, stream: int, positions, k: int, s: int):
+    """The rows of `sjlt_tables` for the given input positions only (any
+    order, any subset): bucket[q, r], sign[q, r] of position positions[q]."""
     if s <= 0 or k <= 0 or k % s:
         raise ValueError("need s >= 1 dividing k")
     m = k // s
-    c = np.arange(d * s, dtype=np.uint64)
-    h = stream_hash(seed, stream, c).reshape(d, s)
+    j = _as_u64(positions).reshape(-1)
+    c = j[:, None] * _U64(s) + np.arange(s, dtype=np.uint64)[None, :]
+    h = stream_hash(seed, stream, c.reshape(-1)).reshape(j.size, s)
     hi = h >> _U64(32)
     within = (hi * _U64(m)) >> _U64(32)                      # < m, no overflow: hi, m < 2**32
     bucket = within + (np.arange(s, dtype=np.uint64) * _U64(m))[None, :]

@@ -154,6 +154,44 @@ def test_factgrass_llama_style_layers_and_score(grass):
     assert np.all(np.abs(got - exact) <= (2.0 ** -8 + 2.0 ** -17 + 2.0 ** -20) * (a @ b.T))
 
 
+def test_sjlt_at_the_largest_input_dimension(grass):
+    """p = 2**31 - 1, the largest the entry points accept (indices are int32): two rows of 8.6 GB, zero except for
+    a few thousand entries that include the first and the last position, so that the oracle needs the table entries
+    of those positions only.  Unmasked (s = 1 and 2) and through a mask that keeps the last coordinate."""
+    p, k = 2**31 - 1, 4096
+    rng = np.random.default_rng(77)
+    g = torch.zeros((2, p), dtype=torch.float32, device=_dev())
+    pos, val = [], []
+    for i in range(2):
+        j = np.unique(np.concatenate([[0, p - 1, p - 2, 2**30, 2**24 + 1], rng.integers(0, p, 3000)])).astype(np.int64)
+        v = rng.standard_normal(j.size).astype(np.float32)
+        g[i, torch.from_numpy(j).to(_dev())] = torch.from_numpy(v).to(_dev())
+        pos.append(j); val.append(v)
+    for s in (1, 2):
+        out = grass.grass_sjlt(g, k, s, seed=5, stream_id=1)
+        torch.cuda.synchronize()
+        ref = np.zeros((2, k))
+        for i in range(2):
+            bucket, sign = orc.sjlt_entries(5, 1, pos[i], k, s)
+            for r in range(s):
+                np.add.at(ref[i], bucket[:, r], sign[:, r] * val[i].astype(np.float64) / np.sqrt(s))
+        assert orc.max_rel_err(out.cpu().numpy(), ref) <= 1e-5, s
+    # fused mask: 6,000 kept coordinates, among them the first and last coordinates and every planted non-zero of row 0
+    keep = np.unique(np.concatenate([pos[0][:2500], [0, p - 1], rng.integers(0, p, 3500)])).astype(np.int32)
+    idx = torch.from_numpy(keep).to(_dev())
+    assert grass.grass_check_indices(idx, p)
+    out = grass.grass_sjlt(g, k, 1, seed=5, stream_id=1, idx=idx)
+    gathered = grass.grass_mask(g, idx)
+    torch.cuda.synchronize()
+    small = g[:, idx.long()].cpu().numpy()
+    assert np.array_equal(gathered.cpu().numpy(), small)
+    ref = orc.sjlt(small, k, 1, 5, 1)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= 1e-5
+    # one past the limit is refused before any launch
+    with pytest.raises(Exception):
+        grass.grass_sjlt_workspace_bytes(2, 2**31, 0, k, 1)
+
+
 def test_calls_follow_the_callers_stream(grass):
     """Every entry point enqueues on the stream it is given (torch's current stream in the binding): run a chain on a
     side stream while the default stream is kept busy, and compare with the same chain on the default stream."""

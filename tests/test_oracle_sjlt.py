@@ -52,6 +52,22 @@ def test_tables_brute_force_from_sequential_generator():
             assert sign[j, r] == (1 if h % 2 == 0 else -1)
 
 
+def test_entries_are_the_table_rows_of_the_asked_positions():
+    """Entries for a subset of positions (any order, beyond any table that fits in memory) are the rows of the full
+    table; at a position near 2**31 the hash counter j*s + r is taken in 64 bits (checked with Python integers)."""
+    d, k, s = 5000, 96, 3
+    bucket, sign = orc.sjlt_tables(11, 1, d, k, s)
+    pos = np.array([4999, 0, 17, 17, 2500], dtype=np.uint64)
+    b, g = orc.sjlt_entries(11, 1, pos, k, s)
+    assert np.array_equal(b, bucket[pos.astype(np.int64)]) and np.array_equal(g, sign[pos.astype(np.int64)])
+    j, m = 2**31 - 2, k // s
+    b, g = orc.sjlt_entries(11, 1, [j], k, s)
+    for r in range(s):
+        h = int(orc.stream_hash(11, 1, np.array([j * s + r], dtype=np.uint64))[0])
+        assert int(b[0, r]) == r * m + (((h >> 32) * m) >> 32)
+        assert int(g[0, r]) == (1 if h & 1 == 0 else -1)
+
+
 def test_tables_reject_s_not_dividing_k():
     with pytest.raises(ValueError):
         orc.sjlt_tables(0, 1, 10, 10, 3)
