@@ -192,6 +192,33 @@ def test_sjlt_at_the_largest_input_dimension(grass):
         grass.grass_sjlt_workspace_bytes(2, 2**31, 0, k, 1)
 
 
+def test_mask_indices_at_the_largest_input_dimension(grass):
+    """Random Mask over p = 2**31 - 1 coordinates.  The oracle cannot rank two billion keys in the time a test has, so
+    the result is checked through what defines it: k' ascending distinct indices in range whose keys (oracle hash of
+    exactly those indices) are all smaller than the key of every coordinate left out -- verified on four million
+    left-out coordinates, among them the neighbours of every kept one and both ends -- and whose largest key sits
+    where the k'-th order statistic of p uniform 64-bit keys must (k'/p of the key range, within 6 sigma)."""
+    p, kp, seed, stream = 2**31 - 1, 65536, 3, 0
+    idx = grass.grass_mask_indices(seed, stream, p, kp, device=_dev())
+    torch.cuda.synchronize()
+    assert grass.grass_check_indices(idx, p)
+    kept = idx.cpu().numpy().astype(np.int64)
+    assert kept.size == kp and np.all(np.diff(kept) > 0) and kept[0] >= 0 and kept[-1] < p
+    keys = orc.stream_hash(seed, stream, kept.astype(np.uint64))
+    T = int(keys.max())
+    rng = np.random.default_rng(5)
+    probe = np.unique(np.concatenate([rng.integers(0, p, 4_000_000), kept + 1, kept - 1, [0, 1, p - 2, p - 1]]))
+    probe = probe[(probe >= 0) & (probe < p)]
+    probe = np.setdiff1d(probe, kept)
+    other = orc.stream_hash(seed, stream, probe.astype(np.uint64))
+    assert int(other.min()) > T
+    frac = T / 2.0**64
+    assert abs(frac - kp / p) <= 6 * np.sqrt(kp) / p
+    # the same call at a small size agrees with the oracle's full ranking (same kernels, same launch path)
+    small = grass.grass_mask_indices(seed, stream, 100003, 777, device=_dev())
+    assert np.array_equal(small.cpu().numpy(), orc.mask_indices(seed, stream, 100003, 777))
+
+
 def test_calls_follow_the_callers_stream(grass):
     """Every entry point enqueues on the stream it is given (torch's current stream in the binding): run a chain on a
     side stream while the default stream is kept busy, and compare with the same chain on the default stream."""
