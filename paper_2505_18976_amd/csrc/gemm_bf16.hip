@@ -206,8 +206,8 @@ struct GemmDmaArgs {
     uint64_t M, N, K, lda, ldb, ldc;
     uint32_t tiles_m, tiles_n;
     int accumulate;       // C += instead of C =
-    uint32_t slices_per_split;   // split-K: workgroup (split, tile) contracts slices [split*sps, (split+1)*sps)
-    uint64_t split_stride_c;     //          into C + split*split_stride_c
+    uint32_t splits;             // split-K: workgroup (split, tile) contracts the 128-byte groups split, split + splits,
+    uint64_t split_stride_c;     //          split + 2*splits, ... of K into C + split*split_stride_c
     int lower_only;              // symmetric product: tiles strictly above the diagonal are skipped
 };
 
@@ -236,13 +236,19 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         tm = logical % a.tiles_m;
     }
     const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
-    const uint64_t slice0 = (uint64_t)split * a.slices_per_split;
     a.C += split * a.split_stride_c;
 
     // DMA map: a stage is 512 rows (A then B) of 128 bytes; wavefront w moves rows 64w..64w+63 with 8
     // instructions of 8 rows; lane i moves row 8j + i/8, LDS chunk position i%8 = global chunk (i%8) ^ swizzle(row).
     // In the half group that ends an odd number of slices the lanes of chunks 4..7 re-read chunks 0..3 (in
     // bounds; their LDS data is never used).
+    const uint64_t nk_all = a.K / SK;         // 64-byte slices; K is a multiple of the slice width here
+    // Groups of two slices = 128 bytes per row.  The K ranges of a split-K launch are interleaved group by group
+    // (split s takes groups s, s + splits, ...): all workgroups walk along the rows together and touch one
+    // narrow window of every row at a time, and no range boundary has to be rounded to a group.
+    const uint64_t ng_all = (nk_all + 1) / 2, gstride = a.splits;
+    const uint64_t ng = (ng_all - split + gstride - 1) / gstride;          // >= 1: the host keeps splits <= ng_all
+    const bool half_tail = (nk_all & 1) != 0 && (ng_all - 1) % gstride == split;   // this split owns the half group
     const unsigned char* gsrc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -251,17 +257,13 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         if (r < TM) {
             const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
             gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16 +
-                      slice0 * 64;
+                      (uint64_t)split * 128;
         } else {                                                    // their products are never stored
             const uint64_t row = n0 + (r - TM);
             gsrc[j] = static_cast<const unsigned char*>(a.B) + ((row < a.N ? row : a.N - 1) * a.ldb) * ESZ + kc * 16 +
-                      slice0 * 64;
+                      (uint64_t)split * 128;
         }
     }
-    const uint64_t nk_all = a.K / SK;         // 64-byte slices; K is a multiple of the slice width here
-    const uint64_t nsl = nk_all - slice0 < a.slices_per_split ? nk_all - slice0 : a.slices_per_split;   // >= 1
-    const uint64_t ng = (nsl + 1) / 2;        // groups of two slices = 128-byte rows
-    const bool half_tail = (nsl & 1) != 0;
     const int upper = (lane >> 2) & 1;        // chunk >= 4 for even j, chunk < 4 for odd j
     auto dma = [&](uint64_t group, int stage) {
         unsigned char* base = smem + stage * kDmaStageBytes + wave * 8192;
@@ -269,7 +271,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const int back = (tail && (upper ^ (j & 1))) ? 64 : 0;
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + group * 128 - back),
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + group * gstride * 128 - back),
                                              reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
         }
     };
@@ -364,10 +366,12 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         }
 }
 
-// Operands the direct-to-LDS kernel can take: whole 64-byte K slices, 16-byte aligned rows.
+// Operands the direct-to-LDS kernel can take: whole 64-byte K slices, 16-byte aligned rows.  (A variant with
+// 4-byte loads for rows of any alignment was measured at 92 TFLOP/s against 120-130 of this one, no better than the
+// register-staged kernel that takes such operands, and was dropped.)
 bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint64_t lda, uint64_t ldb) {
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
-    return K % sk == 0 && (lda * esz) % 16 == 0 && (ldb * esz) % 16 == 0 && aligned(A, 16) && aligned(B, 16);
+    return K > 0 && K % sk == 0 && (lda * esz) % 16 == 0 && (ldb * esz) % 16 == 0 && aligned(A, 16) && aligned(B, 16);
 }
 
 // Split-K factor that fills the chip when there are few output tiles: the number
@@ -378,9 +382,7 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
     uint64_t s = ceil_div(kNumCU, tiles);
     if (s > max_splits) s = max_splits;
     if (s > slices / 32) s = slices / 32;                         // at least 32 slices per range
-    uint64_t sps = ceil_div(slices, s);
-    sps += sps & 1;                                                // ranges start on a 128-byte group
-    return (uint32_t)ceil_div(slices, sps);                        // no empty range
+    return s < 2 ? 1 : (uint32_t)s;
 }
 
 // Host-side launch shared by the score GEMMs and the Gaussian baseline.  Returns
@@ -403,9 +405,8 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     const uint64_t slices = K / sk;
     if (splits < 1 || !partials) splits = 1;
     if (slices == 0 || splits > slices) return false;
-    a.slices_per_split = (uint32_t)ceil_div(slices, splits);
-    if (splits > 1) a.slices_per_split += a.slices_per_split & 1;          // ranges start on a 128-byte group
-    if (ceil_div(slices, a.slices_per_split) != splits) return false;      // every K range non-empty
+    if (splits > ceil_div(slices, 2)) return false;                        // every split gets at least one group
+    a.splits = splits;
     a.split_stride_c = 0;
     if (splits > 1) { a.C = partials; a.ldc = N; a.split_stride_c = M * N; }
     if (lower_only && a.tiles_m != a.tiles_n) return false;

@@ -323,6 +323,7 @@ using namespace grass;
 
 // Workspace plan of grass_score: bf16 copies of both operands (mode 1) and K-range partial sums when the M x N
 // output has too few tiles to fill the chip.
+constexpr uint32_t kScoreMaxSplits = 16;      // K ranges of a score product with few output tiles (16 tiles still fill 256 CUs)
 struct ScorePlan {
     uint64_t kp;               // K rounded up to whole 64-byte bf16 slices
     size_t off_test, off_train, off_part, total;
@@ -336,7 +337,7 @@ static ScorePlan score_plan(uint64_t N, uint64_t M, uint64_t K, int mode) {
     P.off_test = o;  if (mode == 1) o += up256s((size_t)M * P.kp * 2);
     P.off_train = o; if (mode == 1) o += up256s((size_t)N * P.kp * 2);
     P.may_split = ceil_div(M, 128) * ceil_div(N, 128) < 1024 && K >= 4096;
-    P.off_part = o;  if (P.may_split) o += up256s((size_t)8 * M * N * 4);
+    P.off_part = o;  if (P.may_split) o += up256s((size_t)kScoreMaxSplits * M * N * 4);
     P.total = o;
     return P;
 }
@@ -369,7 +370,7 @@ extern "C" grass_status grass_score(const float* train, const float* test, int c
         uint16_t* tr = reinterpret_cast<uint16_t*>(base + P.off_train);
         if (convert_to_bf16(test, M, K, P.kp, ld_test, te, P.kp, hs) != hipSuccess) return GRASS_EHIP;
         if (convert_to_bf16(train, N, K, P.kp, ld_train, tr, P.kp, hs) != hipSuccess) return GRASS_EHIP;
-        uint32_t splits = P.may_split ? gemm_dma_splits(M, N, P.kp, false, 8) : 1;
+        uint32_t splits = P.may_split ? gemm_dma_splits(M, N, P.kp, false, kScoreMaxSplits) : 1;
         float* partials = reinterpret_cast<float*>(base + P.off_part);
         hipError_t derr = hipSuccess;
         if (launch_gemm_dma(false, te, tr, scores, M, N, P.kp, P.kp, P.kp, ld_scores, 0, hs, &derr, splits,
@@ -383,7 +384,7 @@ extern "C" grass_status grass_score(const float* train, const float* test, int c
         // not reachable with the padded copies; fall through to the on-the-fly kernel
     }
     if (compute_mode == 0 && have_ws && P.may_split) {
-        const uint32_t splits = gemm_nt_f32_splits(test, train, M, N, K, ld_test, ld_train, 8);
+        const uint32_t splits = gemm_nt_f32_splits(test, train, M, N, K, ld_test, ld_train, kScoreMaxSplits);
         if (splits > 1) {
             float* partials = reinterpret_cast<float*>(base + P.off_part);
             if (launch_gemm(a, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
