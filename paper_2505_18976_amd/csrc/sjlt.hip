@@ -138,6 +138,9 @@ template <> struct Elem<uint16_t> {
 template <typename T, int V> struct VecT { typedef T type __attribute__((ext_vector_type(V))); };
 template <typename T> struct VecT<T, 1> { using type = T; };
 
+// V consecutive table entries; only the alignment of one entry may be assumed of its address.
+template <int V> struct alignas(2) TableVec { uint16_t e[V]; };
+
 template <typename T, int V>
 __device__ __forceinline__ void unpack(const typename VecT<T, V>::type& x, float* o) {
     if constexpr (V == 1) {
@@ -223,7 +226,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
         uint64_t z = a.sub + ((vbeg + vb * V) * a.s + 1) * kGamma;
         for (; vb < nvec; vb += (uint64_t)nt * U, z += zstep * U) {
             VT x[U][R];
-            typename VecT<uint16_t, V>::type te[U];
+            TableVec<V> te[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
                 const uint64_t vi = vb + (uint64_t)u * nt;
@@ -235,8 +238,8 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
                         x[u][r] = VT{};
                 }
                 if constexpr (MODE == MODE_TABLE) {
-                    using TE = typename VecT<uint16_t, V>::type;
-                    te[u] = vi < nvec ? *reinterpret_cast<const TE*>(a.table + vbeg + vi * V) : TE{};
+                    // the vector loop starts on a line of g, which is any position of the table: 2-byte aligned only
+                    te[u] = vi < nvec ? *reinterpret_cast<const TableVec<V>*>(a.table + vbeg + vi * V) : TableVec<V>{};
                 }
             }
 #pragma unroll
@@ -250,9 +253,7 @@ __global__ void __launch_bounds__(1024) sjlt_kernel(SjltArgs a) {
 #pragma unroll
                     for (int r = 0; r < R; ++r) v[r] = e[r][c];
                     if constexpr (MODE == MODE_TABLE) {
-                        uint32_t e;
-                        if constexpr (V == 1) e = te[u]; else e = te[u][c];
-                        scatter_entry<R, ACC>(acc, v, e, a);
+                        scatter_entry<R, ACC>(acc, v, te[u].e[c], a);
                     } else {
                         scatter_position<R, ACC, MODE>(acc, v, z + zstep * u + zpos * c, a);   // all-zero past nvec: skipped
                     }
