@@ -20,7 +20,6 @@
 // workgroup overlaps with the matrix and SJLT phases of the others and the
 // launch cost is paid once.
 #include <type_traits>
-#include <vector>
 
 #include "grass_device.h"
 
@@ -58,6 +57,17 @@ struct FgArgs {
     float scale;
     uint32_t identity;      // 1: no SJLT, out[a*kb + b] = v[a*kb + b] (the factorised mask Mask_{k_in x k_out})
 };
+
+// Up to 64 layer descriptors handed over as kernel arguments (56 bytes each, under the 4 KB argument limit).
+constexpr int kLayersPerPack = 64;
+struct FgLayerPack {
+    FgLayer l[kLayersPerPack];
+    uint32_t first, count;
+};
+static_assert(sizeof(FgLayerPack) <= 4096, "kernel arguments are limited to 4 KB");
+__global__ void __launch_bounds__(kLayersPerPack) fg_store_layers_kernel(FgLayerPack pack, FgLayer* table) {
+    if (threadIdx.x < pack.count) table[pack.first + threadIdx.x] = pack.l[threadIdx.x];
+}
 
 // TA, TB: number of 32-wide tiles covering k_in' and k_out'.
 template <int TA, int TB, bool F64>
@@ -235,13 +245,9 @@ static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint
 template <int TA, int TB, bool F64>
 static hipError_t launch_fg2(const FgArgs& a, const FgPlan& pl, uint64_t n, uint32_t n_layers, hipStream_t st) {
     auto kern = factgrass_kernel<TA, TB, F64>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsOptIn opt_in;
+    const hipError_t e = allow_large_lds(opt_in, reinterpret_cast<const void*>(kern));
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3(pl.chunks, (uint32_t)n, n_layers), dim3(kFgThreads), pl.lds_bytes, st, a);
     return hipGetLastError();
 }
@@ -368,23 +374,32 @@ extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uin
     const size_t table = layers_table_bytes(n_layers);
     if (!ws || ws_bytes < table + pl.ws_bytes || !aligned(ws, 256)) return GRASS_EWORKSPACE;
 
-    // the descriptor table travels to the head of the workspace; it is built in a
-    // host vector that outlives the (pageable, hence host-synchronous) copy call
-    std::vector<FgLayer> dev(n_layers);
-    for (uint32_t l = 0; l < n_layers; ++l) {
-        const factgrass_layer& h = host_layers[l];
-        dev[l].x = static_cast<const uint16_t*>(h.x);
-        dev[l].g = static_cast<const uint16_t*>(h.gout);
-        dev[l].idx_in = h.idx_in; dev[l].idx_out = h.idx_out; dev[l].out = h.out;
-        dev[l].sub = substream(seed, h.stream_id);
-        dev[l].d_in = h.d_in; dev[l].d_out = h.d_out;
-    }
+    // The descriptor table travels to the head of the workspace as kernel arguments, 64 layers per launch: the
+    // arguments are copied when the launch is enqueued, so nothing depends on host memory staying alive or on how
+    // the runtime treats pageable copies, and the call stays asynchronous.
     hipStream_t hs = as_stream(stream);
-    if (hipMemcpyAsync(ws, dev.data(), (size_t)n_layers * sizeof(FgLayer), hipMemcpyHostToDevice, hs) != hipSuccess)
-        return GRASS_EHIP;
+    FgLayer first_layer{};
+    for (uint32_t l0 = 0; l0 < n_layers; l0 += kLayersPerPack) {
+        FgLayerPack pack;
+        pack.first = l0;
+        pack.count = n_layers - l0 < (uint32_t)kLayersPerPack ? n_layers - l0 : (uint32_t)kLayersPerPack;
+        for (uint32_t q = 0; q < pack.count; ++q) {
+            const factgrass_layer& h = host_layers[l0 + q];
+            FgLayer& d = pack.l[q];
+            d.x = static_cast<const uint16_t*>(h.x);
+            d.g = static_cast<const uint16_t*>(h.gout);
+            d.idx_in = h.idx_in; d.idx_out = h.idx_out; d.out = h.out;
+            d.sub = substream(seed, h.stream_id);
+            d.d_in = h.d_in; d.d_out = h.d_out;
+        }
+        for (uint32_t q = pack.count; q < (uint32_t)kLayersPerPack; ++q) pack.l[q] = FgLayer{};
+        if (l0 == 0) first_layer = pack.l[0];
+        hipLaunchKernelGGL(fg_store_layers_kernel, dim3(1), dim3(kLayersPerPack), 0, hs, pack, static_cast<FgLayer*>(ws));
+        if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+    }
     FgArgs a;
     fill_common(a, pl, n, T, kin_p, kout_p, k, s, ldo);
-    a.one = dev[0];
+    a.one = first_layer;
     a.many = static_cast<const FgLayer*>(ws);
     a.partial = reinterpret_cast<float*>(static_cast<char*>(ws) + table);
     return run_fg(a, pl, n_layers, hs);

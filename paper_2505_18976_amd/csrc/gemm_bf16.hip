@@ -412,14 +412,11 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     if (lower_only && a.tiles_m != a.tiles_n) return false;
     const uint64_t total = (lower_only ? (uint64_t)a.tiles_m * (a.tiles_m + 1) / 2 : (uint64_t)a.tiles_m * a.tiles_n) * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return false;
-    static bool attr_done[2] = {false, false};
+    static LdsOptIn opt_in[2];
     const void* fn = f32 ? reinterpret_cast<const void*>(gemm_dma_kernel<true>)
                          : reinterpret_cast<const void*>(gemm_dma_kernel<false>);
-    if (!attr_done[f32]) {
-        *err = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-        if (*err != hipSuccess) return true;
-        attr_done[f32] = true;
-    }
+    *err = allow_large_lds(opt_in[f32], fn);
+    if (*err != hipSuccess) return true;
     const size_t lds = (size_t)kDmaStages * kDmaStageBytes;
     if (f32)
         hipLaunchKernelGGL(gemm_dma_kernel<true>, dim3((uint32_t)total), dim3(kBf16Threads), lds, st, a);
@@ -493,14 +490,9 @@ extern "C" grass_status grass_score_bf16(const void* train, const void* test, ui
     a.tiles_n = (uint32_t)ceil_div(N, TN);
     const uint64_t total = (uint64_t)a.tiles_m * a.tiles_n;
     if (total > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
-    static bool attr_done = false;
+    static LdsOptIn opt_in;
     const size_t lds_bytes = (size_t)kStages * kStageElems * sizeof(uint16_t);
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(gemm_bf16_nt_kernel),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes) != hipSuccess)
-            return GRASS_EHIP;
-        attr_done = true;
-    }
+    if (allow_large_lds(opt_in, reinterpret_cast<const void*>(gemm_bf16_nt_kernel)) != hipSuccess) return GRASS_EHIP;
     hipError_t derr = hipSuccess;
     if (launch_gemm_dma(false, test, train, scores, M, N, K, ld_test, ld_train, ld_scores, 0, as_stream(stream), &derr, 1,
                         nullptr, 0))

@@ -82,4 +82,18 @@ static __global__ void __launch_bounds__(256) transpose_rows_kernel(const float*
 constexpr int kNumCU = 256;                 // MI355X
 constexpr size_t kLdsBytes = 160 * 1024;    // per CU and per workgroup on gfx950
 
+// A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the setting belongs to
+// the device's copy of the code object).  One LdsOptIn per kernel remembers the devices that have it.
+struct LdsOptIn { bool done[64] = {}; };
+inline hipError_t allow_large_lds(LdsOptIn& state, const void* kernel) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const bool tracked = dev >= 0 && dev < 64;
+    if (tracked && state.done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+    if (e == hipSuccess && tracked) state.done[dev] = true;
+    return e;
+}
+
 }  // namespace grass

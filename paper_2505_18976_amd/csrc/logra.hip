@@ -237,14 +237,9 @@ extern "C" grass_status logra_linear(const void* x, const void* gout, uint64_t n
         a.dst = static_cast<float*>(ws); a.ld_dst = kk; a.chunk_stride = n * kk;
     }
     hipStream_t hs = as_stream(stream);
-    static bool attr_done = false;
+    static LdsOptIn opt_in;
     const size_t lds_bytes = (size_t)2 * kLograStage * sizeof(uint16_t);
-    if (!attr_done) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(logra_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)kLdsBytes) != hipSuccess)
-            return GRASS_EHIP;
-        attr_done = true;
-    }
+    if (allow_large_lds(opt_in, reinterpret_cast<const void*>(logra_kernel)) != hipSuccess) return GRASS_EHIP;
     hipLaunchKernelGGL(logra_kernel, dim3(pl.chunks, (uint32_t)n), dim3(kLograThreads), lds_bytes, hs, a);
     if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
     if (pl.chunks > 1) {

@@ -377,13 +377,9 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
 template <typename T, int R, int V, int U, bool MASKED, int ACC, int MODE>
 static hipError_t launch_one(const SjltArgs& a, const SjltPlan& pl, hipStream_t st) {
     auto kern = sjlt_kernel<T, R, V, U, MASKED, ACC, MODE>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)(kLdsBytes));
-        if (e != hipSuccess) return e;
-        attr_done = true;
-    }
+    static LdsOptIn opt_in;
+    const hipError_t e = allow_large_lds(opt_in, reinterpret_cast<const void*>(kern));
+    if (e != hipSuccess) return e;
     dim3 grid((uint32_t)(ceil_div(a.n, (uint64_t)pl.row_period * R) * pl.row_period), pl.chunks);
     hipLaunchKernelGGL(kern, grid, dim3(pl.threads), pl.lds_bytes, st, a);
     return hipGetLastError();
