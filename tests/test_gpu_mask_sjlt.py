@@ -258,6 +258,37 @@ def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
+@pytest.mark.parametrize("masked", [False, True])
+def test_sjlt_non_finite_values_stay_in_their_buckets(grass, masked):
+    """A NaN or an infinity in a gradient reaches exactly the buckets its coordinate maps to (the zero test that skips
+    exact zeros must not swallow it, and it must not leak into other buckets or rows); -0.0 counts as zero."""
+    n, d, k, s = 6, 5000, 256, 2
+    g = synth.bernoulli_sparse_normal(n, d, 0.5, 1.0, seed=31, device=_dev())
+    g[1, 17] = float("nan")
+    g[2, 4999] = float("inf")
+    g[3, 0] = float("-inf")
+    g[4, 123] = -0.0
+    if masked:
+        keep = np.unique(np.concatenate([[0, 17, 123, 4999], np.arange(5, 5000, 7)])).astype(np.int32)
+        idx = torch.from_numpy(keep).to(_dev())
+        out = grass.grass_sjlt(g, k, s, seed=4, stream_id=1, idx=idx)
+        with np.errstate(invalid="ignore"):
+            ref = orc.grass(g.cpu().numpy(), keep, k, s, 4, 1)
+    else:
+        out = grass.grass_sjlt(g, k, s, seed=4, stream_id=1)
+        with np.errstate(invalid="ignore"):
+            ref = orc.sjlt(g.cpu().numpy(), k, s, 4, 1)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert np.array_equal(np.isnan(got), np.isnan(ref))
+    assert np.array_equal(np.isposinf(got), np.isposinf(ref)) and np.array_equal(np.isneginf(got), np.isneginf(ref))
+    assert np.isnan(ref[1]).sum() == s and np.isinf(ref[2]).sum() == s and np.isinf(ref[3]).sum() == s
+    fin = np.isfinite(ref)
+    for i in range(n):
+        scale = np.abs(ref[i][fin[i]]).max()
+        assert np.abs(got[i][fin[i]] - ref[i][fin[i]]).max() <= TOL_SJLT * scale
+
+
 def test_sjlt_dense_zero_and_offset_output(grass):
     n, d, k = 4, 3000, 256
     g = torch.zeros((n, d), dtype=torch.float32, device=_dev())
