@@ -317,6 +317,9 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     // kernel for the partial sums) and fewer rows per workgroup until there are 32 workgroups
     const bool short_rows = d <= 32768;
     if (short_rows) while (R > 1 && ceil_div(n, R) < 32) R >>= 1;
+    // long masked rows are bound by the gather (one 128-byte line per kept coordinate): up to a few hundred rows,
+    // one workgroup per CU matters more than sharing the hash of a position between the rows of a workgroup
+    if (masked && !short_rows) while (R > 1 && ceil_div(n, R) < (uint64_t)kNumCU) R >>= 1;
     if (g_tune_rows == 1 || g_tune_rows == 2 || g_tune_rows == 4 || g_tune_rows == 8) {
         if ((size_t)g_tune_rows * k * esz <= kLdsBytes) R = g_tune_rows;
     }
@@ -348,7 +351,16 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     if (max_chunks_work < 1) max_chunks_work = 1;
     uint64_t max_chunks_traffic = (d * (masked ? 8 : 1)) / (8ull * k);
     if (max_chunks_traffic < 1) max_chunks_traffic = 1;
-    uint64_t chunks = ceil_div(4 * kNumCU, row_groups);       // four rounds of workgroups even out the tail
+    // unmasked: four rounds of workgroups even out the tail, but no more than 16 chunks of partial sums per row
+    // unless it takes more to give every CU one workgroup (measured for n = 1 ... 1,024 at p = 11 million)
+    uint64_t chunks = ceil_div(4 * kNumCU, row_groups);
+    if (chunks > 16) chunks = 16;
+    if (chunks < ceil_div(kNumCU, row_groups)) chunks = ceil_div(kNumCU, row_groups);
+    if (chunks > 128) chunks = 128;
+    if (masked) {                                             // gather-bound: fill the chip once; every further chunk
+        chunks = ceil_div(kNumCU, row_groups);                // only adds partial sums (measured for n = 4 ... 2,048)
+        if (chunks > 16) chunks = 16;
+    }
     if (chunks > max_chunks_work) chunks = max_chunks_work;
     if (chunks > max_chunks_traffic) chunks = max_chunks_traffic;
     if (short_rows) chunks = 1;
