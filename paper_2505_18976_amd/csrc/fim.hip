@@ -11,6 +11,9 @@
 
 namespace grass {
 
+bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K,
+                            uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err,
+                            uint32_t splits, float* partials, int lower_only);
 hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                        uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st, uint32_t splits,
                        float* partials);
@@ -250,16 +253,25 @@ using namespace grass;
 // rows of G per transposed chunk: long enough that each K range of a chunk product amortises its pipeline fill
 static uint64_t fim_chunk_rows(uint64_t N) { return N < 16384 ? (N + 15) / 16 * 16 : 16384; }
 
-// K ranges per chunk product.  The lower-triangle tiles of a 256 x 256 tiling are few (136 for k = 4,096 on 256
-// CUs), so each chunk's contraction is cut into up to 8 ranges that accumulate separate partial sums.
+// K ranges of the product.  The lower-triangle tiles of a 256 x 256 tiling are few (136 for k = 4,096 on 256 CUs)
+// and all workgroups of a launch take equally long, so the launch runs in rounds of 256 workgroups: the number of
+// ranges (at most 16, each at least 16 groups of 32 rows long) is the one that leaves the last round fullest, with a
+// small penalty per range for its k x k partial sum (k = 4,096: 15 ranges = 2,040 workgroups = 7.97 rounds, where 8
+// ranges = 4.25 rounds idle a quarter of the chip for a fifth of the time).
 static uint32_t fim_splits(uint64_t N, uint32_t k) {
     if (k < 128) return 1;
     const uint64_t t = ((uint64_t)k + 255) / 256, lower = t * (t + 1) / 2;
-    uint64_t s = ceil_div(1024, lower);
-    if (s > 8) s = 8;
-    const uint64_t slices = fim_chunk_rows(N) / 16;        // of the first (largest) chunk
-    if (s > slices / 32) s = slices / 32;
-    return s < 2 ? 1 : (uint32_t)s;
+    const uint64_t groups = ceil_div(N, 32);
+    uint32_t best = 1;
+    double best_score = -1.0;
+    for (uint32_t s = 1; s <= 16; ++s) {
+        if (s > 1 && groups < (uint64_t)s * 16) break;
+        const uint64_t wg = lower * s;
+        const double fill = (double)wg / (double)(ceil_div(wg, kNumCU) * kNumCU);
+        const double score = fill - 0.003 * s;
+        if (score > best_score) { best_score = score; best = s; }
+    }
+    return best;
 }
 
 static size_t fim_gt_bytes(uint64_t N, uint32_t k) { return ((size_t)k * fim_chunk_rows(N) * sizeof(float) + 255) / 256 * 256; }
@@ -283,6 +295,25 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
     float* Gt = static_cast<float*>(ws);
     float* partials = splits > 1 ? reinterpret_cast<float*>(static_cast<unsigned char*>(ws) + fim_gt_bytes(N, k)) : nullptr;
     hipStream_t hs = as_stream(stream);
+    // G^T G contracts over the rows of G: with 16-byte aligned rows the GEMM takes G itself as both (K-major)
+    // operands in one launch, the N rows interleaved between the K ranges; otherwise chunks of G are transposed
+    // into the workspace first.
+    if (k >= 128 && k % 4 == 0 && ldg % 4 == 0 && aligned(G, 16)) {
+        uint32_t s_cur = splits;
+        const uint64_t groups = ceil_div(N, 32);
+        if (s_cur > 1 && groups < (uint64_t)s_cur * 16) s_cur = (uint32_t)(groups / 16);       // short inputs: fewer ranges
+        if (s_cur < 2) s_cur = 1;
+        hipError_t derr = hipSuccess;
+        const bool taken = s_cur > 1
+            ? launch_gemm_dma_kmajor(true, G, G, nullptr, k, k, N, ldg, ldg, k, 0, hs, &derr, s_cur, partials, 1)
+            : launch_gemm_dma_kmajor(true, G, G, F, k, k, N, ldg, ldg, ldf, 0, hs, &derr, 1, nullptr, 1);
+        if (taken) {
+            if (derr != hipSuccess) return GRASS_EHIP;
+            hipLaunchKernelGGL(fim_finish_kernel, dim3((k + 63) / 64, (k + 63) / 64), dim3(256), 0, hs, F, ldf, k,
+                               (float)(1.0 / (double)N), partials, s_cur > 1 ? s_cur : 0);
+            return launch_status();
+        }
+    }
     for (uint64_t r0 = 0; r0 < N; r0 += rows) {
         const uint32_t rc = (uint32_t)(r0 + rows <= N ? rows : N - r0);
         const uint32_t rc_pad = (rc + 15) / 16 * 16;                 // the GEMM contracts over whole 64-byte slices

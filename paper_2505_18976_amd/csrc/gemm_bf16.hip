@@ -26,6 +26,7 @@ namespace grass {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int TM = 256, TN = 256, TK = 32;
 constexpr int RS = TK + 8;                       // bf16 elements per LDS row (80 bytes)
@@ -209,10 +210,20 @@ struct GemmDmaArgs {
     uint32_t splits;             // split-K: workgroup (split, tile) contracts the 128-byte groups split, split + splits,
     uint64_t split_stride_c;     //          split + 2*splits, ... of K into C + split*split_stride_c
     int lower_only;              // symmetric product: tiles strictly above the diagonal are skipped
+    uint64_t m_read, n_read;     // K-major operands: columns that may be read (a multiple of 4, >= M resp. N)
 };
 
-template <bool F32>
+// AKN / BKN (fp32 only): the operand is stored K-major, A as K x M (row distance lda) and B as K x N, i.e. the
+// contraction runs over the rows of a row-major matrix (G^T G, C G) and no transposed copy is needed.  Its part of a
+// stage is then 32 k-rows of 256 columns (1 KB each, one load instruction per k-row); a lane takes 4 (A) or 2 (B)
+// adjacent columns of one k-row per read and feeds one MFMA tile with each, so tile i of a wavefront owns the rows
+// 4q + i (q = 0..31) of its 128 and tile j the columns 2q + j of its 64.  k-rows at or past K are loaded from a zero
+// word, so K needs no padding for such an operand.
+__device__ __align__(16) const uint32_t g_dma_zeros[4] = {0u, 0u, 0u, 0u};
+
+template <bool F32, bool AKN, bool BKN>
 __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
+    static_assert(F32 || (!AKN && !BKN), "K-major operands are built for fp32 only");
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ESZ = F32 ? 4 : 2;                 // bytes per element
     constexpr int SK = 64 / ESZ;                     // elements per slice (64-byte rows)
@@ -242,51 +253,90 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     // instructions of 8 rows; lane i moves row 8j + i/8, LDS chunk position i%8 = global chunk (i%8) ^ swizzle(row).
     // In the half group that ends an odd number of slices the lanes of chunks 4..7 re-read chunks 0..3 (in
     // bounds; their LDS data is never used).
-    const uint64_t nk_all = a.K / SK;         // 64-byte slices; K is a multiple of the slice width here
+    const uint64_t nk_all = (a.K + SK - 1) / SK;   // 64-byte slices; a K that is not a multiple needs K-major operands
     // Groups of two slices = 128 bytes per row.  The K ranges of a split-K launch are interleaved group by group
     // (split s takes groups s, s + splits, ...): all workgroups walk along the rows together and touch one
     // narrow window of every row at a time, and no range boundary has to be rounded to a group.
     const uint64_t ng_all = (nk_all + 1) / 2, gstride = a.splits;
     const uint64_t ng = (ng_all - split + gstride - 1) / gstride;          // >= 1: the host keeps splits <= ng_all
     const bool half_tail = (nk_all & 1) != 0 && (ng_all - 1) % gstride == split;   // this split owns the half group
+    const bool is_a = wave < 4;                  // wavefronts 0..3 move the A part of a stage, 4..7 the B part
+    const bool kmajor = is_a ? AKN : BKN;        // uniform per wavefront
+    const int wq = wave & 3;
     const unsigned char* gsrc[8];
+    uint64_t gadv;                               // bytes from one group of this split to its next
+    if (kmajor) {
+        // instruction j moves k-row 8*wq + j of the group: 256 columns, lane i the columns 4i..4i+3
+        const uint64_t lim = is_a ? a.m_read : a.n_read, ld = is_a ? a.lda : a.ldb;
+        uint64_t col = (is_a ? m0 : n0) + 4 * (uint64_t)lane;
+        if (col + 4 > lim) col = lim - 4;                               // columns past the edge: never stored
+        const unsigned char* mat = static_cast<const unsigned char*>(is_a ? a.A : a.B) + col * 4;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int r = wave * 64 + j * 8 + (lane >> 3);             // 0..511
-        const int kc = (lane & 7) ^ ((r >> 1) & 7);
-        if (r < TM) {
-            const uint64_t row = m0 + r;                            // rows past the edge re-read the last row;
-            gsrc[j] = static_cast<const unsigned char*>(a.A) + ((row < a.M ? row : a.M - 1) * a.lda) * ESZ + kc * 16 +
-                      (uint64_t)split * 128;
-        } else {                                                    // their products are never stored
-            const uint64_t row = n0 + (r - TM);
-            gsrc[j] = static_cast<const unsigned char*>(a.B) + ((row < a.N ? row : a.N - 1) * a.ldb) * ESZ + kc * 16 +
-                      (uint64_t)split * 128;
+        for (int j = 0; j < 8; ++j) gsrc[j] = mat + ((uint64_t)split * 32 + 8 * wq + j) * ld * 4;
+        gadv = gstride * 32 * ld * 4;
+    } else {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int r = wq * 64 + j * 8 + (lane >> 3);               // row of the operand's tile
+            const int kc = (lane & 7) ^ ((r >> 1) & 7);
+            const uint64_t row = (is_a ? m0 : n0) + r, lim = is_a ? a.M : a.N;   // rows past the edge re-read the
+            gsrc[j] = static_cast<const unsigned char*>(is_a ? a.A : a.B) +       // last row; never stored
+                      ((row < lim ? row : lim - 1) * (is_a ? a.lda : a.ldb)) * ESZ + kc * 16 + (uint64_t)split * 128;
         }
+        gadv = gstride * 128;
     }
-    const int upper = (lane >> 2) & 1;        // chunk >= 4 for even j, chunk < 4 for odd j
+    const int upper = (lane >> 2) & 1;        // row-major operand: chunk >= 4 for even j, chunk < 4 for odd j
     auto dma = [&](uint64_t group, int stage) {
         unsigned char* base = smem + stage * kDmaStageBytes + wave * 8192;
         const bool tail = half_tail && group == ng - 1;
+        const uint64_t krow0 = ((uint64_t)split + group * gstride) * 32 + 8 * wq;   // K-major: first k-row of this wavefront
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int back = (tail && (upper ^ (j & 1))) ? 64 : 0;
-            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(gsrc[j] + group * gstride * 128 - back),
+            const unsigned char* src;
+            if (kmajor) {
+                src = krow0 + j < a.K ? gsrc[j] + group * gadv : reinterpret_cast<const unsigned char*>(g_dma_zeros);
+            } else {
+                const int back = (tail && (upper ^ (j & 1))) ? 64 : 0;
+                src = gsrc[j] + group * gadv - back;
+            }
+            __builtin_amdgcn_global_load_lds(reinterpret_cast<const uint32_t*>(src),
                                              reinterpret_cast<uint32_t*>(base + j * 1024), 16, 0, 0);
         }
     };
 
-    // fragment addresses: row*128 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on lane only
+    // fragment addresses.  Row-major operand: row*128 + ((2*ks + lane/32) ^ swizzle) * 16, the swizzle depends on
+    // lane only; MFMA step e of k-step ks uses element e of the chunk (k = 8ks + 4*(lane/32) + e).  K-major operand:
+    // k-row (8ks + 4*(lane/32) + e) * 1024 + column * 4, one read per step e.
     const int fl = (lane >> 1) & 7;
     const int a_row = (wm * 128 + (lane & 31)) * 128;
     const int b_row = (TM + wn * 64 + (lane & 31)) * 128;
-    struct RawFrags { u32x4 a[4], b[2]; };
+    const int a_kn = (4 * (lane >> 5)) * 1024 + (wm * 128 + 4 * (lane & 31)) * 4;
+    const int b_kn = TM * 128 + (4 * (lane >> 5)) * 1024 + (wn * 64 + 2 * (lane & 31)) * 4;
+    struct RawFrags { u32x4 a[4]; uint32_t b[8]; };
     auto load_frags = [&](RawFrags& f, int stage, int ks) {
-        const unsigned char* base = smem + stage * kDmaStageBytes + (((2 * ks + (lane >> 5)) ^ fl) * 16);
+        const unsigned char* st = smem + stage * kDmaStageBytes;
+        const unsigned char* base = st + (((2 * ks + (lane >> 5)) ^ fl) * 16);
+        if constexpr (AKN) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 128);
+            for (int e = 0; e < 4; ++e) f.a[e] = *reinterpret_cast<const u32x4*>(st + a_kn + (8 * ks + e) * 1024);
+        } else {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 128);
+            for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 128);
+        }
+        if constexpr (BKN) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const u32x2 v = *reinterpret_cast<const u32x2*>(st + b_kn + (8 * ks + e) * 1024);
+                f.b[2 * e] = v[0]; f.b[2 * e + 1] = v[1];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const u32x4 v = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 128);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) f.b[4 * j + e] = v[e];
+            }
+        }
     };
 
     f32x16 acc[4][2];
@@ -303,12 +353,18 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
             for (int j = 0; j < 2; ++j) {
                 if constexpr (F32) {
 #pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(f.a[i][e]),
-                                                                         __uint_as_float(f.b[j][e]), acc[i][j], 0, 0, 0);
+                    for (int e = 0; e < 4; ++e) {
+                        const uint32_t av = AKN ? f.a[e][i] : f.a[i][e];
+                        const uint32_t bv = BKN ? f.b[2 * e + j] : f.b[4 * j + e];
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(av), __uint_as_float(bv),
+                                                                         acc[i][j], 0, 0, 0);
+                    }
                 } else {
+                    u32x4 bv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) bv[e] = f.b[4 * j + e];
                     acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f.a[i]),
-                                                                        __builtin_bit_cast(bf16x8, f.b[j]), acc[i][j],
+                                                                        __builtin_bit_cast(bf16x8, bv), acc[i][j],
                                                                         0, 0, 0);
                 }
             }
@@ -342,25 +398,23 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         mma(f1);
     }
 
+    // accumulator element e of a lane belongs to row 8*(e/4) + 4*(lane/32) + e%4 and column lane%32 of its MFMA tile;
+    // which rows and columns of C a tile owns depends on the operand layouts (see above)
     const bool interior = m0 + TM <= a.M && n0 + TN <= a.N;     // uniform
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
-            const uint64_t col = n0 + wn * 64 + j * 32 + (lane & 31);
-            const uint64_t rbase = m0 + wm * 128 + i * 32 + 4 * (lane >> 5);
-            if (interior && !a.accumulate) {
-                float* c = a.C + rbase * a.ldc + col;
+            const uint64_t col = BKN ? n0 + wn * 64 + 2 * (lane & 31) + j : n0 + wn * 64 + j * 32 + (lane & 31);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) c[(uint64_t)(8 * (e >> 2) + (e & 3)) * a.ldc] = acc[i][j][e];
-            } else {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const uint64_t row = rbase + 8 * (e >> 2) + (e & 3);
-                    if (row < a.M && col < a.N) {
-                        float* c = a.C + row * a.ldc + col;
-                        *c = a.accumulate ? *c + acc[i][j][e] : acc[i][j][e];
-                    }
+            for (int e = 0; e < 16; ++e) {
+                const int rit = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+                const uint64_t row = AKN ? m0 + wm * 128 + 4 * rit + i : m0 + wm * 128 + i * 32 + rit;
+                if (interior && !a.accumulate) {
+                    a.C[row * a.ldc + col] = acc[i][j][e];
+                } else if (row < a.M && col < a.N) {
+                    float* c = a.C + row * a.ldc + col;
+                    *c = a.accumulate ? *c + acc[i][j][e] : acc[i][j][e];
                 }
             }
         }
@@ -374,15 +428,22 @@ bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint6
     return K > 0 && K % sk == 0 && (lda * esz) % 16 == 0 && (ldb * esz) % 16 == 0 && aligned(A, 16) && aligned(B, 16);
 }
 
-// Split-K factor that fills the chip when there are few output tiles: the number
-// of K ranges (at most max_splits) such that tiles*splits reaches the CU count.
+// Split-K factor when there are few output tiles.  All workgroups of a launch take equally long, so it runs in rounds
+// of one workgroup per CU: among the admissible numbers of K ranges (at most max_splits, at least 32 slices each)
+// take the one that leaves the last round fullest, with a small penalty per range for its partial sum.
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits) {
     const uint64_t tiles = ceil_div(M, TM) * ceil_div(N, TN), slices = K / (f32 ? 16 : 32);
-    if (tiles == 0 || tiles >= kNumCU || slices < 64) return 1;
-    uint64_t s = ceil_div(kNumCU, tiles);
-    if (s > max_splits) s = max_splits;
-    if (s > slices / 32) s = slices / 32;                         // at least 32 slices per range
-    return s < 2 ? 1 : (uint32_t)s;
+    if (tiles == 0 || tiles >= (uint64_t)kNumCU || slices < 64) return 1;
+    uint32_t best = 1;
+    double best_score = -1.0;
+    for (uint32_t s = 1; s <= max_splits; ++s) {
+        if (s > 1 && slices / 32 < s) break;
+        const uint64_t wg = tiles * s;
+        const double fill = (double)wg / (double)(ceil_div(wg, kNumCU) * kNumCU);
+        const double score = fill - 0.003 * s;
+        if (score > best_score) { best_score = score; best = s; }
+    }
+    return best;
 }
 
 // Host-side launch shared by the score GEMMs and the Gaussian baseline.  Returns
@@ -391,20 +452,27 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
 // splits > 1 (a value from gemm_dma_splits) writes the partial product of K range
 // s to partials + s*M*N (dense M x N, accumulate applies to it) instead of C.
 // lower_only (A == B, M == N): only tiles on or below the diagonal are computed.
-bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
-                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
-                     float* partials, int lower_only) {
-    if (!gemm_dma_eligible(f32, A, B, K, lda, ldb)) return false;
+// a_kn / b_kn (fp32 only): that operand is K-major (K x M resp. K x N, row distance lda / ldb).  A K-major operand
+// needs 16-byte aligned rows and base, a column count that is a multiple of 4, and takes any K; a row-major
+// operand needs K in whole 64-byte slices.
+static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, const void* B, float* C, uint64_t M,
+                                uint64_t N, uint64_t K, uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate,
+                                hipStream_t st, hipError_t* err, uint32_t splits, float* partials, int lower_only) {
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
+    if ((a_kn || b_kn) && !f32) return false;
+    if (K == 0 || M == 0 || N == 0) return false;
+    if ((lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
+    if ((!a_kn || !b_kn) && K % sk != 0) return false;
+    if ((a_kn && (M % 4 != 0 || lda < M)) || (b_kn && (N % 4 != 0 || ldb < N))) return false;
     GemmDmaArgs a;
     a.A = A; a.B = B; a.C = C; a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
+    a.m_read = M; a.n_read = N;
     a.accumulate = accumulate;
     a.lower_only = lower_only;
     a.tiles_m = (uint32_t)ceil_div(M, TM);
     a.tiles_n = (uint32_t)ceil_div(N, TN);
-    const uint64_t slices = K / sk;
+    const uint64_t slices = ceil_div(K, sk);
     if (splits < 1 || !partials) splits = 1;
-    if (slices == 0 || splits > slices) return false;
     if (splits > ceil_div(slices, 2)) return false;                        // every split gets at least one group
     a.splits = splits;
     a.split_stride_c = 0;
@@ -412,18 +480,41 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
     if (lower_only && a.tiles_m != a.tiles_n) return false;
     const uint64_t total = (lower_only ? (uint64_t)a.tiles_m * (a.tiles_m + 1) / 2 : (uint64_t)a.tiles_m * a.tiles_n) * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return false;
-    static LdsOptIn opt_in[2];
-    const void* fn = f32 ? reinterpret_cast<const void*>(gemm_dma_kernel<true>)
-                         : reinterpret_cast<const void*>(gemm_dma_kernel<false>);
-    *err = allow_large_lds(opt_in[f32], fn);
+    const int variant = !f32 ? 0 : (a_kn ? (b_kn ? 3 : -1) : (b_kn ? 2 : 1));
+    if (variant < 0) return false;                                         // K-major A with row-major B: not built
+    static LdsOptIn opt_in[4];
+    const void* fns[4] = {reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, true>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, true, true>)};
+    *err = allow_large_lds(opt_in[variant], fns[variant]);
     if (*err != hipSuccess) return true;
     const size_t lds = (size_t)kDmaStages * kDmaStageBytes;
-    if (f32)
-        hipLaunchKernelGGL(gemm_dma_kernel<true>, dim3((uint32_t)total), dim3(kBf16Threads), lds, st, a);
-    else
-        hipLaunchKernelGGL(gemm_dma_kernel<false>, dim3((uint32_t)total), dim3(kBf16Threads), lds, st, a);
+    const dim3 grid((uint32_t)total), block(kBf16Threads);
+    switch (variant) {
+        case 0: hipLaunchKernelGGL((gemm_dma_kernel<false, false, false>), grid, block, lds, st, a); break;
+        case 1: hipLaunchKernelGGL((gemm_dma_kernel<true, false, false>), grid, block, lds, st, a); break;
+        case 2: hipLaunchKernelGGL((gemm_dma_kernel<true, false, true>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((gemm_dma_kernel<true, true, true>), grid, block, lds, st, a); break;
+    }
     *err = hipGetLastError();
     return true;
+}
+
+bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
+                     uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err, uint32_t splits,
+                     float* partials, int lower_only) {
+    return launch_gemm_dma_any(f32, false, false, A, B, C, M, N, K, lda, ldb, ldc, accumulate, st, err, splits, partials,
+                               lower_only);
+}
+
+// fp32 products with K-major operands: C (M x N) = A^T B for A stored K x M and B stored K x N (a_kn and b_kn), or
+// C = A B for A stored M x K and B stored K x N (b_kn only).  Same return convention as launch_gemm_dma.
+bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K,
+                            uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err,
+                            uint32_t splits, float* partials, int lower_only) {
+    return launch_gemm_dma_any(true, a_kn, true, A, B, C, M, N, K, lda, ldb, ldc, accumulate, st, err, splits, partials,
+                               lower_only);
 }
 
 // fp32 -> bf16, round to nearest even; 4 elements per thread.  Columns cols..cols_pad of dst are zero-filled.

@@ -28,7 +28,10 @@ def _dev():
 
 
 @pytest.mark.parametrize("N,k", [(50, 7), (300, 130), (1000, 256), (9000, 300), (20000, 512), (17, 64), (8192, 128),
-                                 (40000, 384), (2100, 640)])
+                                 (40000, 384), (2100, 640),
+                                 # 16-byte aligned rows take G itself as both K-major operands: row counts that are not
+                                 # whole slices or groups (zero-filled k-rows), a ragged column tile, a single row
+                                 (33, 128), (1, 128), (4100, 132), (65, 260), (70001, 256)])
 def test_fim_parity(grass, N, k):
     G = synth.compressed_gradients(N, k, seed=2000 + k, device=_dev())
     F = grass.grass_fim(G)
