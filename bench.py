@@ -208,6 +208,19 @@ def main() -> int:
                                                                  ws=w_sm), 2, 1, torch)
         tf = 2 * 2.0 * n * msm * p / (t / 2 * 1e-3) / 1e12
         extras["selective_mask_grad_mlp"] = {"ms": round(t / 2, 2), "TFLOPs": round(tf, 1), "train_rows": n, "test_rows": msm}
+        # the same step on the same gradients stored with the row distance rounded up to a multiple of 4 elements
+        # (p = 1,863,690 is not one): 16-byte aligned rows take the direct-to-LDS GEMM in both contractions and the
+        # backward one reads G in place instead of through transposed copies
+        gpad = torch.empty((n, (p + 3) // 4 * 4), dtype=torch.float32, device=dev)
+        gpad[:, :p].copy_(g)
+        gtpad = torch.empty((msm, (p + 3) // 4 * 4), dtype=torch.float32, device=dev)
+        gtpad[:, :p].copy_(gt_sm)
+        t, _, _ = _timed(lambda: grass.grass_selective_mask_grad(gpad[:, :p], gtpad[:, :p], a_sm, s_sm, 1e-6, 1.0, grad=gr_sm,
+                                                                 objective=ob_sm, ws=w_sm), 2, 1, torch)
+        extras["selective_mask_grad_mlp_aligned_rows"] = {"ms": round(t / 2, 2),
+                                                          "TFLOPs": round(2 * 2.0 * n * msm * p / (t / 2 * 1e-3) / 1e12, 1),
+                                                          "row_distance": gpad.shape[1]}
+        del gpad, gtpad
         t, _, _ = _timed(lambda: grass.grass_selective_mask_indices(s_sm, kp), 3, 1, torch)
         extras["selective_mask_indices_top_k"] = {"ms": round(t / 3, 3)}
         del g, gt_sm, s_sm, a_sm, w_sm, gr_sm, ob_sm

@@ -13,7 +13,7 @@ namespace grass {
 
 bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K,
                             uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err,
-                            uint32_t splits, float* partials, int lower_only);
+                            uint32_t splits, float* partials, int lower_only, uint64_t k_rows, uint64_t b_cols_avail);
 hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                        uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st, uint32_t splits,
                        float* partials);
@@ -305,8 +305,8 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
         if (s_cur < 2) s_cur = 1;
         hipError_t derr = hipSuccess;
         const bool taken = s_cur > 1
-            ? launch_gemm_dma_kmajor(true, G, G, nullptr, k, k, N, ldg, ldg, k, 0, hs, &derr, s_cur, partials, 1)
-            : launch_gemm_dma_kmajor(true, G, G, F, k, k, N, ldg, ldg, ldf, 0, hs, &derr, 1, nullptr, 1);
+            ? launch_gemm_dma_kmajor(true, G, G, nullptr, k, k, N, ldg, ldg, k, 0, hs, &derr, s_cur, partials, 1, 0, 0)
+            : launch_gemm_dma_kmajor(true, G, G, F, k, k, N, ldg, ldg, ldf, 0, hs, &derr, 1, nullptr, 1, 0, 0);
         if (taken) {
             if (derr != hipSuccess) return GRASS_EHIP;
             hipLaunchKernelGGL(fim_finish_kernel, dim3((k + 63) / 64, (k + 63) / 64), dim3(256), 0, hs, F, ldf, k,

@@ -211,6 +211,7 @@ struct GemmDmaArgs {
     uint64_t split_stride_c;     //          split + 2*splits, ... of K into C + split*split_stride_c
     int lower_only;              // symmetric product: tiles strictly above the diagonal are skipped
     uint64_t m_read, n_read;     // K-major operands: columns that may be read (a multiple of 4, >= M resp. N)
+    uint64_t k_rows;             // K-major operands: rows that exist (<= K); k-rows from there on count as zero
 };
 
 // AKN / BKN (fp32 only): the operand is stored K-major, A as K x M (row distance lda) and B as K x N, i.e. the
@@ -294,7 +295,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         for (int j = 0; j < 8; ++j) {
             const unsigned char* src;
             if (kmajor) {
-                src = krow0 + j < a.K ? gsrc[j] + group * gadv : reinterpret_cast<const unsigned char*>(g_dma_zeros);
+                src = krow0 + j < a.k_rows ? gsrc[j] + group * gadv : reinterpret_cast<const unsigned char*>(g_dma_zeros);
             } else {
                 const int back = (tail && (upper ^ (j & 1))) ? 64 : 0;
                 src = gsrc[j] + group * gadv - back;
@@ -457,16 +458,22 @@ uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t 
 // operand needs K in whole 64-byte slices.
 static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, const void* B, float* C, uint64_t M,
                                 uint64_t N, uint64_t K, uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate,
-                                hipStream_t st, hipError_t* err, uint32_t splits, float* partials, int lower_only) {
+                                hipStream_t st, hipError_t* err, uint32_t splits, float* partials, int lower_only,
+                                uint64_t k_rows = 0, uint64_t b_cols_avail = 0) {
     const uint64_t esz = f32 ? 4 : 2, sk = 64 / esz;
     if ((a_kn || b_kn) && !f32) return false;
     if (K == 0 || M == 0 || N == 0) return false;
     if ((lda * esz) % 16 != 0 || (ldb * esz) % 16 != 0 || !aligned(A, 16) || !aligned(B, 16)) return false;
     if ((!a_kn || !b_kn) && K % sk != 0) return false;
-    if ((a_kn && (M % 4 != 0 || lda < M)) || (b_kn && (N % 4 != 0 || ldb < N))) return false;
+    // a K-major operand is read in 16-byte pieces: its column count rounded up to 4 must exist in every row
+    if (k_rows == 0 || k_rows > K) k_rows = K;
+    if (b_cols_avail == 0) b_cols_avail = ldb;
+    const uint64_t n_read = (N + 3) / 4 * 4;
+    if (a_kn && (M % 4 != 0 || lda < M)) return false;
+    if (b_kn && (n_read > b_cols_avail || b_cols_avail > ldb)) return false;
     GemmDmaArgs a;
     a.A = A; a.B = B; a.C = C; a.M = M; a.N = N; a.K = K; a.lda = lda; a.ldb = ldb; a.ldc = ldc;
-    a.m_read = M; a.n_read = N;
+    a.m_read = M; a.n_read = n_read; a.k_rows = k_rows;
     a.accumulate = accumulate;
     a.lower_only = lower_only;
     a.tiles_m = (uint32_t)ceil_div(M, TM);
@@ -509,12 +516,15 @@ bool launch_gemm_dma(bool f32, const void* A, const void* B, float* C, uint64_t 
 }
 
 // fp32 products with K-major operands: C (M x N) = A^T B for A stored K x M and B stored K x N (a_kn and b_kn), or
-// C = A B for A stored M x K and B stored K x N (b_kn only).  Same return convention as launch_gemm_dma.
+// C = A B for A stored M x K and B stored K x N (b_kn only).  k_rows (0 = K): rows the K-major operands really have;
+// K itself may be larger when a row-major A is zero-padded to whole slices.  b_cols_avail (0 = ldb): columns that
+// exist from B's base to the end of a row (B may be a column block of a wider matrix).  Same return convention as
+// launch_gemm_dma.
 bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K,
                             uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err,
-                            uint32_t splits, float* partials, int lower_only) {
+                            uint32_t splits, float* partials, int lower_only, uint64_t k_rows, uint64_t b_cols_avail) {
     return launch_gemm_dma_any(true, a_kn, true, A, B, C, M, N, K, lda, ldb, ldc, accumulate, st, err, splits, partials,
-                               lower_only);
+                               lower_only, k_rows, b_cols_avail);
 }
 
 // fp32 -> bf16, round to nearest even; 4 elements per thread.  Columns cols..cols_pad of dst are zero-filled.

@@ -15,6 +15,9 @@
 
 namespace grass {
 
+bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K,
+                            uint64_t lda, uint64_t ldb, uint64_t ldc, int accumulate, hipStream_t st, hipError_t* err,
+                            uint32_t splits, float* partials, int lower_only, uint64_t k_rows, uint64_t b_cols_avail);
 hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uint64_t N, uint64_t K, uint64_t lda,
                        uint64_t ldb, uint64_t ldc, int accumulate, int lower_only, hipStream_t st, uint32_t splits,
                        float* partials);
@@ -179,13 +182,27 @@ static grass_status sm_backward(const SmLayout& L, unsigned char* base, const fl
                                 float lambda, const float* C, float* grad, hipStream_t hs) {
     float* GTc = reinterpret_cast<float*>(base + L.off_gt);
     float* Rc = reinterpret_cast<float*>(base + L.off_r);
+    const bool kmajor = m >= 128 && ldg % 4 == 0 && aligned(G, 16);      // chunk starts j0 are multiples of 64
     for (uint64_t j0 = 0; j0 < p; j0 += L.pc) {
         const uint64_t pc = j0 + L.pc <= p ? L.pc : p - j0;
-        // GTc (pc x n_pad) = transpose of the column block [j0, j0 + pc) of G
-        hipLaunchKernelGGL(transpose_rows_kernel, dim3((uint32_t)ceil_div(pc, 64), (uint32_t)ceil_div(L.n_pad, 64)), dim3(256), 0,
-                           hs, G + j0, ldg, (uint64_t)0, (uint32_t)n, (uint32_t)L.n_pad, (uint32_t)pc, GTc, L.n_pad);
-        if (gemm_nt_f32(C, GTc, Rc, m, pc, L.n_pad, L.n_pad, L.n_pad, L.pc, 0, 0, hs, 1, nullptr) != hipSuccess)
-            return GRASS_EHIP;
+        // Rc (m x pc) = C G[:, j0 : j0+pc], a contraction over the n rows of G.  With 16-byte aligned rows the GEMM
+        // reads the column block of G in place as a K-major operand (C is zero beyond column n, G's rows end at n);
+        // otherwise the block is transposed into the workspace first.
+        bool taken = false;
+        if (kmajor) {
+            hipError_t derr = hipSuccess;
+            taken = launch_gemm_dma_kmajor(false, C, G + j0, Rc, m, pc, L.n_pad, L.n_pad, ldg, L.pc, 0, hs, &derr, 1, nullptr,
+                                           0, n, ldg - j0);
+            if (taken && derr != hipSuccess) return GRASS_EHIP;
+        }
+        if (!taken) {
+            // GTc (pc x n_pad) = transpose of the column block [j0, j0 + pc) of G
+            hipLaunchKernelGGL(transpose_rows_kernel, dim3((uint32_t)ceil_div(pc, 64), (uint32_t)ceil_div(L.n_pad, 64)),
+                               dim3(256), 0, hs, G + j0, ldg, (uint64_t)0, (uint32_t)n, (uint32_t)L.n_pad, (uint32_t)pc, GTc,
+                               L.n_pad);
+            if (gemm_nt_f32(C, GTc, Rc, m, pc, L.n_pad, L.n_pad, L.n_pad, L.pc, 0, 0, hs, 1, nullptr) != hipSuccess)
+                return GRASS_EHIP;
+        }
         hipLaunchKernelGGL(sm_grad_kernel, dim3((uint32_t)ceil_div(pc, 256)), dim3(256), 0, hs, Gt, ldgt, m, Rc, L.pc, j0, pc,
                            S, inv_temp, lambda, grad);
     }

@@ -35,7 +35,9 @@ def _problem(n, m, p, seed, pad=0):
 
 @pytest.mark.parametrize("n,m,p,lam,temp,pad", [(9, 3, 7, 0.03, 1.0, 0), (50, 5, 333, 0.01, 1.0, 1),
                                                 (200, 130, 4096, 1e-3, 0.5, 0), (300, 140, 5002, 1e-4, 2.0, 2),
-                                                (130, 129, 70000, 1e-5, 1.0, 0)])
+                                                (130, 129, 70000, 1e-5, 1.0, 0),
+                                                # 16-byte aligned rows: the backward product reads G in place
+                                                (131, 128, 70004, 1e-5, 1.0, 0), (77, 260, 4098, 1e-3, 1.0, 2)])
 def test_selective_mask_grad_parity(grass, n, m, p, lam, temp, pad):
     G, Gt, S = _problem(n, m, p, seed=3000 + p, pad=pad)
     A = grass.grass_score(G, Gt, compute_mode=0)
