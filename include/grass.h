@@ -241,9 +241,11 @@ grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t p, uint64_
  *
  * grass_fim: F = (1/N) sum_i g_i g_i^T for the rows of G (N x k fp32 device,
  * ldg >= k).  F is k x k fp32 (ldf >= k), written in full and exactly
- * symmetric.  fp32 MFMA, accumulated over row chunks of G in a fixed order
- * (bit-reproducible).  Workspace from grass_fim_workspace_bytes(N, k), 256-byte
- * aligned.
+ * symmetric.  fp32 MFMA, accumulated over interleaved ranges of the rows of G
+ * in a fixed order (bit-reproducible).  Fastest when G is 16-byte aligned and k
+ * and ldg are multiples of 4: G is then read in place, otherwise transposed
+ * chunks go through the workspace.  Workspace from
+ * grass_fim_workspace_bytes(N, k), 256-byte aligned.
  *
  * grass_fim_inverse: W = (F + lambda I)^{-1}, k x k fp32 (ldw >= k), lambda >= 0
  * absolute.  Only the lower triangle of F is read.  The factorisation runs in
@@ -278,7 +280,9 @@ grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint64_t ldg,
  * first-order method needs, the caller owns the update rule.
  *
  * grass_selective_mask_grad: objective value and gradient with respect to S.
- *   G  (n x p fp32, ldg)  train gradients;  Gt (m x p fp32, ldgt) test gradients;
+ *   G  (n x p fp32, ldg)  train gradients;  Gt (m x p fp32, ldgt) test gradients
+ *      (fastest when G is 16-byte aligned and ldg is a multiple of 4: both large
+ *      products then take G in place from HBM; any 4-byte alignment works);
  *   A  (m x n fp32, lda)  exact scores A[t][i] = <gt_t, g_i>, i.e.
  *                         grass_score(train = G, test = Gt), computed once;
  *   S  (p fp32) logits;  grad (p fp32) receives d objective / d S;
