@@ -51,6 +51,25 @@ def test_selective_mask_grad_parity(grass, n, m, p, lam, temp, pad):
     assert np.abs(got - want_grad).max() <= 2e-4 * np.abs(want_grad).max()
 
 
+def test_selective_mask_grad_column_chunks_aligned_and_unaligned_rows_agree(grass):
+    """66,000 train rows make the backward product run over two column chunks.  The oracle would need minutes for this
+    size, so the two GPU routes are held against each other instead: rows 16-byte aligned (G read in place as a
+    K-major operand) and the same values stored with an odd row distance (transposed chunks, register-staged forward
+    product), each route oracle-checked at smaller sizes above.  They differ only in fp32 summation order."""
+    n, m, p, lam = 66000, 128, 5000, 1e-4
+    G, Gt, S = _problem(n, m, p, seed=3900)                                   # row distance 5,000
+    G2 = torch.empty((n, p + 1), dtype=torch.float32, device=_dev())[:, :p]
+    G2.copy_(G)                                                               # row distance 5,001
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    g1, o1 = grass.grass_selective_mask_grad(G, Gt, A, S, lam, 1.0)
+    g2, o2 = grass.grass_selective_mask_grad(G2, Gt, A, S, lam, 1.0)
+    torch.cuda.synchronize()
+    assert abs(float(o1.item()) - float(o2.item())) <= 1e-6
+    a, b = g1.cpu().numpy().astype(np.float64), g2.cpu().numpy().astype(np.float64)
+    assert np.all(np.isfinite(a)) and np.abs(a).max() > 0
+    assert np.abs(a - b).max() <= 2e-5 * np.abs(b).max()
+
+
 def test_selective_mask_grad_constant_logits_and_degenerate_rows(grass):
     """Constant logits: corr = 1 for every test row, the objective is 1 - lambda p sigma.  A test row of zeros has
     constant scores: it contributes nothing (the oracle would divide by zero, the library defines it as 0)."""
