@@ -5,7 +5,10 @@ Headline workload ("mlp_mask_sjlt"): n = 4,096 per-sample gradients of an MLP
 784-1024-1024-10 (p = 1,863,690 fp32, ReLU-style zeros), Random Mask to
 k' = 65,536, SJLT to k = 4,096 with s = 1, fused (Sec. 3.3.1).  A step is one
 call of grass_sjlt with the mask indices over the whole batch, inputs resident
-in HBM.  Prints ONE JSON line; see the design doc for how each field is derived.
+in HBM.  Prints ONE JSON line: value = n / time per step; roofline.achieved =
+algorithmic bytes per launch (n (4k' + 4k) + 4k') / kernel time measured with
+HIP events; roofline.traffic = HBM bytes per launch from the rocprofv3 counter
+runs summarised under profiles/; cpu_baseline = the CPU oracle on the same rows.
 
 The other paths (s = 4, the plain gather, ResNet-scale SJLT, FactGraSS, score
 GEMM) are timed briefly afterwards and reported under "extras".
@@ -63,8 +66,8 @@ def main() -> int:
                     help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU only (samples are independent; see DESIGN.md "
-              "for how the path would shard); run with --gpus 1", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (samples are independent: more GPUs would compress "
+              "disjoint row ranges with identical tables and exchange nothing); run with --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np

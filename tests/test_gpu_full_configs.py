@@ -1,7 +1,8 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py
 times, checked on sampled outputs the oracle can compute one by one.
 
-Workloads (synthetic stand-ins, recipe in the design doc): MLP-scale Mask+SJLT
+Workloads (seeded synthetic stand-ins from synth.py for gradients that are not
+available): MLP-scale Mask+SJLT
 (n=4,096, p=1,863,690, k'=65,536, k=4,096, s=1 and 4); ResNet-scale SJLT
 (n=1,024, p=11,173,962, k=8,192) and a column slice of the dense Gaussian
 baseline; FactGraSS on a 4,096 x 4,096 linear layer (n=32, T=512); FactGraSS
