@@ -67,16 +67,27 @@ __device__ __forceinline__ double lane_bcast(double v, int src) {
 // Cholesky factor of the NB x NB diagonal block j (lower, in place) and its inverse D = L_jj^{-1} into the
 // same block of X64 (zeros above the diagonal).  A non-positive pivot records its 1-based index in *info
 // (first one wins) and is replaced by 1 so that the run stays finite.
-// One wavefront, no LDS and no barriers: the column recurrence is a chain of dependent fp64 operations (32 cycles
-// each on this chip), so what matters is the length of that chain, not parallel width.  Lane r keeps row r of the
-// block in registers; in step c the pivot and the entries l[q][c] reach the other lanes through readlane, and the
-// trailing update a[r][q] -= l[r][c] l[q][c] is 63-c independent FMAs per lane.  The inverse is computed the same
-// way: lane t solves L x = e_t, the entries L[r][m] arriving by readlane from lane r.
+// One wavefront and no barriers: the column recurrence is a chain of dependent fp64 operations (32 cycles each on
+// this chip), so what matters is the length of that chain and the number of instructions the one wavefront has to
+// issue, not parallel width.  Lane r keeps row r of the block in registers.  In step c every lane scales its entry
+// of column c and writes it to LDS; the entries l[q][c] that the trailing update a[r][q] -= l[r][c] l[q][c] needs
+// come back as broadcast reads of two doubles each (all lanes read the same address).  The first form of this
+// kernel fetched them with two v_readlane per value: 16,700 instructions (8,500 v_readlane, 3,300 hazard nops),
+// 45 us per block; this one issues 12,600 and takes 39 us.  The inverse is computed the same way: lane t solves
+// L x = e_t with the rows of L read back from LDS by broadcast.
+// The loop bodies must stay free of branches (every lane stores the same 1/pivot): with a conditional store per
+// column the compiler sank the trailing updates of far columns across 30 to 40 basic blocks towards their use and
+// spilled 2,200 registers to scratch.  The empty asm statements bound how far it may move LDS reads.
+constexpr int kPotrfLd = NB + 2;              // doubles per LDS row: 16-byte aligned rows, lanes spread over the banks
+struct f64x2 { double x, y; };
 __global__ void __launch_bounds__(64) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
+    __shared__ __align__(16) double Lc[NB][NB];          // Lc[c][q] = L[q][c]: column c contiguous
+    __shared__ __align__(16) double Lr[NB][kPotrfLd];    // Lr[i][m] = L[i][m]: row i contiguous
+    __shared__ __align__(16) double Ys[NB];              // 1 / L[c][c]
     const int r = threadIdx.x;
     double* Ab = A64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
     double* Xb = X64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
-    double a[NB], yv[NB];
+    double a[NB];
 #pragma unroll
     for (int q = 0; q < NB; ++q) a[q] = Ab[(uint64_t)r * kp + q];
     int bad = 0;
@@ -89,30 +100,45 @@ __global__ void __launch_bounds__(64) potrf_block_kernel(double* A64, double* X6
         double y = __builtin_amdgcn_rsq(pv);                         // pivot^(-1/2): estimate + two Newton steps
         y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
         y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
-        yv[c] = y;
+        Ys[c] = y;                                                   // every lane stores the same value: no branch
         const double lc = r == c ? pv * y : (r > c ? a[c] * y : 0.0);
         a[c] = lc;
+        if (c + 1 < NB) {
+            Lc[c][r] = lc;                                           // LDS operations of one wavefront stay in order
 #pragma unroll
-        for (int q = c + 1; q < NB; ++q) a[q] = fma(-lc, lane_bcast(lc, q), a[q]);    // only rows r >= q are used later
+            for (int q0 = (c + 1) & ~1; q0 < NB; q0 += 2) {          // pairs (q0, q0 + 1), q0 even
+                const f64x2 l = *reinterpret_cast<const f64x2*>(&Lc[c][q0]);
+                if (q0 > c) a[q0] = fma(-lc, l.x, a[q0]);            // only rows r >= q are used later
+                a[q0 + 1] = fma(-lc, l.y, a[q0 + 1]);
+                if ((q0 & 14) == 14) asm volatile("" ::: "memory");   // at most 8 reads in flight (measured best)
+            }
+        }
+        asm volatile("" ::: "memory");
     }
     if (r == 0 && bad != 0 && info) atomicCAS(info, 0, (int)(j * NB) + bad);
 #pragma unroll
-    for (int q = 0; q < NB; ++q) Ab[(uint64_t)r * kp + q] = q <= r ? a[q] : 0.0;
-    // lane t = r: column t of the inverse
+    for (int q = 0; q < NB; ++q) {
+        const double v = q <= r ? a[q] : 0.0;
+        Ab[(uint64_t)r * kp + q] = v;
+        Lr[r][q] = v;
+    }
+    // lane t = r: column t of the inverse, x[i] = (delta_it - sum_{m<i} L[i][m] x[m]) / L[i][i]
     double x[NB];
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
         double acc0 = i == r ? 1.0 : 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
 #pragma unroll
-        for (int m = 0; m < i; ++m) {
-            const double lim = lane_bcast(a[m], i);                  // L[i][m]
-            if ((m & 3) == 0) acc0 = fma(-lim, x[m], acc0);
-            else if ((m & 3) == 1) acc1 = fma(-lim, x[m], acc1);
-            else if ((m & 3) == 2) acc2 = fma(-lim, x[m], acc2);
-            else acc3 = fma(-lim, x[m], acc3);
+        for (int m0 = 0; m0 < i; m0 += 2) {
+            const f64x2 l = *reinterpret_cast<const f64x2*>(&Lr[i][m0]);      // L[i][m0], L[i][m0 + 1]
+            if ((m0 & 2) == 0) acc0 = fma(-l.x, x[m0], acc0); else acc2 = fma(-l.x, x[m0], acc2);
+            if (m0 + 1 < i) {
+                if ((m0 & 2) == 0) acc1 = fma(-l.y, x[m0 + 1], acc1); else acc3 = fma(-l.y, x[m0 + 1], acc3);
+            }
+            if ((m0 & 14) == 14) asm volatile("" ::: "memory");
         }
-        const double v = ((acc0 + acc1) + (acc2 + acc3)) * yv[i];
+        const double v = ((acc0 + acc1) + (acc2 + acc3)) * Ys[i];
         x[i] = i >= r ? v : 0.0;
+        asm volatile("" ::: "memory");
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i) Xb[(uint64_t)i * kp + r] = x[i];
