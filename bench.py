@@ -62,6 +62,8 @@ def main() -> int:
     ap.add_argument("--sweep", action="store_true",
                     help="SJLT (s = 1) against the dense Gaussian projection at p = 131,072 over target dimensions and "
                          "input sparsity levels (the setting of the paper's SJLT benchmark figure); prints one JSON object")
+    ap.add_argument("--full-score", action="store_true",
+                    help="run only the attribute-stage GEMM over all 112 concatenated layer blocks (K = 458,752, bf16)")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -89,6 +91,27 @@ def main() -> int:
         t, _, _ = _timed(lambda: b.copy_(a), 5, 2, torch)
         print(json.dumps({"copy_reference_bytes_read": nbytes, "copy_reference_bytes_written": nbytes,
                           "ms": round(t / 5, 4), "GBps_read_plus_write": round(2 * nbytes / (t / 5 * 1e-3) / 1e9, 1)}))
+        return 0
+
+    if args.full_score:
+        # the attribute stage of the Llama-style configuration at its full width: 65,536 train rows and 1,024 test
+        # rows of 112 x 4,096 = 458,752 compressed coordinates, kept in bf16 (60 GB; fp32 would be 120 GB)
+        N5, M5, K5 = 65536, 1024, 112 * 4096
+        trb = torch.empty((N5, K5), dtype=torch.bfloat16, device=dev)
+        for r0 in range(0, N5, 4096):
+            trb[r0:r0 + 4096] = synth.dense_normal(4096, K5, seed=1400 + r0, device=dev).to(torch.bfloat16)
+        teb = synth.dense_normal(M5, K5, seed=1399, device=dev).to(torch.bfloat16)
+        sc = torch.empty((M5, N5), dtype=torch.float32, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_score_bf16(trb, teb, out=sc), 1, 0, torch)
+        tf = 2.0 * N5 * M5 * K5 / (t * 1e-3) / 1e12
+        # spot check of four entries against fp64 inner products of the same bf16 values
+        worst = 0.0
+        for (mi, ni) in ((0, 0), (1023, 65535), (517, 40000), (3, 12345)):
+            ref = float((teb[mi].double() * trb[ni].double()).sum().item())
+            worst = max(worst, abs(float(sc[mi, ni].item()) - ref) / (abs(ref) + K5 ** 0.5))
+        print(json.dumps({"workload": "score_gemm_full_width_bf16", "N": N5, "M": M5, "K": K5, "ms": round(t, 1),
+                          "TFLOPs": round(tf, 1), "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4),
+                          "spot_check_rel_err": worst}))
         return 0
 
     if args.sweep:
@@ -385,6 +408,20 @@ def main() -> int:
         t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=1, out=sc, ws=None), 5, 1, torch)
         extras["score_gemm_mode1_no_workspace"] = {"ms": round(t / 5, 4),
                                                    "TFLOPs": round(2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12, 2)}
+        # 16 layer blocks wide (K = 65,536): the fraction of the roofline does not depend on K once K is a few thousand
+        tr16 = synth.dense_normal(N5, 16 * K5, seed=1007, device=dev)
+        te16 = synth.dense_normal(M5, 16 * K5, seed=1008, device=dev)
+        t, _, _ = _timed(lambda: grass.grass_score(tr16, te16, compute_mode=0, out=sc, ws=None), 2, 1, torch)
+        tf = 2.0 * N5 * M5 * 16 * K5 / (t / 2 * 1e-3) / 1e12
+        extras["score_gemm_mode0_K65536"] = {"ms": round(t / 2, 3), "TFLOPs": round(tf, 2),
+                                             "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4)}
+        tr16b, te16b = grass.grass_to_bf16(tr16), grass.grass_to_bf16(te16)
+        del tr16, te16
+        t, _, _ = _timed(lambda: grass.grass_score_bf16(tr16b, te16b, out=sc), 3, 1, torch)
+        tf = 2.0 * N5 * M5 * 16 * K5 / (t / 3 * 1e-3) / 1e12
+        extras["score_gemm_bf16_inputs_K65536"] = {"ms": round(t / 3, 3), "TFLOPs": round(tf, 2),
+                                                   "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4)}
+        del tr16b, te16b
         trb, teb = grass.grass_to_bf16(tr), grass.grass_to_bf16(te)
         t, _, _ = _timed(lambda: grass.grass_score_bf16(trb, teb, out=sc), 10, 2, torch)
         tf = 2.0 * N5 * M5 * K5 / (t / 10 * 1e-3) / 1e12
