@@ -261,6 +261,17 @@ def main() -> int:
         gbps = n3 * (4 * p3 + 4 * k3) / (t / 10 * 1e-3) / 1e9
         extras["resnet_sjlt_s1"] = {"ms": round(t / 10, 4), "samples_per_s": round(n3 / (t / 10 * 1e-3), 1),
                                     "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
+        # the dense Gaussian baseline on the same full input (P is 366 GB as a matrix: it is generated chunk by chunk
+        # inside the call and never stored); one call per mode, 1.87e17 FLOP each
+        wg3 = torch.empty(grass.grass_gauss_project_workspace_bytes(n3, p3, k3, 32768), dtype=torch.uint8, device=dev)
+        for mode in (1, 0):
+            t, _, _ = _timed(lambda: grass.grass_gauss_project(g3, k3, seed, 2, 32768, compute_mode=mode, out=o3, ws=wg3),
+                             1, 0, torch)
+            extras[f"resnet_gauss_project_full_p_mode{mode}"] = {
+                "ms": round(t, 1), "samples_per_s": round(n3 / (t * 1e-3), 1),
+                "TFLOPs_incl_generation": round(2.0 * n3 * p3 * k3 / (t * 1e-3) / 1e12, 1),
+                "sjlt_speedup": round(t / extras["resnet_sjlt_s1"]["ms"], 1)}
+        del wg3
         g3h = g3.to(torch.bfloat16)
         del g3
         t, _, _ = _timed(lambda: grass.grass_sjlt_bf16(g3h, k3, 1, seed, 1, out=o3, ws=w3), 10, 2, torch)

@@ -404,6 +404,15 @@ extern "C" grass_status grass_gauss_matrix(uint64_t seed, uint64_t stream_id, ui
     return launch_status();
 }
 
+// dst (rows x cols_pad, row distance ld_dst) = src (rows x cols), columns cols..cols_pad zero; rows dealt to blockIdx.y.
+__global__ void __launch_bounds__(256) copy_pad_f32_kernel(const float* src, uint64_t ld_src, uint64_t rows, uint64_t cols,
+                                                           uint64_t cols_pad, float* dst, uint64_t ld_dst) {
+    const uint64_t c = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (c >= cols_pad) return;
+    for (uint64_t r = blockIdx.y; r < rows; r += gridDim.y)
+        dst[r * ld_dst + c] = c < cols ? __builtin_nontemporal_load(src + r * ld_src + c) : 0.0f;
+}
+
 static uint64_t gauss_chunk(uint64_t p, uint64_t p_chunk) {
     uint64_t pc = p_chunk == 0 ? 8192 : p_chunk;
     pc = (pc + 31) / 32 * 32;              // whole 64-byte K slices of fp32 and of bf16
@@ -428,7 +437,9 @@ static GaussPlan gauss_plan(uint64_t n, uint64_t p, uint32_t k, uint64_t p_chunk
     if (big && (mode == 0 || G.bf16_path) && first % 32 == 0) G.splits = gemm_dma_splits(n, k, first, mode == 0, 8);
     size_t o = 0;
     G.off_p = o; o += up256s((size_t)k * G.pc * (G.bf16_path ? 2 : 4));
-    G.off_g = o; if (G.bf16_path) o += up256s((size_t)n * G.pc * 2);
+    // a chunk of g: rounded to bf16 (mode 1), or copied to 16-byte aligned rows when g's own rows are not (mode 0;
+    // the query does not know the alignment, so the room is always there)
+    G.off_g = o; if (G.bf16_path) o += up256s((size_t)n * G.pc * 2); else if (big && mode == 0) o += up256s((size_t)n * G.pc * 4);
     G.off_part = o; if (G.splits > 1) o += up256s((size_t)G.splits * n * k * 4);
     G.total = o;
     return G;
@@ -453,8 +464,9 @@ extern "C" grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t
     const uint64_t pc = G.pc;
     if (ceil_div(pc, 256) > 0x7FFFFFFFull) return GRASS_EUNSUPPORTED;
     if (!ws || ws_bytes < G.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
-    // the split fp32 path needs every chunk of g to qualify for the direct-to-LDS kernel
-    if (G.splits > 1 && compute_mode == 0 && (!aligned(g, 16) || ldg % 4 != 0)) G.splits = 1;
+    // the fp32 direct-to-LDS kernel needs 16-byte aligned rows: chunks of a g that has none are copied to the workspace
+    // first (2 x 4 bytes of traffic per element against 2k flops: nothing next to the product)
+    const bool stage_g = compute_mode == 0 && n >= 128 && k >= 128 && (!aligned(g, 16) || ldg % 4 != 0);
     unsigned char* base = static_cast<unsigned char*>(ws);
     float* partials = G.splits > 1 ? reinterpret_cast<float*>(base + G.off_part) : nullptr;
     hipStream_t hs = as_stream(stream);
@@ -480,13 +492,22 @@ extern "C" grass_status grass_gauss_project(const float* g, uint64_t n, uint64_t
             continue;
         }
         float* P = reinterpret_cast<float*>(base + G.off_p);
-        launch_gauss_matrix(sub, p, k, p0, cur, cur, false, P, pc, hs);
         GemmArgs a;
         a.A = g + p0; a.B = P; a.C = out;
         a.M = n; a.N = k; a.K = cur; a.lda = ldg; a.ldb = pc; a.ldc = ldo;
         a.accumulate = accumulate;
+        if (stage_g) {
+            const uint64_t cur_pad = (cur + 15) / 16 * 16;         // zero-padded to whole K slices, like P
+            float* gs = reinterpret_cast<float*>(base + G.off_g);
+            hipLaunchKernelGGL(copy_pad_f32_kernel, dim3((uint32_t)ceil_div(cur_pad, 256), (uint32_t)(n < 65535 ? n : 65535)),
+                               dim3(256), 0, hs, g + p0, ldg, n, cur, cur_pad, gs, pc);
+            launch_gauss_matrix(sub, p, k, p0, cur, cur_pad, false, P, pc, hs);
+            a.A = gs; a.lda = pc; a.K = cur_pad;
+        } else {
+            launch_gauss_matrix(sub, p, k, p0, cur, cur, false, P, pc, hs);
+        }
         if (G.splits > 1) {
-            uint32_t s_cur = cur % 16 == 0 ? gemm_dma_splits(n, k, cur, true, G.splits) : 1;
+            uint32_t s_cur = a.K % 16 == 0 ? gemm_dma_splits(n, k, a.K, true, G.splits) : 1;
             if (s_cur > G.splits) s_cur = G.splits;
             if (s_cur == 1) {                              // short or ragged tail: a one-range product into partial 0
                 a.C = partials; a.ldc = k;

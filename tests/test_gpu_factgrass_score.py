@@ -351,7 +351,9 @@ def test_gauss_matrix_parity(grass, seed, stream, p, k, p0, pc):
                                               (256, 16384, 256, 4096, 1), (33, 4098, 64, 4096, 0),
                                               # few output tiles: the contraction is split over K ranges
                                               (256, 16384, 256, 4096, 0), (130, 20000, 300, 8192, 1), (200, 5001, 128, 1024, 1), (130, 20000, 300, 8192, 0),
-                                              (128, 9000, 128, 4104, 0), (200, 2048, 128, 0, 0)])
+                                              (128, 9000, 128, 4104, 0), (200, 2048, 128, 0, 0),
+                                              # rows of g not 16-byte aligned: fp32 chunks are staged in the workspace
+                                              (200, 5001, 128, 1024, 0), (130, 20002, 300, 8192, 0), (129, 8191, 130, 0, 0)])
 def test_gauss_project_parity(grass, n, p, k, chunk, mode):
     g = synth.laplace_sparse(n, p, 0.3, 1e-3, seed=80, device=_dev())
     out = grass.grass_gauss_project(g, k, seed=1, stream_id=2, p_chunk=chunk, compute_mode=mode)
