@@ -32,7 +32,7 @@ MFMA_PEAK_BF16_TFLOPS = 2500.0
 # HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc
 # (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a plain copy of known
 # size; see profiles/sjlt_fused_mlp_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": 21087481721}
+MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": 21087231664}
 
 
 def _timed(fn, steps, warmup, torch):
