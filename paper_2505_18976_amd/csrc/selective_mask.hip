@@ -163,16 +163,24 @@ static grass_status sm_masked_scores(const SmLayout& L, unsigned char* base, con
     const uint64_t ld_w = (p + 3) / 4 * 4;
     hipLaunchKernelGGL(sm_weight_kernel, dim3((uint32_t)ceil_div(ld_w, 256)), dim3(256), 0, hs, Gt, ldgt, m, p, S, inv_temp, Gtw,
                        ld_w, sig_part);
+    // The direct-to-LDS GEMM contracts over whole 64-byte slices.  With 16-byte aligned rows of G the bulk of the
+    // contraction (p rounded down to a multiple of 16) goes through it and the last p % 16 columns are added by a
+    // second, tiny product; otherwise one product over all p columns runs on the register-staged kernel.
+    uint64_t p_main = p;
+    if (p % 16 != 0 && p >= 4096 && ldg % 4 == 0 && aligned(G, 16) && m >= 128 && n >= 128) p_main = p / 16 * 16;
     uint32_t splits = 1;
-    if (ceil_div(m, 128) * ceil_div(n, 128) < 1024) splits = gemm_nt_f32_splits(Gtw, G, m, n, p, ld_w, ldg, kSmMaxSplits);
+    if (ceil_div(m, 128) * ceil_div(n, 128) < 1024) splits = gemm_nt_f32_splits(Gtw, G, m, n, p_main, ld_w, ldg, kSmMaxSplits);
     if (splits > 1) {
         float* partials = reinterpret_cast<float*>(base + L.off_part);
-        if (gemm_nt_f32(Gtw, G, nullptr, m, n, p, ld_w, ldg, n, 0, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
+        if (gemm_nt_f32(Gtw, G, nullptr, m, n, p_main, ld_w, ldg, n, 0, 0, hs, splits, partials) != hipSuccess) return GRASS_EHIP;
         hipLaunchKernelGGL(reduce_partials_kernel, dim3((uint32_t)ceil_div(m * n, 256)), dim3(256), 0, hs, partials, m,
                            (uint32_t)n, splits, 1.0f, B, L.n_pad);
-    } else if (gemm_nt_f32(Gtw, G, B, m, n, p, ld_w, ldg, L.n_pad, 0, 0, hs, 1, nullptr) != hipSuccess) {
+    } else if (gemm_nt_f32(Gtw, G, B, m, n, p_main, ld_w, ldg, L.n_pad, 0, 0, hs, 1, nullptr) != hipSuccess) {
         return GRASS_EHIP;
     }
+    if (p_main < p &&
+        gemm_nt_f32(Gtw + p_main, G + p_main, B, m, n, p - p_main, ld_w, ldg, L.n_pad, 1, 0, hs, 1, nullptr) != hipSuccess)
+        return GRASS_EHIP;
     return GRASS_OK;
 }
 
