@@ -22,7 +22,9 @@
  *     (seed, stream_id, counter) through the splitmix64 generator
  *         sm(seed, c)            = finalise(seed + (c + 1) * 0x9E3779B97F4A7C15)
  *         H(seed, stream_id, c)  = sm(sm(seed, stream_id), c)
- *     evaluated in registers; no table is ever stored on the hot path.
+ *     evaluated in registers; no table is kept between calls (the unmasked
+ *     SJLT of long rows fills a transient table of 2 bytes per position in its
+ *     workspace, see grass_sjlt).
  *     Suggested stream ids: 0 mask and 1 SJLT for general vectors; for linear
  *     layer l, 16+4l input mask, 17+4l output-gradient mask, 18+4l SJLT.
  *   - Determinism: integer outputs (indices, tables) are bit-reproducible.
