@@ -31,6 +31,10 @@
  *     Floating-point outputs use a fixed cross-block reduction order; inside
  *     a block, additions into LDS buckets happen in hardware-arbitrated order,
  *     so results can differ between runs in the last bits.
+ *   - Threads: the library keeps no mutable process-wide settings.  Entry
+ *     points may be called from several host threads at once as long as calls
+ *     that share a workspace or an output buffer are ordered by the caller
+ *     (same stream, or events).
  */
 #ifndef GRASS_H
 #define GRASS_H
@@ -52,6 +56,25 @@ typedef enum {
 
 typedef void* grass_stream;
 
+/* Optional launch-shape overrides for experiments, handed to the calls that
+ * take a `host_tuning` argument (a HOST pointer, read during the call only;
+ * NULL = the library's heuristics).  A field that is 0 or not one of the listed
+ * values leaves that choice to the heuristic.  The workspace query and the call
+ * must be given the same values.  There is no process-wide setting.
+ *   sjlt_rows_per_block  1, 2, 4 or 8 rows (samples) per workgroup
+ *   sjlt_column_chunks   chunks of SJLT input positions per row group
+ *   sjlt_threads         256, 512 or 1024 threads per workgroup
+ *   sjlt_accumulator     2 = fp32 LDS buckets updated by compare-and-swap,
+ *                        3 = fp64 LDS buckets updated by the fp64 atomic add
+ *   factgrass_tokens_per_block  tokens per workgroup (rounded up to 32)      */
+typedef struct {
+    int sjlt_rows_per_block;
+    int sjlt_column_chunks;
+    int sjlt_threads;
+    int sjlt_accumulator;
+    int factgrass_tokens_per_block;
+} grass_tuning;
+
 /* Largest SJLT output dimension k the LDS-resident accumulators cover. */
 #define GRASS_MAX_K 32768u
 /* Largest masked factor width (k_in', k_out') of factgrass_linear. */
@@ -71,7 +94,8 @@ grass_status grass_mask_indices(uint64_t seed, uint64_t stream_id, uint64_t p, u
                                 int32_t* idx, void* ws, size_t ws_bytes, grass_stream stream);
 
 /* Debug helper: *host_ok = 1 iff idx[0..kprime) is strictly ascending and
- * within [0, p).  Synchronises the stream.                                   */
+ * within [0, p).  Synchronises the stream; concurrent calls are serialised
+ * inside the library (they share one result word per device).               */
 grass_status grass_check_indices(const int32_t* idx, uint32_t kprime, uint64_t p, int* host_ok,
                                  grass_stream stream);
 
@@ -108,12 +132,13 @@ grass_status grass_sjlt_tables(uint64_t seed, uint64_t stream_id, uint64_t d, ui
  * that holds them but not the table is accepted and the call hashes every
  * position instead (same result bit for bit, a few per cent slower).         */
 grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint32_t kprime_or_0,
-                                        uint32_t k, uint32_t s, size_t* host_bytes);
+                                        uint32_t k, uint32_t s, const grass_tuning* host_tuning,
+                                        size_t* host_bytes);
 grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
                         const int32_t* idx, uint32_t kprime,
                         uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
                         float* out, uint64_t ldo,
-                        void* ws, size_t ws_bytes, grass_stream stream);
+                        void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
 /* The same operation on gradients stored as bf16 (n x p 16-bit words, ldg in
  * elements, 2-byte aligned): every value is used exactly (a bf16 is the upper
  * half of an fp32), accumulation and output are as in grass_sjlt.  Workspace:
@@ -123,7 +148,7 @@ grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg
                              const int32_t* idx, uint32_t kprime,
                              uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
                              float* out, uint64_t ldo,
-                             void* ws, size_t ws_bytes, grass_stream stream);
+                             void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
 
 /* ------------------------------------------------------------------ FactGraSS
  * Sec. 3.3.2 "Factorized GraSS" for one linear layer, using Eq. (2)/(3):
@@ -136,14 +161,15 @@ grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg
  * out: n x k fp32 with row distance ldo (lets the caller place layer l at a
  * column offset of a concatenated row).  k_in', k_out' <= GRASS_MAX_FACTOR.  */
 grass_status factgrass_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
-                                              uint32_t k, uint32_t s, size_t* host_bytes);
+                                              uint32_t k, uint32_t s, const grass_tuning* host_tuning,
+                                              size_t* host_bytes);
 grass_status factgrass_linear(const void* x, const void* gout,
                               uint64_t n, uint64_t T, uint32_t d_in, uint32_t d_out,
                               const int32_t* idx_in, uint32_t kin_p,
                               const int32_t* idx_out, uint32_t kout_p,
                               uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
                               float* out, uint64_t ldo,
-                              void* ws, size_t ws_bytes, grass_stream stream);
+                              void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
 
 /* The same for many linear layers of one model pass in a single launch (the
  * per-layer gradients are compressed independently, Sec. 3.3.2; concatenating
@@ -161,11 +187,12 @@ typedef struct {
     float* out;               /* n x k block of this layer, row distance ldo */
 } factgrass_layer;
 grass_status factgrass_layers_workspace_bytes(uint32_t n_layers, uint64_t n, uint64_t T, uint32_t kin_p,
-                                              uint32_t kout_p, uint32_t k, uint32_t s, size_t* host_bytes);
+                                              uint32_t kout_p, uint32_t k, uint32_t s,
+                                              const grass_tuning* host_tuning, size_t* host_bytes);
 grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_layers,
                               uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
                               uint32_t k, uint32_t s, uint64_t seed, uint64_t ldo,
-                              void* ws, size_t ws_bytes, grass_stream stream);
+                              void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
 
 /* ---------------------------------------------------------- LoGra baseline
  * Sec. 3.3.2 "Recap on LoGra", Eq. (3): the factorised dense projection
@@ -358,16 +385,6 @@ grass_status factmask_linear(const void* x, const void* gout,
 grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_id, uint64_t p,
                                      const int32_t* idx, uint32_t kprime,
                                      uint32_t k, uint32_t s, float* P, uint64_t ldP, grass_stream stream);
-
-/* ------------------------------------------------------------------- tuning
- * Overrides the launch heuristics of grass_sjlt for experiments: rows per
- * block (1,2,4,8), column chunks per row group, threads per block
- * (256,512,1024) and the LDS accumulator (2 fp32 compare-and-swap, 3 fp64
- * atomic add); 0 or any other value restores the heuristic for that field.
- * Process-wide; changes the workspace size the query reports.                  */
-void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads, int accumulator);
-/* Same for factgrass_linear: tokens per block (multiple of 32; 0 = heuristic). */
-void grass_set_factgrass_tuning(int tokens_per_block);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,14 @@ class FactgrassLayer(ctypes.Structure):
                 ("d_in", _u32), ("d_out", _u32), ("stream_id", _u64), ("out", _vp)]
 
 
+class GrassTuning(ctypes.Structure):
+    """Mirror of `grass_tuning` in include/grass.h (launch-shape overrides of one call; 0 = heuristic)."""
+    _fields_ = [("sjlt_rows_per_block", _int), ("sjlt_column_chunks", _int), ("sjlt_threads", _int),
+                ("sjlt_accumulator", _int), ("factgrass_tokens_per_block", _int)]
+
+
+_tun = ctypes.POINTER(GrassTuning)
+
 # name -> (restype, argtypes); the list the ABI test checks against the header.
 SIGNATURES = {
     "grass_strerror": (ctypes.c_char_p, [_int]),
@@ -37,15 +45,16 @@ SIGNATURES = {
     "grass_check_indices": (_int, [_vp, _u32, _u64, ctypes.POINTER(_int), _vp]),
     "grass_mask": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _vp, _u64, _vp]),
     "grass_sjlt_tables": (_int, [_u64, _u64, _u64, _u32, _u32, _vp, _vp, _vp]),
-    "grass_sjlt_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
-    "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
-    "grass_sjlt_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _vp]),
-    "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
+    "grass_sjlt_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _tun, ctypes.POINTER(_sz)]),
+    "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun, _vp]),
+    "grass_sjlt_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun,
+                               _vp]),
+    "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, _tun, ctypes.POINTER(_sz)]),
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
-                                _vp, _u64, _vp, _sz, _vp]),
-    "factgrass_layers_workspace_bytes": (_int, [_u32, _u64, _u64, _u32, _u32, _u32, _u32, ctypes.POINTER(_sz)]),
+                                _vp, _u64, _vp, _sz, _tun, _vp]),
+    "factgrass_layers_workspace_bytes": (_int, [_u32, _u64, _u64, _u32, _u32, _u32, _u32, _tun, ctypes.POINTER(_sz)]),
     "factgrass_layers": (_int, [ctypes.POINTER(FactgrassLayer), _u32, _u64, _u64, _u32, _u32, _u32, _u32, _u64, _u64,
-                                _vp, _sz, _vp]),
+                                _vp, _sz, _tun, _vp]),
     "logra_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
     "logra_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
     "grass_score_workspace_bytes": (_int, [_u64, _u64, _u64, _int, ctypes.POINTER(_sz)]),
@@ -72,8 +81,6 @@ SIGNATURES = {
     "factmask_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
     "factmask_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
     "grass_projection_matrix": (_int, [_u64, _u64, _u64, _vp, _u32, _u32, _u32, _vp, _u64, _vp]),
-    "grass_set_sjlt_tuning": (None, [_int, _int, _int, _int]),
-    "grass_set_factgrass_tuning": (None, [_int]),
 }
 
 _lib = None
@@ -123,6 +130,15 @@ def _ptr(t):
 def _ld(t: torch.Tensor) -> int:
     assert t.dim() == 2 and t.stride(1) == 1, "row-major matrix expected"
     return t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1])
+
+
+def _tuning(tuning):
+    """None, a GrassTuning, or a dict of its fields -> pointer argument."""
+    if tuning is None:
+        return None
+    if isinstance(tuning, dict):
+        tuning = GrassTuning(**tuning)
+    return ctypes.byref(tuning)
 
 
 def _workspace(nbytes: int, device) -> torch.Tensor | None:
@@ -176,15 +192,15 @@ def grass_sjlt_tables(seed: int, stream_id: int, d: int, k: int, s: int, device=
     return bucket, sign
 
 
-def grass_sjlt_workspace_bytes(n: int, p: int, kprime_or_0: int, k: int, s: int) -> int:
+def grass_sjlt_workspace_bytes(n: int, p: int, kprime_or_0: int, k: int, s: int, tuning=None) -> int:
     out = _sz(0)
-    _check(load_library().grass_sjlt_workspace_bytes(n, p, kprime_or_0, k, s, ctypes.byref(out)),
+    _check(load_library().grass_sjlt_workspace_bytes(n, p, kprime_or_0, k, s, _tuning(tuning), ctypes.byref(out)),
            "grass_sjlt_workspace_bytes")
     return out.value
 
 
 def grass_sjlt(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, idx: torch.Tensor | None = None,
-               out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+               out: torch.Tensor | None = None, ws: torch.Tensor | None = None, tuning=None) -> torch.Tensor:
     """SJLT_k of the rows of g, or fused GraSS when idx is given."""
     assert g.dtype == torch.float32
     n, p = g.shape
@@ -192,15 +208,16 @@ def grass_sjlt(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, i
     if out is None:
         out = torch.empty((n, k), dtype=torch.float32, device=g.device)
     if ws is None:
-        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s), g.device)
+        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s, tuning), g.device)
     _check(load_library().grass_sjlt(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
-                                     _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+                                     _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _tuning(tuning),
+                                     _stream()),
            "grass_sjlt")
     return out
 
 
 def grass_sjlt_bf16(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int = 1, idx: torch.Tensor | None = None,
-                    out: torch.Tensor | None = None, ws: torch.Tensor | None = None) -> torch.Tensor:
+                    out: torch.Tensor | None = None, ws: torch.Tensor | None = None, tuning=None) -> torch.Tensor:
     """grass_sjlt on gradients stored as bf16 (fp32 accumulation and output)."""
     assert g.dtype == torch.bfloat16
     n, p = g.shape
@@ -208,23 +225,25 @@ def grass_sjlt_bf16(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int =
     if out is None:
         out = torch.empty((n, k), dtype=torch.float32, device=g.device)
     if ws is None:
-        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s), g.device)
+        ws = _workspace(grass_sjlt_workspace_bytes(n, p, kprime, k, s, tuning), g.device)
     _check(load_library().grass_sjlt_bf16(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
-                                          _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+                                          _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(),
+                                          _tuning(tuning), _stream()),
            "grass_sjlt_bf16")
     return out
 
 
-def factgrass_linear_workspace_bytes(n: int, T: int, kin_p: int, kout_p: int, k: int, s: int) -> int:
+def factgrass_linear_workspace_bytes(n: int, T: int, kin_p: int, kout_p: int, k: int, s: int, tuning=None) -> int:
     out = _sz(0)
-    _check(load_library().factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, k, s, ctypes.byref(out)),
+    _check(load_library().factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, k, s, _tuning(tuning),
+                                                           ctypes.byref(out)),
            "factgrass_linear_workspace_bytes")
     return out.value
 
 
 def factgrass_linear(x: torch.Tensor, gout: torch.Tensor, idx_in: torch.Tensor, idx_out: torch.Tensor,
                      k: int, s: int, seed: int, stream_id: int, out: torch.Tensor | None = None,
-                     ws: torch.Tensor | None = None) -> torch.Tensor:
+                     ws: torch.Tensor | None = None, tuning=None) -> torch.Tensor:
     assert x.dtype == torch.bfloat16 and gout.dtype == torch.bfloat16
     assert x.is_contiguous() and gout.is_contiguous()
     n, T, d_in = x.shape
@@ -233,22 +252,27 @@ def factgrass_linear(x: torch.Tensor, gout: torch.Tensor, idx_in: torch.Tensor, 
     if out is None:
         out = torch.empty((n, k), dtype=torch.float32, device=x.device)
     if ws is None:
-        ws = _workspace(factgrass_linear_workspace_bytes(n, T, idx_in.numel(), idx_out.numel(), k, s), x.device)
+        ws = _workspace(factgrass_linear_workspace_bytes(n, T, idx_in.numel(), idx_out.numel(), k, s, tuning),
+                        x.device)
     _check(load_library().factgrass_linear(_ptr(x), _ptr(gout), n, T, d_in, d_out, _ptr(idx_in), idx_in.numel(),
                                            _ptr(idx_out), idx_out.numel(), k, s, seed, stream_id, _ptr(out),
-                                           _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _stream()),
+                                           _ld(out), _ptr(ws), 0 if ws is None else ws.numel(), _tuning(tuning),
+                                           _stream()),
            "factgrass_linear")
     return out
 
 
-def factgrass_layers_workspace_bytes(n_layers: int, n: int, T: int, kin_p: int, kout_p: int, k: int, s: int) -> int:
+def factgrass_layers_workspace_bytes(n_layers: int, n: int, T: int, kin_p: int, kout_p: int, k: int, s: int,
+                                     tuning=None) -> int:
     out = _sz(0)
-    _check(load_library().factgrass_layers_workspace_bytes(n_layers, n, T, kin_p, kout_p, k, s, ctypes.byref(out)),
+    _check(load_library().factgrass_layers_workspace_bytes(n_layers, n, T, kin_p, kout_p, k, s, _tuning(tuning),
+                                                           ctypes.byref(out)),
            "factgrass_layers_workspace_bytes")
     return out.value
 
 
-def factgrass_layers(layers, k: int, s: int, seed: int, out: torch.Tensor, ws: torch.Tensor | None = None):
+def factgrass_layers(layers, k: int, s: int, seed: int, out: torch.Tensor, ws: torch.Tensor | None = None,
+                     tuning=None):
     """layers: list of (x, gout, idx_in, idx_out, stream_id); layer l is written to out[:, l*k:(l+1)*k]."""
     n, T = layers[0][0].shape[0], layers[0][0].shape[1]
     kin_p, kout_p = layers[0][2].numel(), layers[0][3].numel()
@@ -260,9 +284,10 @@ def factgrass_layers(layers, k: int, s: int, seed: int, out: torch.Tensor, ws: t
         table[l] = FactgrassLayer(x.data_ptr(), g.data_ptr(), ii.data_ptr(), io.data_ptr(), x.shape[2], g.shape[2],
                                   stream_id, out.data_ptr() + 4 * l * k)
     if ws is None:
-        ws = _workspace(factgrass_layers_workspace_bytes(len(layers), n, T, kin_p, kout_p, k, s), out.device)
+        ws = _workspace(factgrass_layers_workspace_bytes(len(layers), n, T, kin_p, kout_p, k, s, tuning), out.device)
     _check(load_library().factgrass_layers(table, len(layers), n, T, kin_p, kout_p, k, s, seed, _ld(out), _ptr(ws),
-                                           0 if ws is None else ws.numel(), _stream()), "factgrass_layers")
+                                           0 if ws is None else ws.numel(), _tuning(tuning), _stream()),
+           "factgrass_layers")
     return out
 
 
@@ -522,12 +547,3 @@ def grass_projection_matrix(seed: int, stream_id: int, p: int, k: int, s: int, i
     _check(load_library().grass_projection_matrix(seed, stream_id, p, _ptr(idx), kprime, k, s, _ptr(P), _ld(P), _stream()),
            "grass_projection_matrix")
     return P
-
-
-def grass_set_sjlt_tuning(rows_per_block: int = 0, column_chunks: int = 0, threads: int = 0,
-                          accumulator: int = 0) -> None:
-    load_library().grass_set_sjlt_tuning(rows_per_block, column_chunks, threads, accumulator)
-
-
-def grass_set_factgrass_tuning(tokens_per_block: int = 0) -> None:
-    load_library().grass_set_factgrass_tuning(tokens_per_block)

@@ -25,8 +25,6 @@
 
 namespace grass {
 
-static int g_tune_tokens = 0;
-
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
@@ -217,7 +215,9 @@ struct FgPlan {
 
 static int tiles_for(uint32_t kq) { return kq <= 32 ? 1 : (kq <= 64 ? 2 : 4); }
 
-static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, FgPlan* pl) {
+static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, FgPlan* pl,
+                    const grass_tuning* tune = nullptr) {
+    const int tune_tokens = tune ? tune->factgrass_tokens_per_block : 0;   // override of this call; 0 = heuristic
     if (ka == 0 || kb == 0 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR) return false;
     pl->TA = tiles_for(ka);
     pl->TB = tiles_for(kb);
@@ -232,7 +232,7 @@ static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint
         if (n_layers * n * ceil_div(T, cand) >= need) { tpb = cand; break; }
     }
     if (tpb > ceil_div(T, kTokTile) * kTokTile) tpb = ceil_div(T, kTokTile) * kTokTile;
-    if (g_tune_tokens > 0) tpb = ceil_div((uint64_t)g_tune_tokens, kTokTile) * kTokTile;
+    if (tune_tokens > 0) tpb = ceil_div((uint64_t)tune_tokens, kTokTile) * kTokTile;
     uint64_t chunks = ceil_div(T, tpb);
     if (chunks > 65535) { chunks = 65535; tpb = ceil_div(ceil_div(T, chunks), kTokTile) * kTokTile; chunks = ceil_div(T, tpb); }
     pl->tokens_per_block = (uint32_t)tpb;
@@ -288,8 +288,6 @@ static grass_status run_fg(FgArgs& a, const FgPlan& pl, uint32_t n_layers, hipSt
 
 using namespace grass;
 
-extern "C" void grass_set_factgrass_tuning(int tokens_per_block) { g_tune_tokens = tokens_per_block; }
-
 static grass_status check_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, uint32_t k, uint32_t s) {
     if (T == 0 || ka == 0 || kb == 0 || k == 0 || s == 0 || k % s != 0) return GRASS_EINVAL;
     if (n > 65535 || ka > GRASS_MAX_FACTOR || kb > GRASS_MAX_FACTOR || k > GRASS_MAX_K) return GRASS_EUNSUPPORTED;
@@ -297,13 +295,14 @@ static grass_status check_fg(uint64_t n, uint64_t T, uint32_t ka, uint32_t kb, u
 }
 
 extern "C" grass_status factgrass_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t kin_p, uint32_t kout_p,
-                                                         uint32_t k, uint32_t s, size_t* host_bytes) {
+                                                         uint32_t k, uint32_t s, const grass_tuning* host_tuning,
+                                                         size_t* host_bytes) {
     if (!host_bytes) return GRASS_EINVAL;
     grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
     if (st != GRASS_OK) return st;
     if (n == 0) { *host_bytes = 0; return GRASS_OK; }
     FgPlan pl;
-    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl, host_tuning)) return GRASS_EUNSUPPORTED;
     *host_bytes = pl.ws_bytes;
     return GRASS_OK;
 }
@@ -322,14 +321,14 @@ extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64
                                          uint32_t d_out, const int32_t* idx_in, uint32_t kin_p,
                                          const int32_t* idx_out, uint32_t kout_p, uint32_t k, uint32_t s,
                                          uint64_t seed, uint64_t stream_id, float* out, uint64_t ldo, void* ws,
-                                         size_t ws_bytes, grass_stream stream) {
+                                         size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream) {
     grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
     if (st != GRASS_OK) return st;
     if (kin_p > d_in || kout_p > d_out) return GRASS_EINVAL;
     if (n == 0) return GRASS_OK;
     if (!x || !gout || !idx_in || !idx_out || !out || ldo < k) return GRASS_EINVAL;
     FgPlan pl;
-    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(1, n, T, kin_p, kout_p, k, &pl, host_tuning)) return GRASS_EUNSUPPORTED;
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
 
     FgArgs a;
@@ -346,21 +345,23 @@ extern "C" grass_status factgrass_linear(const void* x, const void* gout, uint64
 static size_t layers_table_bytes(uint32_t n_layers) { return ((size_t)n_layers * sizeof(FgLayer) + 255) / 256 * 256; }
 
 extern "C" grass_status factgrass_layers_workspace_bytes(uint32_t n_layers, uint64_t n, uint64_t T, uint32_t kin_p,
-                                                         uint32_t kout_p, uint32_t k, uint32_t s, size_t* host_bytes) {
+                                                         uint32_t kout_p, uint32_t k, uint32_t s,
+                                                         const grass_tuning* host_tuning, size_t* host_bytes) {
     if (!host_bytes || n_layers == 0) return GRASS_EINVAL;
     if (n_layers > 65535) return GRASS_EUNSUPPORTED;
     grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
     if (st != GRASS_OK) return st;
     if (n == 0) { *host_bytes = 0; return GRASS_OK; }
     FgPlan pl;
-    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl, host_tuning)) return GRASS_EUNSUPPORTED;
     *host_bytes = layers_table_bytes(n_layers) + pl.ws_bytes;
     return GRASS_OK;
 }
 
 extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_layers, uint64_t n, uint64_t T,
                                          uint32_t kin_p, uint32_t kout_p, uint32_t k, uint32_t s, uint64_t seed,
-                                         uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+                                         uint64_t ldo, void* ws, size_t ws_bytes, const grass_tuning* host_tuning,
+                                         grass_stream stream) {
     if (!host_layers || n_layers == 0) return GRASS_EINVAL;
     if (n_layers > 65535) return GRASS_EUNSUPPORTED;
     grass_status st = check_fg(n, T, kin_p, kout_p, k, s);
@@ -373,7 +374,7 @@ extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uin
         if (kin_p > h.d_in || kout_p > h.d_out) return GRASS_EINVAL;
     }
     FgPlan pl;
-    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl)) return GRASS_EUNSUPPORTED;
+    if (!plan_fg(n_layers, n, T, kin_p, kout_p, k, &pl, host_tuning)) return GRASS_EUNSUPPORTED;
     const size_t table = layers_table_bytes(n_layers);
     if (!ws || ws_bytes < table + pl.ws_bytes || !aligned(ws, 256)) return GRASS_EWORKSPACE;
 
@@ -414,7 +415,7 @@ extern "C" grass_status factmask_linear_workspace_bytes(uint64_t n, uint64_t T, 
                                                         size_t* host_bytes) {
     if (!host_bytes) return GRASS_EINVAL;
     if (kin_p == 0 || kout_p == 0 || kin_p > GRASS_MAX_FACTOR || kout_p > GRASS_MAX_FACTOR) return GRASS_EINVAL;
-    return factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, kin_p * kout_p, 1, host_bytes);
+    return factgrass_linear_workspace_bytes(n, T, kin_p, kout_p, kin_p * kout_p, 1, nullptr, host_bytes);
 }
 
 extern "C" grass_status factmask_linear(const void* x, const void* gout, uint64_t n, uint64_t T, uint32_t d_in,

@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "grass.h"
 
 namespace grass {
@@ -83,16 +85,18 @@ constexpr int kNumCU = 256;                 // MI355X
 constexpr size_t kLdsBytes = 160 * 1024;    // per CU and per workgroup on gfx950
 
 // A kernel that uses more than 64 KB of dynamic LDS has to be allowed to, once per device (the setting belongs to
-// the device's copy of the code object).  One LdsOptIn per kernel remembers the devices that have it.
-struct LdsOptIn { bool done[64] = {}; };
+// the device's copy of the code object).  One LdsOptIn per kernel remembers the devices that have it; the flags are
+// atomic so that host threads may call the library concurrently (two threads that race on a fresh device both set
+// the attribute, which is harmless).
+struct LdsOptIn { std::atomic<bool> done[64] = {}; };
 inline hipError_t allow_large_lds(LdsOptIn& state, const void* kernel) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
     const bool tracked = dev >= 0 && dev < 64;
-    if (tracked && state.done[dev]) return hipSuccess;
+    if (tracked && state.done[dev].load(std::memory_order_acquire)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-    if (e == hipSuccess && tracked) state.done[dev] = true;
+    if (e == hipSuccess && tracked) state.done[dev].store(true, std::memory_order_release);
     return e;
 }
 

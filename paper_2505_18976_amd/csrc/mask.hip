@@ -9,6 +9,8 @@
 // histogram) finds the k'-th smallest key T exactly; a counting pass and an
 // ordered compaction then emit, in ascending j, every j with key_j < T plus the
 // first `need` coordinates with key_j == T.
+#include <mutex>
+
 #include "grass_device.h"
 
 namespace grass {
@@ -282,7 +284,10 @@ __global__ void __launch_bounds__(256) check_indices_kernel(const int32_t* idx, 
     if (!ok) atomicOr(bad, 1u);
 }
 
+// Result word of grass_check_indices (one per device, inside the code object).  The call synchronises anyway, so a
+// host mutex held from the reset of the word to its read-back makes concurrent calls from several threads safe.
 __device__ uint32_t bad_flag;
+static std::mutex bad_flag_mutex;
 
 struct SelectLayout {
     size_t off_state, off_hist, off_less, off_eq, total;
@@ -396,6 +401,7 @@ extern "C" grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_i
 extern "C" grass_status grass_check_indices(const int32_t* idx, uint32_t kprime, uint64_t p, int* host_ok,
                                             grass_stream stream) {
     if (!idx || !host_ok || kprime == 0 || p == 0) return GRASS_EINVAL;
+    std::lock_guard<std::mutex> guard(bad_flag_mutex);
     uint32_t* dflag = nullptr;
     if (hipGetSymbolAddress(reinterpret_cast<void**>(&dflag), HIP_SYMBOL(bad_flag)) != hipSuccess) return GRASS_EHIP;
     hipStream_t hs = as_stream(stream);

@@ -34,8 +34,6 @@
 
 namespace grass {
 
-static int g_tune_rows = 0, g_tune_chunks = 0, g_tune_threads = 0, g_tune_acc = 0;
-
 enum { ACC_CAS = 2, ACC_F64 = 3 };
 template <int ACC> struct AccT { using type = float; };
 template <> struct AccT<ACC_F64> { using type = double; };
@@ -302,12 +300,17 @@ struct SjltPlan {
 // consecutive rows give the fewest row groups and so the most chunks, an upper bound for every layout.
 // in_bytes: 4 (fp32 input) or 2 (bf16 input).
 static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const void* g, uint64_t ldg,
-                      SjltPlan* pl, int force_v = 0, uint32_t in_bytes = 4, uint32_t s = 1) {
+                      SjltPlan* pl, int force_v, uint32_t in_bytes, uint32_t s, const grass_tuning* tune) {
+    // launch-shape overrides of this call (experiments); zero = heuristic
+    const int tune_rows = tune ? tune->sjlt_rows_per_block : 0;
+    const int tune_chunks = tune ? tune->sjlt_column_chunks : 0;
+    const int tune_threads = tune ? tune->sjlt_threads : 0;
+    const int tune_acc = tune ? tune->sjlt_accumulator : 0;
     if ((size_t)k * 4 > 128 * 1024) return false;
     int acc = ACC_F64;
     if ((size_t)k * 8 > 128 * 1024) acc = ACC_CAS;            // fp64 buckets of one row no longer fit
-    if ((g_tune_acc == ACC_CAS || g_tune_acc == ACC_F64) && (size_t)k * (g_tune_acc == ACC_F64 ? 8 : 4) <= 128 * 1024)
-        acc = g_tune_acc;
+    if ((tune_acc == ACC_CAS || tune_acc == ACC_F64) && (size_t)k * (tune_acc == ACC_F64 ? 8 : 4) <= 128 * 1024)
+        acc = tune_acc;
     const size_t esz = acc == ACC_F64 ? 8 : 4;
     int R = 8;
     while (R > 1 && (size_t)R * k * esz > 128 * 1024) R >>= 1;
@@ -320,13 +323,13 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     // long masked rows are bound by the gather (one 128-byte line per kept coordinate): up to a few hundred rows,
     // one workgroup per CU matters more than sharing the hash of a position between the rows of a workgroup
     if (masked && !short_rows) while (R > 1 && ceil_div(n, R) < (uint64_t)kNumCU) R >>= 1;
-    if (g_tune_rows == 1 || g_tune_rows == 2 || g_tune_rows == 4 || g_tune_rows == 8) {
-        if ((size_t)g_tune_rows * k * esz <= kLdsBytes) R = g_tune_rows;
+    if (tune_rows == 1 || tune_rows == 2 || tune_rows == 4 || tune_rows == 8) {
+        if ((size_t)tune_rows * k * esz <= kLdsBytes) R = tune_rows;
     }
     int threads = 1024;
     if ((size_t)R * k * esz <= 64 * 1024) threads = 512;      // two or more groups per CU anyway
     if (short_rows && ceil_div(n, R) <= (uint64_t)kNumCU) threads = 1024;   // one workgroup per CU at most: widest
-    if (g_tune_threads == 256 || g_tune_threads == 512 || g_tune_threads == 1024) threads = g_tune_threads;
+    if (tune_threads == 256 || tune_threads == 512 || tune_threads == 1024) threads = tune_threads;
     int V = 1;
     uint32_t P = 1;
     bool align_lines = false;
@@ -364,7 +367,7 @@ static bool plan_sjlt(uint64_t n, uint64_t d, bool masked, uint32_t k, const voi
     if (chunks > max_chunks_work) chunks = max_chunks_work;
     if (chunks > max_chunks_traffic) chunks = max_chunks_traffic;
     if (short_rows) chunks = 1;
-    if (g_tune_chunks > 0) chunks = g_tune_chunks;
+    if (tune_chunks > 0) chunks = tune_chunks;
     if (chunks > 65535) chunks = 65535;
     uint64_t ppc = ceil_div(d, chunks);
     ppc = ceil_div(ppc, step) * step;             // keeps chunk starts V-aligned
@@ -436,13 +439,6 @@ static hipError_t launch_t(const SjltArgs& a, const SjltPlan& pl, bool masked, i
 
 using namespace grass;
 
-extern "C" void grass_set_sjlt_tuning(int rows_per_block, int column_chunks, int threads, int accumulator) {
-    g_tune_rows = rows_per_block;
-    g_tune_chunks = column_chunks;
-    g_tune_threads = threads;
-    g_tune_acc = accumulator;
-}
-
 static grass_status check_sjlt_dims(uint64_t n, uint64_t p, bool masked, uint32_t kprime, uint32_t k, uint32_t s) {
     (void)n;
     if (p == 0 || p >= (1ull << 31)) return GRASS_EINVAL;
@@ -453,7 +449,7 @@ static grass_status check_sjlt_dims(uint64_t n, uint64_t p, bool masked, uint32_
 }
 
 extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint32_t kprime_or_0, uint32_t k,
-                                                   uint32_t s, size_t* host_bytes) {
+                                                   uint32_t s, const grass_tuning* host_tuning, size_t* host_bytes) {
     if (!host_bytes) return GRASS_EINVAL;
     const bool masked = kprime_or_0 != 0;
     grass_status st = check_sjlt_dims(n, p, masked, kprime_or_0, k, s);
@@ -464,7 +460,7 @@ extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint3
     size_t worst = 0;
     for (int v = 1; v <= 4; v *= 2) {
         SjltPlan pl;
-        if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, nullptr, 0, &pl, v, 4, s)) return GRASS_EUNSUPPORTED;
+        if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, nullptr, 0, &pl, v, 4, s, host_tuning)) return GRASS_EUNSUPPORTED;
         const size_t need = pl.table ? pl.table_offset + pl.table_bytes : pl.ws_bytes;
         if (need > worst) worst = need;
     }
@@ -474,7 +470,7 @@ extern "C" grass_status grass_sjlt_workspace_bytes(uint64_t n, uint64_t p, uint3
 
 static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
                              uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id, float* out,
-                             uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
+                             uint64_t ldo, void* ws, size_t ws_bytes, const grass_tuning* tune, grass_stream stream) {
     const bool masked = idx != nullptr;
     grass_status st = check_sjlt_dims(n, p, masked, kprime, k, s);
     if (st != GRASS_OK) return st;
@@ -483,7 +479,7 @@ static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint6
     if (n * ldg >= (1ull << 62)) return GRASS_EINVAL;
     const uint64_t d = masked ? kprime : p;
     SjltPlan pl;
-    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl, 0, in_bytes, s)) return GRASS_EUNSUPPORTED;
+    if (!plan_sjlt(n, d, masked, k, g, ldg, &pl, 0, in_bytes, s, tune)) return GRASS_EUNSUPPORTED;
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;
 
     SjltArgs a;
@@ -529,12 +525,14 @@ static grass_status run_sjlt(const void* g, uint32_t in_bytes, uint64_t n, uint6
 
 extern "C" grass_status grass_sjlt(const float* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
                                    uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
-                                   float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
-    return run_sjlt(g, 4, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, stream);
+                                   float* out, uint64_t ldo, void* ws, size_t ws_bytes,
+                                   const grass_tuning* host_tuning, grass_stream stream) {
+    return run_sjlt(g, 4, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, host_tuning, stream);
 }
 
 extern "C" grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
                                         uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
-                                        float* out, uint64_t ldo, void* ws, size_t ws_bytes, grass_stream stream) {
-    return run_sjlt(g, 2, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, stream);
+                                        float* out, uint64_t ldo, void* ws, size_t ws_bytes,
+                                        const grass_tuning* host_tuning, grass_stream stream) {
+    return run_sjlt(g, 2, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, host_tuning, stream);
 }

@@ -50,20 +50,20 @@ def test_version_and_strerror(lib):
 def test_workspace_queries_validate_on_the_host(lib):
     from paper_2505_18976_amd import binding as b
     out = ctypes.c_size_t(123)
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, ctypes.byref(out)) == b.GRASS_OK
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 0, 1, ctypes.byref(out)) == b.GRASS_EINVAL      # k = 0
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 0, ctypes.byref(out)) == b.GRASS_EINVAL     # s = 0
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 3, ctypes.byref(out)) == b.GRASS_EINVAL     # s does not divide k
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 2000, 64, 1, ctypes.byref(out)) == b.GRASS_EINVAL  # k' > p
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 1 << 20, 1, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
-    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, None) == b.GRASS_EINVAL
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, None, ctypes.byref(out)) == b.GRASS_OK
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 0, 1, None, ctypes.byref(out)) == b.GRASS_EINVAL      # k = 0
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 0, None, ctypes.byref(out)) == b.GRASS_EINVAL     # s = 0
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 3, None, ctypes.byref(out)) == b.GRASS_EINVAL     # s does not divide k
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 2000, 64, 1, None, ctypes.byref(out)) == b.GRASS_EINVAL  # k' > p
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 1 << 20, 1, None, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
+    assert lib.grass_sjlt_workspace_bytes(16, 1000, 0, 64, 1, None, None) == b.GRASS_EINVAL
     assert lib.grass_mask_indices_workspace_bytes(1000, 10, ctypes.byref(out)) == b.GRASS_OK
     assert out.value > 4 * 65536 * 4
     assert lib.grass_mask_indices_workspace_bytes(1000, 1001, ctypes.byref(out)) == b.GRASS_EINVAL
     assert lib.grass_mask_indices_workspace_bytes(1 << 31, 10, ctypes.byref(out)) == b.GRASS_EINVAL
-    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 64, 1024, 1, ctypes.byref(out)) == b.GRASS_OK
-    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 129, 1024, 1, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
-    assert lib.factgrass_linear_workspace_bytes(8, 0, 64, 64, 1024, 1, ctypes.byref(out)) == b.GRASS_EINVAL
+    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 64, 1024, 1, None, ctypes.byref(out)) == b.GRASS_OK
+    assert lib.factgrass_linear_workspace_bytes(8, 128, 64, 129, 1024, 1, None, ctypes.byref(out)) == b.GRASS_EUNSUPPORTED
+    assert lib.factgrass_linear_workspace_bytes(8, 0, 64, 64, 1024, 1, None, ctypes.byref(out)) == b.GRASS_EINVAL
 
 
 def test_bad_arguments_are_rejected_before_any_launch(lib):
@@ -72,23 +72,44 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     null = ctypes.c_void_p(0)
     fake = ctypes.c_void_p(4096)
     # null pointers
-    assert lib.grass_sjlt(null, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EINVAL
+    assert lib.grass_sjlt(null, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, None, null) == b.GRASS_EINVAL
     # leading dimension smaller than the row
-    assert lib.grass_sjlt(fake, 4, 100, 99, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EINVAL
-    assert lib.grass_sjlt(fake, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 15, null, 0, null) == b.GRASS_EINVAL
+    assert lib.grass_sjlt(fake, 4, 100, 99, null, 0, 16, 1, 0, 1, fake, 16, null, 0, None, null) == b.GRASS_EINVAL
+    assert lib.grass_sjlt(fake, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 15, null, 0, None, null) == b.GRASS_EINVAL
     # n = 0 is a no-op
-    assert lib.grass_sjlt(fake, 0, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_OK
+    assert lib.grass_sjlt(fake, 0, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null, 0, None, null) == b.GRASS_OK
     assert lib.grass_mask(fake, 0, 100, 100, fake, 10, fake, 10, null) == b.GRASS_OK
     assert lib.grass_mask(fake, 4, 100, 100, fake, 101, fake, 101, null) == b.GRASS_EINVAL
     assert lib.grass_mask(fake, 4, 100, 100, null, 10, fake, 10, null) == b.GRASS_EINVAL
     # workspace required but missing: many chunks for a single long row
-    assert lib.grass_sjlt(fake, 1, 1 << 22, 1 << 22, null, 0, 16, 1, 0, 1, fake, 16, null, 0, null) == b.GRASS_EWORKSPACE
+    assert lib.grass_sjlt(fake, 1, 1 << 22, 1 << 22, null, 0, 16, 1, 0, 1, fake, 16, null, 0, None, null) == b.GRASS_EWORKSPACE
     assert lib.grass_mask_indices(0, 0, 1000, 10, fake, null, 0, null) == b.GRASS_EWORKSPACE
     assert lib.grass_score(fake, fake, 2, 8, 8, 8, 8, 8, fake, 8, null, 0, null) == b.GRASS_EINVAL
     assert lib.grass_score(fake, fake, 0, 8, 8, 8, 7, 8, fake, 8, null, 0, null) == b.GRASS_EINVAL
     assert lib.factgrass_linear(fake, fake, 2, 16, 64, 64, fake, 65, fake, 8, 32, 1, 0, 18, fake, 32, null, 0,
-                                null) == b.GRASS_EINVAL                                                  # k_in' > d_in
+                                None, null) == b.GRASS_EINVAL                                                  # k_in' > d_in
     assert lib.grass_gauss_project(fake, 2, 64, 64, 8, 0, 2, 0, 0, fake, 8, null, 0, null) == b.GRASS_EWORKSPACE
+
+
+def test_tuning_is_a_per_call_argument(lib):
+    """Launch-shape overrides travel with the call: the same query with and without them, interleaved, keeps
+    answering the same (there is no process-wide setting to leak from one call into the next)."""
+    from paper_2505_18976_amd import binding as b
+    plain, tuned = ctypes.c_size_t(0), ctypes.c_size_t(0)
+    t = b.GrassTuning(sjlt_rows_per_block=1, sjlt_column_chunks=7, sjlt_threads=256, sjlt_accumulator=2)
+    for _ in range(2):
+        assert lib.grass_sjlt_workspace_bytes(64, 40000, 0, 1024, 1, None, ctypes.byref(plain)) == b.GRASS_OK
+        assert lib.grass_sjlt_workspace_bytes(64, 40000, 0, 1024, 1, ctypes.byref(t), ctypes.byref(tuned)) == b.GRASS_OK
+        assert tuned.value == 7 * 64 * 1024 * 4 and plain.value != tuned.value
+    ft = b.GrassTuning(factgrass_tokens_per_block=64)
+    for _ in range(2):
+        assert lib.factgrass_linear_workspace_bytes(4, 256, 64, 64, 512, 1, None, ctypes.byref(plain)) == b.GRASS_OK
+        assert lib.factgrass_linear_workspace_bytes(4, 256, 64, 64, 512, 1, ctypes.byref(ft), ctypes.byref(tuned)) == b.GRASS_OK
+        assert tuned.value == 4 * 4 * 512 * 4 and plain.value != tuned.value
+    # a missing workspace is reported for the tuned plan, before any launch
+    fake, null = ctypes.c_void_p(4096), ctypes.c_void_p(0)
+    assert lib.grass_sjlt(fake, 64, 40000, 40000, null, 0, 1024, 1, 0, 1, fake, 1024, null, 0, ctypes.byref(t),
+                          null) == b.GRASS_EWORKSPACE
 
 
 def test_binding_refuses_to_run_without_the_library(monkeypatch, tmp_path):

@@ -37,7 +37,6 @@ def grass():
     import paper_2505_18976_amd as g
     g.load_library()
     yield g
-    g.grass_set_factgrass_tuning(0)
 
 
 def _dev():
@@ -63,7 +62,6 @@ FACT_CASES = [
 
 @pytest.mark.parametrize("n,T,d_in,d_out,ka,kb,k,s,layer", FACT_CASES)
 def test_factgrass_parity(grass, n, T, d_in, d_out, ka, kb, k, s, layer):
-    grass.grass_set_factgrass_tuning(0)
     x, g = synth.linear_layer_factors(n, T, d_in, d_out, seed=40 + layer, device=_dev())
     s_in, s_out, s_sjlt = orc.layer_streams(layer)
     ii = grass.grass_mask_indices(0, s_in, d_in, ka, device=_dev())
@@ -76,7 +74,6 @@ def test_factgrass_parity(grass, n, T, d_in, d_out, ka, kb, k, s, layer):
 
 def test_factgrass_random_shapes(grass):
     """30 seeded random layers: tokens, widths, mask sizes (1..128), k and s vary, including non-multiples of every tile."""
-    grass.grass_set_factgrass_tuning(0)
     rng = np.random.default_rng(777)
     for case in range(30):
         n, T = int(rng.integers(1, 6)), int(rng.integers(1, 300))
@@ -150,12 +147,8 @@ def test_factgrass_token_chunking(grass, tokens):
     ii = grass.grass_mask_indices(0, 16, d_in, ka, device=_dev())
     io = grass.grass_mask_indices(0, 17, d_out, kb, device=_dev())
     ref = orc.factgrass_linear(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy(), k, 1, 0, 18)
-    grass.grass_set_factgrass_tuning(tokens)
-    try:
-        out = grass.factgrass_linear(x, g, ii, io, k, 1, 0, 18)
-        torch.cuda.synchronize()
-    finally:
-        grass.grass_set_factgrass_tuning(0)
+    out = grass.factgrass_linear(x, g, ii, io, k, 1, 0, 18, tuning=dict(factgrass_tokens_per_block=tokens))
+    torch.cuda.synchronize()
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_FACT
 
 
@@ -192,12 +185,8 @@ def test_factgrass_many_layers_in_one_launch(grass, tokens):
         io = grass.grass_mask_indices(0, s_out, d_out, kf, device=_dev())
         layers.append((x, g, ii, io, s_sjlt))
         refs.append(orc.factgrass_linear(_np(x), _np(g), ii.cpu().numpy(), io.cpu().numpy(), k_l, 1, 0, s_sjlt))
-    grass.grass_set_factgrass_tuning(tokens)
-    try:
-        grass.factgrass_layers(layers, k_l, 1, 0, cat)
-        torch.cuda.synchronize()
-    finally:
-        grass.grass_set_factgrass_tuning(0)
+    grass.factgrass_layers(layers, k_l, 1, 0, cat, tuning=dict(factgrass_tokens_per_block=tokens))
+    torch.cuda.synchronize()
     got = cat.cpu().numpy()
     for l, ref in enumerate(refs):
         assert orc.max_rel_err(got[:, l * k_l:(l + 1) * k_l], ref) <= TOL_FACT

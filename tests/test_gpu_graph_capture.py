@@ -15,8 +15,6 @@ pytestmark = pytest.mark.gpu
 def grass():
     import paper_2505_18976_amd as g
     g.load_library()
-    g.grass_set_sjlt_tuning(0, 0, 0, 0)
-    g.grass_set_factgrass_tuning(0)
     return g
 
 

@@ -22,7 +22,6 @@ def grass():
     import paper_2505_18976_amd as g
     g.load_library()
     yield g
-    g.grass_set_sjlt_tuning(0, 0, 0, 0)
 
 
 def _dev():
@@ -103,7 +102,6 @@ SJLT_CASES = [
 
 @pytest.mark.parametrize("n,d,k,s,pad", SJLT_CASES)
 def test_sjlt_parity(grass, n, d, k, s, pad):
-    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     full = synth.bernoulli_sparse_normal(n, d + pad, 0.6, 1.0, seed=21, device=_dev())
     g = full[:, :d]
     out = grass.grass_sjlt(g, k, s, seed=0, stream_id=1)
@@ -130,7 +128,6 @@ ALIGNED_CASES = [
 
 @pytest.mark.parametrize("n,d,pad,off,k,s", ALIGNED_CASES)
 def test_sjlt_line_aligned_row_groups(grass, n, d, pad, off, k, s):
-    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=23, device=_dev())
     g = full[:, off:off + d]
     out = grass.grass_sjlt(g, k, s, seed=3, stream_id=1)
@@ -160,7 +157,6 @@ BF16_CASES = [
 
 @pytest.mark.parametrize("n,d,pad,off,k,s,kp", BF16_CASES)
 def test_sjlt_bf16_inputs(grass, n, d, pad, off, k, s, kp):
-    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=24, device=_dev()).to(torch.bfloat16)
     g = full[:, off:off + d]
     exact = g.float().cpu().numpy()                              # bf16 values are exact in fp32
@@ -192,7 +188,6 @@ TABLE_CASES = [
 
 @pytest.mark.parametrize("n,d,pad,off,k,bf16", TABLE_CASES)
 def test_sjlt_bucket_table_path(grass, n, d, pad, off, k, bf16):
-    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     full = synth.bernoulli_sparse_normal(n, off + d + pad, 0.5, 1.0, seed=29, device=_dev())
     if bf16:
         full = full.to(torch.bfloat16)
@@ -213,7 +208,6 @@ def test_sjlt_bucket_table_path(grass, n, d, pad, off, k, bf16):
 def test_sjlt_random_shapes_and_alignments(grass):
     """60 seeded random problems: shape, leading dimension, view offset, element type, mask, k and s all vary, so that
     every row period, lead-in length, vector width and chunk count of the planner is hit by something."""
-    grass.grass_set_sjlt_tuning(0, 0, 0, 0)
     rng = np.random.default_rng(12345)
     for case in range(60):
         bf16 = bool(rng.integers(2))
@@ -249,12 +243,9 @@ def test_sjlt_parity_across_launch_shapes(grass, rows, chunks, threads, acc):
     n, d, k, s = 11, 50001, 2048, 2
     g = synth.bernoulli_sparse_normal(n, d, 0.3, 1.0, seed=22, device=_dev())
     ref = orc.sjlt(g.cpu().numpy(), k, s, 5, 1)
-    grass.grass_set_sjlt_tuning(rows, chunks, threads, acc)
-    try:
-        out = grass.grass_sjlt(g, k, s, seed=5, stream_id=1)
-        torch.cuda.synchronize()
-    finally:
-        grass.grass_set_sjlt_tuning(0, 0, 0, 0)
+    tuning = dict(sjlt_rows_per_block=rows, sjlt_column_chunks=chunks, sjlt_threads=threads, sjlt_accumulator=acc)
+    out = grass.grass_sjlt(g, k, s, seed=5, stream_id=1, tuning=tuning)
+    torch.cuda.synchronize()
     assert orc.max_rel_err(out.cpu().numpy(), ref) <= TOL_SJLT
 
 
