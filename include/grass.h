@@ -51,7 +51,9 @@ typedef enum {
     GRASS_EINVAL = 1,       /* a size or pointer argument is invalid            */
     GRASS_EWORKSPACE = 2,   /* workspace missing, misaligned or too small        */
     GRASS_EHIP = 3,         /* the HIP runtime reported an error at launch       */
-    GRASS_EUNSUPPORTED = 4  /* valid request outside what the kernels cover      */
+    GRASS_EUNSUPPORTED = 4, /* valid request outside what the kernels cover      */
+    GRASS_ETOOLARGE = 5     /* needs more scratch memory than the library's fixed
+                               buffer holds (grass_sjlt_noalloc)                 */
 } grass_status;
 
 typedef void* grass_stream;
@@ -149,6 +151,27 @@ grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg
                              uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
                              float* out, uint64_t ldo,
                              void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
+
+/* grass_sjlt for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same operation, arguments and results as grass_sjlt (fp32
+ * input, heuristic launch shape) without `ws`: the partial sums of the column
+ * chunks (and the transient table, when it fits behind them) live in a buffer
+ * of GRASS_NOALLOC_SCRATCH_BYTES that is part of the library's device code, one
+ * copy per GPU for the life of the process.  The call allocates and frees
+ * nothing; its first call on a device looks up the buffer's address.
+ * A problem whose partial sums (column chunks x n x k x 4 bytes) exceed the
+ * buffer is refused with GRASS_ETOOLARGE before anything is launched: use
+ * grass_sjlt with a workspace for those.  Large batches of the fused mask path
+ * need no scratch memory at all and are never refused.
+ * All calls on one GPU share the buffer: calls that may overlap in time (on
+ * different streams, or from different threads) race on it and must be ordered
+ * by the caller.  Nothing in the buffer needs to start at zero.               */
+#define GRASS_NOALLOC_SCRATCH_BYTES (32u << 20)
+grass_status grass_sjlt_noalloc(const float* g, uint64_t n, uint64_t p, uint64_t ldg,
+                                const int32_t* idx, uint32_t kprime,
+                                uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                                float* out, uint64_t ldo, grass_stream stream);
 
 /* ------------------------------------------------------------------ FactGraSS
  * Sec. 3.3.2 "Factorized GraSS" for one linear layer, using Eq. (2)/(3):

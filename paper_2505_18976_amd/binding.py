@@ -16,7 +16,8 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libgrass.so")
 
-GRASS_OK, GRASS_EINVAL, GRASS_EWORKSPACE, GRASS_EHIP, GRASS_EUNSUPPORTED = range(5)
+GRASS_OK, GRASS_EINVAL, GRASS_EWORKSPACE, GRASS_EHIP, GRASS_EUNSUPPORTED, GRASS_ETOOLARGE = range(6)
+GRASS_NOALLOC_SCRATCH_BYTES = 32 << 20
 GRASS_MAX_K = 32768
 GRASS_MAX_FACTOR = 128
 
@@ -49,6 +50,7 @@ SIGNATURES = {
     "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun, _vp]),
     "grass_sjlt_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun,
                                _vp]),
+    "grass_sjlt_noalloc": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp]),
     "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, _tun, ctypes.POINTER(_sz)]),
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
                                 _vp, _u64, _vp, _sz, _tun, _vp]),
@@ -230,6 +232,17 @@ def grass_sjlt_bf16(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int =
                                           _ptr(out), _ld(out), _ptr(ws), 0 if ws is None else ws.numel(),
                                           _tuning(tuning), _stream()),
            "grass_sjlt_bf16")
+    return out
+
+
+def grass_sjlt_noalloc(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int, out: torch.Tensor,
+                       idx: torch.Tensor | None = None) -> torch.Tensor:
+    """grass_sjlt without a workspace (the library's own fixed scratch buffer); `out` is the caller's."""
+    assert g.dtype == torch.float32 and out.dtype == torch.float32
+    n, p = g.shape
+    kprime = 0 if idx is None else idx.numel()
+    _check(load_library().grass_sjlt_noalloc(_ptr(g), n, p, _ld(g), _ptr(idx), kprime, k, s, seed, stream_id,
+                                             _ptr(out), _ld(out), _stream()), "grass_sjlt_noalloc")
     return out
 
 

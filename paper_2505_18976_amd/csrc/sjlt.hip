@@ -30,9 +30,17 @@
 //            order-insensitive to well below fp32 resolution, half as many rows
 //            fit in LDS);
 //   ACC_CAS: fp32 accumulators updated with a compare-and-swap loop.
+#include <mutex>
+
 #include "grass_device.h"
 
 namespace grass {
+
+// Scratch memory of grass_sjlt_noalloc: partial sums of the column chunks and, when it fits behind them, the
+// transient (bucket, sign) table.  One copy per GPU inside the loaded code object, held until the process ends.
+// In host code the array's name is only a handle for hipGetSymbolAddress; kernels and copies get the address that
+// call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[GRASS_NOALLOC_SCRATCH_BYTES];
 
 enum { ACC_CAS = 2, ACC_F64 = 3 };
 template <int ACC> struct AccT { using type = float; };
@@ -535,4 +543,46 @@ extern "C" grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, u
                                         float* out, uint64_t ldo, void* ws, size_t ws_bytes,
                                         const grass_tuning* host_tuning, grass_stream stream) {
     return run_sjlt(g, 2, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, host_tuning, stream);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static hipError_t scratch_address(void** out) {
+    static std::mutex lock;
+    static void* ptr[64] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return hipSuccess;
+}
+
+extern "C" grass_status grass_sjlt_noalloc(const float* g, uint64_t n, uint64_t p, uint64_t ldg, const int32_t* idx,
+                                           uint32_t kprime, uint32_t k, uint32_t s, uint64_t seed, uint64_t stream_id,
+                                           float* out, uint64_t ldo, grass_stream stream) {
+    // all argument and size checks first: nothing below them can fail on the host side except the HIP runtime
+    const bool masked = idx != nullptr;
+    grass_status st = check_sjlt_dims(n, p, masked, kprime, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0) return GRASS_OK;
+    if (!g || !out || ldg < p || ldo < k || !aligned(g, 4) || !aligned(out, 4)) return GRASS_EINVAL;
+    SjltPlan pl;
+    if (!plan_sjlt(n, masked ? kprime : p, masked, k, g, ldg, &pl, 0, 4, s, nullptr)) return GRASS_EUNSUPPORTED;
+    if (pl.ws_bytes > (size_t)GRASS_NOALLOC_SCRATCH_BYTES) return GRASS_ETOOLARGE;
+    void* ws = nullptr;
+    if (pl.ws_bytes > 0 || pl.table) {
+        if (scratch_address(&ws) != hipSuccess) return GRASS_EHIP;
+    }
+    // the partial sums of every (chunk, row) pair and every table entry are written before they are read, so the
+    // contents the previous call left behind need no clearing
+    return run_sjlt(g, 4, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws,
+                    ws ? (size_t)GRASS_NOALLOC_SCRATCH_BYTES : 0, nullptr, stream);
 }

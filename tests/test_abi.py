@@ -91,6 +91,19 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.grass_gauss_project(fake, 2, 64, 64, 8, 0, 2, 0, 0, fake, 8, null, 0, null) == b.GRASS_EWORKSPACE
 
 
+def test_noalloc_entry_point_refuses_oversized_problems_on_the_host(lib):
+    """grass_sjlt_noalloc keeps its scratch memory in a fixed 32 MiB buffer inside the library: a problem whose
+    partial sums need more is refused before anything touches a GPU (this process has none)."""
+    from paper_2505_18976_amd import binding as b
+    fake, null = ctypes.c_void_p(4096), ctypes.c_void_p(0)
+    # 2 column chunks x 1,024 rows x 8,192 buckets x 4 bytes = 64 MiB
+    assert lib.grass_sjlt_noalloc(fake, 1024, 1 << 20, 1 << 20, null, 0, 8192, 1, 0, 1, fake, 8192, null) == b.GRASS_ETOOLARGE
+    assert b"scratch" in lib.grass_strerror(b.GRASS_ETOOLARGE)
+    assert lib.grass_sjlt_noalloc(null, 4, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null) == b.GRASS_EINVAL
+    assert lib.grass_sjlt_noalloc(fake, 0, 100, 100, null, 0, 16, 1, 0, 1, fake, 16, null) == b.GRASS_OK     # n = 0
+    assert lib.grass_sjlt_noalloc(fake, 4, 100, 100, null, 0, 16, 3, 0, 1, fake, 16, null) == b.GRASS_EINVAL  # s does not divide k
+
+
 def test_tuning_is_a_per_call_argument(lib):
     """Launch-shape overrides travel with the call: the same query with and without them, interleaved, keeps
     answering the same (there is no process-wide setting to leak from one call into the next)."""
