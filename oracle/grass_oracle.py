@@ -304,8 +304,8 @@ def influence(train: np.ndarray, test: np.ndarray, lam: float) -> np.ndarray:
 # Readings: the expectation over test points is the mean over the rows handed
 # in; corr is the Pearson correlation over the n training points with
 # population (1/n) moments; ||sigma||_1 is the plain sum (sigma > 0).  The paper
-# names no optimiser, step size or schedule: the oracle (and the library) stop
-# at the objective and its gradient, the update rule is the caller's.
+# names no optimiser, step size or schedule: `selective_mask_train` is plain
+# gradient ascent with a caller-supplied temperature per step.
 # ----------------------------------------------------------------------------
 def _sigmoid(x):
     return 1.0 / (1.0 + np.exp(-x))
@@ -374,6 +374,38 @@ def selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam: floa
         go += ((c * b_in) @ Z_out) * Zt_out[t]
     obj = total / m - lam * (si.sum() + so.sum())
     return obj, gi / m * 2 * si * dsi - lam * dsi, go / m * 2 * so * dso - lam * dso
+
+
+def selective_mask_train(S0, G, Gt, lam: float, lr: float, temperatures):
+    """Solves Eq. (1) by first-order ascent on the logits, with the inverse-temperature annealing of App. B.4
+    ("Ensuring Exact k": S is replaced by S / T and T decreases as training progresses).
+
+    Reading: the paper names no optimiser, step size, batching or schedule.  Here every step is one plain gradient
+    ascent step over all train and test rows handed in,
+        S_{i+1} = S_i + lr * grad L(S_i; T_i),      i = 0 .. len(temperatures) - 1,
+    with the temperature of each step given by the caller (a constant list is training without annealing).
+    Returns (S_final, history) with history[i] = L(S_i; T_i), the objective before step i."""
+    S = np.array(S0, dtype=np.float64, copy=True)
+    history = []
+    for T in temperatures:
+        history.append(selective_mask_objective(S, G, Gt, lam, T))
+        S = S + lr * selective_mask_gradient(S, G, Gt, lam, T)
+    return S, np.asarray(history, dtype=np.float64)
+
+
+def graddot_correlation(G, Gt, idx) -> float:
+    """First term of Eq. (1) for a binary mask: the mean over test rows of the Pearson correlation between the exact
+    GradDot scores <g_i, g_test> and those of the masked gradients <g_i[idx], g_test[idx]> (Sec. 3.2)."""
+    G = np.asarray(G, dtype=np.float64)
+    Gt = np.asarray(Gt, dtype=np.float64)
+    idx = np.asarray(idx, dtype=np.int64)
+    total = 0.0
+    for t in range(Gt.shape[0]):
+        exact = G @ Gt[t]
+        masked = G[:, idx] @ Gt[t, idx]
+        da, db = exact - exact.mean(), masked - masked.mean()
+        total += (da @ db) / np.sqrt((da @ da) * (db @ db))
+    return total / Gt.shape[0]
 
 
 def selective_mask_indices(S, k: int | None = None) -> np.ndarray:

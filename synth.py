@@ -119,3 +119,19 @@ def compressed_gradients(rows: int, k: int, seed: int, device="cpu", decay: floa
     out = torch.empty((rows, k), dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=gen)
     scale = (1.0 + torch.arange(k, dtype=torch.float32, device=device)) ** (-decay)
     return out * scale[None, :]
+
+
+def planted_gradients(n: int, m: int, p: int, informative: int, seed: int, device="cpu", strong: float = 3.0,
+                      weak: float = 0.3):
+    """Train (n x p) and test (m x p) fp32 gradients in which `informative` coordinates, spread evenly over [0, p),
+    carry most of the variance (std `strong`) and the rest is weak noise (std `weak`): a stand-in for per-sample
+    gradients whose attribution scores are dominated by a small set of parameters, the situation the Selective Mask is
+    built for.  Returns (G, Gt, planted) with planted the ascending int64 indices of the informative coordinates."""
+    gen = _gen(seed, device)
+    planted = (torch.arange(informative, dtype=torch.float64) * (p / informative)).floor().to(torch.int64)
+    std = torch.full((p,), weak, dtype=torch.float32, device=device)
+    std[planted.to(device)] = strong
+    G = torch.empty((n, p), dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=gen) * std[None, :]
+    Gt = torch.empty((m, p), dtype=torch.float32, device=device).normal_(0.0, 1.0, generator=gen) * std[None, :]
+    return G, Gt, planted
+

@@ -24,6 +24,7 @@ pins_mask = _load("test_oracle_hash_mask")
 pins_fact = _load("test_oracle_factgrass_score")
 pins_fim = _load("test_oracle_fim")
 pins_sm = _load("test_oracle_selective_mask")
+pins_train = _load("test_oracle_selective_mask_train")
 
 _U64 = np.uint64
 
@@ -226,3 +227,34 @@ def test_selective_mask_threshold_mistake_is_caught(monkeypatch):
                         lambda S, k=None: np.nonzero(np.asarray(S) > 0.5)[0].astype(np.int32))   # thresholds S, not sigma(S)
     with pytest.raises(AssertionError):
         pins_sm.test_index_extraction()
+
+
+def _train_variant(descent=False, stale_temperature=False, no_step_size=False, history_after=False):
+    def train(S0, G, Gt, lam, lr, temperatures):
+        S = np.array(S0, dtype=np.float64, copy=True)
+        history = []
+        for i, T in enumerate(temperatures):
+            Tg = temperatures[0] if stale_temperature else T
+            step = (1.0 if no_step_size else lr) * orc.selective_mask_gradient(S, G, Gt, lam, Tg)
+            if not history_after:
+                history.append(orc.selective_mask_objective(S, G, Gt, lam, T))
+            S = S - step if descent else S + step
+            if history_after:
+                history.append(orc.selective_mask_objective(S, G, Gt, lam, T))
+        return S, np.asarray(history, dtype=np.float64)
+    return train
+
+
+@pytest.mark.parametrize("kwargs,pin", [
+    (dict(descent=True), "test_first_step_moves_along_the_finite_difference_gradient"),
+    (dict(descent=True), "test_small_steps_never_decrease_the_objective"),
+    (dict(stale_temperature=True), "test_annealing_uses_the_temperature_of_its_own_step"),
+    (dict(no_step_size=True), "test_a_dead_coordinate_follows_the_penalty_in_closed_form"),
+    (dict(no_step_size=True), "test_no_steps_and_zero_step_size_leave_the_logits_alone"),
+    (dict(history_after=True), "test_first_step_moves_along_the_finite_difference_gradient"),
+])
+def test_selective_mask_training_mistakes_are_caught(monkeypatch, kwargs, pin):
+    monkeypatch.setattr(orc, "selective_mask_train", _train_variant(**kwargs))
+    with pytest.raises(AssertionError):
+        getattr(pins_train, pin)()
+

@@ -47,3 +47,14 @@ def test_llama_block_shapes():
     shapes = [(d_in, d_out) for _, d_in, d_out in synth.LLAMA_BLOCK_LINEARS]
     assert len(shapes) == 7
     assert shapes.count((2048, 2048)) == 4 and shapes.count((2048, 8192)) == 2 and shapes.count((8192, 2048)) == 1
+
+
+def test_planted_gradients_shapes_and_structure():
+    G, Gt, planted = synth.planted_gradients(200, 16, 1000, 50, seed=3)
+    assert G.shape == (200, 1000) and Gt.shape == (16, 1000) and planted.numel() == 50
+    assert planted[0] == 0 and torch.all(planted[1:] > planted[:-1]) and planted[-1] < 1000
+    rest = torch.ones(1000, dtype=torch.bool)
+    rest[planted] = False
+    assert G[:, planted].std() > 5 * G[:, rest].std()
+    G2, _, _ = synth.planted_gradients(200, 16, 1000, 50, seed=3)
+    assert torch.equal(G, G2)
