@@ -328,8 +328,9 @@ grass_status grass_ifvp(const float* G, uint64_t N, uint32_t k, uint64_t ldg,
  * logits S in R^p are trained to maximise
  *   mean over test rows t of corr_i( <g_i, gt_t>, <sigma*g_i, sigma*gt_t> )  -  lambda * sum_j sigma_j,
  * sigma = sigmoid(S / temperature), corr the Pearson correlation over the n train
- * rows.  The paper fixes no optimiser; the library provides the two pieces every
- * first-order method needs, the caller owns the update rule.
+ * rows.  The paper fixes no optimiser: grass_selective_mask_grad gives the value
+ * and gradient any first-order method needs, grass_selective_mask_train runs
+ * plain gradient ascent with them.
  *
  * grass_selective_mask_grad: objective value and gradient with respect to S.
  *   G  (n x p fp32, ldg)  train gradients;  Gt (m x p fp32, ldgt) test gradients
@@ -356,6 +357,35 @@ grass_status grass_selective_mask_grad(const float* G, uint64_t n, uint64_t ldg,
                                        double lambda, double temperature,
                                        float* grad, double* objective,
                                        void* ws, size_t ws_bytes, grass_stream stream);
+/* grass_selective_mask_train: solves Eq. (1) by first-order ascent (the paper
+ * names no optimiser; this is plain gradient ascent over all rows handed in),
+ *     S <- S + lr * d objective / d S   at temperature host_temperatures[i],
+ * for i = 0 .. steps-1, with the decreasing inverse-temperature schedule of
+ * App. B.4 ("Ensuring Exact k") supplied by the caller as a HOST array of
+ * `steps` positive numbers (a constant array trains without annealing).  S (p
+ * fp32, device) is updated in place; objectives (device double[steps], may be
+ * NULL) receives the objective before each step.  All steps are enqueued back to
+ * back; the host array is read during the call only.  Start from logits that are
+ * not all equal: constant logits give correlation 1 and a zero data gradient.
+ * Follow with grass_selective_mask_indices to extract the mask.  G, Gt, A as in
+ * grass_selective_mask_grad.
+ *
+ * grass_score_correlation: *mean_corr (device double) = mean over the m rows of
+ * the Pearson correlation (1/n moments, fp64, fixed order) between row t of X
+ * and row t of Y, two m x n fp32 score matrices; a row that is constant in X or
+ * Y contributes 0.  With X = grass_score(G, Gt) and Y the scores of the masked
+ * gradients (grass_mask on both, then grass_score) this is the first term of
+ * Eq. (1) for a binary mask.  n >= 2.                                          */
+grass_status grass_selective_mask_train_workspace_bytes(uint64_t n, uint64_t m, uint64_t p, size_t* host_bytes);
+grass_status grass_selective_mask_train(const float* G, uint64_t n, uint64_t ldg,
+                                        const float* Gt, uint64_t m, uint64_t ldgt, uint64_t p,
+                                        const float* A, uint64_t lda, float* S,
+                                        double lambda, double lr, const double* host_temperatures, uint32_t steps,
+                                        double* objectives, void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_score_correlation_workspace_bytes(uint64_t m, size_t* host_bytes);
+grass_status grass_score_correlation(const float* X, uint64_t ldx, const float* Y, uint64_t ldy,
+                                     uint64_t m, uint64_t n, double* mean_corr,
+                                     void* ws, size_t ws_bytes, grass_stream stream);
 /* Factorised form for one linear layer (App. B.4 "Linear Layer", one token per
  * sample as in the paper's formula): per-sample gradients are z_in (x) z_out,
  * the mask is sigma(S_in) (x) sigma(S_out), the penalty lambda * (|sigma(S_in)|_1

@@ -74,6 +74,11 @@ SIGNATURES = {
     "grass_selective_mask_grad_workspace_bytes": (_int, [_u64, _u64, _u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_grad": (_int, [_vp, _u64, _u64, _vp, _u64, _u64, _u64, _vp, _u64, _vp, ctypes.c_double,
                                          ctypes.c_double, _vp, _vp, _vp, _sz, _vp]),
+    "grass_selective_mask_train_workspace_bytes": (_int, [_u64, _u64, _u64, ctypes.POINTER(_sz)]),
+    "grass_selective_mask_train": (_int, [_vp, _u64, _u64, _vp, _u64, _u64, _u64, _vp, _u64, _vp, ctypes.c_double,
+                                          ctypes.c_double, ctypes.POINTER(ctypes.c_double), _u32, _vp, _vp, _sz, _vp]),
+    "grass_score_correlation_workspace_bytes": (_int, [_u64, ctypes.POINTER(_sz)]),
+    "grass_score_correlation": (_int, [_vp, _u64, _vp, _u64, _u64, _u64, _vp, _vp, _sz, _vp]),
     "grass_selective_mask_grad_factorized_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_grad_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
                                                     _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp, _vp,
@@ -482,6 +487,48 @@ def grass_selective_mask_grad(G: torch.Tensor, Gt: torch.Tensor, A: torch.Tensor
                                                     0 if ws is None else ws.numel(), _stream()),
            "grass_selective_mask_grad")
     return grad, objective
+
+
+def grass_selective_mask_train_workspace_bytes(n: int, m: int, p: int) -> int:
+    out = _sz(0)
+    _check(load_library().grass_selective_mask_train_workspace_bytes(n, m, p, ctypes.byref(out)),
+           "grass_selective_mask_train_workspace_bytes")
+    return out.value
+
+
+def grass_selective_mask_train(G: torch.Tensor, Gt: torch.Tensor, A: torch.Tensor, S: torch.Tensor, lam: float, lr: float,
+                               temperatures, objectives: torch.Tensor | None = None, ws: torch.Tensor | None = None):
+    """len(temperatures) gradient-ascent steps on the logits S (updated in place), step i at temperatures[i].
+    Returns (S, objectives float64 [steps]: the objective before each step)."""
+    assert G.dtype == Gt.dtype == A.dtype == S.dtype == torch.float32 and S.is_contiguous()
+    n, p = G.shape
+    m = Gt.shape[0]
+    assert Gt.shape[1] == p and A.shape == (m, n) and S.numel() == p
+    steps = len(temperatures)
+    sched = (ctypes.c_double * max(steps, 1))(*[float(t) for t in temperatures])
+    if objectives is None:
+        objectives = torch.empty(max(steps, 1), dtype=torch.float64, device=G.device)
+    if ws is None:
+        ws = _workspace(grass_selective_mask_train_workspace_bytes(n, m, p), G.device)
+    _check(load_library().grass_selective_mask_train(_ptr(G), n, _ld(G), _ptr(Gt), m, _ld(Gt), p, _ptr(A), _ld(A), _ptr(S),
+                                                     float(lam), float(lr), sched, steps, _ptr(objectives), _ptr(ws),
+                                                     ws.numel(), _stream()), "grass_selective_mask_train")
+    return S, objectives[:steps]
+
+
+def grass_score_correlation(X: torch.Tensor, Y: torch.Tensor, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Mean over rows of the Pearson correlation between matching rows of two m x n score matrices (float64 [1])."""
+    assert X.dtype == Y.dtype == torch.float32 and X.shape == Y.shape
+    m, n = X.shape
+    if out is None:
+        out = torch.empty(1, dtype=torch.float64, device=X.device)
+    nbytes = _sz(0)
+    _check(load_library().grass_score_correlation_workspace_bytes(m, ctypes.byref(nbytes)),
+           "grass_score_correlation_workspace_bytes")
+    ws = _workspace(nbytes.value, X.device)
+    _check(load_library().grass_score_correlation(_ptr(X), _ld(X), _ptr(Y), _ld(Y), m, n, _ptr(out), _ptr(ws), ws.numel(),
+                                                  _stream()), "grass_score_correlation")
+    return out
 
 
 def grass_selective_mask_grad_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam: float, temperature: float = 1.0):

@@ -81,8 +81,15 @@ __global__ void __launch_bounds__(256) sm_corr_kernel(const float* A, uint64_t l
     const double r = ok ? sab / nab : 0.0;
     if (threadIdx.x == 0) corr[t] = r;
     const double ka = ok ? 1.0 / (nab * (double)m) : 0.0, kb = ok ? r / (sbb * (double)m) : 0.0;
+    if (!C) return;                                        // correlation only
     for (uint64_t i = threadIdx.x; i < ld_c; i += 256)
         C[t * ld_c + i] = i < n ? (float)(ka * (a[i] - ma) - kb * (b[i] - mb)) : 0.0f;
+}
+
+// One ascent step on the logits: S_j += lr * grad_j (sum in fp64, rounded to fp32 once).
+__global__ void __launch_bounds__(256) sm_update_kernel(float* S, const float* grad, uint64_t p, double lr) {
+    const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (j < p) S[j] = (float)((double)S[j] + lr * (double)grad[j]);
 }
 
 // grad[j] = 2 sigma_j sigma_j' * sum_t Gt[t][j] R[t][j - j0] - lambda sigma_j' for the columns [j0, j0 + pc).
@@ -236,22 +243,16 @@ extern "C" grass_status grass_selective_mask_grad_workspace_bytes(uint64_t n, ui
     return GRASS_OK;
 }
 
-extern "C" grass_status grass_selective_mask_grad(const float* G, uint64_t n, uint64_t ldg, const float* Gt, uint64_t m,
-                                                  uint64_t ldgt, uint64_t p, const float* A, uint64_t lda,
-                                                  const float* S, double lambda, double temperature, float* grad,
-                                                  double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
-    grass_status st = check_sm(n, m, p);
-    if (st != GRASS_OK) return st;
-    if (!G || !Gt || !A || !S || !grad || ldg < p || ldgt < p || lda < n) return GRASS_EINVAL;
-    if (!(temperature > 0.0) || !(lambda >= 0.0)) return GRASS_EINVAL;
-    const SmLayout L = sm_layout(n, m, p);
-    if (!ws || ws_bytes < L.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
-    unsigned char* base = static_cast<unsigned char*>(ws);
+// Objective and gradient at S for one temperature: the body of grass_selective_mask_grad and of every training step.
+static grass_status sm_value_and_grad(const SmLayout& L, unsigned char* base, const float* G, uint64_t n, uint64_t ldg,
+                                      const float* Gt, uint64_t m, uint64_t ldgt, uint64_t p, const float* A, uint64_t lda,
+                                      const float* S, double lambda, double temperature, float* grad, double* objective,
+                                      hipStream_t hs) {
+    grass_status st;
     float* B = reinterpret_cast<float*>(base + L.off_b);
     float* C = reinterpret_cast<float*>(base + L.off_c);
     double* corr = reinterpret_cast<double*>(base + L.off_corr);
     double* sig_part = reinterpret_cast<double*>(base + L.off_sig);
-    hipStream_t hs = as_stream(stream);
     const float inv_temp = (float)(1.0 / temperature);
 
     st = sm_masked_scores(L, base, G, n, ldg, Gt, m, ldgt, p, S, inv_temp, B, sig_part, hs);
@@ -262,6 +263,80 @@ extern "C" grass_status grass_selective_mask_grad(const float* G, uint64_t n, ui
     if (objective)
         hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_part, ceil_div((p + 3) / 4 * 4, 256),
                            (const double*)nullptr, (uint64_t)0, lambda, objective);
+    return launch_status();
+}
+
+extern "C" grass_status grass_selective_mask_grad(const float* G, uint64_t n, uint64_t ldg, const float* Gt, uint64_t m,
+                                                  uint64_t ldgt, uint64_t p, const float* A, uint64_t lda,
+                                                  const float* S, double lambda, double temperature, float* grad,
+                                                  double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK) return st;
+    if (!G || !Gt || !A || !S || !grad || ldg < p || ldgt < p || lda < n) return GRASS_EINVAL;
+    if (!(temperature > 0.0) || !(lambda >= 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, p);
+    if (!ws || ws_bytes < L.total || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    return sm_value_and_grad(L, static_cast<unsigned char*>(ws), G, n, ldg, Gt, m, ldgt, p, A, lda, S, lambda, temperature,
+                             grad, objective, as_stream(stream));
+}
+
+// Training: `steps` plain gradient-ascent steps on the logits, step i at temperature host_temperatures[i], all
+// enqueued back to back (the host only reads its own schedule array; nothing waits for the device).
+extern "C" grass_status grass_selective_mask_train_workspace_bytes(uint64_t n, uint64_t m, uint64_t p,
+                                                                   size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK) return st;
+    *host_bytes = sm_layout(n, m, p).total + up256((size_t)p * 4);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_selective_mask_train(const float* G, uint64_t n, uint64_t ldg, const float* Gt, uint64_t m,
+                                                   uint64_t ldgt, uint64_t p, const float* A, uint64_t lda, float* S,
+                                                   double lambda, double lr, const double* host_temperatures,
+                                                   uint32_t steps, double* objectives, void* ws, size_t ws_bytes,
+                                                   grass_stream stream) {
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK) return st;
+    if (!G || !Gt || !A || !S || ldg < p || ldgt < p || lda < n) return GRASS_EINVAL;
+    if (!(lambda >= 0.0) || !(lr == lr) || (steps > 0 && !host_temperatures)) return GRASS_EINVAL;
+    for (uint32_t i = 0; i < steps; ++i)
+        if (!(host_temperatures[i] > 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, p);
+    if (!ws || ws_bytes < L.total + up256((size_t)p * 4) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* grad = reinterpret_cast<float*>(base + L.total);
+    hipStream_t hs = as_stream(stream);
+    for (uint32_t i = 0; i < steps; ++i) {
+        st = sm_value_and_grad(L, base, G, n, ldg, Gt, m, ldgt, p, A, lda, S, lambda, host_temperatures[i], grad,
+                               objectives ? objectives + i : nullptr, hs);
+        if (st != GRASS_OK) return st;
+        hipLaunchKernelGGL(sm_update_kernel, dim3((uint32_t)ceil_div(p, 256)), dim3(256), 0, hs, S, grad, p, lr);
+    }
+    return launch_status();
+}
+
+// Mean over the m rows of the Pearson correlation between row t of X and row t of Y (two m x n score matrices): the
+// first term of Eq. (1) when Y holds the scores of masked gradients, and the agreement measure between exact and
+// compressed attribution scores in general.
+extern "C" grass_status grass_score_correlation_workspace_bytes(uint64_t m, size_t* host_bytes) {
+    if (!host_bytes || m == 0) return GRASS_EINVAL;
+    *host_bytes = up256((size_t)m * 8);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_score_correlation(const float* X, uint64_t ldx, const float* Y, uint64_t ldy, uint64_t m,
+                                                uint64_t n, double* mean_corr, void* ws, size_t ws_bytes,
+                                                grass_stream stream) {
+    if (m == 0 || n < 2 || !X || !Y || !mean_corr || ldx < n || ldy < n) return GRASS_EINVAL;
+    if (m >= (1ull << 31)) return GRASS_EUNSUPPORTED;
+    if (!ws || ws_bytes < up256((size_t)m * 8) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    double* corr = static_cast<double*>(ws);
+    hipStream_t hs = as_stream(stream);
+    hipLaunchKernelGGL(sm_corr_kernel, dim3((uint32_t)m), dim3(256), 0, hs, X, ldx, Y, ldy, n, m, (float*)nullptr, (uint64_t)0,
+                       corr);
+    hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, (const double*)nullptr, (uint64_t)0,
+                       (const double*)nullptr, (uint64_t)0, 0.0, mean_corr);
     return launch_status();
 }
 

@@ -167,3 +167,113 @@ def test_selective_mask_argument_checks(grass):
         grass.grass_selective_mask_grad(G[:1], Gt, A[:, :1], S, 0.1)      # n = 1: no correlation
     with pytest.raises(grass.GrassError):
         grass.grass_selective_mask_indices(S, 17)
+
+
+# ------------------------------------------------------------------ training (Sec. 3.2 Eq. (1) by gradient ascent)
+def _oracle_path(S0, Gh, Gth, lam, lr, temps):
+    """The oracle's training run, one step at a time, with the length of the path the logits travelled."""
+    S, hist, path = np.asarray(S0, np.float64), [], 0.0
+    for T in temps:
+        nxt, h = orc.selective_mask_train(S, Gh, Gth, lam, lr, [T])
+        path += np.abs(nxt - S).max()
+        hist.append(h[0])
+        S = nxt
+    return S, np.asarray(hist), path
+
+
+@pytest.mark.parametrize("n,m,p,lam,lr,steps,pad", [(60, 5, 333, 0.01, 3.0, 12, 1), (300, 130, 4096, 1e-3, 40.0, 25, 0),
+                                                    (140, 128, 5004, 1e-4, 60.0, 10, 0)])
+def test_selective_mask_train_parity(grass, n, m, p, lam, lr, steps, pad):
+    """S after `steps` device-side steps against the oracle's loop.  Every step adds lr * grad with the gradient bar
+    of 2e-4 of its largest entry, so the logits may drift apart by 2e-4 of the path length (plus fp32 rounding of S)."""
+    G, Gt, S0 = _problem(n, m, p, seed=3300 + p, pad=pad)
+    S0 = (0.2 * S0).contiguous()
+    temps = np.geomspace(1.0, 0.4, steps)
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    S = S0.clone()
+    _, objs = grass.grass_selective_mask_train(G, Gt, A, S, lam, lr, temps)
+    torch.cuda.synchronize()
+    want, hist, path = _oracle_path(S0.cpu().numpy(), G.cpu().numpy(), Gt.cpu().numpy(), lam, lr, temps)
+    got = S.cpu().numpy().astype(np.float64)
+    assert path > 0 and np.abs(want - S0.cpu().numpy()).max() > 10 * 2e-4 * path       # the run really moved the logits
+    assert np.abs(got - want).max() <= 2e-4 * path + steps * 2.0 ** -23 * np.abs(want).max()
+    assert np.abs(objs.cpu().numpy() - hist).max() <= 1e-5 * max(1.0, np.abs(hist).max())
+    # the same run as separate calls of the gradient entry point and a host-side update gives the same logits
+    S2 = S0.clone()
+    for T in temps:
+        grad, _ = grass.grass_selective_mask_grad(G, Gt, A, S2, lam, float(T))
+        S2 = (S2.double() + lr * grad.double()).float()
+    torch.cuda.synchronize()
+    assert torch.equal(S2, S)
+
+
+def test_selective_mask_train_recovers_planted_coordinates_and_beats_random_mask(grass):
+    """End to end on gradients with planted informative coordinates: device training, extraction (exact k and plain
+    threshold), and the first term of Eq. (1) for the resulting binary mask against a Random Mask of the same size."""
+    n, m, p, kept, lam, lr = 512, 32, 4096, 128, 3e-4, 300.0
+    G, Gt, planted = synth.planted_gradients(n, m, p, kept, seed=3400, device=_dev())
+    S0 = synth.dense_normal(1, p, seed=3401, device=_dev(), std=0.1).reshape(-1).contiguous()
+    temps = np.geomspace(1.0, 0.6, 60)       # mild annealing: saturated logits make the run sensitive to rounding
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    S = S0.clone()
+    _, objs = grass.grass_selective_mask_train(G, Gt, A, S, lam, lr, temps)
+    idx_k = grass.grass_selective_mask_indices(S, kept)
+    idx_thr = grass.grass_selective_mask_indices(S)
+    torch.cuda.synchronize()
+    Gh, Gth = G.cpu().numpy(), Gt.cpu().numpy()
+    want_S, hist = orc.selective_mask_train(S0.cpu().numpy(), Gh, Gth, lam, lr, temps)
+    want_idx = orc.selective_mask_indices(want_S, kept)
+    planted_h = planted.numpy().astype(np.int32)
+    assert np.array_equal(want_idx, planted_h)                       # the oracle's run finds the planted set ...
+    gap = want_S[planted_h].min() - np.delete(want_S, planted_h).max()
+    assert gap > 100 * np.abs(S.cpu().numpy() - want_S).max()        # ... with a margin far above the GPU's deviation,
+    assert np.array_equal(idx_k.cpu().numpy(), want_idx)             # so the extracted indices must agree bit for bit
+    assert np.array_equal(idx_thr.cpu().numpy(), orc.selective_mask_indices(want_S))
+    assert objs[-1].item() > objs[0].item()
+
+    def masked_correlation(idx):
+        Y = grass.grass_score(grass.grass_mask(G, idx), grass.grass_mask(Gt, idx), compute_mode=0)
+        return float(grass.grass_score_correlation(A, Y).item())
+
+    c_sel = masked_correlation(idx_k)
+    assert abs(c_sel - orc.graddot_correlation(Gh, Gth, want_idx)) <= 1e-5
+    c_rand = []
+    for seed in range(5):
+        ridx = grass.grass_mask_indices(seed, 0, p, kept, device=_dev())
+        c = masked_correlation(ridx)
+        assert abs(c - orc.graddot_correlation(Gh, Gth, ridx.cpu().numpy())) <= 1e-5
+        c_rand.append(c)
+    assert c_sel > 0.9 and c_sel > max(c_rand) + 0.2
+
+
+def test_selective_mask_train_edge_cases(grass):
+    G, Gt, S0 = _problem(20, 3, 50, seed=3500)
+    A = grass.grass_score(G, Gt, compute_mode=0)
+    S = S0.clone()
+    grass.grass_selective_mask_train(G, Gt, A, S, 0.01, 1.0, [])     # no steps: nothing happens
+    torch.cuda.synchronize()
+    assert torch.equal(S, S0)
+    grass.grass_selective_mask_train(G, Gt, A, S, 0.01, 0.0, [1.0, 0.5])   # zero step size: logits stay
+    torch.cuda.synchronize()
+    assert torch.equal(S, S0)
+    for bad in ([1.0, 0.0], [-1.0], [float("nan")]):
+        with pytest.raises(grass.GrassError):
+            grass.grass_selective_mask_train(G, Gt, A, S, 0.01, 1.0, bad)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_train(G, Gt, A, S, -0.01, 1.0, [1.0])
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_train(G, Gt, A, S, 0.01, 1.0, [1.0], ws=torch.empty(256, dtype=torch.uint8, device=_dev()))
+    torch.cuda.synchronize()
+    assert torch.equal(S, S0)                                       # refused calls did nothing
+
+
+def test_score_correlation_parity(grass):
+    from scipy import stats
+    m, n = 37, 1000
+    X = synth.dense_normal(m, n, seed=3600, device=_dev())
+    Y = (0.6 * X + synth.dense_normal(m, n, seed=3601, device=_dev()))[:, :n].contiguous()
+    Y[5] = 2.0                                                       # a constant row contributes 0
+    got = float(grass.grass_score_correlation(X, Y).item())
+    Xh, Yh = X.cpu().numpy().astype(np.float64), Y.cpu().numpy().astype(np.float64)
+    want = sum(stats.pearsonr(Xh[t], Yh[t])[0] for t in range(m) if t != 5) / m
+    assert abs(got - want) <= 1e-6
