@@ -29,27 +29,66 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 MFMA_PEAK_F32_TFLOPS = 157.3     # MI355X published dense fp32 matrix rate
 MFMA_PEAK_BF16_TFLOPS = 2500.0
 
-# HBM traffic per launch of the headline kernel measured with rocprofv3 --pmc
-# (FETCH_SIZE, WRITE_SIZE), scaled by the same counters on a plain copy of known
-# size; see profiles/sjlt_fused_mlp_pmc.txt (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000).
-MEASURED_TRAFFIC_BYTES = {"mlp_mask_sjlt_s1": 21087231664}
+# HBM traffic per launch of the headline kernel comes from the rocprofv3 --pmc summary under profiles/ (FETCH_SIZE and
+# WRITE_SIZE, each scaled by what the same counter reads for a plain copy of known size).  The summary ends in a
+# "traffic_record:" line naming the kernel instantiation, launch grid and workload it was taken on; the figure is
+# used only if the library reports the same instantiation and grid for this run, otherwise traffic is null.
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "sjlt_fused_mlp_pmc.txt")
 
 
-def _timed(fn, steps, warmup, torch):
-    for _ in range(warmup):
-        fn()
+def _traffic_record(path):
+    """Parses 'traffic_record: key=value ...' from a profile summary; None if the file or the line is missing."""
+    try:
+        with open(path) as fh:
+            lines = [ln for ln in fh if ln.startswith("traffic_record:")]
+    except OSError:
+        return None
+    if not lines:
+        return None
+    rec = {}
+    for tok in lines[-1].split()[1:]:
+        key, _, val = tok.partition("=")
+        rec[key] = val
+    return rec
+
+
+def _touched_lines(idx, elem_bytes, row_bytes, base_mod, rows):
+    """Number of distinct 128-byte lines that `rows` rows touch when every row reads the elements `idx` (element size
+    elem_bytes) and consecutive rows start row_bytes apart, the first at an address congruent to base_mod mod 128."""
+    import numpy as np
+    off = idx.astype(np.int64) * elem_bytes
+    period = 128 // np.gcd(row_bytes % 128, 128) if row_bytes % 128 else 1
+    per_phase = [np.unique((off + (base_mod + r * row_bytes) % 128) // 128).size for r in range(min(period, rows))]
+    total = 0
+    for r, cnt in enumerate(per_phase):
+        total += cnt * ((rows - r + period - 1) // period)
+    return total
+
+
+def _timed(fn, steps, warmup, torch, indexed=False):
+    """HIP events on torch's current stream (the stream the binding launches on) around every call.
+    indexed=True hands fn the running call number (warm-up included) so that it can rotate its inputs."""
+    for w in range(warmup):
+        fn(w) if indexed else fn()
     torch.cuda.synchronize()
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
     evs[0].record()
     for i in range(steps):
-        fn()
+        fn(warmup + i) if indexed else fn()
         evs[i + 1].record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3
     per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
     total_ms = evs[0].elapsed_time(evs[steps])
     return total_ms, per, wall_ms
+
+
+def _roof(bound, achieved, peak, unit, **more):
+    """A roofline object in the shape of the headline's, for one of the extra paths."""
+    d = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": unit, "frac": round(achieved / peak, 4)}
+    d.update(more)
+    return d
 
 
 def main() -> int:
@@ -161,15 +200,33 @@ def main() -> int:
 
     alg_bytes = n * (4 * kp + 4 * k) + 4 * kp          # useful reads + writes + the index vector once
     achieved = alg_bytes / (kernel_ms * 1e-3) / 1e9
-    roofline = {"bound": "hbm", "kernel": "sjlt_kernel (fused mask gather + SJLT)", "achieved": round(achieved, 2),
+    launched = grass.grass_sjlt_describe(n, p, g.stride(0), kp, k, s, g=g, with_workspace=True)
+    roofline = {"bound": "hbm", "kernel": launched.split()[0], "launch": launched, "achieved": round(achieved, 2),
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 5),
-                "traffic": MEASURED_TRAFFIC_BYTES["mlp_mask_sjlt_s1"], "kernel_ms": round(kernel_ms, 4),
+                "traffic": None, "kernel_ms": round(kernel_ms, 4),
                 "algorithmic_bytes_per_launch": alg_bytes, "launches_per_step": 1 if ws_bytes == 0 else 2}
-    # what the counters say the launch really moves: a kept 4-byte entry costs its whole 128-byte line, and one
-    # coordinate in 28 touches 68 % of the lines of every row; this is the figure the HBM peak applies to
-    traffic = MEASURED_TRAFFIC_BYTES["mlp_mask_sjlt_s1"]
-    roofline["traffic_GBps"] = round(traffic / (kernel_ms * 1e-3) / 1e9, 1)
-    roofline["traffic_frac_of_peak"] = round(traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    # what the launch really moves: a kept 4-byte entry costs its whole 128-byte line, and one coordinate in 28
+    # touches 68 % of the lines of every row.  Counted here on the host from the actual indices, row distance and
+    # base alignment (lines read once each + the output rows + idx), and taken from the counter run if that run was
+    # made on this very kernel instantiation, grid and workload.
+    idx_np = idx.cpu().numpy()
+    lines = _touched_lines(idx_np, 4, g.stride(0) * 4, g.data_ptr() % 128, n)
+    expected = lines * 128 + n * k * 4 + kp * 4
+    roofline["expected_line_traffic"] = int(expected)
+    roofline["expected_line_traffic_GBps"] = round(expected / (kernel_ms * 1e-3) / 1e9, 1)
+    roofline["expected_line_traffic_frac_of_peak"] = round(expected / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    rec = _traffic_record(TRAFFIC_PROFILE)
+    want = {"kernel": launched.split()[0], "grid": launched.split()[1].split("=")[1], "n": str(n), "p": str(p),
+            "kprime": str(kp), "k": str(k), "s": str(s)}
+    if rec and all(rec.get(key) == val for key, val in want.items()):
+        traffic = int(rec["bytes_per_launch"])
+        roofline["traffic"] = traffic
+        roofline["traffic_source"] = "profiles/" + os.path.basename(TRAFFIC_PROFILE)
+        roofline["traffic_GBps"] = round(traffic / (kernel_ms * 1e-3) / 1e9, 1)
+        roofline["traffic_frac_of_peak"] = round(traffic / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)
+    else:
+        roofline["traffic_source"] = ("no counter record for this kernel instantiation, grid and workload under profiles/"
+                                      if rec else "profiles/ summary not found")
 
     result = {
         "metric": "compressed per-sample gradients/sec at 1 GPU",
@@ -216,7 +273,12 @@ def main() -> int:
         # plain gather
         gm = torch.empty((n, kp), dtype=torch.float32, device=dev)
         t, _, _ = _timed(lambda: grass.grass_mask(g, idx, out=gm), st, 2, torch)
-        extras["mlp_mask_gather"] = {"ms": round(t / st, 4), "useful_GBps": round(2 * n * kp * 4 / (t / st * 1e-3) / 1e9, 1)}
+        gather_bytes = lines * 128 + n * kp * 4 + kp * 4
+        extras["mlp_mask_gather"] = {"ms": round(t / st, 4), "useful_GBps": round(2 * n * kp * 4 / (t / st * 1e-3) / 1e9, 1),
+                                     "roofline": _roof("hbm", gather_bytes / (t / st * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                                                       traffic_model_bytes=int(gather_bytes),
+                                                       note="touched 128-byte lines (counted from the indices) + the "
+                                                            "n x k' output")}
         # mask index generation (one-time set-up)
         t, _, _ = _timed(lambda: grass.grass_mask_indices(seed, 0, p, kp, device=dev), 5, 1, torch)
         extras["mask_indices_p1863690"] = {"ms": round(t / 5, 4)}
@@ -251,6 +313,36 @@ def main() -> int:
         extras["selective_mask_indices_top_k"] = {"ms": round(t / 3, 3)}
         del g, gt_sm, s_sm, a_sm, w_sm, gr_sm, ob_sm
         torch.cuda.empty_cache()
+        # Selective Mask training end to end on gradients with 2,048 planted informative coordinates among 65,536:
+        # 60 device-side ascent steps with a decreasing temperature, exact-k extraction, and the first term of Eq. (1)
+        # (correlation between exact and masked GradDot scores) of the trained mask against Random Masks of equal size
+        nt, mt, pt, kt_ = 2048, 128, 65536, 2048
+        Gp, Gtp, planted = synth.planted_gradients(nt, mt, pt, kt_, seed=3700, device=dev)
+        Ap = grass.grass_score(Gp, Gtp, compute_mode=0)
+        Sp = synth.dense_normal(1, pt, seed=3701, device=dev, std=0.1).reshape(-1).contiguous()
+        wtr = torch.empty(grass.grass_selective_mask_train_workspace_bytes(nt, mt, pt), dtype=torch.uint8, device=dev)
+        sched = np.geomspace(1.0, 0.6, 60)
+        S_run = Sp.clone()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        _, objs = grass.grass_selective_mask_train(Gp, Gtp, Ap, S_run, 3e-4 / 16, 4800.0, sched, ws=wtr)
+        torch.cuda.synchronize()
+        train_ms = (time.perf_counter() - t0) * 1e3
+
+        def _mask_corr(ix):
+            Y = grass.grass_score(grass.grass_mask(Gp, ix), grass.grass_mask(Gtp, ix), compute_mode=0)
+            return float(grass.grass_score_correlation(Ap, Y).item())
+        sel = grass.grass_selective_mask_indices(S_run, kt_)
+        hits = int(torch.isin(sel.long(), planted.to(dev)).sum().item())
+        rand_corr = [_mask_corr(grass.grass_mask_indices(sd, 0, pt, kt_, device=dev)) for sd in range(3)]
+        extras["selective_mask_training_planted"] = {
+            "train_rows": nt, "test_rows": mt, "p": pt, "k": kt_, "steps": len(sched), "ms_per_step": round(train_ms / len(sched), 3),
+            "TFLOPs": round(2 * 2.0 * nt * mt * pt * len(sched) / (train_ms * 1e-3) / 1e12, 1),
+            "objective_first_last": [round(float(objs[0].item()), 4), round(float(objs[-1].item()), 4)],
+            "planted_coordinates_recovered": hits, "correlation_selective_mask": round(_mask_corr(sel), 4),
+            "correlation_random_masks": [round(c, 4) for c in rand_corr]}
+        del Gp, Gtp, Ap, Sp, wtr, S_run
+        torch.cuda.empty_cache()
 
         # ResNet-scale unmasked SJLT
         n3, p3, k3 = 1024, 11173962, 8192
@@ -260,7 +352,10 @@ def main() -> int:
         t, _, _ = _timed(lambda: grass.grass_sjlt(g3, k3, 1, seed, 1, out=o3, ws=w3), 10, 2, torch)
         gbps = n3 * (4 * p3 + 4 * k3) / (t / 10 * 1e-3) / 1e9
         extras["resnet_sjlt_s1"] = {"ms": round(t / 10, 4), "samples_per_s": round(n3 / (t / 10 * 1e-3), 1),
-                                    "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4)}
+                                    "algorithmic_GBps": round(gbps, 1), "frac_of_hbm_peak": round(gbps / HBM_PEAK_GBS, 4),
+                                    "launch": grass.grass_sjlt_describe(n3, p3, g3.stride(0), 0, k3, 1, g=g3),
+                                    "roofline": _roof("hbm", gbps, HBM_PEAK_GBS, "GB/s",
+                                                      note="algorithmic bytes n (4p + 4k): every input byte must be read once")}
         # the dense Gaussian baseline on the same full input (P is 366 GB as a matrix: it is generated chunk by chunk
         # inside the call and never stored); one call per mode, 1.87e17 FLOP each
         wg3 = torch.empty(grass.grass_gauss_project_workspace_bytes(n3, p3, k3, 32768), dtype=torch.uint8, device=dev)
@@ -281,37 +376,63 @@ def main() -> int:
         del g3h, o3, w3
         torch.cuda.empty_cache()
 
-        # FactGraSS on one 4096 x 4096 linear layer
-        n4, T4, d4, kf, k4 = 32, 512, 4096, 64, 1024
-        x4, go4 = synth.linear_layer_factors(n4, T4, d4, d4, seed=1004, device=dev)
+        # FactGraSS on one 4096 x 4096 linear layer.  Five (x, g) pairs of 268 MB each are rotated so that no call
+        # finds its inputs in the 256 MB last-level cache (the resident figure is reported next to it)
+        n4, T4, d4, kf, k4, NPAIR = 32, 512, 4096, 64, 1024, 5
+        pairs = [synth.linear_layer_factors(n4, T4, d4, d4, seed=1004 + 50 * q, device=dev) for q in range(NPAIR)]
+        x4, go4 = pairs[0]
         ii = grass.grass_mask_indices(seed, 16, d4, kf, device=dev)
         io = grass.grass_mask_indices(seed, 17, d4, kf, device=dev)
         o4 = torch.empty((n4, k4), dtype=torch.float32, device=dev)
         w4 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n4, T4, kf, kf, k4, 1), 1), dtype=torch.uint8,
                          device=dev)
+        # 128-byte lines a token touches in x and in g (rows of 8,192 bytes start on a line), the floor for a gather
+        ii_h, io_h = ii.cpu().numpy(), io.cpu().numpy()
+        lines4 = _touched_lines(ii_h, 2, d4 * 2, 0, 1) + _touched_lines(io_h, 2, d4 * 2, 0, 1)
+        line_bytes4 = n4 * T4 * lines4 * 128 + n4 * k4 * 4 + 2 * w4.numel()
         t, _, _ = _timed(lambda: grass.factgrass_linear(x4, go4, ii, io, k4, 1, seed, 18, out=o4, ws=w4), 20, 3, torch)
-        extras["factgrass_linear_4096"] = {"ms": round(t / 20, 4), "samples_per_s": round(n4 / (t / 20 * 1e-3), 1),
-                                           "tokens_per_s": round(n4 * T4 / (t / 20 * 1e-3), 1),
-                                           "useful_GBps": round(2 * n4 * T4 * 2 * kf * 2 / 2 / (t / 20 * 1e-3) / 1e9, 2)}
+        resident_ms = t / 20
+        t, _, _ = _timed(lambda c: grass.factgrass_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, k4, 1, seed, 18,
+                                                          out=o4, ws=w4), 40, NPAIR, torch, indexed=True)
+        fg_ms = t / 40
+        extras["factgrass_linear_4096"] = {"ms": round(fg_ms, 4), "ms_inputs_resident": round(resident_ms, 4),
+                                           "rotating_input_pairs": NPAIR,
+                                           "samples_per_s": round(n4 / (fg_ms * 1e-3), 1),
+                                           "tokens_per_s": round(n4 * T4 / (fg_ms * 1e-3), 1),
+                                           "useful_GBps": round(2 * n4 * T4 * 2 * kf / (fg_ms * 1e-3) / 1e9, 2),
+                                           "lines_per_token": int(lines4),
+                                           "roofline": _roof("hbm", line_bytes4 / (fg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                                                             traffic_model_bytes=int(line_bytes4),
+                                                             note="touched 128-byte lines of the gathered columns (counted "
+                                                                  "from the indices) + partial sums + output")}
         # LoGra baseline (dense factorised projection to 64 x 64) on the same layer, for the speed ratio
         Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 40, d4, kf, 0, d4, device=dev))
         Po = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 41, d4, kf, 0, d4, device=dev))
         ol = torch.empty((n4, kf * kf), dtype=torch.float32, device=dev)
         wl = torch.empty(max(grass.logra_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
-        tl, _, _ = _timed(lambda: grass.logra_linear(x4, go4, Pi, Po, out=ol, ws=wl), 20, 3, torch)
-        extras["logra_linear_4096"] = {"ms": round(tl / 20, 4), "tokens_per_s": round(n4 * T4 / (tl / 20 * 1e-3), 1),
-                                       "algorithmic_GBps": round(2 * n4 * T4 * d4 * 2 / (tl / 20 * 1e-3) / 1e9, 1),
-                                       "factgrass_speedup": round((tl / 20) / extras["factgrass_linear_4096"]["ms"], 2)}
+        tl, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Pi, Po, out=ol, ws=wl),
+                          40, NPAIR, torch, indexed=True)
+        lg_ms = tl / 40
+        lg_bytes = 2 * n4 * T4 * d4 * 2 + n4 * kf * kf * 4 + 2 * wl.numel()
+        extras["logra_linear_4096"] = {"ms": round(lg_ms, 4), "tokens_per_s": round(n4 * T4 / (lg_ms * 1e-3), 1),
+                                       "rotating_input_pairs": NPAIR,
+                                       "factgrass_speedup": round(lg_ms / fg_ms, 2),
+                                       "roofline": _roof("hbm", lg_bytes / (lg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                                                         algorithmic_bytes=int(lg_bytes),
+                                                         note="every column of x and g is read once")}
         # the other factorised compressors of the paper's Table 2 on the same layer (64 x 64 -> 4,096 outputs)
         wm = torch.empty(max(grass.factmask_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
-        tm, _, _ = _timed(lambda: grass.factmask_linear(x4, go4, ii, io, out=ol, ws=wm), 20, 3, torch)
+        tm, _, _ = _timed(lambda c: grass.factmask_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, out=ol, ws=wm),
+                          40, NPAIR, torch, indexed=True)
         Si = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 40, d4, kf, 1, device=dev))
         So = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 41, d4, kf, 1, device=dev))
-        ts, _, _ = _timed(lambda: grass.logra_linear(x4, go4, Si, So, out=ol, ws=wl), 20, 3, torch)
-        extras["table2_style_4096_layer_ms"] = {"mask_kin_x_kout": round(tm / 20, 4), "sjlt_kin_x_kout": round(ts / 20, 4),
-                                                "factgrass": extras["factgrass_linear_4096"]["ms"],
-                                                "logra_gauss_kin_x_kout": round(tl / 20, 4)}
-        del x4, go4, o4, w4, Pi, Po, ol, wl, wm, Si, So
+        ts, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Si, So, out=ol, ws=wl),
+                          40, NPAIR, torch, indexed=True)
+        extras["table2_style_4096_layer_ms"] = {"mask_kin_x_kout": round(tm / 40, 4), "sjlt_kin_x_kout": round(ts / 40, 4),
+                                                "factgrass": round(fg_ms, 4), "logra_gauss_kin_x_kout": round(lg_ms, 4),
+                                                "rotating_input_pairs": NPAIR}
+        del pairs, x4, go4, o4, w4, Pi, Po, ol, wl, wm, Si, So
+        torch.cuda.empty_cache()
 
         # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
         # every layer with its own activations and gradients (12.3 GB in total, so nothing is served from
@@ -338,8 +459,17 @@ def main() -> int:
         wb = torch.empty(max(grass.factgrass_layers_workspace_bytes(len(layers), n5, T5, kf, kf, kl, 1), 1),
                          dtype=torch.uint8, device=dev)
         t, _, wall = _timed(lambda: grass.factgrass_layers(batched, kl, 1, seed, cat, ws=wb), 5, 2, torch)
-        extras["factgrass_llama_112_layers_one_launch"] = {"ms": round(t / 5, 4),
-                                                           "tokens_per_s": round(n5 * T5 / (t / 5 * 1e-3), 1)}
+        lines5 = 0
+        for ((xl, gl), a_in, a_out, _sid) in layers:
+            lines5 += (_touched_lines(a_in.cpu().numpy(), 2, xl.shape[2] * 2, 0, 1)
+                       + _touched_lines(a_out.cpu().numpy(), 2, gl.shape[2] * 2, 0, 1))
+        line_bytes5 = n5 * T5 * lines5 * 128 + n5 * kl * len(layers) * 4
+        extras["factgrass_llama_112_layers_one_launch"] = {
+            "ms": round(t / 5, 4), "tokens_per_s": round(n5 * T5 / (t / 5 * 1e-3), 1),
+            "roofline": _roof("hbm", line_bytes5 / (t / 5 * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                              traffic_model_bytes=int(line_bytes5),
+                              note="touched 128-byte lines of the gathered columns of all 112 layers (12.3 GB of "
+                                   "distinct inputs) + output")}
         del wb, batched
         del layers, cat, w5
         torch.cuda.empty_cache()
@@ -414,7 +544,9 @@ def main() -> int:
             t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=mode, out=sc, ws=wsc), 5, 1, torch)
             tf = 2.0 * N5 * M5 * K5 / (t / 5 * 1e-3) / 1e12
             extras[f"score_gemm_mode{mode}"] = {"ms": round(t / 5, 4), "TFLOPs": round(tf, 2),
-                                                "frac_of_mfma_peak": round(tf / peak, 4)}
+                                                "frac_of_mfma_peak": round(tf / peak, 4),
+                                                "roofline": _roof("mfma", tf, peak, "TFLOP/s", target_frac=0.5,
+                                                                  target_met=bool(tf / peak >= 0.5))}
             del wsc
         t, _, _ = _timed(lambda: grass.grass_score(tr, te, compute_mode=1, out=sc, ws=None), 5, 1, torch)
         extras["score_gemm_mode1_no_workspace"] = {"ms": round(t / 5, 4),
@@ -425,19 +557,26 @@ def main() -> int:
         t, _, _ = _timed(lambda: grass.grass_score(tr16, te16, compute_mode=0, out=sc, ws=None), 2, 1, torch)
         tf = 2.0 * N5 * M5 * 16 * K5 / (t / 2 * 1e-3) / 1e12
         extras["score_gemm_mode0_K65536"] = {"ms": round(t / 2, 3), "TFLOPs": round(tf, 2),
-                                             "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4)}
+                                             "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4),
+                                             "roofline": _roof("mfma", tf, MFMA_PEAK_F32_TFLOPS, "TFLOP/s", target_frac=0.5,
+                                                               target_met=bool(tf / MFMA_PEAK_F32_TFLOPS >= 0.5))}
         tr16b, te16b = grass.grass_to_bf16(tr16), grass.grass_to_bf16(te16)
         del tr16, te16
         t, _, _ = _timed(lambda: grass.grass_score_bf16(tr16b, te16b, out=sc), 3, 1, torch)
         tf = 2.0 * N5 * M5 * 16 * K5 / (t / 3 * 1e-3) / 1e12
         extras["score_gemm_bf16_inputs_K65536"] = {"ms": round(t / 3, 3), "TFLOPs": round(tf, 2),
-                                                   "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4)}
+                                                   "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4),
+                                                   "roofline": _roof("mfma", tf, MFMA_PEAK_BF16_TFLOPS, "TFLOP/s",
+                                                                     target_frac=0.5,
+                                                                     target_met=bool(tf / MFMA_PEAK_BF16_TFLOPS >= 0.5))}
         del tr16b, te16b
         trb, teb = grass.grass_to_bf16(tr), grass.grass_to_bf16(te)
         t, _, _ = _timed(lambda: grass.grass_score_bf16(trb, teb, out=sc), 10, 2, torch)
         tf = 2.0 * N5 * M5 * K5 / (t / 10 * 1e-3) / 1e12
         extras["score_gemm_bf16_inputs"] = {"ms": round(t / 10, 4), "TFLOPs": round(tf, 2),
-                                            "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4)}
+                                            "frac_of_mfma_peak": round(tf / MFMA_PEAK_BF16_TFLOPS, 4),
+                                            "roofline": _roof("mfma", tf, MFMA_PEAK_BF16_TFLOPS, "TFLOP/s", target_frac=0.5,
+                                                              target_met=bool(tf / MFMA_PEAK_BF16_TFLOPS >= 0.5))}
         t, _, _ = _timed(lambda: grass.grass_to_bf16(tr, out=trb), 5, 1, torch)
         extras["to_bf16_train_rows"] = {"ms": round(t / 5, 4)}
         del trb, teb, te, sc
@@ -450,14 +589,22 @@ def main() -> int:
         pre = torch.empty((N5, K5), dtype=torch.float32, device=dev)
         t, _, _ = _timed(lambda: grass.grass_fim(tr, out=Fm, ws=wf), 3, 1, torch)
         tf = 2.0 * N5 * K5 * K5 / (t / 3 * 1e-3) / 1e12
+        tiles = K5 // 256
+        tf_exec = tf * (tiles * (tiles + 1) / 2) / (tiles * tiles)
         extras["fim_65536x4096"] = {"ms": round(t / 3, 3), "TFLOPs_full_product": round(tf, 2),
-                                    "note": "only tiles on or below the diagonal are computed"}
+                                    "note": "only tiles on or below the diagonal are computed",
+                                    "roofline": _roof("mfma", tf_exec, MFMA_PEAK_F32_TFLOPS, "TFLOP/s",
+                                                      note="flops of the executed lower 256 x 256 tiles")}
         t, _, _ = _timed(lambda: grass.grass_fim_inverse(Fm, 1e-3, out=Wm, ws=wi), 3, 1, torch)
-        extras["fim_inverse_4096"] = {"ms": round(t / 3, 3), "fp64_GFLOPs_at_k3": round(K5 ** 3 / (t / 3 * 1e-3) / 1e9, 1)}
+        extras["fim_inverse_4096"] = {"ms": round(t / 3, 3), "fp64_GFLOPs_at_k3": round(K5 ** 3 / (t / 3 * 1e-3) / 1e9, 1),
+                                      "roofline": _roof("mfma", K5 ** 3 / (t / 3 * 1e-3) / 1e12, 78.6, "TFLOP/s",
+                                                        note="k^3 flops (k^3/3 factorisation + k^3/3 triangular inverse "
+                                                             "+ k^3/3 product) against the fp64 matrix rate")}
         t, _, _ = _timed(lambda: grass.grass_ifvp(tr, Wm, out=pre), 3, 1, torch)
         tf = 2.0 * N5 * K5 * K5 / (t / 3 * 1e-3) / 1e12
         extras["ifvp_65536x4096"] = {"ms": round(t / 3, 3), "TFLOPs": round(tf, 2),
-                                     "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4)}
+                                     "frac_of_mfma_peak": round(tf / MFMA_PEAK_F32_TFLOPS, 4),
+                                     "roofline": _roof("mfma", tf, MFMA_PEAK_F32_TFLOPS, "TFLOP/s")}
         del Fm, Wm, wf, wi, pre, tr
         result["extras"] = extras
 

@@ -152,6 +152,19 @@ grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, uint64_t ldg
                              float* out, uint64_t ldo,
                              void* ws, size_t ws_bytes, const grass_tuning* host_tuning, grass_stream stream);
 
+/* Introspection for benchmarks and profiles: writes into host_text (a HOST
+ * buffer of host_text_bytes, 160 are enough) which kernel instantiation and
+ * launch shape grass_sjlt / grass_sjlt_bf16 would use for these arguments, e.g.
+ *   "sjlt_kernel<float,4,1,4,true,3,1> grid=1024x1 block=1024 lds=131072 chunks=1 reduce=0 table=0"
+ * (template arguments: input type, rows per workgroup, positions per load,
+ * loads in flight, fused mask, accumulator, hash mode -- the name a profiler
+ * lists, without spaces).  g may be NULL (its alignment then counts as
+ * unknown); with_workspace says whether the call would be given the workspace
+ * the query reports.  Launches nothing.                                       */
+grass_status grass_sjlt_describe(const void* g, int input_is_bf16, uint64_t n, uint64_t p, uint64_t ldg,
+                                 uint32_t kprime_or_0, uint32_t k, uint32_t s, int with_workspace,
+                                 const grass_tuning* host_tuning, char* host_text, size_t host_text_bytes);
+
 /* grass_sjlt for callers that cannot allocate device memory or hand over a
  * workspace: code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc.  Same operation, arguments and results as grass_sjlt (fp32

@@ -50,6 +50,7 @@ SIGNATURES = {
     "grass_sjlt": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun, _vp]),
     "grass_sjlt_bf16": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp, _sz, _tun,
                                _vp]),
+    "grass_sjlt_describe": (_int, [_vp, _int, _u64, _u64, _u64, _u32, _u32, _u32, _int, _tun, ctypes.c_char_p, _sz]),
     "grass_sjlt_noalloc": (_int, [_vp, _u64, _u64, _u64, _vp, _u32, _u32, _u32, _u64, _u64, _vp, _u64, _vp]),
     "factgrass_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, _u32, _u32, _tun, ctypes.POINTER(_sz)]),
     "factgrass_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _u32, _u32, _u64, _u64,
@@ -238,6 +239,15 @@ def grass_sjlt_bf16(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int =
                                           _tuning(tuning), _stream()),
            "grass_sjlt_bf16")
     return out
+
+
+def grass_sjlt_describe(n: int, p: int, ldg: int, kprime_or_0: int, k: int, s: int, g: torch.Tensor | None = None,
+                        bf16: bool = False, with_workspace: bool = True, tuning=None) -> str:
+    """Kernel instantiation and launch shape grass_sjlt would use (host only, launches nothing)."""
+    buf = ctypes.create_string_buffer(256)
+    _check(load_library().grass_sjlt_describe(_ptr(g), int(bf16), n, p, ldg, kprime_or_0, k, s, int(with_workspace),
+                                              _tuning(tuning), buf, 256), "grass_sjlt_describe")
+    return buf.value.decode()
 
 
 def grass_sjlt_noalloc(g: torch.Tensor, k: int, s: int, seed: int, stream_id: int, out: torch.Tensor,

@@ -30,6 +30,7 @@
 //            order-insensitive to well below fp32 resolution, half as many rows
 //            fit in LDS);
 //   ACC_CAS: fp32 accumulators updated with a compare-and-swap loop.
+#include <cstdio>
 #include <mutex>
 
 #include "grass_device.h"
@@ -543,6 +544,35 @@ extern "C" grass_status grass_sjlt_bf16(const void* g, uint64_t n, uint64_t p, u
                                         float* out, uint64_t ldo, void* ws, size_t ws_bytes,
                                         const grass_tuning* host_tuning, grass_stream stream) {
     return run_sjlt(g, 2, n, p, ldg, idx, kprime, k, s, seed, stream_id, out, ldo, ws, ws_bytes, host_tuning, stream);
+}
+
+// Which instantiation a plan launches, spelled the way a profiler lists it (without spaces): the template arguments
+// are <input type, rows per workgroup, positions per load, loads in flight, fused mask, accumulator, hash mode>.
+extern "C" grass_status grass_sjlt_describe(const void* g, int input_is_bf16, uint64_t n, uint64_t p, uint64_t ldg,
+                                            uint32_t kprime_or_0, uint32_t k, uint32_t s, int with_workspace,
+                                            const grass_tuning* host_tuning, char* host_text, size_t host_text_bytes) {
+    if (!host_text || host_text_bytes == 0) return GRASS_EINVAL;
+    const bool masked = kprime_or_0 != 0;
+    grass_status st = check_sjlt_dims(n, p, masked, kprime_or_0, k, s);
+    if (st != GRASS_OK) return st;
+    if (n == 0 || ldg < p) return GRASS_EINVAL;
+    const uint32_t in_bytes = input_is_bf16 ? 2 : 4;
+    SjltPlan pl;
+    if (!plan_sjlt(n, masked ? kprime_or_0 : p, masked, k, g, ldg, &pl, 0, in_bytes, s, host_tuning)) return GRASS_EUNSUPPORTED;
+    const uint32_t m = k / s;
+    int mode = (s == 1 && m >= 2 && (m & (m - 1)) == 0) ? MODE_FAST : MODE_GENERAL;
+    if (pl.table && with_workspace) mode = MODE_TABLE;
+    const int vmax = 16 / (int)in_bytes;
+    const int V = masked ? 1 : pl.V;
+    const int U = (!masked && V == vmax) ? (pl.R >= 8 ? 1 : 2) : (pl.R >= 8 ? 2 : 4);
+    const int acc = mode == MODE_TABLE ? ACC_F64 : pl.acc;
+    const unsigned long long groups = ceil_div(n, (uint64_t)pl.row_period * pl.R) * pl.row_period;
+    const int len = snprintf(host_text, host_text_bytes,
+                             "sjlt_kernel<%s,%d,%d,%d,%s,%d,%d> grid=%llux%u block=%d lds=%zu chunks=%u reduce=%d table=%d",
+                             input_is_bf16 ? "unsignedshort" : "float", pl.R, V, U, masked ? "true" : "false", acc, mode,
+                             groups, pl.chunks, pl.threads, pl.lds_bytes, pl.chunks, pl.chunks > 1 ? 1 : 0,
+                             mode == MODE_TABLE ? 1 : 0);
+    return (len < 0 || (size_t)len >= host_text_bytes) ? GRASS_EINVAL : GRASS_OK;
 }
 
 // Device address of `scratch` on the current device, looked up once per device.
