@@ -72,8 +72,8 @@ template <int TA, int TB, bool F64>
 __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
     using bucket_t = typename std::conditional<F64, double, float>::type;
     extern __shared__ __align__(16) unsigned char smem[];
-    uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                 // [TA*32][kTokStride]
-    uint16_t* gs = xs + TA * 32 * kTokStride;                          // [TB*32][kTokStride]
+    uint16_t* xs = reinterpret_cast<uint16_t*>(smem);                 // two stages of [TA*32][kTokStride] ...
+    uint16_t* gs = xs + TA * 32 * kTokStride;                          // ... followed by [TB*32][kTokStride]
     bucket_t* sk = reinterpret_cast<bucket_t*>(smem);                  // [k], reuses the staging area afterwards
 
     constexpr int KA = TA * 32, KB = TB * 32;
@@ -100,30 +100,49 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
 
-    // The gather of a token tile is pure latency (every 2-byte pick is its own 128-byte line), so the loads of
-    // tile t+1 are issued before the matrix products of tile t.
-    uint16_t xv[kTokTile / XSTEP], gv[kTokTile / GSTEP];
-    auto gather = [&](uint64_t t0) {
+    // The gather of a token tile is pure latency (every 2-byte pick is its own 128-byte line, read once: non-temporal
+    // loads), so two tiles are kept in flight in two register sets behind the tile being multiplied, and the LDS
+    // staging area is double-buffered: one barrier per tile (the barrier of tile t+1 also tells that every wavefront
+    // has finished reading the stage that tile t+2 will overwrite).
+    constexpr int NX = kTokTile / XSTEP, NG = kTokTile / GSTEP;
+    constexpr int kStageElems = (KA + KB) * kTokStride;
+    // Every load is issued unconditionally from an address clamped into the chunk (padding columns read column 0,
+    // tokens past the end read the last token) and the value is zeroed when it is stored to LDS: a load under a
+    // branch would make the compiler wait for it on the spot, one round trip to HBM per load.
+    // The layer descriptor comes out of memory, so the compiler cannot see that its pointers are global: say so
+    // (generic-address loads count against both the memory and the LDS counters and force a full wait each time).
+    typedef const __attribute__((address_space(1))) uint16_t* gptr_t;
+    const gptr_t xbase = (gptr_t)(xrow + t_begin * L.d_in + (xcol >= 0 ? xcol : 0));
+    const gptr_t gbase = (gptr_t)(grow + t_begin * L.d_out + (gcol >= 0 ? gcol : 0));
+    const uint32_t nt = (uint32_t)(t_end - t_begin);      // tokens of this chunk (at most tokens_per_block), > 0
+    const uint32_t xkeep = xcol >= 0 ? 0xFFFFu : 0u, gkeep = gcol >= 0 ? 0xFFFFu : 0u;
+    uint32_t xv0[NX], gv0[NG], xv1[NX], gv1[NG];
+    // r0: first token of the tile, relative to the chunk
+    auto gather = [&](uint32_t (&xv)[NX], uint32_t (&gv)[NG], uint32_t r0) {
 #pragma unroll
-        for (int i = 0; i < kTokTile / XSTEP; ++i) {
-            const uint64_t t = t0 + xt0 + i * XSTEP;
-            xv[i] = (xcol >= 0 && t < t_end) ? xrow[t * L.d_in + xcol] : (uint16_t)0;
+        for (int i = 0; i < NX; ++i) {
+            const uint32_t r = r0 + xt0 + i * XSTEP;
+            xv[i] = __builtin_nontemporal_load(xbase + (uint64_t)(r < nt ? r : nt - 1) * L.d_in);
         }
 #pragma unroll
-        for (int i = 0; i < kTokTile / GSTEP; ++i) {
-            const uint64_t t = t0 + gt0 + i * GSTEP;
-            gv[i] = (gcol >= 0 && t < t_end) ? grow[t * L.d_out + gcol] : (uint16_t)0;
+        for (int i = 0; i < NG; ++i) {
+            const uint32_t r = r0 + gt0 + i * GSTEP;
+            gv[i] = __builtin_nontemporal_load(gbase + (uint64_t)(r < nt ? r : nt - 1) * L.d_out);
         }
     };
-    if (t_begin < t_end) gather(t_begin);
-    for (uint64_t t0 = t_begin; t0 < t_end; t0 += kTokTile) {
-        __syncthreads();   // previous tile's MFMA reads are done
+    auto stash = [&](const uint32_t (&xv)[NX], const uint32_t (&gv)[NG], int stage, uint32_t r0) {
+        uint16_t* xs_ = xs + stage * kStageElems;
+        uint16_t* gs_ = gs + stage * kStageElems;
 #pragma unroll
-        for (int i = 0; i < kTokTile / XSTEP; ++i) xs[xa * kTokStride + xt0 + i * XSTEP] = xv[i];
+        for (int i = 0; i < NX; ++i)
+            xs_[xa * kTokStride + xt0 + i * XSTEP] = (uint16_t)(xv[i] & xkeep & (r0 + xt0 + i * XSTEP < nt ? 0xFFFFu : 0u));
 #pragma unroll
-        for (int i = 0; i < kTokTile / GSTEP; ++i) gs[gb * kTokStride + gt0 + i * GSTEP] = gv[i];
-        __syncthreads();
-        if (t0 + kTokTile < t_end) gather(t0 + kTokTile);
+        for (int i = 0; i < NG; ++i)
+            gs_[gb * kTokStride + gt0 + i * GSTEP] = (uint16_t)(gv[i] & gkeep & (r0 + gt0 + i * GSTEP < nt ? 0xFFFFu : 0u));
+    };
+    auto multiply = [&](int stage) {
+        const uint16_t* xs_ = xs + stage * kStageElems;
+        const uint16_t* gs_ = gs + stage * kStageElems;
 #pragma unroll
         for (int i = 0; i < TPW; ++i) {
             const int tile = wave + 4 * i;
@@ -132,13 +151,44 @@ __global__ void __launch_bounds__(kFgThreads) factgrass_kernel(FgArgs a) {
 #pragma unroll
                 for (int ks = 0; ks < kTokTile / 16; ++ks) {
                     const bf16x8 af = *reinterpret_cast<const bf16x8*>(
-                        xs + (ta * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
+                        xs_ + (ta * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
                     const bf16x8 bf = *reinterpret_cast<const bf16x8*>(
-                        gs + (tb * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
+                        gs_ + (tb * 32 + (lane & 31)) * kTokStride + ks * 16 + (lane >> 5) * 8);
                     acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af, bf, acc[i], 0, 0, 0);
                 }
             }
         }
+    };
+    gather(xv0, gv0, 0);
+    uint32_t r0 = 0;
+    if (nt > 3 * kTokTile) {
+        // Steady state: both lookahead gathers exist on every path into and around this loop, so the compiler can
+        // count how many newer loads may stay in flight when a register set is stored (a gather under a condition on
+        // the way in would make it wait for all of them).
+        gather(xv1, gv1, kTokTile);
+        for (; r0 + 3 * kTokTile < nt; r0 += 2 * kTokTile) {
+            stash(xv0, gv0, 0, r0);                       // waits for the older set only: loads return in order
+            __syncthreads();
+            gather(xv0, gv0, r0 + 2 * kTokTile);
+            multiply(0);
+            stash(xv1, gv1, 1, r0 + kTokTile);
+            __syncthreads();
+            gather(xv1, gv1, r0 + 3 * kTokTile);
+            multiply(1);
+        }
+    } else if (kTokTile < nt) {
+        gather(xv1, gv1, kTokTile);                       // the branches around whole tiles are uniform
+    }
+    for (; r0 < nt; r0 += 2 * kTokTile) {                 // the last tiles, with the bounds checks
+        stash(xv0, gv0, 0, r0);
+        __syncthreads();
+        if (r0 + 2 * kTokTile < nt) gather(xv0, gv0, r0 + 2 * kTokTile);
+        multiply(0);
+        if (r0 + kTokTile >= nt) break;
+        stash(xv1, gv1, 1, r0 + kTokTile);
+        __syncthreads();
+        if (r0 + 3 * kTokTile < nt) gather(xv1, gv1, r0 + 3 * kTokTile);
+        multiply(1);
     }
     __syncthreads();
     for (uint32_t b = tid; b < a.k; b += kFgThreads) sk[b] = (bucket_t)0;
@@ -202,7 +252,15 @@ __global__ void __launch_bounds__(256) fg_reduce_kernel(FgArgs a) {
     const uint32_t b = (uint32_t)(t - i * a.k);
     const float* p = a.partial + (uint64_t)blockIdx.y * a.chunks * total + t;
     float sum = 0.0f;
-    for (uint32_t c = 0; c < a.chunks; ++c) sum += p[(uint64_t)c * total];
+    uint32_t c = 0;
+    for (; c + 8 <= a.chunks; c += 8) {                   // eight loads in flight, added in chunk order
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = __builtin_nontemporal_load(p + (uint64_t)(c + q) * total);
+#pragma unroll
+        for (int q = 0; q < 8; ++q) sum += v[q];
+    }
+    for (; c < a.chunks; ++c) sum += p[(uint64_t)c * total];
     L.out[i * a.ldo + b] = sum * a.scale;
 }
 
@@ -237,7 +295,7 @@ static bool plan_fg(uint64_t n_layers, uint64_t n, uint64_t T, uint32_t ka, uint
     if (chunks > 65535) { chunks = 65535; tpb = ceil_div(ceil_div(T, chunks), kTokTile) * kTokTile; chunks = ceil_div(T, tpb); }
     pl->tokens_per_block = (uint32_t)tpb;
     pl->chunks = (uint32_t)chunks;
-    const size_t stage = (size_t)(pl->TA + pl->TB) * 32 * kTokStride * sizeof(uint16_t);
+    const size_t stage = (size_t)2 * (pl->TA + pl->TB) * 32 * kTokStride * sizeof(uint16_t);   // double-buffered
     pl->f64 = (size_t)k * sizeof(double) <= 64 * 1024;      // keeps at least two workgroups per CU
     const size_t buckets = (size_t)k * (pl->f64 ? sizeof(double) : sizeof(float));
     pl->lds_bytes = stage > buckets ? stage : buckets;

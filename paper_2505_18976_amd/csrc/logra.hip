@@ -53,6 +53,14 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
     const uint16_t* gs = a.g + sample * a.T * a.d_out;
     const uint32_t dmax = a.d_in > a.d_out ? a.d_in : a.d_out;
     const uint32_t nslices = (dmax + LK - 1) / LK;
+    // Workgroups walk through the K slices in rotated order (workgroup w starts at slice 5w mod nslices): all of them
+    // run in lockstep otherwise and would ask the same few L2 channels for the same slice of P_in / P_out at the same
+    // time.  The contraction is a sum over all slices either way.
+    const uint32_t rot = (uint32_t)((blockIdx.x + (uint64_t)blockIdx.y * gridDim.x) * 5 % nslices);
+    auto K0 = [&](uint32_t i) {                         // i < nslices
+        const uint32_t q = i + rot;
+        return (q >= nslices ? q - nslices : q) * (uint32_t)LK;
+    };
 
     // staging map: chunk c = tid + 256*i (i = 0..3) of a 64 x 128 tile: row c/16, 16-byte chunk c%16
     constexpr int CPR = LK / 8;                         // 16-byte chunks per row
@@ -67,29 +75,41 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
 
     struct RegSet { u32x4 rx[NI], rg[NI], rpi[NI], rpo[NI]; };
     for (uint64_t t0 = t_begin; t0 < t_end; t0 += LT) {
+        // Loads are issued unconditionally from addresses clamped into the tensors (rows past the end re-read the last
+        // valid row, columns past d re-read the last 16-byte chunk) and the out-of-range parts are zeroed when the
+        // registers are stored to LDS: a load under a branch makes the compiler wait for every outstanding load.
+        const uint32_t din8 = a.d_in - 8, dout8 = a.d_out - 8;          // d_in, d_out are multiples of 8, >= 8
+        const uint64_t trow_last = t_end - 1;
         auto fetch = [&](RegSet& r, uint32_t k0) {
-            const uint32_t kk = k0 + skc * 8;           // d_in, d_out are multiples of 8: a chunk is all in or all out
+            const uint32_t kk = k0 + skc * 8;           // a 16-byte chunk is all in or all out
+            const uint32_t kx = kk < a.d_in ? kk : din8, kg = kk < a.d_out ? kk : dout8;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
-                const int row = srow + RSTEP * i;
-                const uint64_t t = t0 + row;
-                r.rx[i] = (t < t_end && kk < a.d_in) ? *reinterpret_cast<const u32x4*>(xs + t * a.d_in + kk) : u32x4(0u);
-                r.rg[i] = (t < t_end && kk < a.d_out) ? *reinterpret_cast<const u32x4*>(gs + t * a.d_out + kk) : u32x4(0u);
-                r.rpi[i] = ((uint32_t)row < a.k_in && kk < a.d_in)
-                               ? *reinterpret_cast<const u32x4*>(a.pin + (uint64_t)row * a.d_in + kk) : u32x4(0u);
-                r.rpo[i] = ((uint32_t)row < a.k_out && kk < a.d_out)
-                               ? *reinterpret_cast<const u32x4*>(a.pout + (uint64_t)row * a.d_out + kk) : u32x4(0u);
+                const uint32_t row = srow + RSTEP * i;
+                const uint64_t t = t0 + row < trow_last ? t0 + row : trow_last;
+                // x and g are read exactly once (non-temporal: they must not push the projection matrices, which
+                // every workgroup re-reads, out of L2)
+                r.rx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xs + t * a.d_in + kx));
+                r.rg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gs + t * a.d_out + kg));
+                r.rpi[i] = *reinterpret_cast<const u32x4*>(a.pin + (uint64_t)(row < a.k_in ? row : a.k_in - 1) * a.d_in + kx);
+                r.rpo[i] = *reinterpret_cast<const u32x4*>(a.pout + (uint64_t)(row < a.k_out ? row : a.k_out - 1) * a.d_out + kg);
             }
         };
-        auto stash = [&](const RegSet& r, int stage) {
+        auto stash = [&](const RegSet& r, int stage, uint32_t k0) {
             uint16_t* base = lds + stage * kLograStage;
+            const uint32_t kk = k0 + skc * 8;
+            const uint32_t mx = kk < a.d_in ? ~0u : 0u, mg = kk < a.d_out ? ~0u : 0u;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
-                const int off = (srow + RSTEP * i) * LRS + skc * 8;
-                *reinterpret_cast<u32x4*>(base + off) = r.rx[i];
-                *reinterpret_cast<u32x4*>(base + kTileElems + off) = r.rg[i];
-                *reinterpret_cast<u32x4*>(base + 2 * kTileElems + off) = r.rpi[i];
-                *reinterpret_cast<u32x4*>(base + 3 * kTileElems + off) = r.rpo[i];
+                const uint32_t row = srow + RSTEP * i;
+                const int off = row * LRS + skc * 8;
+                const uint32_t mt = t0 + row < t_end ? ~0u : 0u;
+                const uint32_t mxi = mx & mt, mgi = mg & mt;
+                const uint32_t mpi = mx & (row < a.k_in ? ~0u : 0u), mpo = mg & (row < a.k_out ? ~0u : 0u);
+                *reinterpret_cast<u32x4*>(base + off) = r.rx[i] & u32x4(mxi);
+                *reinterpret_cast<u32x4*>(base + kTileElems + off) = r.rg[i] & u32x4(mgi);
+                *reinterpret_cast<u32x4*>(base + 2 * kTileElems + off) = r.rpi[i] & u32x4(mpi);
+                *reinterpret_cast<u32x4*>(base + 3 * kTileElems + off) = r.rpo[i] & u32x4(mpo);
             }
         };
 
@@ -102,7 +122,7 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
             // operand tiles of this wavefront: tokens (X or G) and projection rows (P_in or P_out)
             const uint16_t* tok = lds + cur * kLograStage + wg * kTileElems + (wh * 32 + (lane & 31)) * LRS + (lane >> 5) * 8;
             const uint16_t* prj = lds + cur * kLograStage + (2 + wg) * kTileElems + (lane & 31) * LRS + (lane >> 5) * 8;
-            const bool live = sl * LK < (wg == 0 ? a.d_in : a.d_out);      // uniform per wavefront
+            const bool live = K0(sl) < (wg == 0 ? a.d_in : a.d_out);       // uniform per wavefront
             if (live) {
 #pragma unroll
                 for (int ks = 0; ks < LK / 16; ++ks) {
@@ -120,20 +140,41 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
         // the even ones); loads complete in order, so storing slice s+1 to LDS waits for that slice only.
         RegSet A, B;
         __syncthreads();                                // stage-2 reads of the previous token tile are done
-        fetch(A, 0);
-        stash(A, 0);
-        if (nslices > 1) fetch(B, LK);
-        if (nslices > 2) fetch(A, 2 * LK);
-        __syncthreads();
-        for (uint32_t sl = 0; sl < nslices; sl += 2) {
-            multiply(0, sl);                            // stage 0: slice sl
-            if (sl + 1 < nslices) stash(B, 1);
-            if (sl + 3 < nslices) fetch(B, (sl + 3) * LK);
+        fetch(A, K0(0));
+        stash(A, 0, K0(0));
+        uint32_t sl = 0;
+        if (nslices > 4) {
+            // Steady state (both prefetches exist on every path into and around the loop): the same straight-line
+            // code every iteration, so the compiler can count how many newer loads may stay in flight when a register
+            // set is stored to LDS (a prefetch under a condition anywhere on the way in would make it wait for all).
+            fetch(B, K0(1));
+            fetch(A, K0(2));
+            __syncthreads();
+            for (; sl + 4 < nslices; sl += 2) {
+                multiply(0, sl);                            // stage 0: slice sl
+                stash(B, 1, K0(sl + 1));
+                fetch(B, K0(sl + 3));
+                __syncthreads();
+                multiply(1, sl + 1);                        // stage 1: slice sl + 1
+                stash(A, 0, K0(sl + 2));
+                fetch(A, K0(sl + 4));
+                __syncthreads();
+            }
+        } else {
+            if (nslices > 1) fetch(B, K0(1));                  // branches around whole slices are uniform
+            if (nslices > 2) fetch(A, K0(2));
+            __syncthreads();
+        }
+        // the last slices, with the bounds checks
+        for (; sl < nslices; sl += 2) {
+            multiply(0, sl);
+            if (sl + 1 < nslices) stash(B, 1, K0(sl + 1));
+            if (sl + 3 < nslices) fetch(B, K0(sl + 3));
             __syncthreads();
             if (sl + 1 >= nslices) break;
-            multiply(1, sl + 1);                        // stage 1: slice sl + 1
-            if (sl + 2 < nslices) stash(A, 0);
-            if (sl + 4 < nslices) fetch(A, (sl + 4) * LK);
+            multiply(1, sl + 1);
+            if (sl + 2 < nslices) stash(A, 0, K0(sl + 2));
+            if (sl + 4 < nslices) fetch(A, K0(sl + 4));
             __syncthreads();
         }
 
