@@ -528,23 +528,32 @@ bool launch_gemm_dma_kmajor(bool a_kn, const float* A, const float* B, float* C,
 }
 
 // fp32 -> bf16, round to nearest even; 4 elements per thread.  Columns cols..cols_pad of dst are zero-filled.
+// VEC: rows and bases are 16-byte (src) and 8-byte (dst) aligned, so a thread moves one 16-byte load and one 8-byte
+// store (non-temporal: the source is read once).
+__device__ __forceinline__ uint16_t bf16_rne_bits(uint32_t u) {
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+template <bool VEC>
 __global__ void __launch_bounds__(256) to_bf16_kernel(const float* src, uint64_t rows, uint64_t cols, uint64_t cols_pad,
                                                       uint64_t ld_src, uint16_t* dst, uint64_t ld_dst) {
     const uint64_t quads = (cols_pad + 3) / 4;
     const uint64_t t = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (t >= rows * quads) return;
     const uint64_t r = t / quads, c0 = (t - r * quads) * 4;
+    if (VEC && c0 + 4 <= cols) {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + r * ld_src + c0));
+        u32x2 o;
+        o[0] = (uint32_t)bf16_rne_bits(v[0]) | ((uint32_t)bf16_rne_bits(v[1]) << 16);
+        o[1] = (uint32_t)bf16_rne_bits(v[2]) | ((uint32_t)bf16_rne_bits(v[3]) << 16);
+        *reinterpret_cast<u32x2*>(dst + r * ld_dst + c0) = o;
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-        if (c0 + j < cols) {
-            uint32_t u = __float_as_uint(src[r * ld_src + c0 + j]);
-            uint16_t h;
-            if ((u & 0x7FFFFFFFu) > 0x7F800000u) h = (uint16_t)((u >> 16) | 0x40u);
-            else { u += 0x7FFFu + ((u >> 16) & 1u); h = (uint16_t)(u >> 16); }
-            dst[r * ld_dst + c0 + j] = h;
-        } else if (c0 + j < cols_pad) {
-            dst[r * ld_dst + c0 + j] = 0;
-        }
+        if (c0 + j < cols) dst[r * ld_dst + c0 + j] = bf16_rne_bits(__float_as_uint(src[r * ld_src + c0 + j]));
+        else if (c0 + j < cols_pad) dst[r * ld_dst + c0 + j] = 0;
     }
 }
 
@@ -554,8 +563,13 @@ hipError_t convert_to_bf16(const float* src, uint64_t rows, uint64_t cols, uint6
     const uint64_t total = rows * ((cols_pad + 3) / 4);
     if (total == 0) return hipSuccess;
     if (ceil_div(total, 256) > 0x7FFFFFFFull) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(to_bf16_kernel, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, st, src, rows, cols, cols_pad,
-                       ld_src, dst, ld_dst);
+    const bool vec = aligned(src, 16) && ld_src % 4 == 0 && aligned(dst, 8) && ld_dst % 4 == 0;
+    if (vec)
+        hipLaunchKernelGGL(to_bf16_kernel<true>, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, st, src, rows, cols,
+                           cols_pad, ld_src, dst, ld_dst);
+    else
+        hipLaunchKernelGGL(to_bf16_kernel<false>, dim3((uint32_t)ceil_div(total, 256)), dim3(256), 0, st, src, rows, cols,
+                           cols_pad, ld_src, dst, ld_dst);
     return hipGetLastError();
 }
 

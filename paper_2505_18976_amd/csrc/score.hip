@@ -297,7 +297,8 @@ __global__ void __launch_bounds__(256) gauss_matrix_kernel(uint64_t sub, uint64_
             const uint64_t h = sm(sub, (uint64_t)row * p + p0 + col);
             const float u1 = ((float)(uint32_t)(h >> 41) + 0.5f) * (1.0f / 8388608.0f);           // (0, 1), exact
             const float u2 = (float)(uint32_t)((h >> 16) & 0xFFFFFFu) * (1.0f / 16777216.0f);      // [0, 1)
-            v = sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2) * inv_sqrt_k;
+            // hardware transcendentals: v_log_f32 is log2, v_cos_f32 takes its argument in revolutions (cos(2 pi u2))
+            v = __builtin_amdgcn_sqrtf(-1.3862943611198906f * __builtin_amdgcn_logf(u1)) * __builtin_amdgcn_cosf(u2) * inv_sqrt_k;
         }
         if constexpr (BF16) static_cast<uint16_t*>(Pv)[(uint64_t)row * ldP + col] = f32_to_bf16_rne(v);
         else static_cast<float*>(Pv)[(uint64_t)row * ldP + col] = v;
