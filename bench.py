@@ -94,6 +94,68 @@ def _roof(bound, achieved, peak, unit, **more):
     return d
 
 
+def bench_single_layer(grass, synth, torch, dev, seed, extras):
+    """FactGraSS, the LoGra baseline and the other factorised compressors on one 4096 x 4096 linear layer
+    (n = 32 sequences of 512 tokens, masks 64/64, k = 1,024), inputs rotated through five tensor pairs."""
+    # FactGraSS on one 4096 x 4096 linear layer.  Five (x, g) pairs of 268 MB each are rotated so that no call
+    # finds its inputs in the 256 MB last-level cache (the resident figure is reported next to it)
+    n4, T4, d4, kf, k4, NPAIR = 32, 512, 4096, 64, 1024, 5
+    pairs = [synth.linear_layer_factors(n4, T4, d4, d4, seed=1004 + 50 * q, device=dev) for q in range(NPAIR)]
+    x4, go4 = pairs[0]
+    ii = grass.grass_mask_indices(seed, 16, d4, kf, device=dev)
+    io = grass.grass_mask_indices(seed, 17, d4, kf, device=dev)
+    o4 = torch.empty((n4, k4), dtype=torch.float32, device=dev)
+    w4 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n4, T4, kf, kf, k4, 1), 1), dtype=torch.uint8,
+                     device=dev)
+    # 128-byte lines a token touches in x and in g (rows of 8,192 bytes start on a line), the floor for a gather
+    ii_h, io_h = ii.cpu().numpy(), io.cpu().numpy()
+    lines4 = _touched_lines(ii_h, 2, d4 * 2, 0, 1) + _touched_lines(io_h, 2, d4 * 2, 0, 1)
+    line_bytes4 = n4 * T4 * lines4 * 128 + n4 * k4 * 4 + 2 * w4.numel()
+    t, _, _ = _timed(lambda: grass.factgrass_linear(x4, go4, ii, io, k4, 1, seed, 18, out=o4, ws=w4), 20, 3, torch)
+    resident_ms = t / 20
+    t, _, _ = _timed(lambda c: grass.factgrass_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, k4, 1, seed, 18,
+                                                      out=o4, ws=w4), 40, NPAIR, torch, indexed=True)
+    fg_ms = t / 40
+    extras["factgrass_linear_4096"] = {"ms": round(fg_ms, 4), "ms_inputs_resident": round(resident_ms, 4),
+                                       "rotating_input_pairs": NPAIR,
+                                       "samples_per_s": round(n4 / (fg_ms * 1e-3), 1),
+                                       "tokens_per_s": round(n4 * T4 / (fg_ms * 1e-3), 1),
+                                       "useful_GBps": round(2 * n4 * T4 * 2 * kf / (fg_ms * 1e-3) / 1e9, 2),
+                                       "lines_per_token": int(lines4),
+                                       "roofline": _roof("hbm", line_bytes4 / (fg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                                                         traffic_model_bytes=int(line_bytes4),
+                                                         note="touched 128-byte lines of the gathered columns (counted "
+                                                              "from the indices) + partial sums + output")}
+    # LoGra baseline (dense factorised projection to 64 x 64) on the same layer, for the speed ratio
+    Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 40, d4, kf, 0, d4, device=dev))
+    Po = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 41, d4, kf, 0, d4, device=dev))
+    ol = torch.empty((n4, kf * kf), dtype=torch.float32, device=dev)
+    wl = torch.empty(max(grass.logra_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
+    tl, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Pi, Po, out=ol, ws=wl),
+                      40, NPAIR, torch, indexed=True)
+    lg_ms = tl / 40
+    lg_bytes = 2 * n4 * T4 * d4 * 2 + n4 * kf * kf * 4 + 2 * wl.numel()
+    extras["logra_linear_4096"] = {"ms": round(lg_ms, 4), "tokens_per_s": round(n4 * T4 / (lg_ms * 1e-3), 1),
+                                   "rotating_input_pairs": NPAIR,
+                                   "factgrass_speedup": round(lg_ms / fg_ms, 2),
+                                   "roofline": _roof("hbm", lg_bytes / (lg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
+                                                     algorithmic_bytes=int(lg_bytes),
+                                                     note="every column of x and g is read once")}
+    # the other factorised compressors of the paper's Table 2 on the same layer (64 x 64 -> 4,096 outputs)
+    wm = torch.empty(max(grass.factmask_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
+    tm, _, _ = _timed(lambda c: grass.factmask_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, out=ol, ws=wm),
+                      40, NPAIR, torch, indexed=True)
+    Si = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 40, d4, kf, 1, device=dev))
+    So = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 41, d4, kf, 1, device=dev))
+    ts, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Si, So, out=ol, ws=wl),
+                      40, NPAIR, torch, indexed=True)
+    extras["table2_style_4096_layer_ms"] = {"mask_kin_x_kout": round(tm / 40, 4), "sjlt_kin_x_kout": round(ts / 40, 4),
+                                            "factgrass": round(fg_ms, 4), "logra_gauss_kin_x_kout": round(lg_ms, 4),
+                                            "rotating_input_pairs": NPAIR}
+    del pairs, x4, go4, o4, w4, Pi, Po, ol, wl, wm, Si, So
+    torch.cuda.empty_cache()
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +168,12 @@ def main() -> int:
                          "input sparsity levels (the setting of the paper's SJLT benchmark figure); prints one JSON object")
     ap.add_argument("--full-score", action="store_true",
                     help="run only the attribute-stage GEMM over all 112 concatenated layer blocks (K = 458,752, bf16)")
+    ap.add_argument("--single-layer-only", action="store_true",
+                    help="run only the 4096 x 4096 linear-layer paths (FactGraSS, LoGra, factorised baselines) on rotating "
+                         "inputs; for counter runs of these kernels alone")
+    ap.add_argument("--accumulators", action="store_true",
+                    help="ResNet-scale and MLP-scale SJLT with the two LDS accumulator policies (fp64 atomic add, fp32 "
+                         "compare-and-swap) forced through the per-call tuning argument")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -133,6 +201,39 @@ def main() -> int:
         t, _, _ = _timed(lambda: b.copy_(a), 5, 2, torch)
         print(json.dumps({"copy_reference_bytes_read": nbytes, "copy_reference_bytes_written": nbytes,
                           "ms": round(t / 5, 4), "GBps_read_plus_write": round(2 * nbytes / (t / 5 * 1e-3) / 1e9, 1)}))
+        return 0
+
+    if args.single_layer_only:
+        extras = {}
+        bench_single_layer(grass, synth, torch, dev, 0, extras)
+        print(json.dumps({"workload": "single_linear_layer_4096", "extras": extras}))
+        return 0
+
+    if args.accumulators:
+        out_rows = []
+        n3, p3, k3 = 1024, 11173962, 8192
+        g3 = synth.laplace_sparse(n3, p3, 0.3, 1e-3, seed=1003, device=dev)
+        o3 = torch.empty((n3, k3), dtype=torch.float32, device=dev)
+        for acc, name in ((3, "fp64 LDS atomic add"), (2, "fp32 compare-and-swap")):
+            tun = dict(sjlt_accumulator=acc)
+            w3 = torch.empty(max(grass.grass_sjlt_workspace_bytes(n3, p3, 0, k3, 1, tun), 1), dtype=torch.uint8, device=dev)
+            t, _, _ = _timed(lambda: grass.grass_sjlt(g3, k3, 1, 0, 1, out=o3, ws=w3, tuning=tun), 10, 2, torch)
+            out_rows.append({"workload": "resnet_sjlt_s1", "accumulator": name, "ms": round(t / 10, 4),
+                             "launch": grass.grass_sjlt_describe(n3, p3, g3.stride(0), 0, k3, 1, g=g3, tuning=tun)})
+            del w3
+        del g3, o3
+        torch.cuda.empty_cache()
+        n, p, kp, k = 4096, synth.mlp_num_params(), 65536, 4096
+        g = synth.mlp_relu_gradients(n, seed=1002, device=dev)
+        idx = grass.grass_mask_indices(0, 0, p, kp, device=dev)
+        out = torch.empty((n, k), dtype=torch.float32, device=dev)
+        for acc, name in ((3, "fp64 LDS atomic add"), (2, "fp32 compare-and-swap")):
+            tun = dict(sjlt_accumulator=acc)
+            w = torch.empty(max(grass.grass_sjlt_workspace_bytes(n, p, kp, k, 1, tun), 1), dtype=torch.uint8, device=dev)
+            t, _, _ = _timed(lambda: grass.grass_sjlt(g, k, 1, 0, 1, idx=idx, out=out, ws=w, tuning=tun), 10, 2, torch)
+            out_rows.append({"workload": "mlp_mask_sjlt_s1", "accumulator": name, "ms": round(t / 10, 4),
+                             "launch": grass.grass_sjlt_describe(n, p, g.stride(0), kp, k, 1, g=g, tuning=tun)})
+        print(json.dumps({"accumulator_policy": out_rows}))
         return 0
 
     if args.full_score:
@@ -379,68 +480,12 @@ def main() -> int:
         del g3h, o3, w3
         torch.cuda.empty_cache()
 
-        # FactGraSS on one 4096 x 4096 linear layer.  Five (x, g) pairs of 268 MB each are rotated so that no call
-        # finds its inputs in the 256 MB last-level cache (the resident figure is reported next to it)
-        n4, T4, d4, kf, k4, NPAIR = 32, 512, 4096, 64, 1024, 5
-        pairs = [synth.linear_layer_factors(n4, T4, d4, d4, seed=1004 + 50 * q, device=dev) for q in range(NPAIR)]
-        x4, go4 = pairs[0]
-        ii = grass.grass_mask_indices(seed, 16, d4, kf, device=dev)
-        io = grass.grass_mask_indices(seed, 17, d4, kf, device=dev)
-        o4 = torch.empty((n4, k4), dtype=torch.float32, device=dev)
-        w4 = torch.empty(max(grass.factgrass_linear_workspace_bytes(n4, T4, kf, kf, k4, 1), 1), dtype=torch.uint8,
-                         device=dev)
-        # 128-byte lines a token touches in x and in g (rows of 8,192 bytes start on a line), the floor for a gather
-        ii_h, io_h = ii.cpu().numpy(), io.cpu().numpy()
-        lines4 = _touched_lines(ii_h, 2, d4 * 2, 0, 1) + _touched_lines(io_h, 2, d4 * 2, 0, 1)
-        line_bytes4 = n4 * T4 * lines4 * 128 + n4 * k4 * 4 + 2 * w4.numel()
-        t, _, _ = _timed(lambda: grass.factgrass_linear(x4, go4, ii, io, k4, 1, seed, 18, out=o4, ws=w4), 20, 3, torch)
-        resident_ms = t / 20
-        t, _, _ = _timed(lambda c: grass.factgrass_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, k4, 1, seed, 18,
-                                                          out=o4, ws=w4), 40, NPAIR, torch, indexed=True)
-        fg_ms = t / 40
-        extras["factgrass_linear_4096"] = {"ms": round(fg_ms, 4), "ms_inputs_resident": round(resident_ms, 4),
-                                           "rotating_input_pairs": NPAIR,
-                                           "samples_per_s": round(n4 / (fg_ms * 1e-3), 1),
-                                           "tokens_per_s": round(n4 * T4 / (fg_ms * 1e-3), 1),
-                                           "useful_GBps": round(2 * n4 * T4 * 2 * kf / (fg_ms * 1e-3) / 1e9, 2),
-                                           "lines_per_token": int(lines4),
-                                           "roofline": _roof("hbm", line_bytes4 / (fg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
-                                                             traffic_model_bytes=int(line_bytes4),
-                                                             note="touched 128-byte lines of the gathered columns (counted "
-                                                                  "from the indices) + partial sums + output")}
-        # LoGra baseline (dense factorised projection to 64 x 64) on the same layer, for the speed ratio
-        Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 40, d4, kf, 0, d4, device=dev))
-        Po = grass.grass_to_bf16(grass.grass_gauss_matrix(seed, 41, d4, kf, 0, d4, device=dev))
-        ol = torch.empty((n4, kf * kf), dtype=torch.float32, device=dev)
-        wl = torch.empty(max(grass.logra_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
-        tl, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Pi, Po, out=ol, ws=wl),
-                          40, NPAIR, torch, indexed=True)
-        lg_ms = tl / 40
-        lg_bytes = 2 * n4 * T4 * d4 * 2 + n4 * kf * kf * 4 + 2 * wl.numel()
-        extras["logra_linear_4096"] = {"ms": round(lg_ms, 4), "tokens_per_s": round(n4 * T4 / (lg_ms * 1e-3), 1),
-                                       "rotating_input_pairs": NPAIR,
-                                       "factgrass_speedup": round(lg_ms / fg_ms, 2),
-                                       "roofline": _roof("hbm", lg_bytes / (lg_ms * 1e-3) / 1e9, HBM_PEAK_GBS, "GB/s",
-                                                         algorithmic_bytes=int(lg_bytes),
-                                                         note="every column of x and g is read once")}
-        # the other factorised compressors of the paper's Table 2 on the same layer (64 x 64 -> 4,096 outputs)
-        wm = torch.empty(max(grass.factmask_linear_workspace_bytes(n4, T4, kf, kf), 1), dtype=torch.uint8, device=dev)
-        tm, _, _ = _timed(lambda c: grass.factmask_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], ii, io, out=ol, ws=wm),
-                          40, NPAIR, torch, indexed=True)
-        Si = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 40, d4, kf, 1, device=dev))
-        So = grass.grass_to_bf16(grass.grass_projection_matrix(seed, 41, d4, kf, 1, device=dev))
-        ts, _, _ = _timed(lambda c: grass.logra_linear(pairs[c % NPAIR][0], pairs[c % NPAIR][1], Si, So, out=ol, ws=wl),
-                          40, NPAIR, torch, indexed=True)
-        extras["table2_style_4096_layer_ms"] = {"mask_kin_x_kout": round(tm / 40, 4), "sjlt_kin_x_kout": round(ts / 40, 4),
-                                                "factgrass": round(fg_ms, 4), "logra_gauss_kin_x_kout": round(lg_ms, 4),
-                                                "rotating_input_pairs": NPAIR}
-        del pairs, x4, go4, o4, w4, Pi, Po, ol, wl, wm, Si, So
-        torch.cuda.empty_cache()
+        bench_single_layer(grass, synth, torch, dev, seed, extras)
 
         # FactGraSS over a Llama-style 1.2B model: 16 blocks x 7 linears, n = 8 sequences x 1,024 tokens,
         # every layer with its own activations and gradients (12.3 GB in total, so nothing is served from
         # cache), per-layer masks and SJLT streams, outputs concatenated
-        n5, T5, kl = 8, 1024, 4096
+        n5, T5, kl, kf = 8, 1024, 4096, 64
         layers = []
         for layer in range(16 * 7):
             name, d_in, d_out = synth.LLAMA_BLOCK_LINEARS[layer % 7]
