@@ -238,7 +238,7 @@ grass_status factgrass_layers(const factgrass_layer* host_layers, uint32_t n_lay
  * P_out: k_out x d_out bf16 (all contiguous; e.g. grass_gauss_matrix followed by
  * grass_to_bf16).  out: n x (k_in*k_out) fp32, ldo >= k_in*k_out.  bf16 products
  * are exact in fp32; both contractions accumulate in fp32.
- * k_in, k_out <= 64; d_in, d_out multiples of 8 (GRASS_EUNSUPPORTED otherwise). */
+ * k_in, k_out <= 64; d_in, d_out multiples of 8 and at most 2^24 (GRASS_EUNSUPPORTED otherwise). */
 grass_status logra_linear_workspace_bytes(uint64_t n, uint64_t T, uint32_t k_in, uint32_t k_out,
                                           size_t* host_bytes);
 grass_status logra_linear(const void* x, const void* gout,

@@ -5,14 +5,18 @@
 // supplied by the caller in bf16.  This is the method FactGraSS is compared with;
 // it has to read every column of x and g, where FactGraSS reads k' of them.
 //
-// One workgroup (4 wavefronts) owns one sample and one chunk of its tokens.
+// One workgroup (8 wavefronts) owns one sample and one chunk of its tokens.
 //   Stage 1: a = X_chunk P_in^T and b = G_chunk P_out^T, 64 tokens at a time, bf16
 //            MFMA with fp32 accumulation; K (= d_in, d_out) is streamed in slices
-//            of 128 through two LDS stages with the next two slices prefetched in
-//            registers (128 KB per workgroup in flight: one workgroup per CU has to
-//            cover the HBM latency by itself).
-//            Wavefronts 0,1 compute a (token halves), wavefronts 2,3 compute b.
-//   Stage 2: acc[a][b] += sum_t a_t[a] * b_t[b] on the fp32 matrix cores from LDS.
+//            of 128 through two LDS stages.  Four producer wavefronts load the
+//            slices, 64 columns at a time, into five rotating register sets (four
+//            loads of 32 KB in flight behind the one being stored to LDS: one
+//            workgroup per CU has to cover the HBM latency by itself) and stage
+//            them; four consumer wavefronts multiply the staged slice meanwhile
+//            (consumers 0,1 compute a for the two token halves, 2,3 compute b), so
+//            the matrix and LDS-read work runs under the producers' wait for memory.
+//   Stage 2: acc[a][b] += sum_t a_t[a] * b_t[b] on the fp32 matrix cores from LDS
+//            (consumers).
 // Per-chunk partial k_in x k_out blocks are added in a fixed order by
 // reduce_partials_kernel.
 #include "grass_device.h"
@@ -29,7 +33,7 @@ constexpr int LRS = LK + 8;            // bf16 per LDS row (272 bytes: conflict-
 constexpr int LP = 64;                 // projected width handled (k_in, k_out <= 64, zero padded)
 constexpr int kTileElems = 64 * LRS;   // one 64-row tile
 constexpr int kLograStage = 4 * kTileElems;   // X, G, P_in, P_out
-constexpr int kLograThreads = 256;
+constexpr int kLograThreads = 512;       // 4 producer + 4 consumer wavefronts
 
 struct LograArgs {
     const uint16_t* x;      // (n, T, d_in) bf16
@@ -42,61 +46,91 @@ struct LograArgs {
     uint32_t tokens_per_block;
 };
 
+constexpr int kHalf = 64;               // columns per register set of the producers (half an LDS slice)
+constexpr int kSets = 5;                // rotating register sets: four halves stay in flight behind the one being stored
+
 __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
     extern __shared__ __align__(16) uint16_t lds[];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wg = wave >> 1, wh = wave & 1;          // stage 1: which product, which token half
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);     // uniform: the role branches below are scalar
+    const bool producer = wave < 4;                   // wavefronts 0..3 load and stage, 4..7 multiply
+    const int ptid = tid & 255;                       // thread index inside its role
+    const int cw = wave & 3;                          // consumer wavefront
+    const int wg = cw >> 1, wh = cw & 1;              // stage 1: which product (a or b), which token half
     const uint64_t sample = blockIdx.y;
     const uint64_t t_begin = (uint64_t)blockIdx.x * a.tokens_per_block;
     const uint64_t t_end = t_begin + a.tokens_per_block < a.T ? t_begin + a.tokens_per_block : a.T;
     const uint16_t* xs = a.x + sample * a.T * a.d_in;
     const uint16_t* gs = a.g + sample * a.T * a.d_out;
     const uint32_t dmax = a.d_in > a.d_out ? a.d_in : a.d_out;
-    const uint32_t nslices = (dmax + LK - 1) / LK;
-    // Workgroups walk through the K slices in rotated order (workgroup w starts at slice 5w mod nslices): all of them
+    const uint32_t ngroups = (dmax + LK - 1) / LK;    // LDS slices of 128 columns
+    const uint32_t nhalves = 2 * ngroups;             // register-set loads of 64 columns
+    // Workgroups walk through the K slices in rotated order (workgroup w starts at slice 5w mod ngroups): all of them
     // run in lockstep otherwise and would ask the same few L2 channels for the same slice of P_in / P_out at the same
     // time.  The contraction is a sum over all slices either way.
-    const uint32_t rot = (uint32_t)((blockIdx.x + (uint64_t)blockIdx.y * gridDim.x) * 5 % nslices);
-    auto K0 = [&](uint32_t i) {                         // i < nslices
-        const uint32_t q = i + rot;
-        return (q >= nslices ? q - nslices : q) * (uint32_t)LK;
+    const uint32_t rot = (uint32_t)((blockIdx.x + (uint64_t)blockIdx.y * gridDim.x) * 5 % ngroups);
+    auto KG = [&](uint32_t g) {                         // first column of group g of this workgroup's order; g >= ngroups
+        if (g >= ngroups) return dmax + (uint32_t)LK;   // gives a column past every operand (loads clamp, stores zero)
+        const uint32_t q = g + rot;
+        return (q >= ngroups ? q - ngroups : q) * (uint32_t)LK;
     };
+    auto KH = [&](uint32_t j) { return KG(j >> 1) + (j & 1) * (uint32_t)kHalf; };   // first column of half j
 
-    // staging map: chunk c = tid + 256*i (i = 0..3) of a 64 x 128 tile: row c/16, 16-byte chunk c%16
-    constexpr int CPR = LK / 8;                         // 16-byte chunks per row
-    constexpr int NI = 64 * CPR / kLograThreads;        // chunks per thread and tile
-    constexpr int RSTEP = kLograThreads / CPR;          // rows between a thread's chunks
-    const int srow = tid / CPR, skc = tid % CPR;
+    // staging map of the 256 producer threads for one half (64 rows x 64 columns per tile): chunk c = ptid + 256*i
+    // (i = 0, 1): row c/8, 16-byte chunk c%8
+    constexpr int CPR = kHalf / 8;                      // 16-byte chunks per row of a half
+    constexpr int NI = 64 * CPR / 256;                  // chunks per thread and tile
+    constexpr int RSTEP = 256 / CPR;                    // rows between a thread's chunks
+    const int srow = ptid / CPR, skc = ptid % CPR;
 
     f32x16 acc2;                                        // stage 2: one 32 x 32 tile of the k_in x k_out block
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc2[v] = 0.0f;
-    const int ta = wave >> 1, tb = wave & 1;
+    const int ta = cw >> 1, tb = cw & 1;
 
     struct RegSet { u32x4 rx[NI], rg[NI], rpi[NI], rpo[NI]; };
     for (uint64_t t0 = t_begin; t0 < t_end; t0 += LT) {
         // Loads are issued unconditionally from addresses clamped into the tensors (rows past the end re-read the last
         // valid row, columns past d re-read the last 16-byte chunk) and the out-of-range parts are zeroed when the
         // registers are stored to LDS: a load under a branch makes the compiler wait for every outstanding load.
+        // Addresses are a uniform 64-bit base (tile of tokens, or the projection matrix) plus a 32-bit byte offset
+        // per lane (the host refuses d > 2^24, so 64 rows of 2-byte elements stay below 2^32): the per-lane part of
+        // an address then costs one register instead of two per outstanding load.
         const uint32_t din8 = a.d_in - 8, dout8 = a.d_out - 8;          // d_in, d_out are multiples of 8, >= 8
-        const uint64_t trow_last = t_end - 1;
+        const uint32_t rows_left = (uint32_t)(t_end - t0 < LT ? t_end - t0 : LT);
+        const char* xb = reinterpret_cast<const char*>(xs + t0 * a.d_in);
+        const char* gb = reinterpret_cast<const char*>(gs + t0 * a.d_out);
+        const char* pib = reinterpret_cast<const char*>(a.pin);
+        const char* pob = reinterpret_cast<const char*>(a.pout);
+        uint32_t ox[NI], og[NI], opi[NI], opo[NI];
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const uint32_t row = srow + RSTEP * i;
+            const uint32_t trow = row < rows_left ? row : rows_left - 1;
+            ox[i] = trow * a.d_in * 2; og[i] = trow * a.d_out * 2;
+            opi[i] = (row < a.k_in ? row : a.k_in - 1) * a.d_in * 2;
+            opo[i] = (row < a.k_out ? row : a.k_out - 1) * a.d_out * 2;
+            // The projection offsets do not depend on the token tile; hidden from the optimiser here, or it computes
+            // the complete 64-bit addresses of the first loads of a tile once, outside the tile loop, and keeps (spills)
+            // them all.
+            asm volatile("" : "+v"(opi[i]), "+v"(opo[i]));
+        }
         auto fetch = [&](RegSet& r, uint32_t k0) {
             const uint32_t kk = k0 + skc * 8;           // a 16-byte chunk is all in or all out
-            const uint32_t kx = kk < a.d_in ? kk : din8, kg = kk < a.d_out ? kk : dout8;
+            const uint32_t kx = (kk < a.d_in ? kk : din8) * 2, kg = (kk < a.d_out ? kk : dout8) * 2;
 #pragma unroll
             for (int i = 0; i < NI; ++i) {
-                const uint32_t row = srow + RSTEP * i;
-                const uint64_t t = t0 + row < trow_last ? t0 + row : trow_last;
                 // x and g are read exactly once (non-temporal: they must not push the projection matrices, which
                 // every workgroup re-reads, out of L2)
-                r.rx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xs + t * a.d_in + kx));
-                r.rg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gs + t * a.d_out + kg));
-                r.rpi[i] = *reinterpret_cast<const u32x4*>(a.pin + (uint64_t)(row < a.k_in ? row : a.k_in - 1) * a.d_in + kx);
-                r.rpo[i] = *reinterpret_cast<const u32x4*>(a.pout + (uint64_t)(row < a.k_out ? row : a.k_out - 1) * a.d_out + kg);
+                r.rx[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(xb + (ox[i] + kx)));
+                r.rg[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(gb + (og[i] + kg)));
+                r.rpi[i] = *reinterpret_cast<const u32x4*>(pib + (opi[i] + kx));
+                r.rpo[i] = *reinterpret_cast<const u32x4*>(pob + (opo[i] + kg));
             }
         };
-        auto stash = [&](const RegSet& r, int stage, uint32_t k0) {
-            uint16_t* base = lds + stage * kLograStage;
+        // half j goes to LDS stage (j >> 1) & 1, columns (j & 1) * 64 .. + 63 of the 128-column rows
+        auto stash = [&](const RegSet& r, uint32_t j, uint32_t k0) {
+            uint16_t* base = lds + ((j >> 1) & 1) * kLograStage + (j & 1) * kHalf;
             const uint32_t kk = k0 + skc * 8;
             const uint32_t mx = kk < a.d_in ? ~0u : 0u, mg = kk < a.d_out ? ~0u : 0u;
 #pragma unroll
@@ -113,97 +147,102 @@ __global__ void __launch_bounds__(kLograThreads) logra_kernel(LograArgs a) {
             }
         };
 
-        f32x16 acc1[2];                                 // 32 tokens x 64 projected columns
+        // Half j (64 columns of all four tiles) travels in register set j mod 5 of the producers and lands in LDS stage
+        // (j / 2) mod 2.  While the consumers multiply group g (halves 2g, 2g+1) out of stage g mod 2, the producers
+        // store halves 2g+2 and 2g+3 into the other stage and refill each register set with the half five further
+        // on: four halves (128 KB per workgroup) stay in flight behind the one being stored, and the matrix work of
+        // the consumers runs under the producers' wait for memory.  Every wavefront passes the same barriers: one at
+        // the start of the tile, one after each group is staged (which is also: after the group before it has been
+        // multiplied), one after the last group has been multiplied.
+        __syncthreads();                                // stage-2 reads of the previous token tile are done
+        if (producer) {
+            RegSet S[kSets];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+            for (int q = 0; q < kSets; ++q) fetch(S[q], KH(q));            // unconditional (clamped past the end)
+            uint32_t j = 0;                                                // next half to store; a multiple of 10
+            // steady state: every fetch is unconditional on every path into and around the loop, so the wait counts
+            // the compiler derives keep the four newer register sets in flight
+            for (; j + 14 < nhalves; j += 10) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc1[j][v] = 0.0f;
-        auto multiply = [&](int cur, uint32_t sl) {
-            // operand tiles of this wavefront: tokens (X or G) and projection rows (P_in or P_out)
-            const uint16_t* tok = lds + cur * kLograStage + wg * kTileElems + (wh * 32 + (lane & 31)) * LRS + (lane >> 5) * 8;
-            const uint16_t* prj = lds + cur * kLograStage + (2 + wg) * kTileElems + (lane & 31) * LRS + (lane >> 5) * 8;
-            const bool live = K0(sl) < (wg == 0 ? a.d_in : a.d_out);       // uniform per wavefront
-            if (live) {
+                for (int u = 0; u < 10; ++u) {
+                    stash(S[u % kSets], j + u, KH(j + u));
+                    fetch(S[u % kSets], KH(j + u + kSets));
+                    if (u & 1) __syncthreads();        // group (j+u)/2 is staged, group (j+u)/2 - 1 has been multiplied
+                }
+            }
+            // the last halves, with the bounds checks (uniform branches)
+            for (; j < nhalves; j += 10) {
 #pragma unroll
-                for (int ks = 0; ks < LK / 16; ++ks) {
-                    const bf16x8 tf = *reinterpret_cast<const bf16x8*>(tok + ks * 16);
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        const bf16x8 pf = *reinterpret_cast<const bf16x8*>(prj + j * 32 * LRS + ks * 16);
-                        acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, pf, acc1[j], 0, 0, 0);
+                for (int u = 0; u < 10; ++u) {
+                    if (j + u < nhalves) {
+                        stash(S[u % kSets], j + u, KH(j + u));
+                        if (j + u + kSets < nhalves) fetch(S[u % kSets], KH(j + u + kSets));
+                        if (u & 1) __syncthreads();
                     }
                 }
             }
-        };
-
-        // Two K slices are in flight in registers behind the one being multiplied (set B holds the odd slices, set A
-        // the even ones); loads complete in order, so storing slice s+1 to LDS waits for that slice only.
-        RegSet A, B;
-        __syncthreads();                                // stage-2 reads of the previous token tile are done
-        fetch(A, K0(0));
-        stash(A, 0, K0(0));
-        uint32_t sl = 0;
-        if (nslices > 4) {
-            // Steady state (both prefetches exist on every path into and around the loop): the same straight-line
-            // code every iteration, so the compiler can count how many newer loads may stay in flight when a register
-            // set is stored to LDS (a prefetch under a condition anywhere on the way in would make it wait for all).
-            fetch(B, K0(1));
-            fetch(A, K0(2));
-            __syncthreads();
-            for (; sl + 4 < nslices; sl += 2) {
-                multiply(0, sl);                            // stage 0: slice sl
-                stash(B, 1, K0(sl + 1));
-                fetch(B, K0(sl + 3));
-                __syncthreads();
-                multiply(1, sl + 1);                        // stage 1: slice sl + 1
-                stash(A, 0, K0(sl + 2));
-                fetch(A, K0(sl + 4));
-                __syncthreads();
-            }
+            __syncthreads();                                               // the last group has been multiplied
         } else {
-            if (nslices > 1) fetch(B, K0(1));                  // branches around whole slices are uniform
-            if (nslices > 2) fetch(A, K0(2));
-            __syncthreads();
-        }
-        // the last slices, with the bounds checks
-        for (; sl < nslices; sl += 2) {
-            multiply(0, sl);
-            if (sl + 1 < nslices) stash(B, 1, K0(sl + 1));
-            if (sl + 3 < nslices) fetch(B, K0(sl + 3));
-            __syncthreads();
-            if (sl + 1 >= nslices) break;
-            multiply(1, sl + 1);
-            if (sl + 2 < nslices) stash(A, 0, K0(sl + 2));
-            if (sl + 4 < nslices) fetch(A, K0(sl + 4));
-            __syncthreads();
-        }
+            f32x16 acc1[2];                                 // 32 tokens x 64 projected columns
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc1[j][v] = 0.0f;
+            auto multiply = [&](int cur, uint32_t g) {
+                // operand tiles of this wavefront: tokens (X or G) and projection rows (P_in or P_out)
+                const uint16_t* tok = lds + cur * kLograStage + wg * kTileElems + (wh * 32 + (lane & 31)) * LRS + (lane >> 5) * 8;
+                const uint16_t* prj = lds + cur * kLograStage + (2 + wg) * kTileElems + (lane & 31) * LRS + (lane >> 5) * 8;
+                const bool live = KG(g) < (wg == 0 ? a.d_in : a.d_out);        // uniform per wavefront
+                if (live) {
+#pragma unroll
+                    for (int ks = 0; ks < LK / 16; ++ks) {
+                        const bf16x8 tf = *reinterpret_cast<const bf16x8*>(tok + ks * 16);
+#pragma unroll
+                        for (int j = 0; j < 2; ++j) {
+                            const bf16x8 pf = *reinterpret_cast<const bf16x8*>(prj + j * 32 * LRS + ks * 16);
+                            acc1[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(tf, pf, acc1[j], 0, 0, 0);
+                        }
+                    }
+                }
+            };
 
-        // a (wavefronts 0,1) and b (wavefronts 2,3) as fp32 [token][64] over the staging area
-        float* ab = reinterpret_cast<float*>(lds) + wg * (LT * LP);
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int row = wh * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);     // token
-                ab[row * LP + j * 32 + (lane & 31)] = acc1[j][e];
+            __syncthreads();                                               // group 0 is staged
+            for (uint32_t g = 0; g < ngroups; ++g) {
+                multiply((int)(g & 1), g);
+                __syncthreads();
             }
+            // a (consumers 0,1) and b (consumers 2,3) as fp32 [token][64] over the staging area, which nobody reads
+            // or writes any more after the last barrier
+            float* ab = reinterpret_cast<float*>(lds) + wg * (LT * LP);
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int row = wh * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);     // token
+                    ab[row * LP + j * 32 + (lane & 31)] = acc1[j][e];
+                }
+        }
         __syncthreads();
-        const float* as = reinterpret_cast<const float*>(lds);
-        const float* bs = as + LT * LP;
+        if (!producer) {
+            const float* as = reinterpret_cast<const float*>(lds);
+            const float* bs = as + LT * LP;
 #pragma unroll 8
-        for (int t = 0; t < LT; t += 2) {
-            const float fa = as[(t + (lane >> 5)) * LP + ta * 32 + (lane & 31)];
-            const float fb = bs[(t + (lane >> 5)) * LP + tb * 32 + (lane & 31)];
-            acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc2, 0, 0, 0);
+            for (int t = 0; t < LT; t += 2) {
+                const float fa = as[(t + (lane >> 5)) * LP + ta * 32 + (lane & 31)];
+                const float fb = bs[(t + (lane >> 5)) * LP + tb * 32 + (lane & 31)];
+                acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa, fb, acc2, 0, 0, 0);
+            }
         }
     }
 
-    float* o = a.dst + (uint64_t)blockIdx.x * a.chunk_stride + sample * a.ld_dst;
+    if (!producer) {
+        float* o = a.dst + (uint64_t)blockIdx.x * a.chunk_stride + sample * a.ld_dst;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-        const uint32_t ai = ta * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-        const uint32_t bi = tb * 32 + (lane & 31);
-        if (ai < a.k_in && bi < a.k_out) o[(uint64_t)ai * a.k_out + bi] = acc2[e];
+        for (int e = 0; e < 16; ++e) {
+            const uint32_t ai = ta * 32 + 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
+            const uint32_t bi = tb * 32 + (lane & 31);
+            if (ai < a.k_in && bi < a.k_out) o[(uint64_t)ai * a.k_out + bi] = acc2[e];
+        }
     }
 }
 
@@ -261,6 +300,7 @@ extern "C" grass_status logra_linear(const void* x, const void* gout, uint64_t n
     if (d_in % 8 != 0 || d_out % 8 != 0 || !aligned(x, 16) || !aligned(gout, 16) || !aligned(P_in, 16) ||
         !aligned(P_out, 16))
         return GRASS_EUNSUPPORTED;
+    if (d_in > (1u << 24) || d_out > (1u << 24)) return GRASS_EUNSUPPORTED;   // 32-bit byte offsets inside a tile
     LograPlan pl;
     plan_logra(n, T, k_in, k_out, &pl);
     if (pl.ws_bytes > 0 && (!ws || ws_bytes < pl.ws_bytes || !aligned(ws, 256))) return GRASS_EWORKSPACE;

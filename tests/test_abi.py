@@ -91,6 +91,16 @@ def test_bad_arguments_are_rejected_before_any_launch(lib):
     assert lib.grass_gauss_project(fake, 2, 64, 64, 8, 0, 2, 0, 0, fake, 8, null, 0, null) == b.GRASS_EWORKSPACE
 
 
+def test_logra_refuses_feature_dimensions_beyond_its_offset_range(lib):
+    """logra_linear addresses a tile of 64 rows with 32-bit byte offsets: d_in, d_out above 2^24 are refused on the host."""
+    from paper_2505_18976_amd import binding as b
+    fake, null = ctypes.c_void_p(4096), ctypes.c_void_p(0)
+    big = (1 << 24) + 8
+    assert lib.logra_linear(fake, fake, 2, 64, big, 64, fake, 8, fake, 8, fake, 64, fake, 1 << 20, null) == b.GRASS_EUNSUPPORTED
+    assert lib.logra_linear(fake, fake, 2, 64, 64, big, fake, 8, fake, 8, fake, 64, fake, 1 << 20, null) == b.GRASS_EUNSUPPORTED
+    assert lib.logra_linear(fake, fake, 2, 64, 60, 64, fake, 8, fake, 8, fake, 64, fake, 1 << 20, null) == b.GRASS_EUNSUPPORTED  # d % 8
+
+
 def test_noalloc_entry_point_refuses_oversized_problems_on_the_host(lib):
     """grass_sjlt_noalloc keeps its scratch memory in a fixed 32 MiB buffer inside the library: a problem whose
     partial sums need more is refused before anything touches a GPU (this process has none)."""

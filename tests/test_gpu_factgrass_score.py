@@ -204,6 +204,7 @@ LOGRA_CASES = [
     (2, 130, 264, 200, 32, 64),
     (2, 300, 512, 384, 64, 64),
     (8, 64, 2048, 2048, 64, 64),
+    (64, 520, 264, 1096, 48, 64),     # two token tiles per workgroup and a ragged last chunk; d_out >> d_in, 18 half slices
 ]
 
 
