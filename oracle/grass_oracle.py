@@ -393,6 +393,24 @@ def selective_mask_train(S0, G, Gt, lam: float, lr: float, temperatures):
     return S, np.asarray(history, dtype=np.float64)
 
 
+def selective_mask_train_factorized(S_in0, S_out0, Z_in, Z_out, Zt_in, Zt_out, lam: float, lr: float, temperatures):
+    """The factorised Selective Mask problem of a linear layer (App. B.4 "Linear Layer") solved the same way as the
+    plain one (same reading: plain gradient ascent over all rows, one caller-given temperature per step): both logit
+    vectors move together,
+        S_in  <- S_in  + lr * dL/dS_in,      S_out <- S_out + lr * dL/dS_out,
+    with both derivatives taken at the logits before the step.
+    Returns (S_in, S_out, history) with history[i] the objective before step i."""
+    S_in = np.array(S_in0, dtype=np.float64, copy=True)
+    S_out = np.array(S_out0, dtype=np.float64, copy=True)
+    history = []
+    for T in temperatures:
+        obj, g_in, g_out = selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, T)
+        history.append(obj)
+        S_in = S_in + lr * g_in
+        S_out = S_out + lr * g_out
+    return S_in, S_out, np.asarray(history, dtype=np.float64)
+
+
 def graddot_correlation(G, Gt, idx) -> float:
     """First term of Eq. (1) for a binary mask: the mean over test rows of the Pearson correlation between the exact
     GradDot scores <g_i, g_test> and those of the masked gradients <g_i[idx], g_test[idx]> (Sec. 3.2)."""

@@ -258,3 +258,43 @@ def test_selective_mask_training_mistakes_are_caught(monkeypatch, kwargs, pin):
     with pytest.raises(AssertionError):
         getattr(pins_train, pin)()
 
+
+
+pins_train_fact = _load("test_oracle_selective_mask_train_factorized")
+
+
+def _train_factorized_variant(descent=False, stale_temperature=False, only_input=False, sequential=False,
+                              no_step_size=False):
+    def train(S_in0, S_out0, Z_in, Z_out, Zt_in, Zt_out, lam, lr, temperatures):
+        S_in = np.array(S_in0, dtype=np.float64, copy=True)
+        S_out = np.array(S_out0, dtype=np.float64, copy=True)
+        history = []
+        step = 1.0 if no_step_size else lr
+        for T in temperatures:
+            Tg = temperatures[0] if stale_temperature else T
+            obj, g_in, g_out = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)
+            history.append(orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, T)[0])
+            S_in = S_in - step * g_in if descent else S_in + step * g_in
+            if sequential:          # output derivative taken after the input logits have already moved
+                g_out = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)[2]
+            if not only_input:
+                S_out = S_out - step * g_out if descent else S_out + step * g_out
+        return S_in, S_out, np.asarray(history, dtype=np.float64)
+    return train
+
+
+@pytest.mark.parametrize("kwargs,pin", [
+    (dict(descent=True), "test_first_step_moves_both_vectors_along_the_finite_difference_gradient"),
+    (dict(descent=True), "test_small_steps_never_decrease_the_objective"),
+    (dict(stale_temperature=True), "test_training_is_a_composition_of_its_steps_each_at_its_own_temperature"),
+    (dict(only_input=True), "test_swapping_the_two_factors_swaps_the_two_results"),
+    (dict(only_input=True), "test_dead_coordinates_of_either_factor_follow_the_penalty_in_closed_form"),
+    (dict(sequential=True), "test_first_step_moves_both_vectors_along_the_finite_difference_gradient"),
+    (dict(sequential=True), "test_swapping_the_two_factors_swaps_the_two_results"),
+    (dict(no_step_size=True), "test_a_trivial_output_factor_reduces_it_to_the_plain_training_loop"),
+    (dict(no_step_size=True), "test_no_steps_and_zero_step_size_leave_the_logits_alone"),
+])
+def test_factorised_selective_mask_training_mistakes_are_caught(monkeypatch, kwargs, pin):
+    monkeypatch.setattr(orc, "selective_mask_train_factorized", _train_factorized_variant(**kwargs))
+    with pytest.raises(AssertionError):
+        getattr(pins_train_fact, pin)()
