@@ -418,6 +418,26 @@ grass_status grass_selective_mask_grad_factorized(const float* Z_in, const float
                                                   double lambda, double temperature,
                                                   float* grad_in, float* grad_out, double* objective,
                                                   void* ws, size_t ws_bytes, grass_stream stream);
+/* grass_selective_mask_train_factorized: the same first-order ascent as
+ * grass_selective_mask_train on the factorised problem: both logit vectors take
+ *     S_in <- S_in + lr * dL/dS_in,   S_out <- S_out + lr * dL/dS_out
+ * per entry of the host temperature schedule, both derivatives evaluated at the
+ * logits before the step.  S_in (d_in) and S_out (d_out) are updated in place;
+ * objectives (device double[steps], may be NULL) receives the objective before
+ * each step.  Other arguments as in grass_selective_mask_grad_factorized.     */
+grass_status grass_selective_mask_train_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
+                                                                   uint64_t d_out, size_t* host_bytes);
+grass_status grass_selective_mask_train_factorized(const float* Z_in, const float* Z_out, uint64_t n,
+                                                   uint64_t ld_zin, uint64_t ld_zout,
+                                                   const float* Zt_in, const float* Zt_out, uint64_t m,
+                                                   uint64_t ld_ztin, uint64_t ld_ztout,
+                                                   uint64_t d_in, uint64_t d_out,
+                                                   const float* A, uint64_t lda,
+                                                   float* S_in, float* S_out,
+                                                   double lambda, double lr,
+                                                   const double* host_temperatures, uint32_t steps,
+                                                   double* objectives,
+                                                   void* ws, size_t ws_bytes, grass_stream stream);
 grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* host_bytes);
 grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
                                           uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream);

@@ -84,6 +84,10 @@ SIGNATURES = {
     "grass_selective_mask_grad_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
                                                     _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp, _vp,
                                                     _vp, _sz, _vp]),
+    "grass_selective_mask_train_factorized_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, ctypes.POINTER(_sz)]),
+    "grass_selective_mask_train_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
+                                                     _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double,
+                                                     ctypes.POINTER(ctypes.c_double), _u32, _vp, _vp, _sz, _vp]),
     "grass_selective_mask_indices_workspace_bytes": (_int, [_u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_indices": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _sz, _vp]),
     "factmask_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
@@ -562,6 +566,32 @@ def grass_selective_mask_grad_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_
         _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(temperature), _ptr(grad_in), _ptr(grad_out),
         _ptr(objective), _ptr(ws), ws.numel(), _stream()), "grass_selective_mask_grad_factorized")
     return grad_in, grad_out, objective
+
+
+def grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam: float, lr: float, temperatures,
+                                          objectives: torch.Tensor | None = None):
+    """len(temperatures) gradient-ascent steps on both logit vectors of a linear layer's factorised mask (updated in
+    place), step i at temperatures[i].  Returns (S_in, S_out, objectives float64 [steps])."""
+    for t in (Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out):
+        assert t.dtype == torch.float32
+    n, d_in = Z_in.shape
+    d_out = Z_out.shape[1]
+    m = Zt_in.shape[0]
+    assert Z_out.shape[0] == n and Zt_in.shape[1] == d_in and Zt_out.shape == (m, d_out) and A.shape == (m, n)
+    assert S_in.is_contiguous() and S_out.is_contiguous() and S_in.numel() == d_in and S_out.numel() == d_out
+    steps = len(temperatures)
+    sched = (ctypes.c_double * max(steps, 1))(*[float(t) for t in temperatures])
+    if objectives is None:
+        objectives = torch.empty(max(steps, 1), dtype=torch.float64, device=Z_in.device)
+    nbytes = _sz(0)
+    _check(load_library().grass_selective_mask_train_factorized_workspace_bytes(n, m, d_in, d_out, ctypes.byref(nbytes)),
+           "grass_selective_mask_train_factorized_workspace_bytes")
+    ws = _workspace(nbytes.value, Z_in.device)
+    _check(load_library().grass_selective_mask_train_factorized(
+        _ptr(Z_in), _ptr(Z_out), n, _ld(Z_in), _ld(Z_out), _ptr(Zt_in), _ptr(Zt_out), m, _ld(Zt_in), _ld(Zt_out), d_in, d_out,
+        _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(lr), sched, steps, _ptr(objectives), _ptr(ws),
+        ws.numel(), _stream()), "grass_selective_mask_train_factorized")
+    return S_in, S_out, objectives[:steps]
 
 
 def grass_selective_mask_indices_workspace_bytes(p: int) -> int:

@@ -351,27 +351,31 @@ extern "C" grass_status grass_selective_mask_grad_factorized_workspace_bytes(uin
     if (st != GRASS_OK || d_in == 0 || d_out == 0) return st != GRASS_OK ? st : GRASS_EINVAL;
     const SmLayout L = sm_layout(n, m, p);
     // + B_out, C_in / C_out scratch and the second factor's sigma partial sums
-    *host_bytes = L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);
+    *host_bytes = L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);   // = sm_factorized_bytes
     return GRASS_OK;
 }
 
-extern "C" grass_status grass_selective_mask_grad_factorized(
-    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
-    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
-    uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature, float* grad_in, float* grad_out,
-    double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
+static grass_status check_sm_factorized(uint64_t n, uint64_t m, uint64_t d_in, uint64_t d_out, const float* Z_in,
+                                        const float* Z_out, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+                                        const float* Zt_out, uint64_t ld_ztin, uint64_t ld_ztout, const float* A,
+                                        uint64_t lda, const float* S_in, const float* S_out, double lambda) {
     const uint64_t p = d_in > d_out ? d_in : d_out;
     grass_status st = check_sm(n, m, p);
     if (st != GRASS_OK) return st;
-    if (d_in == 0 || d_out == 0 || !Z_in || !Z_out || !Zt_in || !Zt_out || !A || !S_in || !S_out || !grad_in || !grad_out)
-        return GRASS_EINVAL;
+    if (d_in == 0 || d_out == 0 || !Z_in || !Z_out || !Zt_in || !Zt_out || !A || !S_in || !S_out) return GRASS_EINVAL;
     if (ld_zin < d_in || ld_ztin < d_in || ld_zout < d_out || ld_ztout < d_out || lda < n) return GRASS_EINVAL;
-    if (!(temperature > 0.0) || !(lambda >= 0.0)) return GRASS_EINVAL;
-    const SmLayout L = sm_layout(n, m, p);
+    if (!(lambda >= 0.0)) return GRASS_EINVAL;
+    return GRASS_OK;
+}
+
+// Value and both gradients; the workspace holds sm_layout(n, m, max(d_in, d_out)) followed by B_out, one m x n_pad
+// scratch matrix and the second factor's sigma partial sums.
+static grass_status sm_value_and_grad_factorized(
+    const SmLayout& L, unsigned char* base, const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin,
+    uint64_t ld_zout, const float* Zt_in, const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout,
+    uint64_t d_in, uint64_t d_out, const float* A, uint64_t lda, const float* S_in, const float* S_out, double lambda,
+    double temperature, float* grad_in, float* grad_out, double* objective, hipStream_t hs) {
     const size_t extra_b = up256((size_t)m * L.n_pad * 4);
-    const size_t need = L.total + 2 * extra_b + up256((size_t)L.parts * 8);
-    if (!ws || ws_bytes < need || !aligned(ws, 256)) return GRASS_EWORKSPACE;
-    unsigned char* base = static_cast<unsigned char*>(ws);
     float* B_in = reinterpret_cast<float*>(base + L.off_b);
     float* C = reinterpret_cast<float*>(base + L.off_c);
     double* corr = reinterpret_cast<double*>(base + L.off_corr);
@@ -379,11 +383,10 @@ extern "C" grass_status grass_selective_mask_grad_factorized(
     float* B_out = reinterpret_cast<float*>(base + L.total);
     float* Cx = reinterpret_cast<float*>(base + L.total + extra_b);
     double* sig_out = reinterpret_cast<double*>(base + L.total + 2 * extra_b);
-    hipStream_t hs = as_stream(stream);
     const float inv_temp = (float)(1.0 / temperature);
     const uint32_t eb = (uint32_t)ceil_div(m * n, 256);
 
-    st = sm_masked_scores(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, B_in, sig_in, hs);
+    grass_status st = sm_masked_scores(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, B_in, sig_in, hs);
     if (st != GRASS_OK) return st;
     st = sm_masked_scores(L, base, Z_out, n, ld_zout, Zt_out, m, ld_ztout, d_out, S_out, inv_temp, B_out, sig_out, hs);
     if (st != GRASS_OK) return st;
@@ -402,5 +405,67 @@ extern "C" grass_status grass_selective_mask_grad_factorized(
     if (objective)
         hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_in, ceil_div((d_in + 3) / 4 * 4, 256),
                            (const double*)sig_out, ceil_div((d_out + 3) / 4 * 4, 256), lambda, objective);
+    return launch_status();
+}
+
+static size_t sm_factorized_bytes(const SmLayout& L, uint64_t m) {
+    return L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);
+}
+
+extern "C" grass_status grass_selective_mask_grad_factorized(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
+    uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature, float* grad_in, float* grad_out,
+    double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
+    grass_status st = check_sm_factorized(n, m, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout,
+                                          A, lda, S_in, S_out, lambda);
+    if (st != GRASS_OK) return st;
+    if (!grad_in || !grad_out || !(temperature > 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, d_in > d_out ? d_in : d_out);
+    if (!ws || ws_bytes < sm_factorized_bytes(L, m) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    return sm_value_and_grad_factorized(L, static_cast<unsigned char*>(ws), Z_in, Z_out, n, ld_zin, ld_zout, Zt_in, Zt_out,
+                                        m, ld_ztin, ld_ztout, d_in, d_out, A, lda, S_in, S_out, lambda, temperature,
+                                        grad_in, grad_out, objective, as_stream(stream));
+}
+
+// Training of the factorised mask: both logit vectors take a plain gradient-ascent step per temperature of the host
+// schedule, both derivatives taken at the logits before the step (the two updates run after both backward passes).
+extern "C" grass_status grass_selective_mask_train_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
+                                                                              uint64_t d_out, size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    const uint64_t p = d_in > d_out ? d_in : d_out;
+    grass_status st = check_sm(n, m, p);
+    if (st != GRASS_OK || d_in == 0 || d_out == 0) return st != GRASS_OK ? st : GRASS_EINVAL;
+    *host_bytes = sm_factorized_bytes(sm_layout(n, m, p), m) + up256((size_t)d_in * 4) + up256((size_t)d_out * 4);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_selective_mask_train_factorized(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
+    uint64_t lda, float* S_in, float* S_out, double lambda, double lr, const double* host_temperatures, uint32_t steps,
+    double* objectives, void* ws, size_t ws_bytes, grass_stream stream) {
+    grass_status st = check_sm_factorized(n, m, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout,
+                                          A, lda, S_in, S_out, lambda);
+    if (st != GRASS_OK) return st;
+    if (!(lr == lr) || (steps > 0 && !host_temperatures)) return GRASS_EINVAL;
+    for (uint32_t i = 0; i < steps; ++i)
+        if (!(host_temperatures[i] > 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(n, m, d_in > d_out ? d_in : d_out);
+    const size_t fb = sm_factorized_bytes(L, m);
+    if (!ws || ws_bytes < fb + up256((size_t)d_in * 4) + up256((size_t)d_out * 4) || !aligned(ws, 256))
+        return GRASS_EWORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* grad_in = reinterpret_cast<float*>(base + fb);
+    float* grad_out = reinterpret_cast<float*>(base + fb + up256((size_t)d_in * 4));
+    hipStream_t hs = as_stream(stream);
+    for (uint32_t i = 0; i < steps; ++i) {
+        st = sm_value_and_grad_factorized(L, base, Z_in, Z_out, n, ld_zin, ld_zout, Zt_in, Zt_out, m, ld_ztin, ld_ztout, d_in,
+                                          d_out, A, lda, S_in, S_out, lambda, host_temperatures[i], grad_in, grad_out,
+                                          objectives ? objectives + i : nullptr, hs);
+        if (st != GRASS_OK) return st;
+        hipLaunchKernelGGL(sm_update_kernel, dim3((uint32_t)ceil_div(d_in, 256)), dim3(256), 0, hs, S_in, grad_in, d_in, lr);
+        hipLaunchKernelGGL(sm_update_kernel, dim3((uint32_t)ceil_div(d_out, 256)), dim3(256), 0, hs, S_out, grad_out, d_out, lr);
+    }
     return launch_status();
 }

@@ -277,3 +277,98 @@ def test_score_correlation_parity(grass):
     Xh, Yh = X.cpu().numpy().astype(np.float64), Y.cpu().numpy().astype(np.float64)
     want = sum(stats.pearsonr(Xh[t], Yh[t])[0] for t in range(m) if t != 5) / m
     assert abs(got - want) <= 1e-6
+
+
+# ------------------------------------------------------------------- factorised training (App. B.4 "Linear Layer")
+def _factor_problem(n, m, d_in, d_out, seed):
+    Z_in = synth.dense_normal(n, d_in, seed=seed, device=_dev())
+    Z_out = synth.dense_normal(n, d_out, seed=seed + 1, device=_dev())
+    Zt_in = synth.dense_normal(m, d_in, seed=seed + 2, device=_dev())
+    Zt_out = synth.dense_normal(m, d_out, seed=seed + 3, device=_dev())
+    S_in = synth.dense_normal(1, d_in, seed=seed + 4, device=_dev(), std=0.3).reshape(-1).contiguous()
+    S_out = synth.dense_normal(1, d_out, seed=seed + 5, device=_dev(), std=0.3).reshape(-1).contiguous()
+    return Z_in, Z_out, Zt_in, Zt_out, S_in, S_out
+
+
+@pytest.mark.parametrize("n,m,d_in,d_out,lam,lr,steps", [(8, 3, 5, 4, 0.05, 0.5, 6), (60, 7, 300, 129, 0.01, 2.0, 12),
+                                                         (200, 130, 1024, 2050, 1e-3, 20.0, 10)])
+def test_selective_mask_train_factorized_parity(grass, n, m, d_in, d_out, lam, lr, steps):
+    """Both logit vectors after `steps` device-side steps against the oracle's loop, with the drift bound of the plain
+    training test (2e-4 of each vector's path length plus fp32 rounding of the logits), and bit for bit against the
+    same run made of separate calls of the factorised gradient entry point with a host-side update."""
+    Z_in, Z_out, Zt_in, Zt_out, S_in0, S_out0 = _factor_problem(n, m, d_in, d_out, seed=3800 + d_in)
+    temps = np.geomspace(1.0, 0.5, steps)
+    A = (grass.grass_score(Z_in, Zt_in) * grass.grass_score(Z_out, Zt_out)).contiguous()
+    S_in, S_out = S_in0.clone(), S_out0.clone()
+    _, _, objs = grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam, lr, temps)
+    torch.cuda.synchronize()
+    h = lambda t: t.cpu().numpy().astype(np.float64)
+    # the oracle's loop, step by step, to get the path lengths as well
+    a, b = h(S_in0), h(S_out0)
+    path_in = path_out = 0.0
+    hist = []
+    for T in temps:
+        a2, b2, h1 = orc.selective_mask_train_factorized(a, b, h(Z_in), h(Z_out), h(Zt_in), h(Zt_out), lam, lr, [T])
+        path_in += np.abs(a2 - a).max(); path_out += np.abs(b2 - b).max()
+        hist.append(h1[0]); a, b = a2, b2
+    whole = orc.selective_mask_train_factorized(h(S_in0), h(S_out0), h(Z_in), h(Z_out), h(Zt_in), h(Zt_out), lam, lr, temps)
+    assert np.array_equal(whole[0], a) and np.array_equal(whole[1], b)
+    assert np.abs(a - h(S_in0)).max() > 10 * 2e-4 * path_in and np.abs(b - h(S_out0)).max() > 10 * 2e-4 * path_out
+    assert np.abs(h(S_in) - a).max() <= 2e-4 * path_in + steps * 2.0 ** -23 * np.abs(a).max()
+    assert np.abs(h(S_out) - b).max() <= 2e-4 * path_out + steps * 2.0 ** -23 * np.abs(b).max()
+    assert np.abs(objs.cpu().numpy() - np.asarray(hist)).max() <= 1e-5 * max(1.0, np.abs(hist).max())
+    T_in, T_out = S_in0.clone(), S_out0.clone()
+    for T in temps:
+        gi, go, _ = grass.grass_selective_mask_grad_factorized(Z_in, Z_out, Zt_in, Zt_out, A, T_in, T_out, lam, float(T))
+        T_in = (T_in.double() + lr * gi.double()).float()
+        T_out = (T_out.double() + lr * go.double()).float()
+    torch.cuda.synchronize()
+    assert torch.equal(T_in, S_in) and torch.equal(T_out, S_out)
+
+
+def test_selective_mask_train_factorized_recovers_the_planted_coordinates_of_both_factors(grass):
+    n, m, d_in, d_out, k_in, k_out, lam, lr = 256, 32, 512, 384, 16, 12, 1e-3, 100.0
+    Z_in, Zt_in, p_in = synth.planted_gradients(n, m, d_in, k_in, seed=3700, device=_dev())
+    Z_out, Zt_out, p_out = synth.planted_gradients(n, m, d_out, k_out, seed=3701, device=_dev())
+    S_in0 = synth.dense_normal(1, d_in, seed=3702, device=_dev(), std=0.1).reshape(-1).contiguous()
+    S_out0 = synth.dense_normal(1, d_out, seed=3703, device=_dev(), std=0.1).reshape(-1).contiguous()
+    temps = np.geomspace(1.0, 0.6, 60)
+    A = (grass.grass_score(Z_in, Zt_in) * grass.grass_score(Z_out, Zt_out)).contiguous()
+    S_in, S_out = S_in0.clone(), S_out0.clone()
+    _, _, objs = grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam, lr, temps)
+    ii = grass.grass_selective_mask_indices(S_in, k_in)
+    io = grass.grass_selective_mask_indices(S_out, k_out)
+    torch.cuda.synchronize()
+    h = lambda t: t.cpu().numpy().astype(np.float64)
+    a, b, hist = orc.selective_mask_train_factorized(h(S_in0), h(S_out0), h(Z_in), h(Z_out), h(Zt_in), h(Zt_out), lam, lr, temps)
+    pi, po = p_in.numpy().astype(np.int32), p_out.numpy().astype(np.int32)
+    assert np.array_equal(orc.selective_mask_indices(a, k_in), pi) and np.array_equal(orc.selective_mask_indices(b, k_out), po)
+    gap = min(a[pi].min() - np.delete(a, pi).max(), b[po].min() - np.delete(b, po).max())
+    assert gap > 100 * max(np.abs(h(S_in) - a).max(), np.abs(h(S_out) - b).max())
+    assert np.array_equal(ii.cpu().numpy(), pi) and np.array_equal(io.cpu().numpy(), po)
+    assert objs[-1].item() > objs[0].item()
+
+    # first term of Eq. (1) for the binary Kronecker mask, from factor scores: <a (x) b, c (x) d> = <a, c> <b, d>
+    def masked_correlation(ji, jo):
+        Y = grass.grass_score(grass.grass_mask(Z_in, ji), grass.grass_mask(Zt_in, ji)) * \
+            grass.grass_score(grass.grass_mask(Z_out, jo), grass.grass_mask(Zt_out, jo))
+        return float(grass.grass_score_correlation(A, Y.contiguous()).item())
+    c_sel = masked_correlation(ii, io)
+    c_rand = [masked_correlation(grass.grass_mask_indices(sd, 0, d_in, k_in, device=_dev()),
+                                 grass.grass_mask_indices(sd, 1, d_out, k_out, device=_dev())) for sd in range(5)]
+    assert c_sel > 0.9 and c_sel > max(c_rand) + 0.2
+
+
+def test_selective_mask_train_factorized_edge_cases(grass):
+    Z_in, Z_out, Zt_in, Zt_out, S_in0, S_out0 = _factor_problem(20, 3, 50, 30, seed=3900)
+    A = (grass.grass_score(Z_in, Zt_in) * grass.grass_score(Z_out, Zt_out)).contiguous()
+    S_in, S_out = S_in0.clone(), S_out0.clone()
+    grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, 0.01, 1.0, [])
+    grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, 0.01, 0.0, [1.0, 0.5])
+    for bad in ([1.0, 0.0], [-1.0], [float("nan")]):
+        with pytest.raises(grass.GrassError):
+            grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, 0.01, 1.0, bad)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, -0.01, 1.0, [1.0])
+    torch.cuda.synchronize()
+    assert torch.equal(S_in, S_in0) and torch.equal(S_out, S_out0)
