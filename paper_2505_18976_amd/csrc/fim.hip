@@ -44,17 +44,17 @@ __global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf,
 constexpr int NB = 64;                        // block size of the factorisation
 typedef double f64x4 __attribute__((ext_vector_type(4)));
 
-// A64 (kp x kp): lower triangle of F + lambda I, identity on the padding rows; X64 = 0.
+// A64 (kp x kp, row distance ld): lower triangle of F + lambda I, identity on the padding rows; X64 = 0.
 __global__ void __launch_bounds__(256) fim_load_kernel(const float* F, uint64_t ldf, uint32_t k, double lambda,
-                                                      double* A64, double* X64, uint32_t kp) {
+                                                      double* A64, double* X64, uint32_t kp, uint32_t ld) {
     const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= (uint64_t)kp * kp) return;
     const uint32_t a = (uint32_t)(t / kp), b = (uint32_t)(t - (uint64_t)a * kp);
     double v = 0.0;
     if (a < k && b <= a) v = (double)F[(uint64_t)a * ldf + b] + (a == b ? lambda : 0.0);
     else if (a >= k && a == b) v = 1.0;
-    A64[t] = v;
-    X64[t] = 0.0;
+    A64[(uint64_t)a * ld + b] = v;
+    X64[(uint64_t)a * ld + b] = 0.0;
 }
 
 // Value of lane `src` (a compile-time constant) of a double, as a wavefront-uniform scalar.
@@ -67,81 +67,102 @@ __device__ __forceinline__ double lane_bcast(double v, int src) {
 // Cholesky factor of the NB x NB diagonal block j (lower, in place) and its inverse D = L_jj^{-1} into the
 // same block of X64 (zeros above the diagonal).  A non-positive pivot records its 1-based index in *info
 // (first one wins) and is replaced by 1 so that the run stays finite.
-// One wavefront and no barriers: the column recurrence is a chain of dependent fp64 operations (32 cycles each on
-// this chip), so what matters is the length of that chain and the number of instructions the one wavefront has to
-// issue, not parallel width.  Lane r keeps row r of the block in registers.  In step c every lane scales its entry
-// of column c and writes it to LDS; the entries l[q][c] that the trailing update a[r][q] -= l[r][c] l[q][c] needs
-// come back as broadcast reads of two doubles each (all lanes read the same address).  The first form of this
-// kernel fetched them with two v_readlane per value: 16,700 instructions (8,500 v_readlane, 3,300 hazard nops),
-// 45 us per block; this one issues 12,600 and takes 39 us.  The inverse is computed the same way: lane t solves
-// L x = e_t with the rows of L read back from LDS by broadcast.
+// Two wavefronts and one barrier (at the start): the column recurrence is a chain of dependent fp64 operations (32
+// cycles each on this chip), so what matters is the length of that chain and the number of instructions a wavefront
+// has to issue, not parallel width.
+//   Wavefront 0 factorises.  Lane r keeps row r of the block in registers.  In step c every lane scales its entry of
+//   column c and writes it to LDS; the entries l[q][c] that the trailing update a[r][q] -= l[r][c] l[q][c] needs come
+//   back as broadcast reads of two doubles each (all lanes read the same address).  (Fetching them with two v_readlane
+//   per value instead took 16,700 instructions, 8,500 of them v_readlane and 3,300 hazard nops, against 12,600.)
+//   Wavefront 1 inverts, one column behind: lane t keeps column t of X = L^{-1}, x[q] = delta_qt - sum_{m<c} l[q][m]
+//   X[m][t] after c steps; in step c it finishes X[c][t] = x[c] / l[c][c] and subtracts l[q][c] X[c][t] from the x[q]
+//   below, with the same broadcast reads of column c.  It waits for column c on a counter in LDS that wavefront 0
+//   advances after its writes of the column (LDS operations of one wavefront complete in order); wavefront 0 never
+//   waits for anybody, so every wait ends.  Doing the inverse afterwards in the factorising wavefront (forward
+//   substitution with the rows of L read back from LDS) took 39 us per block against 24 us for the two in step.
 // The loop bodies must stay free of branches (every lane stores the same 1/pivot): with a conditional store per
 // column the compiler sank the trailing updates of far columns across 30 to 40 basic blocks towards their use and
 // spilled 2,200 registers to scratch.  The empty asm statements bound how far it may move LDS reads.
-constexpr int kPotrfLd = NB + 2;              // doubles per LDS row: 16-byte aligned rows, lanes spread over the banks
 struct f64x2 { double x, y; };
-__global__ void __launch_bounds__(64) potrf_block_kernel(double* A64, double* X64, uint32_t kp, uint32_t j, int* info) {
+__global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X64, uint32_t ld, uint32_t j, int* info) {
     __shared__ __align__(16) double Lc[NB][NB];          // Lc[c][q] = L[q][c]: column c contiguous
-    __shared__ __align__(16) double Lr[NB][kPotrfLd];    // Lr[i][m] = L[i][m]: row i contiguous
     __shared__ __align__(16) double Ys[NB];              // 1 / L[c][c]
-    const int r = threadIdx.x;
-    double* Ab = A64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
-    double* Xb = X64 + ((uint64_t)j * NB) * kp + (uint64_t)j * NB;
-    double a[NB];
+    __shared__ int columns_done;
+    const int r = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    double* Ab = A64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
+    double* Xb = X64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
+    if (threadIdx.x == 0) columns_done = 0;
+    __syncthreads();
+    if (wave == 0) {
+        double a[NB];
 #pragma unroll
-    for (int q = 0; q < NB; ++q) a[q] = Ab[(uint64_t)r * kp + q];
-    int bad = 0;
+        for (int q = 0; q < NB; ++q) a[q] = Ab[(uint64_t)r * ld + q];
+        int bad = 0;
 #pragma unroll
-    for (int c = 0; c < NB; ++c) {
-        const double piv = lane_bcast(a[c], c);
-        const bool ok = piv > 0.0;                                   // false for NaN too
-        if (!ok && bad == 0) bad = c + 1;
-        const double pv = ok ? piv : 1.0;
-        double y = __builtin_amdgcn_rsq(pv);                         // pivot^(-1/2): estimate + two Newton steps
-        y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
-        y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
-        Ys[c] = y;                                                   // every lane stores the same value: no branch
-        const double lc = r == c ? pv * y : (r > c ? a[c] * y : 0.0);
-        a[c] = lc;
-        if (c + 1 < NB) {
-            Lc[c][r] = lc;                                           // LDS operations of one wavefront stay in order
+        for (int c = 0; c < NB; ++c) {
+            const double piv = lane_bcast(a[c], c);
+            const bool ok = piv > 0.0;                                   // false for NaN too
+            if (!ok && bad == 0) bad = c + 1;
+            const double pv = ok ? piv : 1.0;
+            double y = __builtin_amdgcn_rsq(pv);                         // pivot^(-1/2): estimate + two Newton steps
+            y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
+            y = fma(0.5 * y, fma(-pv * y, y, 1.0), y);
+            Ys[c] = y;                                                   // every lane stores the same value: no branch
+            const double lc = r == c ? pv * y : (r > c ? a[c] * y : 0.0);
+            a[c] = lc;
+            Lc[c][r] = lc;                                               // LDS operations of one wavefront stay in order
+            __hip_atomic_store(&columns_done, c + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            if (c + 1 < NB) {
 #pragma unroll
-            for (int q0 = (c + 1) & ~1; q0 < NB; q0 += 2) {          // pairs (q0, q0 + 1), q0 even
-                const f64x2 l = *reinterpret_cast<const f64x2*>(&Lc[c][q0]);
-                if (q0 > c) a[q0] = fma(-lc, l.x, a[q0]);            // only rows r >= q are used later
-                a[q0 + 1] = fma(-lc, l.y, a[q0 + 1]);
-                if ((q0 & 14) == 14) asm volatile("" ::: "memory");   // at most 8 reads in flight (measured best)
+                for (int q0 = (c + 1) & ~1; q0 < NB; q0 += 2) {          // pairs (q0, q0 + 1), q0 even
+                    const f64x2 l = *reinterpret_cast<const f64x2*>(&Lc[c][q0]);
+                    if (q0 > c) a[q0] = fma(-lc, l.x, a[q0]);            // only rows r >= q are used later
+                    a[q0 + 1] = fma(-lc, l.y, a[q0 + 1]);
+                    if ((q0 & 14) == 14) asm volatile("" ::: "memory");   // at most 8 reads in flight (measured best)
+                }
             }
+            asm volatile("" ::: "memory");
         }
-        asm volatile("" ::: "memory");
-    }
-    if (r == 0 && bad != 0 && info) atomicCAS(info, 0, (int)(j * NB) + bad);
+        if (r == 0 && bad != 0 && info) atomicCAS(info, 0, (int)(j * NB) + bad);
 #pragma unroll
-    for (int q = 0; q < NB; ++q) {
-        const double v = q <= r ? a[q] : 0.0;
-        Ab[(uint64_t)r * kp + q] = v;
-        Lr[r][q] = v;
-    }
-    // lane t = r: column t of the inverse, x[i] = (delta_it - sum_{m<i} L[i][m] x[m]) / L[i][i]
-    double x[NB];
+        for (int q = 0; q < NB; ++q) Ab[(uint64_t)r * ld + q] = q <= r ? a[q] : 0.0;
+    } else {
+        const uint32_t done_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&columns_done;   // LDS offset
+        double x[NB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-        double acc0 = i == r ? 1.0 : 0.0, acc1 = 0.0, acc2 = 0.0, acc3 = 0.0;
+        for (int q = 0; q < NB; ++q) x[q] = q == r ? 1.0 : 0.0;
 #pragma unroll
-        for (int m0 = 0; m0 < i; m0 += 2) {
-            const f64x2 l = *reinterpret_cast<const f64x2*>(&Lr[i][m0]);      // L[i][m0], L[i][m0 + 1]
-            if ((m0 & 2) == 0) acc0 = fma(-l.x, x[m0], acc0); else acc2 = fma(-l.x, x[m0], acc2);
-            if (m0 + 1 < i) {
-                if ((m0 & 2) == 0) acc1 = fma(-l.y, x[m0 + 1], acc1); else acc3 = fma(-l.y, x[m0 + 1], acc3);
+        for (int c = 0; c < NB; ++c) {
+            // wait until columns_done > c.  The polling loop lives inside one asm statement: as a loop of the C++
+            // source it would split every unrolled step into basic blocks (see above).  The value read stays inside
+            // the statement and has arrived (lgkmcnt(0)) before the statement ends.
+            {
+                uint32_t seen;
+                asm volatile("1:\n\t"
+                             "ds_read_b32 %0, %1\n\t"
+                             "s_waitcnt lgkmcnt(0)\n\t"
+                             "v_cmp_gt_i32_e32 vcc, %2, %0\n\t"
+                             "s_sleep 1\n\t"
+                             "s_cbranch_vccnz 1b"
+                             : "=&v"(seen)
+                             : "v"(done_addr), "v"(c + 1)
+                             : "vcc", "memory");
             }
-            if ((m0 & 14) == 14) asm volatile("" ::: "memory");
-        }
-        const double v = ((acc0 + acc1) + (acc2 + acc3)) * Ys[i];
-        x[i] = i >= r ? v : 0.0;
-        asm volatile("" ::: "memory");
-    }
+            const double xc = x[c] * Ys[c];                              // X[c][t], final; zero for t > c
+            Xb[(uint64_t)c * ld + r] = xc;
+            if (c + 1 < NB) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i) Xb[(uint64_t)i * kp + r] = x[i];
+                for (int q0 = (c + 1) & ~1; q0 < NB; q0 += 2) {
+                    const f64x2 l = *reinterpret_cast<const f64x2*>(&Lc[c][q0]);      // l[q0][c], l[q0 + 1][c]
+                    if (q0 > c) x[q0] = fma(-l.x, xc, x[q0]);
+                    x[q0 + 1] = fma(-l.y, xc, x[q0 + 1]);
+                    if ((q0 & 14) == 14) asm volatile("" ::: "memory");
+                }
+            }
+            asm volatile("" ::: "memory");
+        }
+    }
 }
 
 // C = alpha * A B + beta * C in fp64 with v_mfma_f64_16x16x4_f64.  A is M x K, B is K x N, C is M x N, each given
@@ -183,9 +204,10 @@ __global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
     int ai, ak, bi, bk;                       // first (i, k) element of this thread, 4 elements along the contiguous dimension
     if (a_k_contig) { ai = tid >> 2; ak = (tid & 3) * 4; } else { ak = tid >> 4; ai = (tid & 15) * 4; }
     if (b_k_contig) { bi = tid >> 2; bk = (tid & 3) * 4; } else { bk = tid >> 4; bi = (tid & 15) * 4; }
+    // a thread's 4 elements are adjacent in memory (the host checks that each operand has a unit stride and 32-byte
+    // aligned rows): one 32-byte load instead of four 8-byte ones, whole 128-byte lines per wavefront instruction
     const double* ap = A + (int64_t)(m0 + ai) * g.rsA + (int64_t)ak * g.csA;
     const double* bp = B + (int64_t)bk * g.rsB + (int64_t)(n0 + bi) * g.csB;
-    const int64_t a_step = a_k_contig ? g.csA : g.rsA, b_step = b_k_contig ? g.rsB : g.csB;
 
     f64x4 acc[2][2];
 #pragma unroll
@@ -193,13 +215,10 @@ __global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-    double ra[4], rb[4];
+    f64x4 ra, rb;
     auto fetch = [&](uint32_t k0) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            ra[q] = ap[(int64_t)k0 * g.csA + q * a_step];
-            rb[q] = bp[(int64_t)k0 * g.rsB + q * b_step];
-        }
+        ra = *reinterpret_cast<const f64x4*>(ap + (int64_t)k0 * g.csA);
+        rb = *reinterpret_cast<const f64x4*>(bp + (int64_t)k0 * g.rsB);
     };
     if (kb < ke) fetch(kb);
     for (uint32_t k0 = kb; k0 < ke; k0 += 16) {
@@ -249,13 +268,197 @@ __global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
             }
 }
 
-// W[a][b] = (float) S[max(a,b)][min(a,b)] for the leading k x k part of a kp x kp matrix whose lower triangle is valid.
-__global__ void __launch_bounds__(256) fim_store_kernel(const double* S, uint32_t kp, uint32_t k, float* W, uint64_t ldw) {
+// The product for K = 64 exactly (the panel scaling and the rank-64 updates inside an outer block of the
+// factorisation): such a launch is a few tiles deep and its time is memory latency, so a tile asks for everything it
+// needs at once - all four K steps of both operands and, for beta != 0, its tile of C - and then runs the steps out of
+// registers.  beta != 0 requires alpha = -1 or 1 (the accumulators start from C * beta / alpha, exact for those).
+__global__ void __launch_bounds__(256) dgemm_k64_kernel(DgemmArgs g) {
+    __shared__ double As[16][kDLd];
+    __shared__ double Bs[16][kDLd];
+    const uint32_t m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    if ((g.flags & LOWER_TILES) && n0 > m0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const double* A = g.A + (int64_t)blockIdx.z * g.bsA;
+    const double* B = g.B + (int64_t)blockIdx.z * g.bsB;
+    double* C = g.C + (int64_t)blockIdx.z * g.bsC;
+    const bool a_k_contig = g.csA == 1, b_k_contig = g.rsB == 1;
+    int ai, ak, bi, bk;
+    if (a_k_contig) { ai = tid >> 2; ak = (tid & 3) * 4; } else { ak = tid >> 4; ai = (tid & 15) * 4; }
+    if (b_k_contig) { bi = tid >> 2; bk = (tid & 3) * 4; } else { bk = tid >> 4; bi = (tid & 15) * 4; }
+    const double* ap = A + (int64_t)(m0 + ai) * g.rsA + (int64_t)ak * g.csA;
+    const double* bp = B + (int64_t)bk * g.rsB + (int64_t)(n0 + bi) * g.csB;
+    f64x4 ra[4], rb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        ra[s] = *reinterpret_cast<const f64x4*>(ap + (int64_t)(16 * s) * g.csA);
+        rb[s] = *reinterpret_cast<const f64x4*>(bp + (int64_t)(16 * s) * g.rsB);
+    }
+    f64x4 acc[2][2];
+    const double c_scale = g.beta / g.alpha;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t row = m0 + wm * 32 + i * 16 + 4 * e + (lane >> 4);
+                const uint32_t col = n0 + wn * 32 + j * 16 + (lane & 15);
+                acc[i][j][e] = g.beta != 0.0 ? c_scale * C[(int64_t)row * g.rsC + (int64_t)col * g.csC] : 0.0;
+            }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+        if (s) __syncthreads();                            // previous step's reads are done
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (a_k_contig) As[ak + q][ai] = ra[s][q]; else As[ak][ai + q] = ra[s][q];
+            if (b_k_contig) Bs[bk + q][bi] = rb[s][q]; else Bs[bk][bi + q] = rb[s][q];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; kk += 4) {
+            const int kr = kk + (lane >> 4);
+            double fa[2], fb[2];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = As[kr][wm * 32 + i * 16 + (lane & 15)];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) fb[j] = Bs[kr][wn * 32 + j * 16 + (lane & 15)];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 2; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t row = m0 + wm * 32 + i * 16 + 4 * e + (lane >> 4);
+                const uint32_t col = n0 + wn * 32 + j * 16 + (lane & 15);
+                C[(int64_t)row * g.rsC + (int64_t)col * g.csC] = g.alpha * acc[i][j][e];
+            }
+}
+
+// The same product with a 128 x 128 tile per workgroup: 8 wavefronts of 32 x 64 (2 x 4 MFMA blocks), K steps of 16
+// through two LDS stages (k-major, row stride 144 doubles), the next step's operands prefetched in registers, one
+// barrier per step.  A 64 x 64 tile moves 16 bytes per 128 flops from L2 to LDS, which bounds it near 20 TFLOP/s on this
+// chip whatever the matrix cores could do; this one moves half of that.  M and N may be any multiples of 64 (rows and
+// columns of a half-empty edge tile are loaded from the last valid row / column and never stored); the structure
+// flags mean the same, with K_TO_ROW ending the range at the end of the tile's 128 rows.
+constexpr int kD2Ld = 144;
+constexpr int kD2Stage = 2 * 16 * kD2Ld;          // doubles per LDS stage: A then B
+
+__global__ void __launch_bounds__(512) dgemm128_kernel(DgemmArgs g) {
+    extern __shared__ __align__(16) double d2s[];
+    const uint32_t m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
+    if ((g.flags & LOWER_TILES) && n0 > m0) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts of 32 x 64
+    const double* A = g.A + (int64_t)blockIdx.z * g.bsA;
+    const double* B = g.B + (int64_t)blockIdx.z * g.bsB;
+
+    uint32_t kb = 0, ke = g.K;
+    if ((g.flags & K_FROM_ROW) && m0 > kb) kb = m0;
+    if ((g.flags & K_FROM_COL) && n0 > kb) kb = n0;
+    if ((g.flags & K_TO_ROW) && m0 + 128 < ke) ke = m0 + 128;
+
+    // staging map: 128 x 16 elements per operand and step, 4 per thread along the operand's contiguous direction
+    const bool a_k_contig = g.csA == 1, b_k_contig = g.rsB == 1;
+    int ai, ak, bi, bk;
+    if (a_k_contig) { ai = tid >> 2; ak = (tid & 3) * 4; } else { ak = tid >> 5; ai = (tid & 31) * 4; }
+    if (b_k_contig) { bi = tid >> 2; bk = (tid & 3) * 4; } else { bk = tid >> 5; bi = (tid & 31) * 4; }
+    // rows / columns past the edge re-read the last valid one (their results are not stored)
+    // (M and N are multiples of 64, so a thread's group of 4 is all in or all out).  The 4 elements of a thread are
+    // adjacent in memory: one 32-byte load each.
+    uint32_t ia = m0 + ai, nb = n0 + bi;
+    if (ia >= g.M) ia = g.M - 4;
+    if (nb >= g.N) nb = g.N - 4;
+    const double* ap = A + (int64_t)ia * g.rsA + (int64_t)ak * g.csA;
+    const double* bp = B + (int64_t)bk * g.rsB + (int64_t)nb * g.csB;
+
+    f64x4 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
+
+    f64x4 ra, rb;
+    auto fetch = [&](uint32_t k0) {
+        ra = *reinterpret_cast<const f64x4*>(ap + (int64_t)k0 * g.csA);
+        rb = *reinterpret_cast<const f64x4*>(bp + (int64_t)k0 * g.rsB);
+    };
+    auto stash = [&](int stage) {
+        double* As = d2s + stage * kD2Stage;
+        double* Bs = As + 16 * kD2Ld;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            if (a_k_contig) As[(ak + q) * kD2Ld + ai] = ra[q]; else As[ak * kD2Ld + ai + q] = ra[q];
+            if (b_k_contig) Bs[(bk + q) * kD2Ld + bi] = rb[q]; else Bs[bk * kD2Ld + bi + q] = rb[q];
+        }
+    };
+    if (kb < ke) {                                           // uniform
+        fetch(kb);
+        stash(0);
+    }
+    __syncthreads();
+    int cur = 0;
+    for (uint32_t k0 = kb; k0 < ke; k0 += 16) {
+        const bool more = k0 + 16 < ke;                      // uniform
+        if (more) fetch(k0 + 16);
+        const double* As = d2s + cur * kD2Stage;
+        const double* Bs = As + 16 * kD2Ld;
+#pragma unroll
+        for (int kk = 0; kk < 16; kk += 4) {
+            const int kr = kk + (lane >> 4);
+            double fa[2], fb[4];
+#pragma unroll
+            for (int i = 0; i < 2; ++i) fa[i] = As[kr * kD2Ld + wm * 32 + i * 16 + (lane & 15)];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) fb[j] = Bs[kr * kD2Ld + wn * 64 + j * 16 + (lane & 15)];
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+        }
+        if (more) stash(cur ^ 1);
+        __syncthreads();          // the other stage is complete, and everybody is done reading this one
+        cur ^= 1;
+    }
+
+    // accumulator element e of a lane: row 4*e + lane/16, column lane%16 of the 16 x 16 block
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t row = m0 + wm * 32 + i * 16 + 4 * e + (lane >> 4);
+                const uint32_t col = n0 + wn * 64 + j * 16 + (lane & 15);
+                if (row >= g.M || col >= g.N) continue;
+                double v = g.alpha * acc[i][j][e];
+                if (g.Cf) {
+                    float* c = g.Cf + (int64_t)blockIdx.z * g.bsC;
+                    c[(int64_t)row * g.rsC + (int64_t)col * g.csC] = (float)v;
+                    if ((g.flags & MIRROR) && m0 != n0) c[(int64_t)col * g.rsC + (int64_t)row * g.csC] = (float)v;
+                } else {
+                    double* c = g.C + (int64_t)blockIdx.z * g.bsC + (int64_t)row * g.rsC + (int64_t)col * g.csC;
+                    if (g.beta != 0.0) v += g.beta * *c;
+                    *c = v;
+                }
+            }
+}
+
+// W[a][b] = (float) S[max(a,b)][min(a,b)] for the leading k x k part of a matrix (row distance ld) whose lower triangle is valid.
+__global__ void __launch_bounds__(256) fim_store_kernel(const double* S, uint32_t ld, uint32_t k, float* W, uint64_t ldw) {
     const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= (uint64_t)k * k) return;
     const uint32_t a = (uint32_t)(t / k), b = (uint32_t)(t - (uint64_t)a * k);
     const uint32_t hi = a > b ? a : b, lo = a > b ? b : a;
-    W[(uint64_t)a * ldw + b] = (float)S[(uint64_t)hi * kp + lo];
+    W[(uint64_t)a * ldw + b] = (float)S[(uint64_t)hi * ld + lo];
 }
 
 __global__ void fill_i32_kernel(int* p, int count, int value) {
@@ -265,11 +468,33 @@ __global__ void fill_i32_kernel(int* p, int count, int value) {
 static hipError_t dgemm(const DgemmArgs& g, uint32_t batch, hipStream_t st) {
     if (g.M == 0 || g.N == 0 || batch == 0) return hipSuccess;
     if (g.M % 64 || g.N % 64 || g.K % 64) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(dgemm_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
+    // the kernels load 4 adjacent doubles at once: one unit stride per operand, the other stride and the base keep
+    // 32-byte alignment
+    const bool a_ok = (g.csA == 1 && g.rsA % 4 == 0) || (g.rsA == 1 && g.csA % 4 == 0);
+    const bool b_ok = (g.rsB == 1 && g.csB % 4 == 0) || (g.csB == 1 && g.rsB % 4 == 0);
+    if (!a_ok || !b_ok || !aligned(g.A, 32) || !aligned(g.B, 32) || g.bsA % 4 || g.bsB % 4) return hipErrorInvalidValue;
+    if (g.K == 64 && !g.Cf && (g.flags & ~LOWER_TILES) == 0 && (g.beta == 0.0 || g.alpha == 1.0 || g.alpha == -1.0)) {
+        hipLaunchKernelGGL(dgemm_k64_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
+        return hipGetLastError();
+    }
+    // The larger tile pays only where there are enough of them to keep every CU busy
+    const uint64_t t128 = (uint64_t)((g.M + 127) / 128) * ((g.N + 127) / 128) * batch;
+    if (g.M >= 128 && g.N >= 128 && t128 >= 4096) {
+        static LdsOptIn opt_in;
+        const size_t lds_bytes = (size_t)2 * kD2Stage * sizeof(double);
+        hipError_t e = allow_large_lds(opt_in, reinterpret_cast<const void*>(dgemm128_kernel));
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(dgemm128_kernel, dim3((g.N + 127) / 128, (g.M + 127) / 128, batch), dim3(512), lds_bytes, st, g);
+    } else {
+        hipLaunchKernelGGL(dgemm_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
+    }
     return hipGetLastError();
 }
 
 static uint32_t padded(uint32_t k) { return (k + NB - 1) / NB * NB; }
+// Row distance of the fp64 work matrices: 16 doubles (one 128-byte line) more than the padded size.  With a power-of-two
+// row distance (k = 4,096: 32 KB) the rows of an operand tile all fall on the same memory channels.
+static uint32_t row_distance(uint32_t kp) { return kp + 16; }
 
 }  // namespace grass
 
@@ -367,7 +592,7 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
 extern "C" grass_status grass_fim_inverse_workspace_bytes(uint32_t k, size_t* host_bytes) {
     if (!host_bytes || k == 0) return GRASS_EINVAL;
     const size_t kp = padded(k);
-    *host_bytes = 2 * kp * kp * sizeof(double);
+    *host_bytes = 2 * kp * row_distance((uint32_t)kp) * sizeof(double);
     return GRASS_OK;
 }
 
@@ -377,36 +602,54 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
     if (!F || !W || ldf < k || ldw < k) return GRASS_EINVAL;
     if (k > 32768) return GRASS_EUNSUPPORTED;
     const uint32_t kp = padded(k), nblk = kp / NB;
-    const size_t mat = (size_t)kp * kp * sizeof(double);
+    const int64_t ld = row_distance(kp);
+    const size_t mat = (size_t)kp * ld * sizeof(double);
     if (!ws || ws_bytes < 2 * mat || !aligned(ws, 256)) return GRASS_EWORKSPACE;
     double* A64 = static_cast<double*>(ws);
-    double* X64 = A64 + (size_t)kp * kp;
+    double* X64 = A64 + (size_t)kp * ld;
     hipStream_t hs = as_stream(stream);
-    const int64_t ld = kp;
 
     if (info) hipLaunchKernelGGL(fill_i32_kernel, dim3(1), dim3(64), 0, hs, info, 1, 0);
     hipLaunchKernelGGL(fim_load_kernel, dim3((uint32_t)ceil_div((uint64_t)kp * kp, 256)), dim3(256), 0, hs, F, ldf, k, lambda,
-                       A64, X64, kp);
+                       A64, X64, kp, (uint32_t)ld);
 
-    // right-looking blocked Cholesky: A = L L^T, L overwrites the lower triangle of A64
+    // Blocked Cholesky, A = L L^T, L overwrites the lower triangle of A64.  Two levels: inside an outer block of kOuter
+    // diagonal blocks (256 columns) every factorised 64-column panel updates the remaining columns of the outer block
+    // only (right-looking, K = 64, a few tiles per row); the rest of the matrix receives the whole outer block at once
+    // (K = 256).  A rank-64 update of the full trailing matrix moves 16 bytes of C per 128 flops and was bound by that
+    // traffic (58 us for the first one, 1.8 ms over the factorisation); with K = 256 it is a quarter of it.
+    constexpr uint32_t kOuter = 4;
     for (uint32_t j = 0; j < nblk; ++j) {
-        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(64), 0, hs, A64, X64, kp, j, info);
+        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(128), 0, hs, A64, X64, (uint32_t)ld, j, info);
         const uint32_t below = kp - (j + 1) * NB;
         if (below == 0) break;
-        double* panel = A64 + (size_t)(j + 1) * NB * kp + (size_t)j * NB;
-        const double* D = X64 + (size_t)j * NB * kp + (size_t)j * NB;
+        double* panel = A64 + (size_t)(j + 1) * NB * ld + (size_t)j * NB;
+        const double* D = X64 + (size_t)j * NB * ld + (size_t)j * NB;
         DgemmArgs p{};                                     // panel <- panel * D^T   (in place: one tile per 64 rows)
         p.A = panel; p.rsA = ld; p.csA = 1;
         p.B = D; p.rsB = 1; p.csB = ld;                     // B[kk][n] = D[n][kk]
         p.C = panel; p.rsC = ld; p.csC = 1;
         p.M = below; p.N = NB; p.K = NB; p.alpha = 1.0; p.beta = 0.0; p.flags = 0;
         if (dgemm(p, 1, hs) != hipSuccess) return GRASS_EHIP;
-        DgemmArgs u{};                                     // trailing lower triangle -= panel * panel^T
-        u.A = panel; u.rsA = ld; u.csA = 1;
-        u.B = panel; u.rsB = 1; u.csB = ld;
-        u.C = A64 + (size_t)(j + 1) * NB * kp + (size_t)(j + 1) * NB; u.rsC = ld; u.csC = 1;
-        u.M = below; u.N = below; u.K = NB; u.alpha = -1.0; u.beta = 1.0; u.flags = LOWER_TILES;
-        if (dgemm(u, 1, hs) != hipSuccess) return GRASS_EHIP;
+        const uint32_t outer_end = (j / kOuter + 1) * kOuter < nblk ? (j / kOuter + 1) * kOuter : nblk;   // first block after this outer block
+        const uint32_t inner_cols = (outer_end - (j + 1)) * NB;
+        if (inner_cols > 0) {                              // remaining columns of the outer block -= panel * panel^T
+            DgemmArgs u{};
+            u.A = panel; u.rsA = ld; u.csA = 1;
+            u.B = panel; u.rsB = 1; u.csB = ld;
+            u.C = A64 + (size_t)(j + 1) * NB * ld + (size_t)(j + 1) * NB; u.rsC = ld; u.csC = 1;
+            u.M = below; u.N = inner_cols; u.K = NB; u.alpha = -1.0; u.beta = 1.0; u.flags = LOWER_TILES;
+            if (dgemm(u, 1, hs) != hipSuccess) return GRASS_EHIP;
+        } else if (outer_end < nblk) {                     // the outer block is complete: the rest -= P * P^T, P its rows below
+            const uint32_t c0 = (outer_end - kOuter) * NB, r0 = outer_end * NB;
+            const double* P = A64 + (size_t)r0 * ld + c0;
+            DgemmArgs u{};
+            u.A = P; u.rsA = ld; u.csA = 1;
+            u.B = P; u.rsB = 1; u.csB = ld;
+            u.C = A64 + (size_t)r0 * ld + r0; u.rsC = ld; u.csC = 1;
+            u.M = kp - r0; u.N = kp - r0; u.K = kOuter * NB; u.alpha = -1.0; u.beta = 1.0; u.flags = LOWER_TILES;
+            if (dgemm(u, 1, hs) != hipSuccess) return GRASS_EHIP;
+        }
     }
 
     // X = L^{-1} by doubling: with the inverses X11, X22 of two adjacent diagonal blocks of size b in place,
@@ -421,15 +664,15 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
             const size_t o = pass == 0 ? 0 : (size_t)full * 2 * b;
             const int64_t bs = (int64_t)2 * b * (ld + 1);  // next pair: 2b down the diagonal
             DgemmArgs t{};                                 // T (M2 x b) = L21 * X11, X11 lower: k >= n0
-            t.A = A64 + (o + b) * kp + o; t.rsA = ld; t.csA = 1; t.bsA = bs;
-            t.B = X64 + o * kp + o; t.rsB = ld; t.csB = 1; t.bsB = bs;
-            t.C = A64 + o * kp + (o + b); t.rsC = 1; t.csC = ld; t.bsC = bs;      // T[r][c] at A64[o+c][o+b+r]
+            t.A = A64 + (o + b) * ld + o; t.rsA = ld; t.csA = 1; t.bsA = bs;
+            t.B = X64 + o * ld + o; t.rsB = ld; t.csB = 1; t.bsB = bs;
+            t.C = A64 + o * ld + (o + b); t.rsC = 1; t.csC = ld; t.bsC = bs;      // T[r][c] at A64[o+c][o+b+r]
             t.M = M2; t.N = b; t.K = b; t.alpha = 1.0; t.beta = 0.0; t.flags = K_FROM_COL;
             if (dgemm(t, batch, hs) != hipSuccess) return GRASS_EHIP;
             DgemmArgs x{};                                 // X21 (M2 x b) = -X22 * T, X22 lower: k < m0 + 64
-            x.A = X64 + (o + b) * kp + (o + b); x.rsA = ld; x.csA = 1; x.bsA = bs;
-            x.B = A64 + o * kp + (o + b); x.rsB = 1; x.csB = ld; x.bsB = bs;      // B[kk][n] = T[kk][n]
-            x.C = X64 + (o + b) * kp + o; x.rsC = ld; x.csC = 1; x.bsC = bs;
+            x.A = X64 + (o + b) * ld + (o + b); x.rsA = ld; x.csA = 1; x.bsA = bs;
+            x.B = A64 + o * ld + (o + b); x.rsB = 1; x.csB = ld; x.bsB = bs;      // B[kk][n] = T[kk][n]
+            x.C = X64 + (o + b) * ld + o; x.rsC = ld; x.csC = 1; x.bsC = bs;
             x.M = M2; x.N = b; x.K = M2; x.alpha = -1.0; x.beta = 0.0; x.flags = K_TO_ROW;
             if (dgemm(x, batch, hs) != hipSuccess) return GRASS_EHIP;
         }
@@ -450,7 +693,7 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
         w.C = A64; w.rsC = ld; w.csC = 1;
         w.M = kp; w.N = kp; w.K = kp; w.alpha = 1.0; w.beta = 0.0; w.flags = K_FROM_ROW | LOWER_TILES;
         if (dgemm(w, 1, hs) != hipSuccess) return GRASS_EHIP;
-        hipLaunchKernelGGL(fim_store_kernel, dim3((uint32_t)ceil_div((uint64_t)k * k, 256)), dim3(256), 0, hs, A64, kp, k, W,
+        hipLaunchKernelGGL(fim_store_kernel, dim3((uint32_t)ceil_div((uint64_t)k * k, 256)), dim3(256), 0, hs, A64, (uint32_t)ld, k, W,
                            ldw);
     }
     return launch_status();
