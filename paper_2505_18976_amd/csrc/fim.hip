@@ -84,20 +84,19 @@ __device__ __forceinline__ double lane_bcast(double v, int src) {
 // column the compiler sank the trailing updates of far columns across 30 to 40 basic blocks towards their use and
 // spilled 2,200 registers to scratch.  The empty asm statements bound how far it may move LDS reads.
 struct f64x2 { double x, y; };
-__global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X64, uint32_t ld, uint32_t j, int* info) {
-    __shared__ __align__(16) double Lc[NB][NB];          // Lc[c][q] = L[q][c]: column c contiguous
-    __shared__ __align__(16) double Ys[NB];              // 1 / L[c][c]
-    __shared__ int columns_done;
+// The two wavefronts' work, for threads 0..127 of a workgroup.  `tile` is the block to factorise (row distance
+// tile_ld, global memory or LDS); its factor goes to Lout (row distance ld, global; may be null: nobody needs the
+// diagonal blocks of L once their inverses exist) and the inverse to Xb (row distance ld, global).  *columns_done
+// must be 0 and visible to both wavefronts (a barrier after it is set) on entry; no barrier inside.
+__device__ __forceinline__ void potrf_two_wavefronts(double (*Lc)[NB], double* Ys, int* columns_done, const double* tile,
+                                                     uint32_t tile_ld, double* Lout, double* Xb, uint32_t ld,
+                                                     uint32_t j, int* info) {
     const int r = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    double* Ab = A64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
-    double* Xb = X64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
-    if (threadIdx.x == 0) columns_done = 0;
-    __syncthreads();
     if (wave == 0) {
         double a[NB];
 #pragma unroll
-        for (int q = 0; q < NB; ++q) a[q] = Ab[(uint64_t)r * ld + q];
+        for (int q = 0; q < NB; ++q) a[q] = tile[(uint64_t)r * tile_ld + q];
         int bad = 0;
 #pragma unroll
         for (int c = 0; c < NB; ++c) {
@@ -112,7 +111,7 @@ __global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X
             const double lc = r == c ? pv * y : (r > c ? a[c] * y : 0.0);
             a[c] = lc;
             Lc[c][r] = lc;                                               // LDS operations of one wavefront stay in order
-            __hip_atomic_store(&columns_done, c + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
+            __hip_atomic_store(columns_done, c + 1, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
             if (c + 1 < NB) {
 #pragma unroll
                 for (int q0 = (c + 1) & ~1; q0 < NB; q0 += 2) {          // pairs (q0, q0 + 1), q0 even
@@ -125,16 +124,18 @@ __global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X
             asm volatile("" ::: "memory");
         }
         if (r == 0 && bad != 0 && info) atomicCAS(info, 0, (int)(j * NB) + bad);
+        if (Lout) {
 #pragma unroll
-        for (int q = 0; q < NB; ++q) Ab[(uint64_t)r * ld + q] = q <= r ? a[q] : 0.0;
-    } else {
-        const uint32_t done_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)&columns_done;   // LDS offset
+            for (int q = 0; q < NB; ++q) Lout[(uint64_t)r * ld + q] = q <= r ? a[q] : 0.0;
+        }
+    } else if (wave == 1) {
+        const uint32_t done_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) int*)columns_done;   // LDS offset
         double x[NB];
 #pragma unroll
         for (int q = 0; q < NB; ++q) x[q] = q == r ? 1.0 : 0.0;
 #pragma unroll
         for (int c = 0; c < NB; ++c) {
-            // wait until columns_done > c.  The polling loop lives inside one asm statement: as a loop of the C++
+            // wait until *columns_done > c.  The polling loop lives inside one asm statement: as a loop of the C++
             // source it would split every unrolled step into basic blocks (see above).  The value read stays inside
             // the statement and has arrived (lgkmcnt(0)) before the statement ends.
             {
@@ -163,6 +164,17 @@ __global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X
             asm volatile("" ::: "memory");
         }
     }
+}
+
+__global__ void __launch_bounds__(128) potrf_block_kernel(double* A64, double* X64, uint32_t ld, uint32_t j, int* info) {
+    __shared__ __align__(16) double Lc[NB][NB];          // Lc[c][q] = L[q][c]: column c contiguous
+    __shared__ __align__(16) double Ys[NB];              // 1 / L[c][c]
+    __shared__ int columns_done;
+    double* Ab = A64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
+    double* Xb = X64 + ((uint64_t)j * NB) * ld + (uint64_t)j * NB;
+    if (threadIdx.x == 0) columns_done = 0;
+    __syncthreads();
+    potrf_two_wavefronts(Lc, Ys, &columns_done, Ab, ld, nullptr, Xb, ld, j, info);
 }
 
 // C = alpha * A B + beta * C in fp64 with v_mfma_f64_16x16x4_f64.  A is M x K, B is K x N, C is M x N, each given
@@ -340,6 +352,125 @@ __global__ void __launch_bounds__(256) dgemm_k64_kernel(DgemmArgs g) {
                 const uint32_t col = n0 + wn * 32 + j * 16 + (lane & 15);
                 C[(int64_t)row * g.rsC + (int64_t)col * g.csC] = g.alpha * acc[i][j][e];
             }
+}
+
+// One step of the factorisation inside an outer block, fused into one launch because every dependent launch costs
+// about 6 us here whatever it computes: for the factorised diagonal block j (inverse D_j in X64) workgroup (m, n), n <= m,
+// of the grid (inner column blocks, row blocks below j)
+//   1. scales its two row blocks of the panel itself, P_m = A[m][j] D_j^T and P_n = A[n][j] D_j^T (the unscaled panel in
+//      A64 is only read in this launch; the workgroups of column 0 write P_m to the same block position of X64, where
+//      the lower blocks of L live from here on),
+//   2. updates its tile, A[m][n] -= P_m P_n^T,
+//   3. and workgroup (0, 0), whose tile is the next diagonal block, goes on to factorise and invert it
+//      (potrf_two_wavefronts out of LDS), so the next step can start right away.
+// Everything a tile needs (two panel blocks, D_j, its tile of A) is requested at the start.  All blocks are 64 x 64.
+constexpr int kStepBuf = 64 * kDLd;                    // doubles per LDS operand buffer ([k][row], 64 k)
+constexpr size_t kStepLdsBytes = (size_t)(3 * kStepBuf + NB) * sizeof(double) + 16;
+
+__global__ void __launch_bounds__(256) chol_step_kernel(double* A64, double* X64, uint32_t ld, uint32_t j, int* info) {
+    extern __shared__ __align__(16) double step_lds[];
+    const uint32_t m = blockIdx.y, n = blockIdx.x;
+    if (n > m) return;
+    double* buf0 = step_lds;
+    double* buf1 = step_lds + kStepBuf;
+    double* buf2 = step_lds + 2 * kStepBuf;
+    double* Ys = step_lds + 3 * kStepBuf;
+    int* columns_done = reinterpret_cast<int*>(Ys + NB);
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const uint64_t j0 = (uint64_t)j * NB, j1 = j0 + NB;
+    const double* Am = A64 + (j1 + (uint64_t)m * NB) * ld + j0;
+    const double* An = A64 + (j1 + (uint64_t)n * NB) * ld + j0;
+    const double* Dj = X64 + j0 * ld + j0;
+    double* Ct = A64 + (j1 + (uint64_t)m * NB) * ld + j1 + (uint64_t)n * NB;
+    const bool square = m == n;                        // uniform: P_n is P_m
+
+    // row-major 64 x 64 blocks: thread -> row tid/4, columns (tid%4)*4 + 16 s .. + 3
+    const int srow = tid >> 2, scol = (tid & 3) * 4;
+    f64x4 ra[4], rn[4], rd[4];
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4) {
+        ra[s4] = *reinterpret_cast<const f64x4*>(Am + (uint64_t)srow * ld + scol + 16 * s4);
+        rd[s4] = *reinterpret_cast<const f64x4*>(Dj + (uint64_t)srow * ld + scol + 16 * s4);
+        rn[s4] = *reinterpret_cast<const f64x4*>(An + (uint64_t)srow * ld + scol + 16 * s4);
+    }
+    // accumulator element e of block (bi, bj): row wm*32 + bi*16 + 4e + lane/16, column wn*32 + bj*16 + lane%16
+    f64x4 accC[2][2];
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = wm * 32 + bi * 16 + 4 * e + (lane >> 4), col = wn * 32 + bj * 16 + (lane & 15);
+                accC[bi][bj][e] = -Ct[(uint64_t)row * ld + col];       // result = -(-C + P_m P_n^T)
+            }
+#pragma unroll
+    for (int s4 = 0; s4 < 4; ++s4)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int k = scol + 16 * s4 + q;
+            buf0[k * kDLd + srow] = ra[s4][q];                          // [k][i]  = A[m][i][k]
+            buf1[k * kDLd + srow] = rn[s4][q];
+            buf2[k * kDLd + srow] = rd[s4][q];                          // [k][n'] = D[n'][k]
+        }
+    __syncthreads();
+    auto product = [&](const double* Aop, const double* Bop, f64x4 (&acc)[2][2]) {      // acc += Aop^T-layout x Bop, K = 64
+#pragma unroll
+        for (int kk = 0; kk < NB; kk += 4) {
+            const int kr = kk + (lane >> 4);
+            double fa[2], fb[2];
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi) fa[bi] = Aop[kr * kDLd + wm * 32 + bi * 16 + (lane & 15)];
+#pragma unroll
+            for (int bj = 0; bj < 2; ++bj) fb[bj] = Bop[kr * kDLd + wn * 32 + bj * 16 + (lane & 15)];
+#pragma unroll
+            for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+                for (int bj = 0; bj < 2; ++bj)
+                    acc[bi][bj] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[bi], fb[bj], acc[bi][bj], 0, 0, 0);
+        }
+    };
+    f64x4 accP[2][2], accQ[2][2];
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj) { accP[bi][bj] = f64x4{0.0, 0.0, 0.0, 0.0}; accQ[bi][bj] = f64x4{0.0, 0.0, 0.0, 0.0}; }
+    product(buf0, buf2, accP);                                           // P_m = A_m D^T
+    if (!square) product(buf1, buf2, accQ);                              // P_n = A_n D^T
+    __syncthreads();                                                     // everybody is done reading the operands
+    double* Pout = X64 + (j1 + (uint64_t)m * NB) * ld + j0;
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = wm * 32 + bi * 16 + 4 * e + (lane >> 4), col = wn * 32 + bj * 16 + (lane & 15);
+                buf0[col * kDLd + row] = accP[bi][bj][e];                // [k][i] = P_m[i][k]
+                if (!square) buf1[col * kDLd + row] = accQ[bi][bj][e];   // [k][n] = P_n[n][k]
+                if (n == 0) Pout[(uint64_t)row * ld + col] = accP[bi][bj][e];
+            }
+    __syncthreads();
+    product(buf0, square ? buf0 : buf1, accC);
+    const bool next_diagonal = m == 0;                                   // (0, 0): uniform
+#pragma unroll
+    for (int bi = 0; bi < 2; ++bi)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int row = wm * 32 + bi * 16 + 4 * e + (lane >> 4), col = wn * 32 + bj * 16 + (lane & 15);
+                const double v = -accC[bi][bj][e];
+                Ct[(uint64_t)row * ld + col] = v;
+                if (next_diagonal) buf2[row * kDLd + col] = v;           // row-major copy for the factorisation
+            }
+    if (!next_diagonal) return;
+    if (tid == 0) *columns_done = 0;
+    __syncthreads();                                                     // the tile copy and the counter are visible; buf0 is free
+    if (tid < 128)
+        potrf_two_wavefronts(reinterpret_cast<double (*)[NB]>(buf0), Ys, columns_done, buf2, kDLd, nullptr,
+                             X64 + j1 * ld + j1, ld, j + 1, info);
 }
 
 // The same product with a 128 x 128 tile per workgroup: 8 wavefronts of 32 x 64 (2 x 4 MFMA blocks), K steps of 16
@@ -619,30 +750,36 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
     // (K = 256).  A rank-64 update of the full trailing matrix moves 16 bytes of C per 128 flops and was bound by that
     // traffic (58 us for the first one, 1.8 ms over the factorisation); with K = 256 it is a quarter of it.
     constexpr uint32_t kOuter = 4;
+    static LdsOptIn step_opt_in;
+    if (allow_large_lds(step_opt_in, reinterpret_cast<const void*>(chol_step_kernel)) != hipSuccess) return GRASS_EHIP;
+    bool factorised = false;                               // block j already factorised by the step before it
     for (uint32_t j = 0; j < nblk; ++j) {
-        hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(128), 0, hs, A64, X64, (uint32_t)ld, j, info);
+        if (!factorised)
+            hipLaunchKernelGGL(potrf_block_kernel, dim3(1), dim3(128), 0, hs, A64, X64, (uint32_t)ld, j, info);
+        factorised = false;
         const uint32_t below = kp - (j + 1) * NB;
         if (below == 0) break;
-        double* panel = A64 + (size_t)(j + 1) * NB * ld + (size_t)j * NB;
-        const double* D = X64 + (size_t)j * NB * ld + (size_t)j * NB;
-        DgemmArgs p{};                                     // panel <- panel * D^T   (in place: one tile per 64 rows)
-        p.A = panel; p.rsA = ld; p.csA = 1;
-        p.B = D; p.rsB = 1; p.csB = ld;                     // B[kk][n] = D[n][kk]
-        p.C = panel; p.rsC = ld; p.csC = 1;
+        const uint32_t outer_end = (j / kOuter + 1) * kOuter < nblk ? (j / kOuter + 1) * kOuter : nblk;   // first block after this outer block
+        const uint32_t inner_blocks = outer_end - (j + 1);
+        if (inner_blocks > 0) {
+            // panel scaling, update of the remaining columns of the outer block, factorisation of block j + 1
+            hipLaunchKernelGGL(chol_step_kernel, dim3(inner_blocks, below / NB), dim3(256), kStepLdsBytes, hs, A64, X64,
+                               (uint32_t)ld, j, info);
+            if (hipGetLastError() != hipSuccess) return GRASS_EHIP;
+            factorised = true;
+            continue;
+        }
+        // last block of the outer block: scaled panel (into X64), then the rest of the matrix -= P P^T with P the
+        // rows of the whole outer block below it
+        DgemmArgs p{};
+        p.A = A64 + (size_t)(j + 1) * NB * ld + (size_t)j * NB; p.rsA = ld; p.csA = 1;
+        p.B = X64 + (size_t)j * NB * ld + (size_t)j * NB; p.rsB = 1; p.csB = ld;          // B[kk][n] = D[n][kk]
+        p.C = X64 + (size_t)(j + 1) * NB * ld + (size_t)j * NB; p.rsC = ld; p.csC = 1;
         p.M = below; p.N = NB; p.K = NB; p.alpha = 1.0; p.beta = 0.0; p.flags = 0;
         if (dgemm(p, 1, hs) != hipSuccess) return GRASS_EHIP;
-        const uint32_t outer_end = (j / kOuter + 1) * kOuter < nblk ? (j / kOuter + 1) * kOuter : nblk;   // first block after this outer block
-        const uint32_t inner_cols = (outer_end - (j + 1)) * NB;
-        if (inner_cols > 0) {                              // remaining columns of the outer block -= panel * panel^T
-            DgemmArgs u{};
-            u.A = panel; u.rsA = ld; u.csA = 1;
-            u.B = panel; u.rsB = 1; u.csB = ld;
-            u.C = A64 + (size_t)(j + 1) * NB * ld + (size_t)(j + 1) * NB; u.rsC = ld; u.csC = 1;
-            u.M = below; u.N = inner_cols; u.K = NB; u.alpha = -1.0; u.beta = 1.0; u.flags = LOWER_TILES;
-            if (dgemm(u, 1, hs) != hipSuccess) return GRASS_EHIP;
-        } else if (outer_end < nblk) {                     // the outer block is complete: the rest -= P * P^T, P its rows below
+        if (outer_end < nblk) {
             const uint32_t c0 = (outer_end - kOuter) * NB, r0 = outer_end * NB;
-            const double* P = A64 + (size_t)r0 * ld + c0;
+            const double* P = X64 + (size_t)r0 * ld + c0;
             DgemmArgs u{};
             u.A = P; u.rsA = ld; u.csA = 1;
             u.B = P; u.rsB = 1; u.csB = ld;
@@ -664,7 +801,7 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
             const size_t o = pass == 0 ? 0 : (size_t)full * 2 * b;
             const int64_t bs = (int64_t)2 * b * (ld + 1);  // next pair: 2b down the diagonal
             DgemmArgs t{};                                 // T (M2 x b) = L21 * X11, X11 lower: k >= n0
-            t.A = A64 + (o + b) * ld + o; t.rsA = ld; t.csA = 1; t.bsA = bs;
+            t.A = X64 + (o + b) * ld + o; t.rsA = ld; t.csA = 1; t.bsA = bs;      // L21 (scaled panels live in X64)
             t.B = X64 + o * ld + o; t.rsB = ld; t.csB = 1; t.bsB = bs;
             t.C = A64 + o * ld + (o + b); t.rsC = 1; t.csC = ld; t.bsC = bs;      // T[r][c] at A64[o+c][o+b+r]
             t.M = M2; t.N = b; t.K = b; t.alpha = 1.0; t.beta = 0.0; t.flags = K_FROM_COL;
