@@ -196,10 +196,23 @@ struct DgemmArgs {
 };
 constexpr int kDLd = 80;
 
+// Pipeline: the operands of the next four K steps travel in four rotating register sets (every tile's K range is a
+// multiple of 64, so the loop runs in rounds of four steps with static set numbers and unconditional loads, and the
+// compiler's wait counts leave the three newer sets in flight), two LDS stages, one barrier per step.  With one set
+// and two barriers per step the kernel needed eight workgroups per CU to cover the load latency, and the tiles with
+// the longest K range, each at an eighth of a CU's speed, set the time of the triangular products.
+// Workgroups are numbered so that the tiles with the longest K range start first (the hardware hands out workgroups
+// in launch order): by columns for K_FROM_COL, by rows from the bottom for K_TO_ROW, by rows from the top otherwise.
 __global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
-    __shared__ double As[16][kDLd];
-    __shared__ double Bs[16][kDLd];
-    const uint32_t m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    __shared__ double As[2][16][kDLd];
+    __shared__ double Bs[2][16][kDLd];
+    uint32_t tm = blockIdx.y, tn = blockIdx.x;
+    {
+        const uint32_t t = blockIdx.y * gridDim.x + blockIdx.x;
+        if (g.flags & K_FROM_COL) { tn = t / gridDim.y; tm = t % gridDim.y; }
+        else if (g.flags & K_TO_ROW) { tm = gridDim.y - 1 - blockIdx.y; }
+    }
+    const uint32_t m0 = tm * 64, n0 = tn * 64;
     if ((g.flags & LOWER_TILES) && n0 > m0) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -227,34 +240,46 @@ __global__ void __launch_bounds__(256) dgemm_kernel(DgemmArgs g) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
 
-    f64x4 ra, rb;
-    auto fetch = [&](uint32_t k0) {
-        ra = *reinterpret_cast<const f64x4*>(ap + (int64_t)k0 * g.csA);
-        rb = *reinterpret_cast<const f64x4*>(bp + (int64_t)k0 * g.rsB);
-    };
-    if (kb < ke) fetch(kb);
-    for (uint32_t k0 = kb; k0 < ke; k0 += 16) {
-        __syncthreads();                                   // previous step's reads are done
+    if (kb < ke) {                                              // uniform
+        const uint32_t klast = ke - 16;
+        f64x4 ra[4], rb[4];
+        auto fetch = [&](int set, uint32_t k0) {               // steps past the end re-read the last one (never used)
+            const uint32_t kq = k0 < klast ? k0 : klast;
+            ra[set] = *reinterpret_cast<const f64x4*>(ap + (int64_t)kq * g.csA);
+            rb[set] = *reinterpret_cast<const f64x4*>(bp + (int64_t)kq * g.rsB);
+        };
+        auto stash = [&](int set, int stage) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (a_k_contig) As[ak + q][ai] = ra[q]; else As[ak][ai + q] = ra[q];
-            if (b_k_contig) Bs[bk + q][bi] = rb[q]; else Bs[bk][bi + q] = rb[q];
-        }
+            for (int q = 0; q < 4; ++q) {
+                if (a_k_contig) As[stage][ak + q][ai] = ra[set][q]; else As[stage][ak][ai + q] = ra[set][q];
+                if (b_k_contig) Bs[stage][bk + q][bi] = rb[set][q]; else Bs[stage][bk][bi + q] = rb[set][q];
+            }
+        };
+#pragma unroll
+        for (int u = 0; u < 4; ++u) fetch(u, kb + 16 * u);
+        stash(0, 0);
         __syncthreads();
-        if (k0 + 16 < ke) fetch(k0 + 16);
+        for (uint32_t k0 = kb; k0 < ke; k0 += 64) {            // four steps per round; step u computes out of stage u & 1
 #pragma unroll
-        for (int kk = 0; kk < 16; kk += 4) {
-            const int kr = kk + (lane >> 4);
-            double fa[2], fb[2];
+            for (int u = 0; u < 4; ++u) {
+                fetch(u, k0 + 16 * (u + 4));                   // set u went to LDS one step ago
 #pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = As[kr][wm * 32 + i * 16 + (lane & 15)];
+                for (int kk = 0; kk < 16; kk += 4) {
+                    const int kr = kk + (lane >> 4);
+                    double fa[2], fb[2];
 #pragma unroll
-            for (int j = 0; j < 2; ++j) fb[j] = Bs[kr][wn * 32 + j * 16 + (lane & 15)];
+                    for (int i = 0; i < 2; ++i) fa[i] = As[u & 1][kr][wm * 32 + i * 16 + (lane & 15)];
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+                    for (int j = 0; j < 2; ++j) fb[j] = Bs[u & 1][kr][wn * 32 + j * 16 + (lane & 15)];
 #pragma unroll
-                for (int j = 0; j < 2; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    for (int i = 0; i < 2; ++i)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                }
+                stash((u + 1) & 3, (u + 1) & 1);               // the next step's operands (past the end: unused)
+                __syncthreads();                               // that stage is complete; everybody is done with this one
+            }
         }
     }
 
@@ -473,116 +498,6 @@ __global__ void __launch_bounds__(256) chol_step_kernel(double* A64, double* X64
                              X64 + j1 * ld + j1, ld, j + 1, info);
 }
 
-// The same product with a 128 x 128 tile per workgroup: 8 wavefronts of 32 x 64 (2 x 4 MFMA blocks), K steps of 16
-// through two LDS stages (k-major, row stride 144 doubles), the next step's operands prefetched in registers, one
-// barrier per step.  A 64 x 64 tile moves 16 bytes per 128 flops from L2 to LDS, which bounds it near 20 TFLOP/s on this
-// chip whatever the matrix cores could do; this one moves half of that.  M and N may be any multiples of 64 (rows and
-// columns of a half-empty edge tile are loaded from the last valid row / column and never stored); the structure
-// flags mean the same, with K_TO_ROW ending the range at the end of the tile's 128 rows.
-constexpr int kD2Ld = 144;
-constexpr int kD2Stage = 2 * 16 * kD2Ld;          // doubles per LDS stage: A then B
-
-__global__ void __launch_bounds__(512) dgemm128_kernel(DgemmArgs g) {
-    extern __shared__ __align__(16) double d2s[];
-    const uint32_t m0 = blockIdx.y * 128, n0 = blockIdx.x * 128;
-    if ((g.flags & LOWER_TILES) && n0 > m0) return;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;                 // 4 x 2 wavefronts of 32 x 64
-    const double* A = g.A + (int64_t)blockIdx.z * g.bsA;
-    const double* B = g.B + (int64_t)blockIdx.z * g.bsB;
-
-    uint32_t kb = 0, ke = g.K;
-    if ((g.flags & K_FROM_ROW) && m0 > kb) kb = m0;
-    if ((g.flags & K_FROM_COL) && n0 > kb) kb = n0;
-    if ((g.flags & K_TO_ROW) && m0 + 128 < ke) ke = m0 + 128;
-
-    // staging map: 128 x 16 elements per operand and step, 4 per thread along the operand's contiguous direction
-    const bool a_k_contig = g.csA == 1, b_k_contig = g.rsB == 1;
-    int ai, ak, bi, bk;
-    if (a_k_contig) { ai = tid >> 2; ak = (tid & 3) * 4; } else { ak = tid >> 5; ai = (tid & 31) * 4; }
-    if (b_k_contig) { bi = tid >> 2; bk = (tid & 3) * 4; } else { bk = tid >> 5; bi = (tid & 31) * 4; }
-    // rows / columns past the edge re-read the last valid one (their results are not stored)
-    // (M and N are multiples of 64, so a thread's group of 4 is all in or all out).  The 4 elements of a thread are
-    // adjacent in memory: one 32-byte load each.
-    uint32_t ia = m0 + ai, nb = n0 + bi;
-    if (ia >= g.M) ia = g.M - 4;
-    if (nb >= g.N) nb = g.N - 4;
-    const double* ap = A + (int64_t)ia * g.rsA + (int64_t)ak * g.csA;
-    const double* bp = B + (int64_t)bk * g.rsB + (int64_t)nb * g.csB;
-
-    f64x4 acc[2][4];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f64x4{0.0, 0.0, 0.0, 0.0};
-
-    f64x4 ra, rb;
-    auto fetch = [&](uint32_t k0) {
-        ra = *reinterpret_cast<const f64x4*>(ap + (int64_t)k0 * g.csA);
-        rb = *reinterpret_cast<const f64x4*>(bp + (int64_t)k0 * g.rsB);
-    };
-    auto stash = [&](int stage) {
-        double* As = d2s + stage * kD2Stage;
-        double* Bs = As + 16 * kD2Ld;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            if (a_k_contig) As[(ak + q) * kD2Ld + ai] = ra[q]; else As[ak * kD2Ld + ai + q] = ra[q];
-            if (b_k_contig) Bs[(bk + q) * kD2Ld + bi] = rb[q]; else Bs[bk * kD2Ld + bi + q] = rb[q];
-        }
-    };
-    if (kb < ke) {                                           // uniform
-        fetch(kb);
-        stash(0);
-    }
-    __syncthreads();
-    int cur = 0;
-    for (uint32_t k0 = kb; k0 < ke; k0 += 16) {
-        const bool more = k0 + 16 < ke;                      // uniform
-        if (more) fetch(k0 + 16);
-        const double* As = d2s + cur * kD2Stage;
-        const double* Bs = As + 16 * kD2Ld;
-#pragma unroll
-        for (int kk = 0; kk < 16; kk += 4) {
-            const int kr = kk + (lane >> 4);
-            double fa[2], fb[4];
-#pragma unroll
-            for (int i = 0; i < 2; ++i) fa[i] = As[kr * kD2Ld + wm * 32 + i * 16 + (lane & 15)];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) fb[j] = Bs[kr * kD2Ld + wn * 64 + j * 16 + (lane & 15)];
-#pragma unroll
-            for (int i = 0; i < 2; ++i)
-#pragma unroll
-                for (int j = 0; j < 4; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f64_16x16x4f64(fa[i], fb[j], acc[i][j], 0, 0, 0);
-        }
-        if (more) stash(cur ^ 1);
-        __syncthreads();          // the other stage is complete, and everybody is done reading this one
-        cur ^= 1;
-    }
-
-    // accumulator element e of a lane: row 4*e + lane/16, column lane%16 of the 16 x 16 block
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const uint32_t row = m0 + wm * 32 + i * 16 + 4 * e + (lane >> 4);
-                const uint32_t col = n0 + wn * 64 + j * 16 + (lane & 15);
-                if (row >= g.M || col >= g.N) continue;
-                double v = g.alpha * acc[i][j][e];
-                if (g.Cf) {
-                    float* c = g.Cf + (int64_t)blockIdx.z * g.bsC;
-                    c[(int64_t)row * g.rsC + (int64_t)col * g.csC] = (float)v;
-                    if ((g.flags & MIRROR) && m0 != n0) c[(int64_t)col * g.rsC + (int64_t)row * g.csC] = (float)v;
-                } else {
-                    double* c = g.C + (int64_t)blockIdx.z * g.bsC + (int64_t)row * g.rsC + (int64_t)col * g.csC;
-                    if (g.beta != 0.0) v += g.beta * *c;
-                    *c = v;
-                }
-            }
-}
-
 // W[a][b] = (float) S[max(a,b)][min(a,b)] for the leading k x k part of a matrix (row distance ld) whose lower triangle is valid.
 __global__ void __launch_bounds__(256) fim_store_kernel(const double* S, uint32_t ld, uint32_t k, float* W, uint64_t ldw) {
     const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
@@ -608,17 +523,7 @@ static hipError_t dgemm(const DgemmArgs& g, uint32_t batch, hipStream_t st) {
         hipLaunchKernelGGL(dgemm_k64_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
         return hipGetLastError();
     }
-    // The larger tile pays only where there are enough of them to keep every CU busy
-    const uint64_t t128 = (uint64_t)((g.M + 127) / 128) * ((g.N + 127) / 128) * batch;
-    if (g.M >= 128 && g.N >= 128 && t128 >= 4096) {
-        static LdsOptIn opt_in;
-        const size_t lds_bytes = (size_t)2 * kD2Stage * sizeof(double);
-        hipError_t e = allow_large_lds(opt_in, reinterpret_cast<const void*>(dgemm128_kernel));
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(dgemm128_kernel, dim3((g.N + 127) / 128, (g.M + 127) / 128, batch), dim3(512), lds_bytes, st, g);
-    } else {
-        hipLaunchKernelGGL(dgemm_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
-    }
+    hipLaunchKernelGGL(dgemm_kernel, dim3(g.N / 64, g.M / 64, batch), dim3(256), 0, st, g);
     return hipGetLastError();
 }
 
@@ -744,12 +649,14 @@ extern "C" grass_status grass_fim_inverse(const float* F, uint32_t k, uint64_t l
     hipLaunchKernelGGL(fim_load_kernel, dim3((uint32_t)ceil_div((uint64_t)kp * kp, 256)), dim3(256), 0, hs, F, ldf, k, lambda,
                        A64, X64, kp, (uint32_t)ld);
 
-    // Blocked Cholesky, A = L L^T, L overwrites the lower triangle of A64.  Two levels: inside an outer block of kOuter
-    // diagonal blocks (256 columns) every factorised 64-column panel updates the remaining columns of the outer block
-    // only (right-looking, K = 64, a few tiles per row); the rest of the matrix receives the whole outer block at once
-    // (K = 256).  A rank-64 update of the full trailing matrix moves 16 bytes of C per 128 flops and was bound by that
-    // traffic (58 us for the first one, 1.8 ms over the factorisation); with K = 256 it is a quarter of it.
-    constexpr uint32_t kOuter = 4;
+    // Blocked Cholesky, A = L L^T.  Two levels: inside an outer block of kOuter diagonal blocks (512 columns) every
+    // factorised 64-column panel updates the remaining columns of the outer block only (right-looking, K = 64, one
+    // fused launch per step, see chol_step_kernel); the rest of the matrix receives the whole outer block at once
+    // (K = 512).  A rank-64 update of the full trailing matrix moves 16 bytes of C per 128 flops and was bound by that
+    // traffic (58 us for the first one, 1.8 ms over the factorisation).  The inverses of the diagonal blocks and the
+    // scaled panels (the lower blocks of L) go to X64; A64 keeps the matrix being updated.  Wider outer blocks make the
+    // steps longer than the factorisation of the next diagonal block that hides behind them (16: no faster).
+    constexpr uint32_t kOuter = 8;
     static LdsOptIn step_opt_in;
     if (allow_large_lds(step_opt_in, reinterpret_cast<const void*>(chol_step_kernel)) != hipSuccess) return GRASS_EHIP;
     bool factorised = false;                               // block j already factorised by the step before it

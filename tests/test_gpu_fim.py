@@ -63,7 +63,7 @@ def _inverse_case(k, lam, seed, N=None):
 
 
 @pytest.mark.parametrize("k,lam", [(5, 0.1), (64, 1e-3), (100, 0.1), (128, 10.0), (192, 1e-2), (320, 1e-3),
-                                   (448, 0.1), (1000, 1e-2), (1024, 1e-4), (2048, 1e-3)])
+                                   (448, 0.1), (576, 1e-2), (1000, 1e-2), (1024, 1e-4), (1100, 1e-3), (2048, 1e-3)])
 def test_fim_inverse_parity(grass, k, lam):
     F32, A = _inverse_case(k, lam, seed=2200 + k)
     info = torch.full((1,), -1, dtype=torch.int32, device=_dev())
