@@ -376,6 +376,58 @@ def selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam: floa
     return obj, gi / m * 2 * si * dsi - lam * dsi, go / m * 2 * so * dso - lam * dso
 
 
+def graddot_factorized_seq(X_in, X_out, Xt_in, Xt_out) -> np.ndarray:
+    """Exact GradDot scores of a linear layer on sequences without forming the layer gradients: with per-sample
+    gradients sum_t x_t (x) g_t (Eq. (2)) and <a (x) b, c (x) d> = <a, c> <b, d> (App. B.4 "Linear Layer"),
+        score[test][i] = sum_{t, t'} <x_{i,t}, x_{test,t'}> <g_{i,t}, g_{test,t'}>.
+    X_in (n, T, d_in), X_out (n, T, d_out) train; Xt_in (m, T', d_in), Xt_out (m, T', d_out) test.  Returns (m, n)."""
+    X_in, X_out = np.asarray(X_in, np.float64), np.asarray(X_out, np.float64)
+    Xt_in, Xt_out = np.asarray(Xt_in, np.float64), np.asarray(Xt_out, np.float64)
+    m, n = Xt_in.shape[0], X_in.shape[0]
+    out = np.zeros((m, n))
+    for te in range(m):
+        for i in range(n):
+            k_in = X_in[i] @ Xt_in[te].T            # (T, T') token-pair inner products of the input factor
+            k_out = X_out[i] @ Xt_out[te].T
+            out[te, i] = np.sum(k_in * k_out)
+    return out
+
+
+def selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam: float, temperature: float = 1.0):
+    """Factorised Selective Mask of a linear layer (App. B.4 "Linear Layer") for samples that are sequences of tokens.
+    Reading: the paper writes the factorised problem for one token per sample; for T tokens the layer gradient is
+    sum_t x_t (x) g_t (Eq. (2)), the mask sigma(S_in) (x) sigma(S_out) acts on it, and every inner product of two such
+    gradients is the sum over all token pairs of the product of the two factors' (masked) inner products.
+    Returns (objective, d objective / d S_in, d objective / d S_out)."""
+    S_in, S_out = np.asarray(S_in, np.float64), np.asarray(S_out, np.float64)
+    X_in, X_out = np.asarray(X_in, np.float64), np.asarray(X_out, np.float64)
+    Xt_in, Xt_out = np.asarray(Xt_in, np.float64), np.asarray(Xt_out, np.float64)
+    si, so = _sigmoid(S_in / temperature), _sigmoid(S_out / temperature)
+    dsi, dso = si * (1 - si) / temperature, so * (1 - so) / temperature
+    m, n = Xt_in.shape[0], X_in.shape[0]
+    exact_all = graddot_factorized_seq(X_in, X_out, Xt_in, Xt_out)
+    total, gi, go = 0.0, np.zeros_like(S_in), np.zeros_like(S_out)
+    for te in range(m):
+        masked = np.zeros(n)
+        k_in, k_out = [], []
+        for i in range(n):
+            k_in.append((X_in[i] * si) @ (Xt_in[te] * si).T)        # (T, T'), weights sigma^2 in total
+            k_out.append((X_out[i] * so) @ (Xt_out[te] * so).T)
+            masked[i] = np.sum(k_in[i] * k_out[i])
+        exact = exact_all[te]
+        da, db = exact - exact.mean(), masked - masked.mean()
+        na, nb = np.sqrt(da @ da), np.sqrt(db @ db)
+        corr = (da @ db) / (na * nb)
+        total += corr
+        c = da / (na * nb) - corr * db / (nb * nb)
+        for i in range(n):
+            # d masked_i / d w_in_j = sum_{t,t'} k_out[t,t'] x_in[i,t,j] xt_in[te,t',j], w = sigma^2
+            gi += c[i] * np.einsum("ab,aj,bj->j", k_out[i], X_in[i], Xt_in[te])
+            go += c[i] * np.einsum("ab,aj,bj->j", k_in[i], X_out[i], Xt_out[te])
+    obj = total / m - lam * (si.sum() + so.sum())
+    return obj, gi / m * 2 * si * dsi - lam * dsi, go / m * 2 * so * dso - lam * dso
+
+
 def selective_mask_train(S0, G, Gt, lam: float, lr: float, temperatures):
     """Solves Eq. (1) by first-order ascent on the logits, with the inverse-temperature annealing of App. B.4
     ("Ensuring Exact k": S is replaced by S / T and T decreases as training progresses).

@@ -298,3 +298,60 @@ def test_factorised_selective_mask_training_mistakes_are_caught(monkeypatch, kwa
     monkeypatch.setattr(orc, "selective_mask_train_factorized", _train_factorized_variant(**kwargs))
     with pytest.raises(AssertionError):
         getattr(pins_train_fact, pin)()
+
+
+def _seq_variant(diagonal_pairs=False, unsquared=False, wrong_factor_in_grad=False):
+    """Planted mistakes in the sequence form: only matching token positions (t = t') instead of all pairs; weights
+    sigma instead of sigma^2; the input gradient weighted by the input factor's own token products."""
+    def f(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam, temperature=1.0):
+        S_in, S_out = np.asarray(S_in, np.float64), np.asarray(S_out, np.float64)
+        si, so = 1 / (1 + np.exp(-S_in / temperature)), 1 / (1 + np.exp(-S_out / temperature))
+        dsi, dso = si * (1 - si) / temperature, so * (1 - so) / temperature
+        wi, wo = (si, so) if unsquared else (si * si, so * so)
+        m, n = Xt_in.shape[0], X_in.shape[0]
+        total, gi, go = 0.0, np.zeros_like(S_in), np.zeros_like(S_out)
+        for te in range(m):
+            exact, masked, kin, kout = np.zeros(n), np.zeros(n), [], []
+            for i in range(n):
+                e_in, e_out = X_in[i] @ Xt_in[te].T, X_out[i] @ Xt_out[te].T
+                a, b = (X_in[i] * wi) @ Xt_in[te].T, (X_out[i] * wo) @ Xt_out[te].T
+                if diagonal_pairs:
+                    q = min(a.shape)
+                    keep = np.zeros_like(a); keep[np.arange(q), np.arange(q)] = 1
+                    e_in, a = e_in * keep, a * keep
+                exact[i], masked[i] = np.sum(e_in * e_out), np.sum(a * b)
+                kin.append(a); kout.append(b)
+            da, db = exact - exact.mean(), masked - masked.mean()
+            na, nb = np.sqrt(da @ da), np.sqrt(db @ db)
+            corr = (da @ db) / (na * nb)
+            total += corr
+            c = da / (na * nb) - corr * db / (nb * nb)
+            for i in range(n):
+                gi += c[i] * np.einsum("ab,aj,bj->j", kin[i] if wrong_factor_in_grad else kout[i], X_in[i], Xt_in[te])
+                go += c[i] * np.einsum("ab,aj,bj->j", kin[i], X_out[i], Xt_out[te])
+        obj = total / m - lam * (si.sum() + so.sum())
+        return obj, gi / m * 2 * si * dsi - lam * dsi, go / m * 2 * so * dso - lam * dso
+    return f
+
+
+@pytest.mark.parametrize("kwargs,pin,args", [
+    (dict(diagonal_pairs=True), "test_sequence_factorized_objective_equals_the_plain_one_on_materialised_gradients", ()),
+    (dict(diagonal_pairs=True), "test_sequence_form_ignores_token_order_and_all_zero_tokens", ()),
+    (dict(unsquared=True), "test_sequence_factorized_objective_equals_the_plain_one_on_materialised_gradients", ()),
+    (dict(unsquared=True), "test_sequence_form_with_one_token_is_the_single_token_form", ()),
+    (dict(wrong_factor_in_grad=True), "test_sequence_factorized_gradients_match_central_differences", (1.0, 0.0, 3)),
+    (dict(wrong_factor_in_grad=True), "test_sequence_form_with_one_token_is_the_single_token_form", ()),
+])
+def test_sequence_factorised_selective_mask_mistakes_are_caught(monkeypatch, kwargs, pin, args):
+    monkeypatch.setattr(orc, "selective_mask_factorized_seq", _seq_variant(**kwargs))
+    with pytest.raises(AssertionError):
+        getattr(pins_sm, pin)(*args)
+
+
+def test_sequence_graddot_with_matching_positions_only_is_caught(monkeypatch):
+    def diag_only(X_in, X_out, Xt_in, Xt_out):
+        q = min(X_in.shape[1], Xt_in.shape[1])
+        return np.einsum("ita,mta,itb,mtb->mi", X_in[:, :q], Xt_in[:, :q], X_out[:, :q], Xt_out[:, :q])
+    monkeypatch.setattr(orc, "graddot_factorized_seq", diag_only)
+    with pytest.raises(AssertionError):
+        pins_sm.test_sequence_graddot_equals_inner_products_of_materialised_layer_gradients()

@@ -125,3 +125,76 @@ def test_factorized_gradients_match_central_differences(temperature, lam, seed):
     for j in range(S_out.size):
         e = np.zeros_like(S_out); e[j] = h
         assert np.isclose(go[j], (f(S_in, S_out + e) - f(S_in, S_out - e)) / (2 * h), rtol=2e-6, atol=1e-9)
+
+
+# ------------------------------------------------------------------ factorised form on sequences of tokens
+def _seq_problem(n=7, m=3, T=4, Tt=3, d_in=5, d_out=4, seed=0):
+    rng = np.random.default_rng(seed)
+    return (0.4 * rng.standard_normal(d_in), 0.4 * rng.standard_normal(d_out), rng.standard_normal((n, T, d_in)),
+            rng.standard_normal((n, T, d_out)), rng.standard_normal((m, Tt, d_in)), rng.standard_normal((m, Tt, d_out)))
+
+
+def _layer_gradients(X_in, X_out):
+    """Materialised per-sample layer gradients sum_t x_t (x) g_t (Eq. (2)), flattened input index major."""
+    return np.einsum("nta,ntb->nab", X_in, X_out).reshape(X_in.shape[0], -1)
+
+
+def test_sequence_graddot_equals_inner_products_of_materialised_layer_gradients():
+    _, _, X_in, X_out, Xt_in, Xt_out = _seq_problem(seed=1)
+    G, Gt = _layer_gradients(X_in, X_out), _layer_gradients(Xt_in, Xt_out)
+    assert np.allclose(orc.graddot_factorized_seq(X_in, X_out, Xt_in, Xt_out), Gt @ G.T, rtol=1e-12, atol=1e-12)
+
+
+def test_sequence_factorized_objective_equals_the_plain_one_on_materialised_gradients():
+    """With logits whose sigmoid is sigma(S_in) (x) sigma(S_out), the plain objective of Eq. (1) on the materialised
+    layer gradients is the factorised one (no penalty: the two forms penalise different sums)."""
+    S_in, S_out, X_in, X_out, Xt_in, Xt_out = _seq_problem(seed=2)
+    for T in (1.0, 0.6):
+        sig = np.kron(1 / (1 + np.exp(-S_in / T)), 1 / (1 + np.exp(-S_out / T)))
+        S_flat = T * np.log(sig / (1 - sig))
+        plain = orc.selective_mask_objective(S_flat, _layer_gradients(X_in, X_out), _layer_gradients(Xt_in, Xt_out), 0.0, T)
+        obj, _, _ = orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, 0.0, T)
+        assert np.isclose(obj, plain, rtol=1e-10)
+    lam = 0.07
+    pen = lam * ((1 / (1 + np.exp(-S_in))).sum() + (1 / (1 + np.exp(-S_out))).sum())
+    assert np.isclose(orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam)[0],
+                      orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, 0.0)[0] - pen, rtol=1e-12)
+
+
+@pytest.mark.parametrize("temperature,lam,seed", [(1.0, 0.0, 3), (0.7, 0.05, 4)])
+def test_sequence_factorized_gradients_match_central_differences(temperature, lam, seed):
+    S_in, S_out, X_in, X_out, Xt_in, Xt_out = _seq_problem(seed=seed)
+    _, gi, go = orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam, temperature)
+    f = lambda a, b: orc.selective_mask_factorized_seq(a, b, X_in, X_out, Xt_in, Xt_out, lam, temperature)[0]
+    h = 1e-6
+    for j in range(S_in.size):
+        e = np.zeros_like(S_in); e[j] = h
+        assert np.isclose(gi[j], (f(S_in + e, S_out) - f(S_in - e, S_out)) / (2 * h), rtol=1e-5, atol=1e-9)
+    for j in range(S_out.size):
+        e = np.zeros_like(S_out); e[j] = h
+        assert np.isclose(go[j], (f(S_in, S_out + e) - f(S_in, S_out - e)) / (2 * h), rtol=1e-5, atol=1e-9)
+
+
+def test_sequence_form_with_one_token_is_the_single_token_form():
+    S_in, S_out, X_in, X_out, Xt_in, Xt_out = _seq_problem(T=1, Tt=1, seed=5)
+    a = orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, 0.03, 0.8)
+    b = orc.selective_mask_factorized(S_in, S_out, X_in[:, 0], X_out[:, 0], Xt_in[:, 0], Xt_out[:, 0], 0.03, 0.8)
+    assert np.isclose(a[0], b[0], rtol=1e-12) and np.allclose(a[1], b[1], rtol=1e-11, atol=1e-14)
+    assert np.allclose(a[2], b[2], rtol=1e-11, atol=1e-14)
+
+
+def test_sequence_form_ignores_token_order_and_all_zero_tokens():
+    """The layer gradient is a sum over tokens: permuting the tokens of a sample (both factors alike) or appending a
+    token whose factors are zero changes nothing."""
+    S_in, S_out, X_in, X_out, Xt_in, Xt_out = _seq_problem(seed=6)
+    base = orc.selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, 0.02, 1.0)
+    perm = np.array([2, 0, 3, 1])
+    X_in2, X_out2 = X_in.copy(), X_out.copy()
+    X_in2[1], X_out2[1] = X_in[1][perm], X_out[1][perm]
+    pad = lambda a: np.concatenate([a, np.zeros_like(a[:, :1])], axis=1)
+    other = orc.selective_mask_factorized_seq(S_in, S_out, pad(X_in2), pad(X_out2), pad(Xt_in), pad(Xt_out), 0.02, 1.0)
+    assert np.isclose(base[0], other[0], rtol=1e-12)
+    assert np.allclose(base[1], other[1], rtol=1e-10, atol=1e-14) and np.allclose(base[2], other[2], rtol=1e-10, atol=1e-14)
+    # permuting the tokens of one factor only is a different gradient
+    X_in3 = X_in.copy(); X_in3[1] = X_in[1][perm]
+    assert not np.isclose(orc.selective_mask_factorized_seq(S_in, S_out, X_in3, X_out, Xt_in, Xt_out, 0.02, 1.0)[0], base[0])
