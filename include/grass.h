@@ -418,6 +418,40 @@ grass_status grass_selective_mask_grad_factorized(const float* Z_in, const float
                                                   double lambda, double temperature,
                                                   float* grad_in, float* grad_out, double* objective,
                                                   void* ws, size_t ws_bytes, grass_stream stream);
+/* Samples that are sequences of tokens (the case FactGraSS compresses): the
+ * layer gradient of a sample is sum_t z_in_t (x) z_out_t (Eq. (2)), so an inner
+ * product of two layer gradients is the sum over all token pairs of
+ * <z_in_t, z_in_t'> * <z_out_t, z_out_t'>, with or without the mask weights.
+ * Rows of Z_in / Z_out are tokens: train sample i owns rows i*T .. i*T+T-1 of
+ * the (n*T)-row matrices, test sample t rows t*Tt .. t*Tt+Tt-1 of the
+ * (m*Tt)-row matrices.  T = Tt = 1 is grass_selective_mask_grad_factorized.
+ *
+ * grass_graddot_factorized: A (m x n fp32, lda) receives the exact scores
+ *   A[t][i] = <layer gradient of test sample t, layer gradient of train sample i>.
+ * grass_selective_mask_grad_factorized_seq: objective and both gradients for
+ *   such samples; A as produced by grass_graddot_factorized.
+ * Both use the workspace of the _seq query; n*T and m*Tt below 2^31.          */
+grass_status grass_graddot_factorized_workspace_bytes(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt,
+                                                      uint64_t d_in, uint64_t d_out, size_t* host_bytes);
+grass_status grass_graddot_factorized(const float* Z_in, const float* Z_out, uint64_t n, uint64_t T,
+                                      uint64_t ld_zin, uint64_t ld_zout,
+                                      const float* Zt_in, const float* Zt_out, uint64_t m, uint64_t Tt,
+                                      uint64_t ld_ztin, uint64_t ld_ztout,
+                                      uint64_t d_in, uint64_t d_out, float* A, uint64_t lda,
+                                      void* ws, size_t ws_bytes, grass_stream stream);
+grass_status grass_selective_mask_grad_factorized_seq_workspace_bytes(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt,
+                                                                      uint64_t d_in, uint64_t d_out,
+                                                                      size_t* host_bytes);
+grass_status grass_selective_mask_grad_factorized_seq(const float* Z_in, const float* Z_out, uint64_t n, uint64_t T,
+                                                      uint64_t ld_zin, uint64_t ld_zout,
+                                                      const float* Zt_in, const float* Zt_out, uint64_t m, uint64_t Tt,
+                                                      uint64_t ld_ztin, uint64_t ld_ztout,
+                                                      uint64_t d_in, uint64_t d_out,
+                                                      const float* A, uint64_t lda,
+                                                      const float* S_in, const float* S_out,
+                                                      double lambda, double temperature,
+                                                      float* grad_in, float* grad_out, double* objective,
+                                                      void* ws, size_t ws_bytes, grass_stream stream);
 /* grass_selective_mask_train_factorized: the same first-order ascent as
  * grass_selective_mask_train on the factorised problem: both logit vectors take
  *     S_in <- S_in + lr * dL/dS_in,   S_out <- S_out + lr * dL/dS_out

@@ -84,6 +84,14 @@ SIGNATURES = {
     "grass_selective_mask_grad_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
                                                     _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double, _vp, _vp, _vp,
                                                     _vp, _sz, _vp]),
+    "grass_graddot_factorized_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, _u64, _u64, ctypes.POINTER(_sz)]),
+    "grass_graddot_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64, _u64,
+                                        _vp, _u64, _vp, _sz, _vp]),
+    "grass_selective_mask_grad_factorized_seq_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, _u64, _u64,
+                                                                        ctypes.POINTER(_sz)]),
+    "grass_selective_mask_grad_factorized_seq": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64,
+                                                        _u64, _u64, _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double,
+                                                        _vp, _vp, _vp, _vp, _sz, _vp]),
     "grass_selective_mask_train_factorized_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_train_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
                                                      _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double,
@@ -565,6 +573,54 @@ def grass_selective_mask_grad_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_
         _ptr(Z_in), _ptr(Z_out), n, _ld(Z_in), _ld(Z_out), _ptr(Zt_in), _ptr(Zt_out), m, _ld(Zt_in), _ld(Zt_out), d_in, d_out,
         _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(temperature), _ptr(grad_in), _ptr(grad_out),
         _ptr(objective), _ptr(ws), ws.numel(), _stream()), "grass_selective_mask_grad_factorized")
+    return grad_in, grad_out, objective
+
+
+def _seq_shapes(Z_in, Z_out, Zt_in, Zt_out):
+    """(n, T, d) token tensors, contiguous over (sample, token): returns the flattened (n*T, d) views and the sizes."""
+    for t in (Z_in, Z_out, Zt_in, Zt_out):
+        assert t.dtype == torch.float32 and t.dim() == 3
+    n, T, d_in = Z_in.shape
+    m, Tt, d_out = Zt_out.shape
+    assert Z_out.shape[:2] == (n, T) and Z_out.shape[2] == d_out and Zt_in.shape == (m, Tt, d_in)
+    flat = [t.reshape(t.shape[0] * t.shape[1], t.shape[2]) for t in (Z_in, Z_out, Zt_in, Zt_out)]
+    return flat, n, T, m, Tt, d_in, d_out
+
+
+def grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out, out: torch.Tensor | None = None) -> torch.Tensor:
+    """Exact GradDot scores (m x n) of a linear layer on sequences: Z_* are (samples, tokens, features) tensors."""
+    (zi, zo, zti, zto), n, T, m, Tt, d_in, d_out = _seq_shapes(Z_in, Z_out, Zt_in, Zt_out)
+    if out is None:
+        out = torch.empty((m, n), dtype=torch.float32, device=Z_in.device)
+    nbytes = _sz(0)
+    _check(load_library().grass_graddot_factorized_workspace_bytes(n, T, m, Tt, d_in, d_out, ctypes.byref(nbytes)),
+           "grass_graddot_factorized_workspace_bytes")
+    ws = _workspace(nbytes.value, Z_in.device)
+    _check(load_library().grass_graddot_factorized(_ptr(zi), _ptr(zo), n, T, _ld(zi), _ld(zo), _ptr(zti), _ptr(zto), m, Tt,
+                                                   _ld(zti), _ld(zto), d_in, d_out, _ptr(out), _ld(out), _ptr(ws),
+                                                   ws.numel(), _stream()), "grass_graddot_factorized")
+    return out
+
+
+def grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam: float,
+                                             temperature: float = 1.0):
+    """Factorised Selective Mask step of a linear layer on sequences ((samples, tokens, features) tensors).
+    Returns (grad_in, grad_out, objective float64 [1])."""
+    (zi, zo, zti, zto), n, T, m, Tt, d_in, d_out = _seq_shapes(Z_in, Z_out, Zt_in, Zt_out)
+    assert A.dtype == S_in.dtype == S_out.dtype == torch.float32 and A.shape == (m, n)
+    assert S_in.is_contiguous() and S_out.is_contiguous() and S_in.numel() == d_in and S_out.numel() == d_out
+    grad_in = torch.empty(d_in, dtype=torch.float32, device=Z_in.device)
+    grad_out = torch.empty(d_out, dtype=torch.float32, device=Z_in.device)
+    objective = torch.empty(1, dtype=torch.float64, device=Z_in.device)
+    nbytes = _sz(0)
+    _check(load_library().grass_selective_mask_grad_factorized_seq_workspace_bytes(n, T, m, Tt, d_in, d_out,
+                                                                                   ctypes.byref(nbytes)),
+           "grass_selective_mask_grad_factorized_seq_workspace_bytes")
+    ws = _workspace(nbytes.value, Z_in.device)
+    _check(load_library().grass_selective_mask_grad_factorized_seq(
+        _ptr(zi), _ptr(zo), n, T, _ld(zi), _ld(zo), _ptr(zti), _ptr(zto), m, Tt, _ld(zti), _ld(zto), d_in, d_out,
+        _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(temperature), _ptr(grad_in), _ptr(grad_out),
+        _ptr(objective), _ptr(ws), ws.numel(), _stream()), "grass_selective_mask_grad_factorized_seq")
     return grad_in, grad_out, objective
 
 

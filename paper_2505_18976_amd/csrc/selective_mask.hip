@@ -41,7 +41,8 @@ __device__ __forceinline__ double block_sum(double v, double* red) {
     return r;
 }
 
-// Gtw[t][j] = Gt[t][j] * sigma_j^2 for a block of 256 columns and all m rows; columns p..ld_w are zero-filled.
+// Gtw[t][j] = Gt[t][j] * sigma_j^2 (S null: Gt[t][j]) for a block of 256 columns and all m rows; columns p..ld_w are
+// zero-filled.
 // sig_part[blockIdx.x] = sum of sigma_j over the block's columns.
 __global__ void __launch_bounds__(256) sm_weight_kernel(const float* Gt, uint64_t ldgt, uint64_t m, uint64_t p,
                                                        const float* S, float inv_temp, float* Gtw, uint64_t ld_w,
@@ -49,7 +50,10 @@ __global__ void __launch_bounds__(256) sm_weight_kernel(const float* Gt, uint64_
     __shared__ double red[256];
     const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     float w = 0.0f, sig = 0.0f;
-    if (j < p) { sig = sigmoidf(S[j] * inv_temp); w = sig * sig; }
+    if (j < p) {
+        if (S) { sig = sigmoidf(S[j] * inv_temp); w = sig * sig; }
+        else w = 1.0f;                                     // no mask: plain inner products
+    }
     if (j < ld_w)
         for (uint64_t t = 0; t < m; ++t) Gtw[t * ld_w + j] = j < p ? Gt[t * ldgt + j] * w : 0.0f;
     const double total = block_sum((double)sig, red);
@@ -106,14 +110,33 @@ __global__ void __launch_bounds__(256) sm_grad_kernel(const float* Gt, uint64_t 
     grad[j] = (float)(2.0 * (double)sig * (double)dsig * acc - (double)lambda * (double)dsig);
 }
 
-// out[t][i] = x[t][i] * y[t][i] for i < n_valid and 0 for n_valid <= i < n (row distance ld for all three): the
-// padding columns of the workspace matrices may hold anything, the product must not.
-__global__ void __launch_bounds__(256) sm_hadamard_kernel(const float* x, const float* y, float* out, uint64_t m, uint64_t n,
-                                                         uint64_t n_valid, uint64_t ld) {
-    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t >= m * n) return;
-    const uint64_t r = t / n, c = t - r * n;
-    out[r * ld + c] = c < n_valid ? x[r * ld + c] * y[r * ld + c] : 0.0f;
+// Samples that are sequences of tokens: X and Y are (m * Tt) x (n * T) matrices of token-pair products (row distance
+// ldk), B[te][i] = sum over the Tt x T block of (te, i) of X * Y (fp64 sum, fixed order), i < n; columns n..n_write of B
+// are zero (row distance ldb).  With one token per sample this is the elementwise product.
+__global__ void __launch_bounds__(256) sm_block_dot_kernel(const float* X, const float* Y, uint64_t ldk, uint64_t m, uint64_t n,
+                                                          uint64_t Tt, uint64_t T, float* B, uint64_t ldb, uint64_t n_write) {
+    const uint64_t id = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= m * n_write) return;
+    const uint64_t te = id / n_write, i = id - te * n_write;
+    double acc = 0.0;
+    if (i < n)
+        for (uint64_t a = 0; a < Tt; ++a) {
+            const uint64_t row = (te * Tt + a) * ldk + i * T;
+            for (uint64_t b = 0; b < T; ++b) acc += (double)X[row + b] * (double)Y[row + b];
+        }
+    B[te * ldb + i] = (float)acc;
+}
+
+// D[v][u] = C[v / Tt][u / T] * K[v][u] for u < n_tok, 0 for n_tok <= u < ldd: the derivative of the objective with
+// respect to one factor's token-pair products (C is the m x n row matrix of sm_corr_kernel, K the other factor's
+// token-pair products).  The padding columns of the workspace matrices may hold anything, D must not.
+__global__ void __launch_bounds__(256) sm_expand_kernel(const float* C, uint64_t ldc, const float* K, uint64_t ldk,
+                                                       uint64_t m_tok, uint64_t n_tok, uint64_t Tt, uint64_t T, float* D,
+                                                       uint64_t ldd) {
+    const uint64_t id = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= m_tok * ldd) return;
+    const uint64_t v = id / ldd, u = id - v * ldd;
+    D[v * ldd + u] = u < n_tok ? C[(v / Tt) * ldc + u / T] * K[v * ldk + u] : 0.0f;
 }
 
 // objective = mean of corr - lambda * sum of the sigma partial sums; one workgroup, fixed order.
@@ -342,74 +365,143 @@ extern "C" grass_status grass_score_correlation(const float* X, uint64_t ldx, co
 
 // Factorised form for a linear layer (App. B.4 "Linear Layer"): gradients z_in (x) z_out, mask sigma(S_in) (x) sigma(S_out),
 // <a (x) b, c (x) d> = <a, c><b, d>, so the masked scores are the elementwise product of the two factors' masked scores
-// and each factor's gradient is the plain backward pass with C multiplied by the other factor's masked scores.
+// and each factor's gradient is the plain backward pass with C multiplied by the other factor's masked scores.  Samples
+// that are sequences of tokens have gradients sum_t z_in_t (x) z_out_t (Eq. (2)): the factors' products are then taken
+// between all tokens of a test and a train sample and summed over the token pairs; one token per sample is the case
+// the paper writes out.
 extern "C" grass_status grass_selective_mask_grad_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
                                                                              uint64_t d_out, size_t* host_bytes) {
-    if (!host_bytes) return GRASS_EINVAL;
-    const uint64_t p = d_in > d_out ? d_in : d_out;
-    grass_status st = check_sm(n, m, p);
-    if (st != GRASS_OK || d_in == 0 || d_out == 0) return st != GRASS_OK ? st : GRASS_EINVAL;
-    const SmLayout L = sm_layout(n, m, p);
-    // + B_out, C_in / C_out scratch and the second factor's sigma partial sums
-    *host_bytes = L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);   // = sm_factorized_bytes
-    return GRASS_OK;
+    return grass_selective_mask_grad_factorized_seq_workspace_bytes(n, 1, m, 1, d_in, d_out, host_bytes);
 }
 
-static grass_status check_sm_factorized(uint64_t n, uint64_t m, uint64_t d_in, uint64_t d_out, const float* Z_in,
-                                        const float* Z_out, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
-                                        const float* Zt_out, uint64_t ld_ztin, uint64_t ld_ztout, const float* A,
-                                        uint64_t lda, const float* S_in, const float* S_out, double lambda) {
-    const uint64_t p = d_in > d_out ? d_in : d_out;
-    grass_status st = check_sm(n, m, p);
-    if (st != GRASS_OK) return st;
-    if (d_in == 0 || d_out == 0 || !Z_in || !Z_out || !Zt_in || !Zt_out || !A || !S_in || !S_out) return GRASS_EINVAL;
-    if (ld_zin < d_in || ld_ztin < d_in || ld_zout < d_out || ld_ztout < d_out || lda < n) return GRASS_EINVAL;
-    if (!(lambda >= 0.0)) return GRASS_EINVAL;
+// Sizes of the factorised problem on sequences: n samples of T tokens against m samples of Tt tokens.
+struct SmSeq {
+    uint64_t n, T, m, Tt, n_tok, m_tok, nb_pad;
+};
+static grass_status check_sm_factorized(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt, uint64_t d_in, uint64_t d_out,
+                                        SmSeq* q) {
+    if (T == 0 || Tt == 0 || d_in == 0 || d_out == 0) return GRASS_EINVAL;
+    if (n >= (1ull << 31) / T || m >= (1ull << 31) / Tt) return GRASS_EUNSUPPORTED;
+    q->n = n; q->T = T; q->m = m; q->Tt = Tt; q->n_tok = n * T; q->m_tok = m * Tt; q->nb_pad = (n + 15) / 16 * 16;
+    return check_sm(n, m, d_in > d_out ? d_in : d_out);
+}
+static grass_status check_sm_factorized_args(const SmSeq& q, uint64_t d_in, uint64_t d_out, const float* Z_in,
+                                             const float* Z_out, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+                                             const float* Zt_out, uint64_t ld_ztin, uint64_t ld_ztout) {
+    if (!Z_in || !Z_out || !Zt_in || !Zt_out) return GRASS_EINVAL;
+    if (ld_zin < d_in || ld_ztin < d_in || ld_zout < d_out || ld_ztout < d_out) return GRASS_EINVAL;
     return GRASS_OK;
 }
+// workspace: sm_layout over the token matrices, then the second factor's token-pair products, its sigma partial sums,
+// and the m x n matrices B and C
+static size_t sm_factorized_bytes(const SmLayout& L, const SmSeq& q) {
+    return L.total + up256((size_t)q.m_tok * L.n_pad * 4) + up256((size_t)L.parts * 8) + 2 * up256((size_t)q.m * q.nb_pad * 4);
+}
 
-// Value and both gradients; the workspace holds sm_layout(n, m, max(d_in, d_out)) followed by B_out, one m x n_pad
-// scratch matrix and the second factor's sigma partial sums.
+// Value and both gradients.  Rows of Z_* are tokens (sample i owns rows i*T .. i*T + T - 1).
 static grass_status sm_value_and_grad_factorized(
-    const SmLayout& L, unsigned char* base, const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin,
-    uint64_t ld_zout, const float* Zt_in, const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout,
-    uint64_t d_in, uint64_t d_out, const float* A, uint64_t lda, const float* S_in, const float* S_out, double lambda,
-    double temperature, float* grad_in, float* grad_out, double* objective, hipStream_t hs) {
-    const size_t extra_b = up256((size_t)m * L.n_pad * 4);
-    float* B_in = reinterpret_cast<float*>(base + L.off_b);
-    float* C = reinterpret_cast<float*>(base + L.off_c);
+    const SmLayout& L, const SmSeq& q, unsigned char* base, const float* Z_in, const float* Z_out, uint64_t ld_zin,
+    uint64_t ld_zout, const float* Zt_in, const float* Zt_out, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in,
+    uint64_t d_out, const float* A, uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature,
+    float* grad_in, float* grad_out, double* objective, hipStream_t hs) {
+    const size_t tok_bytes = up256((size_t)q.m_tok * L.n_pad * 4), small = up256((size_t)q.m * q.nb_pad * 4);
+    float* K_in = reinterpret_cast<float*>(base + L.off_b);            // token-pair products, m_tok x n_pad
+    float* D = reinterpret_cast<float*>(base + L.off_c);               // derivative with respect to a factor's products
     double* corr = reinterpret_cast<double*>(base + L.off_corr);
     double* sig_in = reinterpret_cast<double*>(base + L.off_sig);
-    float* B_out = reinterpret_cast<float*>(base + L.total);
-    float* Cx = reinterpret_cast<float*>(base + L.total + extra_b);
-    double* sig_out = reinterpret_cast<double*>(base + L.total + 2 * extra_b);
+    float* K_out = reinterpret_cast<float*>(base + L.total);
+    double* sig_out = reinterpret_cast<double*>(base + L.total + tok_bytes);
+    float* B = reinterpret_cast<float*>(base + L.total + tok_bytes + up256((size_t)L.parts * 8));
+    float* C = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(B) + small);
     const float inv_temp = (float)(1.0 / temperature);
-    const uint32_t eb = (uint32_t)ceil_div(m * n, 256);
+    const uint32_t small_blocks = (uint32_t)ceil_div(q.m * q.nb_pad, 256);
+    const uint32_t tok_blocks = (uint32_t)ceil_div(q.m_tok * L.n_pad, 256);
 
-    grass_status st = sm_masked_scores(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, B_in, sig_in, hs);
+    grass_status st = sm_masked_scores(L, base, Z_in, q.n_tok, ld_zin, Zt_in, q.m_tok, ld_ztin, d_in, S_in, inv_temp, K_in, sig_in, hs);
     if (st != GRASS_OK) return st;
-    st = sm_masked_scores(L, base, Z_out, n, ld_zout, Zt_out, m, ld_ztout, d_out, S_out, inv_temp, B_out, sig_out, hs);
+    st = sm_masked_scores(L, base, Z_out, q.n_tok, ld_zout, Zt_out, q.m_tok, ld_ztout, d_out, S_out, inv_temp, K_out, sig_out, hs);
     if (st != GRASS_OK) return st;
-    // masked scores of the Kronecker gradients, their correlation with A and the row c
-    hipLaunchKernelGGL(sm_hadamard_kernel, dim3(eb), dim3(256), 0, hs, B_in, B_out, Cx, m, n, n, L.n_pad);
-    hipLaunchKernelGGL(sm_corr_kernel, dim3((uint32_t)m), dim3(256), 0, hs, A, lda, Cx, L.n_pad, n, m, C, L.n_pad, corr);
-    // input factor: C * B_out (padding columns of C are zero and stay zero)
-    hipLaunchKernelGGL(sm_hadamard_kernel, dim3((uint32_t)ceil_div(m * L.n_pad, 256)), dim3(256), 0, hs, C, B_out, Cx, m,
-                       L.n_pad, n, L.n_pad);
-    st = sm_backward(L, base, Z_in, n, ld_zin, Zt_in, m, ld_ztin, d_in, S_in, inv_temp, (float)lambda, Cx, grad_in, hs);
+    // masked scores of the layer gradients (Kronecker products summed over tokens), their correlation with A, the row c
+    hipLaunchKernelGGL(sm_block_dot_kernel, dim3(small_blocks), dim3(256), 0, hs, K_in, K_out, L.n_pad, q.m, q.n, q.Tt, q.T, B,
+                       q.nb_pad, q.nb_pad);
+    hipLaunchKernelGGL(sm_corr_kernel, dim3((uint32_t)q.m), dim3(256), 0, hs, A, lda, B, q.nb_pad, q.n, q.m, C, q.nb_pad, corr);
+    // each factor's gradient is the plain backward pass over its token matrices with c spread over the token pairs and
+    // multiplied by the other factor's products
+    hipLaunchKernelGGL(sm_expand_kernel, dim3(tok_blocks), dim3(256), 0, hs, C, q.nb_pad, K_out, L.n_pad, q.m_tok, q.n_tok, q.Tt,
+                       q.T, D, L.n_pad);
+    st = sm_backward(L, base, Z_in, q.n_tok, ld_zin, Zt_in, q.m_tok, ld_ztin, d_in, S_in, inv_temp, (float)lambda, D, grad_in, hs);
     if (st != GRASS_OK) return st;
-    hipLaunchKernelGGL(sm_hadamard_kernel, dim3((uint32_t)ceil_div(m * L.n_pad, 256)), dim3(256), 0, hs, C, B_in, Cx, m,
-                       L.n_pad, n, L.n_pad);
-    st = sm_backward(L, base, Z_out, n, ld_zout, Zt_out, m, ld_ztout, d_out, S_out, inv_temp, (float)lambda, Cx, grad_out, hs);
+    hipLaunchKernelGGL(sm_expand_kernel, dim3(tok_blocks), dim3(256), 0, hs, C, q.nb_pad, K_in, L.n_pad, q.m_tok, q.n_tok, q.Tt,
+                       q.T, D, L.n_pad);
+    st = sm_backward(L, base, Z_out, q.n_tok, ld_zout, Zt_out, q.m_tok, ld_ztout, d_out, S_out, inv_temp, (float)lambda, D, grad_out, hs);
     if (st != GRASS_OK) return st;
     if (objective)
-        hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, m, sig_in, ceil_div((d_in + 3) / 4 * 4, 256),
+        hipLaunchKernelGGL(sm_objective_kernel, dim3(1), dim3(256), 0, hs, corr, q.m, sig_in, ceil_div((d_in + 3) / 4 * 4, 256),
                            (const double*)sig_out, ceil_div((d_out + 3) / 4 * 4, 256), lambda, objective);
     return launch_status();
 }
 
-static size_t sm_factorized_bytes(const SmLayout& L, uint64_t m) {
-    return L.total + 2 * up256((size_t)m * L.n_pad * 4) + up256((size_t)L.parts * 8);
+extern "C" grass_status grass_selective_mask_grad_factorized_seq_workspace_bytes(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt,
+                                                                                 uint64_t d_in, uint64_t d_out,
+                                                                                 size_t* host_bytes) {
+    if (!host_bytes) return GRASS_EINVAL;
+    SmSeq q;
+    grass_status st = check_sm_factorized(n, T, m, Tt, d_in, d_out, &q);
+    if (st != GRASS_OK) return st;
+    *host_bytes = sm_factorized_bytes(sm_layout(q.n_tok, q.m_tok, d_in > d_out ? d_in : d_out), q);
+    return GRASS_OK;
+}
+
+extern "C" grass_status grass_selective_mask_grad_factorized_seq(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t T, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t Tt, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out,
+    const float* A, uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature, float* grad_in,
+    float* grad_out, double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
+    SmSeq q;
+    grass_status st = check_sm_factorized(n, T, m, Tt, d_in, d_out, &q);
+    if (st != GRASS_OK) return st;
+    st = check_sm_factorized_args(q, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout);
+    if (st != GRASS_OK) return st;
+    if (!A || lda < n || !S_in || !S_out || !grad_in || !grad_out) return GRASS_EINVAL;
+    if (!(temperature > 0.0) || !(lambda >= 0.0)) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(q.n_tok, q.m_tok, d_in > d_out ? d_in : d_out);
+    if (!ws || ws_bytes < sm_factorized_bytes(L, q) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    return sm_value_and_grad_factorized(L, q, static_cast<unsigned char*>(ws), Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out,
+                                        ld_ztin, ld_ztout, d_in, d_out, A, lda, S_in, S_out, lambda, temperature, grad_in,
+                                        grad_out, objective, as_stream(stream));
+}
+
+// Exact GradDot scores of the layer on sequences, A[te][i] = sum over token pairs of <z_in, zt_in> <z_out, zt_out>:
+// the same token-pair products without weights, then the block sums.
+extern "C" grass_status grass_graddot_factorized_workspace_bytes(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt,
+                                                                 uint64_t d_in, uint64_t d_out, size_t* host_bytes) {
+    return grass_selective_mask_grad_factorized_seq_workspace_bytes(n, T, m, Tt, d_in, d_out, host_bytes);
+}
+
+extern "C" grass_status grass_graddot_factorized(const float* Z_in, const float* Z_out, uint64_t n, uint64_t T, uint64_t ld_zin,
+                                                 uint64_t ld_zout, const float* Zt_in, const float* Zt_out, uint64_t m,
+                                                 uint64_t Tt, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out,
+                                                 float* A, uint64_t lda, void* ws, size_t ws_bytes, grass_stream stream) {
+    SmSeq q;
+    grass_status st = check_sm_factorized(n, T, m, Tt, d_in, d_out, &q);
+    if (st != GRASS_OK) return st;
+    st = check_sm_factorized_args(q, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout);
+    if (st != GRASS_OK) return st;
+    if (!A || lda < n) return GRASS_EINVAL;
+    const SmLayout L = sm_layout(q.n_tok, q.m_tok, d_in > d_out ? d_in : d_out);
+    if (!ws || ws_bytes < sm_factorized_bytes(L, q) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(ws);
+    float* K_in = reinterpret_cast<float*>(base + L.off_b);
+    float* K_out = reinterpret_cast<float*>(base + L.total);
+    double* sig = reinterpret_cast<double*>(base + L.off_sig);
+    hipStream_t hs = as_stream(stream);
+    st = sm_masked_scores(L, base, Z_in, q.n_tok, ld_zin, Zt_in, q.m_tok, ld_ztin, d_in, nullptr, 1.0f, K_in, sig, hs);
+    if (st != GRASS_OK) return st;
+    st = sm_masked_scores(L, base, Z_out, q.n_tok, ld_zout, Zt_out, q.m_tok, ld_ztout, d_out, nullptr, 1.0f, K_out, sig, hs);
+    if (st != GRASS_OK) return st;
+    hipLaunchKernelGGL(sm_block_dot_kernel, dim3((uint32_t)ceil_div(q.m * q.n, 256)), dim3(256), 0, hs, K_in, K_out, L.n_pad, q.m,
+                       q.n, q.Tt, q.T, A, lda, q.n);                       // exactly the n columns of the caller's rows
+    return launch_status();
 }
 
 extern "C" grass_status grass_selective_mask_grad_factorized(
@@ -417,15 +509,9 @@ extern "C" grass_status grass_selective_mask_grad_factorized(
     const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
     uint64_t lda, const float* S_in, const float* S_out, double lambda, double temperature, float* grad_in, float* grad_out,
     double* objective, void* ws, size_t ws_bytes, grass_stream stream) {
-    grass_status st = check_sm_factorized(n, m, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout,
-                                          A, lda, S_in, S_out, lambda);
-    if (st != GRASS_OK) return st;
-    if (!grad_in || !grad_out || !(temperature > 0.0)) return GRASS_EINVAL;
-    const SmLayout L = sm_layout(n, m, d_in > d_out ? d_in : d_out);
-    if (!ws || ws_bytes < sm_factorized_bytes(L, m) || !aligned(ws, 256)) return GRASS_EWORKSPACE;
-    return sm_value_and_grad_factorized(L, static_cast<unsigned char*>(ws), Z_in, Z_out, n, ld_zin, ld_zout, Zt_in, Zt_out,
-                                        m, ld_ztin, ld_ztout, d_in, d_out, A, lda, S_in, S_out, lambda, temperature,
-                                        grad_in, grad_out, objective, as_stream(stream));
+    return grass_selective_mask_grad_factorized_seq(Z_in, Z_out, n, 1, ld_zin, ld_zout, Zt_in, Zt_out, m, 1, ld_ztin, ld_ztout,
+                                                    d_in, d_out, A, lda, S_in, S_out, lambda, temperature, grad_in, grad_out,
+                                                    objective, ws, ws_bytes, stream);
 }
 
 // Training of the factorised mask: both logit vectors take a plain gradient-ascent step per temperature of the host
@@ -433,10 +519,11 @@ extern "C" grass_status grass_selective_mask_grad_factorized(
 extern "C" grass_status grass_selective_mask_train_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
                                                                               uint64_t d_out, size_t* host_bytes) {
     if (!host_bytes) return GRASS_EINVAL;
-    const uint64_t p = d_in > d_out ? d_in : d_out;
-    grass_status st = check_sm(n, m, p);
-    if (st != GRASS_OK || d_in == 0 || d_out == 0) return st != GRASS_OK ? st : GRASS_EINVAL;
-    *host_bytes = sm_factorized_bytes(sm_layout(n, m, p), m) + up256((size_t)d_in * 4) + up256((size_t)d_out * 4);
+    SmSeq q;
+    grass_status st = check_sm_factorized(n, 1, m, 1, d_in, d_out, &q);
+    if (st != GRASS_OK) return st;
+    *host_bytes = sm_factorized_bytes(sm_layout(n, m, d_in > d_out ? d_in : d_out), q) + up256((size_t)d_in * 4) +
+                  up256((size_t)d_out * 4);
     return GRASS_OK;
 }
 
@@ -445,14 +532,17 @@ extern "C" grass_status grass_selective_mask_train_factorized(
     const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
     uint64_t lda, float* S_in, float* S_out, double lambda, double lr, const double* host_temperatures, uint32_t steps,
     double* objectives, void* ws, size_t ws_bytes, grass_stream stream) {
-    grass_status st = check_sm_factorized(n, m, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout,
-                                          A, lda, S_in, S_out, lambda);
+    SmSeq q;
+    grass_status st = check_sm_factorized(n, 1, m, 1, d_in, d_out, &q);
     if (st != GRASS_OK) return st;
-    if (!(lr == lr) || (steps > 0 && !host_temperatures)) return GRASS_EINVAL;
+    st = check_sm_factorized_args(q, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout);
+    if (st != GRASS_OK) return st;
+    if (!A || lda < n || !S_in || !S_out) return GRASS_EINVAL;
+    if (!(lambda >= 0.0) || !(lr == lr) || (steps > 0 && !host_temperatures)) return GRASS_EINVAL;
     for (uint32_t i = 0; i < steps; ++i)
         if (!(host_temperatures[i] > 0.0)) return GRASS_EINVAL;
     const SmLayout L = sm_layout(n, m, d_in > d_out ? d_in : d_out);
-    const size_t fb = sm_factorized_bytes(L, m);
+    const size_t fb = sm_factorized_bytes(L, q);
     if (!ws || ws_bytes < fb + up256((size_t)d_in * 4) + up256((size_t)d_out * 4) || !aligned(ws, 256))
         return GRASS_EWORKSPACE;
     unsigned char* base = static_cast<unsigned char*>(ws);
@@ -460,8 +550,8 @@ extern "C" grass_status grass_selective_mask_train_factorized(
     float* grad_out = reinterpret_cast<float*>(base + fb + up256((size_t)d_in * 4));
     hipStream_t hs = as_stream(stream);
     for (uint32_t i = 0; i < steps; ++i) {
-        st = sm_value_and_grad_factorized(L, base, Z_in, Z_out, n, ld_zin, ld_zout, Zt_in, Zt_out, m, ld_ztin, ld_ztout, d_in,
-                                          d_out, A, lda, S_in, S_out, lambda, host_temperatures[i], grad_in, grad_out,
+        st = sm_value_and_grad_factorized(L, q, base, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout, d_in, d_out,
+                                          A, lda, S_in, S_out, lambda, host_temperatures[i], grad_in, grad_out,
                                           objectives ? objectives + i : nullptr, hs);
         if (st != GRASS_OK) return st;
         hipLaunchKernelGGL(sm_update_kernel, dim3((uint32_t)ceil_div(d_in, 256)), dim3(256), 0, hs, S_in, grad_in, d_in, lr);

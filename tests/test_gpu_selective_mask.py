@@ -372,3 +372,61 @@ def test_selective_mask_train_factorized_edge_cases(grass):
         grass.grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, -0.01, 1.0, [1.0])
     torch.cuda.synchronize()
     assert torch.equal(S_in, S_in0) and torch.equal(S_out, S_out0)
+
+
+# ------------------------------------------------------------------- factorised form on sequences of tokens
+def _seq_tensors(n, T, m, Tt, d_in, d_out, seed):
+    def t(rows, tok, d, sd):
+        return synth.dense_normal(rows * tok, d, seed=sd, device=_dev()).reshape(rows, tok, d)
+    return (t(n, T, d_in, seed), t(n, T, d_out, seed + 1), t(m, Tt, d_in, seed + 2), t(m, Tt, d_out, seed + 3),
+            synth.dense_normal(1, d_in, seed=seed + 4, device=_dev(), std=1.0).reshape(-1).contiguous(),
+            synth.dense_normal(1, d_out, seed=seed + 5, device=_dev(), std=1.0).reshape(-1).contiguous())
+
+
+@pytest.mark.parametrize("n,T,m,Tt,d_in,d_out,lam,temp", [(6, 3, 2, 2, 5, 4, 0.05, 1.0), (20, 7, 5, 9, 70, 33, 0.01, 0.7),
+                                                          (40, 16, 9, 16, 260, 129, 1e-3, 1.0), (130, 2, 129, 1, 64, 512, 1e-3, 2.0)])
+def test_selective_mask_factorized_sequences_parity(grass, n, T, m, Tt, d_in, d_out, lam, temp):
+    """Exact scores and the factorised objective / gradients for samples of T (train) and Tt (test) tokens: the token
+    sum of Eq. (2) inside the Kronecker inner products of App. B.4; the layer gradients are never formed."""
+    Z_in, Z_out, Zt_in, Zt_out, S_in, S_out = _seq_tensors(n, T, m, Tt, d_in, d_out, seed=4000 + d_in)
+    h = lambda t: t.cpu().numpy().astype(np.float64)
+    A = grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out)
+    torch.cuda.synchronize()
+    want_A = orc.graddot_factorized_seq(h(Z_in), h(Z_out), h(Zt_in), h(Zt_out))
+    assert orc.max_rel_err(h(A), want_A) <= 1e-5
+    gi, go, obj = grass.grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam, temp)
+    torch.cuda.synchronize()
+    want_obj, want_gi, want_go = orc.selective_mask_factorized_seq(h(S_in), h(S_out), h(Z_in), h(Z_out), h(Zt_in), h(Zt_out),
+                                                                   lam, temp)
+    assert abs(float(obj.item()) - want_obj) <= 1e-5 * max(1.0, abs(want_obj))
+    assert np.abs(h(gi) - want_gi).max() <= 2e-4 * np.abs(want_gi).max()
+    assert np.abs(h(go) - want_go).max() <= 2e-4 * np.abs(want_go).max()
+    assert torch.isfinite(gi).all() and torch.isfinite(go).all()
+
+
+def test_selective_mask_factorized_sequences_of_one_token_are_the_single_token_entry_point(grass):
+    n, m, d_in, d_out = 60, 7, 300, 129
+    Z_in, Z_out, Zt_in, Zt_out, S_in, S_out = _seq_tensors(n, 1, m, 1, d_in, d_out, seed=4100)
+    A = grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out)
+    A1 = (grass.grass_score(Z_in[:, 0], Zt_in[:, 0]) * grass.grass_score(Z_out[:, 0], Zt_out[:, 0])).contiguous()
+    a = grass.grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, 0.01, 0.7)
+    b = grass.grass_selective_mask_grad_factorized(Z_in[:, 0], Z_out[:, 0], Zt_in[:, 0], Zt_out[:, 0], A, S_in, S_out, 0.01, 0.7)
+    torch.cuda.synchronize()
+    assert orc.max_rel_err(A.cpu().numpy(), A1.cpu().numpy().astype(np.float64)) <= 1e-5
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
+
+
+def test_selective_mask_factorized_sequences_argument_checks(grass):
+    Z_in, Z_out, Zt_in, Zt_out, S_in, S_out = _seq_tensors(4, 3, 2, 2, 8, 6, seed=4200)
+    A = grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, -1.0, 1.0)
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, 0.1, 0.0)
+    with pytest.raises(grass.GrassError):       # one train sample: no correlation over the train rows
+        grass.grass_graddot_factorized(Z_in[:1], Z_out[:1], Zt_in, Zt_out)
+    # the scores land in the first n columns of the caller's rows and nowhere else
+    wide = torch.full((2, 9), -7.0, dtype=torch.float32, device=_dev())
+    grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out, out=wide[:, :4])
+    torch.cuda.synchronize()
+    assert torch.equal(wide[:, :4], A) and bool((wide[:, 4:] == -7.0).all())
