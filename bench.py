@@ -176,6 +176,9 @@ def main() -> int:
                          "compare-and-swap) forced through the per-call tuning argument")
     ap.add_argument("--copy-reference", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    ap.add_argument("--probe", action="store_true",
+                    help="run only the memory-system probe: pseudo-random 128-byte line reads over 16 GiB, alone and with "
+                         "the write stream of the plain mask gather (what the chip sustains for the gather's pattern)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (samples are independent: more GPUs would compress "
@@ -201,6 +204,20 @@ def main() -> int:
         t, _, _ = _timed(lambda: b.copy_(a), 5, 2, torch)
         print(json.dumps({"copy_reference_bytes_read": nbytes, "copy_reference_bytes_written": nbytes,
                           "ms": round(t / 5, 4), "GBps_read_plus_write": round(2 * nbytes / (t / 5 * 1e-3) / 1e9, 1)}))
+        return 0
+
+    if args.probe:
+        blocks, reads = 65536, 16
+        src = torch.zeros((16 << 30) // 4, dtype=torch.float32, device=dev)
+        dst = torch.empty(blocks * 256 * reads, dtype=torch.float32, device=dev)
+        lines = blocks * 256 * reads
+        out = {"probe": "random_line_reads", "footprint_GiB": 16, "lines_per_launch": lines}
+        for mode, name in ((0, "reads_nontemporal"), (1, "reads_nontemporal_plus_gather_write_stream"), (2, "reads_plain")):
+            t, _, _ = _timed(lambda c: grass.grass_probe_line_reads(src, dst, mode, 100 + c, blocks), 5, 2, torch, indexed=True)
+            nbytes = lines * 128 + (lines * 4 if mode == 1 else 0)
+            out[name] = {"ms": round(t / 5, 3), "G_lines_per_s": round(lines / (t / 5 * 1e-3) / 1e9, 2),
+                         "line_plus_write_GBps": round(nbytes / (t / 5 * 1e-3) / 1e9, 1)}
+        print(json.dumps(out))
         return 0
 
     if args.single_layer_only:

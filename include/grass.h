@@ -506,6 +506,22 @@ grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_id, uint64_t
                                      const int32_t* idx, uint32_t kprime,
                                      uint32_t k, uint32_t s, float* P, uint64_t ldP, grass_stream stream);
 
+/* --------------------------------------------------------- measurement aid
+ * Not part of the method; for whoever measures this library against the memory
+ * system it runs on.  grass_probe_line_reads launches `blocks` workgroups of 256
+ * threads; every thread reads one float from each of 16 pseudo-randomly chosen
+ * 128-byte lines of src (src_floats floats, 128-byte aligned, expected to hold
+ * zeros and to be far larger than the caches): the mask gather of Sec. 3.1
+ * reduced to its memory traffic.
+ *   mode 0  non-temporal reads only
+ *   mode 1  and each value written to dst with coalesced non-temporal stores
+ *           (dst_floats >= blocks * 256 * 16): 4 bytes written per line read,
+ *           the ratio of grass_mask at the headline sizes
+ *   mode 2  reads without the non-temporal hint
+ * Lines read per launch: blocks * 256 * 16.  dst needs one float in modes 0, 2. */
+grass_status grass_probe_line_reads(const float* src, uint64_t src_floats, float* dst, uint64_t dst_floats,
+                                    int mode, uint64_t salt, uint32_t blocks, grass_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -101,6 +101,7 @@ SIGNATURES = {
     "factmask_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
     "factmask_linear": (_int, [_vp, _vp, _u64, _u64, _u32, _u32, _vp, _u32, _vp, _u32, _vp, _u64, _vp, _sz, _vp]),
     "grass_projection_matrix": (_int, [_u64, _u64, _u64, _vp, _u32, _u32, _u32, _vp, _u64, _vp]),
+    "grass_probe_line_reads": (_int, [_vp, _u64, _vp, _u64, _int, _u64, _u32, _vp]),
 }
 
 _lib = None
@@ -703,3 +704,10 @@ def grass_projection_matrix(seed: int, stream_id: int, p: int, k: int, s: int, i
     _check(load_library().grass_projection_matrix(seed, stream_id, p, _ptr(idx), kprime, k, s, _ptr(P), _ld(P), _stream()),
            "grass_projection_matrix")
     return P
+
+
+def grass_probe_line_reads(src: torch.Tensor, dst: torch.Tensor, mode: int, salt: int, blocks: int) -> None:
+    """Measurement aid: blocks * 256 * 16 pseudo-random line reads of src (fp32), see include/grass.h."""
+    assert src.dtype == dst.dtype == torch.float32 and src.is_contiguous() and dst.is_contiguous()
+    _check(load_library().grass_probe_line_reads(_ptr(src), src.numel(), _ptr(dst), dst.numel(), int(mode), int(salt),
+                                                 int(blocks), _stream()), "grass_probe_line_reads")

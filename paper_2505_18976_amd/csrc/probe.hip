@@ -1,0 +1,54 @@
+// Measurement aid, not part of the method: the access pattern of the mask gather (Sec. 3.1 / 3.3.1: one kept fp32
+// coordinate per 128-byte line, the lines scattered over a matrix far larger than the caches) reduced to its memory
+// traffic, so that what the memory system sustains for it can be measured next to the library's kernels.
+#include <hip/hip_runtime.h>
+
+#include "grass.h"
+#include "grass_device.h"
+
+namespace grass {
+
+constexpr int kProbeReads = 16;         // line reads in flight per thread
+
+// Every thread reads one float from each of 16 lines chosen by the counter hash (line index reduced modulo the number
+// of whole lines of src, so every read is in bounds).  MODE 0: non-temporal reads only.  MODE 1: and writes the 16
+// values with non-temporal stores, coalesced (256 bytes per wavefront and value): 4 bytes written per 128 read, the
+// ratio of the plain gather at the headline sizes.  MODE 2: reads without the non-temporal hint.
+template <int MODE>
+__global__ void __launch_bounds__(256) probe_line_reads_kernel(const float* src, uint64_t lines, float* dst, uint64_t salt) {
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    float v[kProbeReads];
+#pragma unroll
+    for (int i = 0; i < kProbeReads; ++i) {
+        const uint64_t line = sm(sm(salt, t), (uint64_t)i) % lines;
+        const float* p = src + line * 32 + (t & 31);
+        v[i] = MODE == 2 ? *p : __builtin_nontemporal_load(p);
+    }
+    if (MODE == 1) {
+        const uint64_t total = (uint64_t)gridDim.x * 256;
+#pragma unroll
+        for (int i = 0; i < kProbeReads; ++i) __builtin_nontemporal_store(v[i], dst + (uint64_t)i * total + t);
+    } else {
+        float acc = 0.0f;
+#pragma unroll
+        for (int i = 0; i < kProbeReads; ++i) acc += v[i];
+        if (acc == 1234.5f) dst[0] = acc;               // keeps the reads alive; src is expected to hold zeros
+    }
+}
+
+}  // namespace grass
+
+using namespace grass;
+
+extern "C" grass_status grass_probe_line_reads(const float* src, uint64_t src_floats, float* dst, uint64_t dst_floats,
+                                               int mode, uint64_t salt, uint32_t blocks, grass_stream stream) {
+    if (!src || !dst || src_floats < 32 || dst_floats == 0 || blocks == 0 || mode < 0 || mode > 2) return GRASS_EINVAL;
+    if (!aligned(src, 128)) return GRASS_EUNSUPPORTED;
+    if (mode == 1 && dst_floats < (uint64_t)blocks * 256 * kProbeReads) return GRASS_EINVAL;
+    const uint64_t lines = src_floats / 32;
+    hipStream_t hs = as_stream(stream);
+    if (mode == 0) hipLaunchKernelGGL(probe_line_reads_kernel<0>, dim3(blocks), dim3(256), 0, hs, src, lines, dst, salt);
+    else if (mode == 1) hipLaunchKernelGGL(probe_line_reads_kernel<1>, dim3(blocks), dim3(256), 0, hs, src, lines, dst, salt);
+    else hipLaunchKernelGGL(probe_line_reads_kernel<2>, dim3(blocks), dim3(256), 0, hs, src, lines, dst, salt);
+    return launch_status();
+}

@@ -101,6 +101,15 @@ def test_logra_refuses_feature_dimensions_beyond_its_offset_range(lib):
     assert lib.logra_linear(fake, fake, 2, 64, 60, 64, fake, 8, fake, 8, fake, 64, fake, 1 << 20, null) == b.GRASS_EUNSUPPORTED  # d % 8
 
 
+def test_probe_checks_its_buffers_on_the_host(lib):
+    from paper_2505_18976_amd import binding as b
+    fake, null = ctypes.c_void_p(4096), ctypes.c_void_p(0)
+    assert lib.grass_probe_line_reads(null, 1 << 20, fake, 1, 0, 0, 8, null) == b.GRASS_EINVAL
+    assert lib.grass_probe_line_reads(fake, 1 << 20, fake, 100, 1, 0, 8, null) == b.GRASS_EINVAL      # 8*256*16 floats needed
+    assert lib.grass_probe_line_reads(fake, 1 << 20, fake, 1, 7, 0, 8, null) == b.GRASS_EINVAL        # no such mode
+    assert lib.grass_probe_line_reads(ctypes.c_void_p(4100), 1 << 20, fake, 1, 0, 0, 8, null) == b.GRASS_EUNSUPPORTED
+
+
 def test_noalloc_entry_point_refuses_oversized_problems_on_the_host(lib):
     """grass_sjlt_noalloc keeps its scratch memory in a fixed 32 MiB buffer inside the library: a problem whose
     partial sums need more is refused before anything touches a GPU (this process has none)."""
