@@ -138,3 +138,26 @@ def test_cache_stage_at_benchmark_size(grass):
         ratio = np.abs(got[r0:r0 + 4096] - ref) / bound
         worst = max(worst, float(ratio.max()))
     assert worst <= 1.0, worst
+
+
+def test_logra_and_factorised_mask_on_the_4096_layer(grass):
+    """The comparison baselines of the single-layer benchmark at its size (n = 32 sequences of 512 tokens, 4,096 x 4,096
+    layer, factors of 64): LoGra with dense Gaussian factors (Sec. 3.3.2 "Recap on LoGra", Eq. (3)) on the
+    producer/consumer kernel - every workgroup streams one whole token tile through all 32 K slices - and the factorised
+    mask Mask_{64 (x) 64}, every output against the oracle."""
+    n, T, d, kf = 32, 512, 4096, 64
+    x, g = synth.linear_layer_factors(n, T, d, d, seed=1004, device=_dev())      # the benchmark's first input pair
+    Pi = grass.grass_to_bf16(grass.grass_gauss_matrix(0, 40, d, kf, 0, d, device=_dev()))
+    Po = grass.grass_to_bf16(grass.grass_gauss_matrix(0, 41, d, kf, 0, d, device=_dev()))
+    out = grass.logra_linear(x, g, Pi, Po)
+    ii = grass.grass_mask_indices(0, 16, d, kf, device=_dev())
+    io = grass.grass_mask_indices(0, 17, d, kf, device=_dev())
+    fm = grass.factmask_linear(x, g, ii, io)
+    torch.cuda.synchronize()
+    h = lambda t: t.float().cpu().numpy().astype(np.float64)
+    ref = orc.logra_linear(h(x), h(g), h(Pi), h(Po))
+    assert out.shape == (n, kf * kf)
+    assert orc.max_rel_err(out.cpu().numpy(), ref) <= 1e-4        # exact bf16 products, fp32 sums over d and over T
+    xs, gs = h(x[:, :, ii.long()]), h(g[:, :, io.long()])
+    ref_m = orc.factgrass_sparsified_gradient(xs, gs, np.arange(kf), np.arange(kf))
+    assert orc.max_rel_err(fm.cpu().numpy(), ref_m) <= TOL_FACT
