@@ -324,7 +324,7 @@ using namespace grass;
 
 // Workspace plan of grass_score: bf16 copies of both operands (mode 1) and K-range partial sums when the M x N
 // output has too few tiles to fill the chip.
-constexpr uint32_t kScoreMaxSplits = 16;      // K ranges of a score product with few output tiles (16 tiles still fill 256 CUs)
+constexpr uint32_t kScoreMaxSplits = 32;      // K ranges of a score product with few output tiles (8 tiles still fill 256 CUs)
 struct ScorePlan {
     uint64_t kp;               // K rounded up to whole 64-byte bf16 slices
     size_t off_test, off_train, off_part, total;

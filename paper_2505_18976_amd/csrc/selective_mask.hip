@@ -23,7 +23,7 @@ hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uin
                        float* partials);
 uint32_t gemm_nt_f32_splits(const float* A, const float* B, uint64_t M, uint64_t N, uint64_t K, uint64_t lda, uint64_t ldb,
                             uint32_t max_splits);
-constexpr uint32_t kSmMaxSplits = 16;
+constexpr uint32_t kSmMaxSplits = 32;
 
 __device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
 
