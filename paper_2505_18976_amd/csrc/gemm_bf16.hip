@@ -222,12 +222,20 @@ struct GemmDmaArgs {
 // word, so K needs no padding for such an operand.
 __device__ __align__(16) const uint32_t g_dma_zeros[4] = {0u, 0u, 0u, 0u};
 
-template <bool F32, bool AKN, bool BKN>
+// SKINNY (row-major operands only): the same 512 stage rows split 128 : 384, i.e. a 128 x 384 tile of C with the
+// wavefronts 2 x 4 over it, 64 x 96 = 2 x 3 MFMA tiles each.  For products with at most 128 (or 257 to 384) rows of A
+// - a handful of test gradients against many train gradients - the square tile would spend half of its matrix work
+// on rows that do not exist.
+template <bool F32, bool AKN, bool BKN, bool SKINNY = false>
 __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     static_assert(F32 || (!AKN && !BKN), "K-major operands are built for fp32 only");
+    static_assert(!SKINNY || (!AKN && !BKN), "the 128 x 384 tile is built for row-major operands only");
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ESZ = F32 ? 4 : 2;                 // bytes per element
     constexpr int SK = 64 / ESZ;                     // elements per slice (64-byte rows)
+    constexpr int TMk = SKINNY ? 128 : TM, TNk = SKINNY ? 384 : TN;      // tile of C; TMk + TNk = 512 stage rows
+    constexpr int WM = TMk / 2, WN = TNk / 4;        // wavefront tile
+    constexpr int MI = WM / 32, NJ = WN / 32;        // MFMA tiles per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 2, wn = wave & 3;
 
@@ -247,7 +255,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         tn = logical / a.tiles_m;
         tm = logical % a.tiles_m;
     }
-    const uint64_t m0 = (uint64_t)tm * TM, n0 = (uint64_t)tn * TN;
+    const uint64_t m0 = (uint64_t)tm * TMk, n0 = (uint64_t)tn * TNk;
     a.C += split * a.split_stride_c;
 
     // DMA map: a stage is 512 rows (A then B) of 128 bytes; wavefront w moves rows 64w..64w+63 with 8
@@ -261,9 +269,10 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     const uint64_t ng_all = (nk_all + 1) / 2, gstride = a.splits;
     const uint64_t ng = (ng_all - split + gstride - 1) / gstride;          // >= 1: the host keeps splits <= ng_all
     const bool half_tail = (nk_all & 1) != 0 && (ng_all - 1) % gstride == split;   // this split owns the half group
-    const bool is_a = wave < 4;                  // wavefronts 0..3 move the A part of a stage, 4..7 the B part
+    const bool is_a = wave * 64 < TMk;           // wavefront w moves stage rows 64w .. 64w+63: the A part comes first
     const bool kmajor = is_a ? AKN : BKN;        // uniform per wavefront
-    const int wq = wave & 3;
+    const int wq = wave & 3;                     // K-major operands (square tile): wavefront within its operand
+    const int op_row0 = is_a ? wave * 64 : wave * 64 - TMk;        // first row of this wavefront inside its operand's tile
     const unsigned char* gsrc[8];
     uint64_t gadv;                               // bytes from one group of this split to its next
     if (kmajor) {
@@ -278,7 +287,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     } else {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int r = wq * 64 + j * 8 + (lane >> 3);               // row of the operand's tile
+            const int r = op_row0 + j * 8 + (lane >> 3);               // row of the operand's tile
             const int kc = (lane & 7) ^ ((r >> 1) & 7);
             const uint64_t row = (is_a ? m0 : n0) + r, lim = is_a ? a.M : a.N;   // rows past the edge re-read the
             gsrc[j] = static_cast<const unsigned char*>(is_a ? a.A : a.B) +       // last row; never stored
@@ -309,11 +318,11 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     // lane only; MFMA step e of k-step ks uses element e of the chunk (k = 8ks + 4*(lane/32) + e).  K-major operand:
     // k-row (8ks + 4*(lane/32) + e) * 1024 + column * 4, one read per step e.
     const int fl = (lane >> 1) & 7;
-    const int a_row = (wm * 128 + (lane & 31)) * 128;
-    const int b_row = (TM + wn * 64 + (lane & 31)) * 128;
+    const int a_row = (wm * WM + (lane & 31)) * 128;
+    const int b_row = (TMk + wn * WN + (lane & 31)) * 128;
     const int a_kn = (4 * (lane >> 5)) * 1024 + (wm * 128 + 4 * (lane & 31)) * 4;
     const int b_kn = TM * 128 + (4 * (lane >> 5)) * 1024 + (wn * 64 + 2 * (lane & 31)) * 4;
-    struct RawFrags { u32x4 a[4]; uint32_t b[8]; };
+    struct RawFrags { u32x4 a[4]; uint32_t b[4 * (SKINNY ? 3 : 2)]; };
     auto load_frags = [&](RawFrags& f, int stage, int ks) {
         const unsigned char* st = smem + stage * kDmaStageBytes;
         const unsigned char* base = st + (((2 * ks + (lane >> 5)) ^ fl) * 16);
@@ -322,7 +331,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
             for (int e = 0; e < 4; ++e) f.a[e] = *reinterpret_cast<const u32x4*>(st + a_kn + (8 * ks + e) * 1024);
         } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 128);
+            for (int i = 0; i < MI; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(base + a_row + i * 32 * 128);
         }
         if constexpr (BKN) {
 #pragma unroll
@@ -332,7 +341,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 const u32x4 v = *reinterpret_cast<const u32x4*>(base + b_row + j * 32 * 128);
 #pragma unroll
                 for (int e = 0; e < 4; ++e) f.b[4 * j + e] = v[e];
@@ -340,18 +349,18 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         }
     };
 
-    f32x16 acc[4][2];
+    f32x16 acc[MI][NJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < NJ; ++j)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
     auto mma = [&](const RawFrags& f) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
+        for (int i = 0; i < MI; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
+            for (int j = 0; j < NJ; ++j) {
                 if constexpr (F32) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -401,16 +410,16 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
 
     // accumulator element e of a lane belongs to row 8*(e/4) + 4*(lane/32) + e%4 and column lane%32 of its MFMA tile;
     // which rows and columns of C a tile owns depends on the operand layouts (see above)
-    const bool interior = m0 + TM <= a.M && n0 + TN <= a.N;     // uniform
+    const bool interior = m0 + TMk <= a.M && n0 + TNk <= a.N;     // uniform
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < MI; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const uint64_t col = BKN ? n0 + wn * 64 + 2 * (lane & 31) + j : n0 + wn * 64 + j * 32 + (lane & 31);
+        for (int j = 0; j < NJ; ++j) {
+            const uint64_t col = BKN ? n0 + wn * WN + 2 * (lane & 31) + j : n0 + wn * WN + j * 32 + (lane & 31);
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int rit = 8 * (e >> 2) + 4 * (lane >> 5) + (e & 3);
-                const uint64_t row = AKN ? m0 + wm * 128 + 4 * rit + i : m0 + wm * 128 + i * 32 + rit;
+                const uint64_t row = AKN ? m0 + wm * WM + 4 * rit + i : m0 + wm * WM + i * 32 + rit;
                 if (interior && !a.accumulate) {
                     a.C[row * a.ldc + col] = acc[i][j][e];
                 } else if (row < a.M && col < a.N) {
@@ -432,8 +441,21 @@ bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint6
 // Split-K factor when there are few output tiles.  All workgroups of a launch take equally long, so it runs in rounds
 // of one workgroup per CU: among the admissible numbers of K ranges (at most max_splits, at least 32 slices each)
 // take the one that leaves the last round fullest, with a small penalty per range for its partial sum.
+// Row-major products with few rows of A (up to 128, or 257 to 384: three tile rows of 128 instead of two of 256) take
+// the 128 x 384 tile when that is less work for the chip.  One workgroup runs per CU at a time, so a launch with
+// enough tiles to do without K ranges costs (rounds of 256 tiles) x (tile area): 65,536 rows of B against 300 rows of
+// A are 512 square tiles = 2 rounds, but 513 tiles of 128 x 384 = 3 rounds, and the square tile wins although 41 % of
+// its rows are padding.  With few tiles the K ranges fill the chip either way and the smaller padding decides.
+static bool gemm_dma_skinny(uint64_t M, uint64_t N) {
+    if (!(M <= 128 || (M > 256 && M <= 384))) return false;
+    const uint64_t sq = ceil_div(M, TM) * ceil_div(N, TN), sk = ceil_div(M, 128) * ceil_div(N, 384);
+    if (sq < 128) return true;
+    return ceil_div(sk, kNumCU) * (128 * 384) < ceil_div(sq, kNumCU) * (uint64_t)(TM * TN);
+}
+
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits) {
-    const uint64_t tiles = ceil_div(M, TM) * ceil_div(N, TN), slices = K / (f32 ? 16 : 32);
+    const uint64_t tiles = gemm_dma_skinny(M, N) ? ceil_div(M, 128) * ceil_div(N, 384) : ceil_div(M, TM) * ceil_div(N, TN);
+    const uint64_t slices = K / (f32 ? 16 : 32);
     if (tiles == 0 || tiles >= (uint64_t)kNumCU || slices < 64) return 1;
     uint32_t best = 1;
     double best_score = -1.0;
@@ -476,8 +498,9 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
     a.m_read = M; a.n_read = n_read; a.k_rows = k_rows;
     a.accumulate = accumulate;
     a.lower_only = lower_only;
-    a.tiles_m = (uint32_t)ceil_div(M, TM);
-    a.tiles_n = (uint32_t)ceil_div(N, TN);
+    const bool skinny = !a_kn && !b_kn && !lower_only && gemm_dma_skinny(M, N);
+    a.tiles_m = (uint32_t)ceil_div(M, skinny ? 128 : TM);
+    a.tiles_n = (uint32_t)ceil_div(N, skinny ? 384 : TN);
     const uint64_t slices = ceil_div(K, sk);
     if (splits < 1 || !partials) splits = 1;
     if (splits > ceil_div(slices, 2)) return false;                        // every split gets at least one group
@@ -487,13 +510,16 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
     if (lower_only && a.tiles_m != a.tiles_n) return false;
     const uint64_t total = (lower_only ? (uint64_t)a.tiles_m * (a.tiles_m + 1) / 2 : (uint64_t)a.tiles_m * a.tiles_n) * splits;
     if (total == 0 || total > 0x7FFFFFFFull) return false;
-    const int variant = !f32 ? 0 : (a_kn ? (b_kn ? 3 : -1) : (b_kn ? 2 : 1));
+    int variant = !f32 ? 0 : (a_kn ? (b_kn ? 3 : -1) : (b_kn ? 2 : 1));
     if (variant < 0) return false;                                         // K-major A with row-major B: not built
-    static LdsOptIn opt_in[4];
-    const void* fns[4] = {reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false>),
+    if (skinny) variant = f32 ? 5 : 4;
+    static LdsOptIn opt_in[6];
+    const void* fns[6] = {reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<true, false, true>),
-                          reinterpret_cast<const void*>(gemm_dma_kernel<true, true, true>)};
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, true, true>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false, true>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false, true>)};
     *err = allow_large_lds(opt_in[variant], fns[variant]);
     if (*err != hipSuccess) return true;
     const size_t lds = (size_t)kDmaStages * kDmaStageBytes;
@@ -502,7 +528,9 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
         case 0: hipLaunchKernelGGL((gemm_dma_kernel<false, false, false>), grid, block, lds, st, a); break;
         case 1: hipLaunchKernelGGL((gemm_dma_kernel<true, false, false>), grid, block, lds, st, a); break;
         case 2: hipLaunchKernelGGL((gemm_dma_kernel<true, false, true>), grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL((gemm_dma_kernel<true, true, true>), grid, block, lds, st, a); break;
+        case 3: hipLaunchKernelGGL((gemm_dma_kernel<true, true, true>), grid, block, lds, st, a); break;
+        case 4: hipLaunchKernelGGL((gemm_dma_kernel<false, false, false, true>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((gemm_dma_kernel<true, false, false, true>), grid, block, lds, st, a); break;
     }
     *err = hipGetLastError();
     return true;

@@ -237,7 +237,8 @@ def test_logra_with_selection_matrices_matches_factgrass_mask_stage(grass):
 # ------------------------------------------------------------------- score
 SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70),
                (200, 130, 8192), (130, 129, 12304), (129, 3, 5000),      # few tiles, long K: split over K ranges
-               (128, 128, 16), (256, 256, 48), (384, 130, 4112)]         # an odd number of 64-byte slices: half group last
+               (128, 128, 16), (256, 256, 48), (384, 130, 4112),         # an odd number of 64-byte slices: half group last
+               (1000, 128, 8192), (700, 100, 4096), (400, 300, 4096), (2048, 384, 1040), (513, 257, 4112)]   # few test rows: 128 x 384 tiles
 
 
 @pytest.mark.parametrize("N,M,K", SCORE_CASES)
