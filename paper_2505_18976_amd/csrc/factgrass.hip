@@ -21,6 +21,10 @@
 // launch cost is paid once.
 #include <type_traits>
 
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
 #include "grass_device.h"
 
 namespace grass {
@@ -440,13 +444,28 @@ extern "C" grass_status factgrass_layers(const factgrass_layer* host_layers, uin
     // arguments are copied when the launch is enqueued, so nothing depends on host memory staying alive or on how
     // the runtime treats pageable copies, and the call stays asynchronous.
     hipStream_t hs = as_stream(stream);
+    // Workgroups are handed out in launch order, layer after layer, and a workgroup's time follows the number of
+    // 128-byte lines its picks touch per token, which depends on the layer's widths: the layers go into the table
+    // most expensive first, so that the last round of workgroups is made of the cheap ones (every layer writes to
+    // its own `out`, so the order is free).
+    std::vector<uint32_t> order(n_layers);
+    std::vector<double> cost(n_layers);
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        auto lines = [](double d, double picks) {               // expected distinct lines of `picks` random 2-byte columns
+            const double L = d * 2.0 / 128.0 < 1.0 ? 1.0 : d * 2.0 / 128.0;
+            return L * (1.0 - std::pow(1.0 - 1.0 / L, picks));
+        };
+        order[l] = l;
+        cost[l] = lines((double)host_layers[l].d_in, (double)kin_p) + lines((double)host_layers[l].d_out, (double)kout_p);
+    }
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t a, uint32_t b) { return cost[a] > cost[b]; });
     FgLayer first_layer{};
     for (uint32_t l0 = 0; l0 < n_layers; l0 += kLayersPerPack) {
         FgLayerPack pack;
         pack.first = l0;
         pack.count = n_layers - l0 < (uint32_t)kLayersPerPack ? n_layers - l0 : (uint32_t)kLayersPerPack;
         for (uint32_t q = 0; q < pack.count; ++q) {
-            const factgrass_layer& h = host_layers[l0 + q];
+            const factgrass_layer& h = host_layers[order[l0 + q]];
             FgLayer& d = pack.l[q];
             d.x = static_cast<const uint16_t*>(h.x);
             d.g = static_cast<const uint16_t*>(h.gout);
