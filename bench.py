@@ -217,6 +217,9 @@ def main() -> int:
             nbytes = lines * 128 + (lines * 4 if mode == 1 else 0)
             out[name] = {"ms": round(t / 5, 3), "G_lines_per_s": round(lines / (t / 5 * 1e-3) / 1e9, 2),
                          "line_plus_write_GBps": round(nbytes / (t / 5 * 1e-3) / 1e9, 1)}
+        sblocks = (16 << 30) // (64 << 10)                      # one pass over the buffer
+        t, _, _ = _timed(lambda: grass.grass_probe_line_reads(src, dst, 3, 0, sblocks), 5, 2, torch)
+        out["sequential_stream_nontemporal"] = {"ms": round(t / 5, 3), "GBps": round((16 << 30) / (t / 5 * 1e-3) / 1e9, 1)}
         print(json.dumps(out))
         return 0
 

@@ -518,7 +518,10 @@ grass_status grass_projection_matrix(uint64_t seed, uint64_t stream_id, uint64_t
  *           (dst_floats >= blocks * 256 * 16): 4 bytes written per line read,
  *           the ratio of grass_mask at the headline sizes
  *   mode 2  reads without the non-temporal hint
- * Lines read per launch: blocks * 256 * 16.  dst needs one float in modes 0, 2. */
+ *   mode 3  for comparison, a plain stream: every thread reads 16 x 16 bytes,
+ *           workgroup after workgroup through src (blocks * 64 KB per launch)
+ * Lines read per launch: blocks * 256 * 16 (mode 3: blocks * 512, every byte of
+ * them).  dst needs one float in modes 0, 2, 3.                                 */
 grass_status grass_probe_line_reads(const float* src, uint64_t src_floats, float* dst, uint64_t dst_floats,
                                     int mode, uint64_t salt, uint32_t blocks, grass_stream stream);
 

@@ -19,7 +19,7 @@ def test_probe_runs_in_every_mode_and_writes_only_what_it_owns(grass):
     src = torch.zeros(1 << 20, dtype=torch.float32, device=dev)
     guard = 64
     dst = torch.full((blocks * 256 * 16 + guard,), -3.0, dtype=torch.float32, device=dev)
-    for mode in (0, 2):
+    for mode in (0, 2, 3):
         grass.grass_probe_line_reads(src, dst[:1], mode, 5, blocks)
     torch.cuda.synchronize()
     assert bool((dst == -3.0).all())                       # read-only modes leave dst alone (src holds zeros)
@@ -29,4 +29,4 @@ def test_probe_runs_in_every_mode_and_writes_only_what_it_owns(grass):
     with pytest.raises(grass.GrassError):                  # destination too small for the write stream
         grass.grass_probe_line_reads(src, dst[:100], 1, 5, blocks)
     with pytest.raises(grass.GrassError):
-        grass.grass_probe_line_reads(src, dst, 3, 5, blocks)
+        grass.grass_probe_line_reads(src, dst, 4, 5, blocks)
