@@ -463,6 +463,23 @@ def selective_mask_train_factorized(S_in0, S_out0, Z_in, Z_out, Zt_in, Zt_out, l
     return S_in, S_out, np.asarray(history, dtype=np.float64)
 
 
+def selective_mask_train_factorized_seq(S_in0, S_out0, X_in, X_out, Xt_in, Xt_out, lam: float, lr: float, temperatures):
+    """The training loop of the factorised Selective Mask for samples that are sequences of tokens: the loop of
+    selective_mask_train_factorized with the objective and derivatives of selective_mask_factorized_seq (same readings:
+    plain gradient ascent, one caller-given temperature per step, both derivatives taken at the logits before the step).
+    X_in (n, T, d_in), X_out (n, T, d_out) train; Xt_in (m, T', d_in), Xt_out (m, T', d_out) test.
+    Returns (S_in, S_out, history) with history[i] the objective before step i."""
+    S_in = np.array(S_in0, dtype=np.float64, copy=True)
+    S_out = np.array(S_out0, dtype=np.float64, copy=True)
+    history = []
+    for T in temperatures:
+        obj, g_in, g_out = selective_mask_factorized_seq(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam, T)
+        history.append(obj)
+        S_in = S_in + lr * g_in
+        S_out = S_out + lr * g_out
+    return S_in, S_out, np.asarray(history, dtype=np.float64)
+
+
 def graddot_correlation(G, Gt, idx) -> float:
     """First term of Eq. (1) for a binary mask: the mean over test rows of the Pearson correlation between the exact
     GradDot scores <g_i, g_test> and those of the masked gradients <g_i[idx], g_test[idx]> (Sec. 3.2)."""

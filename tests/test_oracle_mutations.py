@@ -264,7 +264,7 @@ pins_train_fact = _load("test_oracle_selective_mask_train_factorized")
 
 
 def _train_factorized_variant(descent=False, stale_temperature=False, only_input=False, sequential=False,
-                              no_step_size=False):
+                              no_step_size=False, step_fn="selective_mask_factorized"):
     def train(S_in0, S_out0, Z_in, Z_out, Zt_in, Zt_out, lam, lr, temperatures):
         S_in = np.array(S_in0, dtype=np.float64, copy=True)
         S_out = np.array(S_out0, dtype=np.float64, copy=True)
@@ -272,11 +272,11 @@ def _train_factorized_variant(descent=False, stale_temperature=False, only_input
         step = 1.0 if no_step_size else lr
         for T in temperatures:
             Tg = temperatures[0] if stale_temperature else T
-            obj, g_in, g_out = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)
-            history.append(orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, T)[0])
+            obj, g_in, g_out = getattr(orc, step_fn)(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)
+            history.append(getattr(orc, step_fn)(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, T)[0])
             S_in = S_in - step * g_in if descent else S_in + step * g_in
             if sequential:          # output derivative taken after the input logits have already moved
-                g_out = orc.selective_mask_factorized(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)[2]
+                g_out = getattr(orc, step_fn)(S_in, S_out, Z_in, Z_out, Zt_in, Zt_out, lam, Tg)[2]
             if not only_input:
                 S_out = S_out - step * g_out if descent else S_out + step * g_out
         return S_in, S_out, np.asarray(history, dtype=np.float64)
@@ -355,3 +355,25 @@ def test_sequence_graddot_with_matching_positions_only_is_caught(monkeypatch):
     monkeypatch.setattr(orc, "graddot_factorized_seq", diag_only)
     with pytest.raises(AssertionError):
         pins_sm.test_sequence_graddot_equals_inner_products_of_materialised_layer_gradients()
+
+
+@pytest.mark.parametrize("kwargs,pin", [
+    (dict(descent=True), "test_sequence_training_first_step_follows_the_finite_difference_gradient_of_the_sequence_objective"),
+    (dict(descent=True), "test_sequence_training_small_steps_never_decrease_the_objective"),
+    (dict(stale_temperature=True), "test_sequence_training_is_a_composition_of_its_steps_and_moves_both_vectors"),
+    (dict(only_input=True), "test_sequence_training_is_a_composition_of_its_steps_and_moves_both_vectors"),
+    (dict(sequential=True), "test_sequence_training_first_step_follows_the_finite_difference_gradient_of_the_sequence_objective"),
+    (dict(sequential=True), "test_sequence_training_with_one_token_is_the_single_token_loop"),
+    (dict(no_step_size=True), "test_sequence_training_with_a_trivial_output_factor_is_the_plain_loop_on_token_sums"),
+    (dict(step_fn="_single_token_step"), "test_sequence_training_with_a_trivial_output_factor_is_the_plain_loop_on_token_sums"),
+])
+def test_sequence_factorised_training_mistakes_are_caught(monkeypatch, kwargs, pin):
+    """The loop variants above around the sequence objective; the last one trains on the first token only."""
+    def first_token(S_in, S_out, X_in, X_out, Xt_in, Xt_out, lam, temperature=1.0):
+        return orc.selective_mask_factorized(S_in, S_out, X_in[:, 0], X_out[:, 0], Xt_in[:, 0], Xt_out[:, 0], lam, temperature)
+    monkeypatch.setattr(orc, "_single_token_step", first_token, raising=False)
+    kw = dict(step_fn="selective_mask_factorized_seq")
+    kw.update(kwargs)
+    monkeypatch.setattr(orc, "selective_mask_train_factorized_seq", _train_factorized_variant(**kw))
+    with pytest.raises(AssertionError):
+        getattr(pins_train_fact, pin)()

@@ -126,3 +126,75 @@ def test_trained_factor_masks_find_the_planted_coordinates_of_both_factors():
     c_sel = corr(orc.selective_mask_indices(a, k_in), orc.selective_mask_indices(b, k_out))
     c_rand = np.mean([corr(orc.mask_indices(sd, 0, d_in, k_in), orc.mask_indices(sd, 1, d_out, k_out)) for sd in range(20)])
     assert c_sel > 0.9 and c_sel > c_rand + 0.2
+
+
+# ------------------------------------------------------------------ the same loop on sequences of tokens
+def _seq_problem(n=7, m=3, T=4, Tt=3, d_in=5, d_out=4, seed=0):
+    rng = np.random.default_rng(seed)
+    return (0.4 * rng.standard_normal(d_in), 0.4 * rng.standard_normal(d_out), rng.standard_normal((n, T, d_in)),
+            rng.standard_normal((n, T, d_out)), rng.standard_normal((m, Tt, d_in)), rng.standard_normal((m, Tt, d_out)))
+
+
+def _seq_objective(S_in, S_out, X, lam, T):
+    return orc.selective_mask_factorized_seq(S_in, S_out, *X, lam, T)[0]
+
+
+def test_sequence_training_with_one_token_is_the_single_token_loop():
+    S_in, S_out, *X = _seq_problem(T=1, Tt=1, seed=20)
+    temps = [1.0, 0.7, 0.5]
+    a, b, hist = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.02, 0.6, temps)
+    a1, b1, hist1 = orc.selective_mask_train_factorized(S_in, S_out, *(x[:, 0] for x in X), 0.02, 0.6, temps)
+    assert np.allclose(a, a1, rtol=1e-12, atol=1e-14) and np.allclose(b, b1, rtol=1e-12, atol=1e-14)
+    assert np.allclose(hist, hist1, rtol=1e-12, atol=1e-14)
+
+
+def test_sequence_training_first_step_follows_the_finite_difference_gradient_of_the_sequence_objective():
+    S_in, S_out, *X = _seq_problem(seed=21)
+    lam, lr, T, h = 0.02, 0.7, 0.8, 1e-6
+    a, b, hist = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, lam, lr, [T])
+    for got, S, which in ((a, S_in, 0), (b, S_out, 1)):
+        fd = np.empty_like(S)
+        for j in range(S.size):
+            e = np.zeros_like(S); e[j] = h
+            plus = _seq_objective(S_in + e, S_out, X, lam, T) if which == 0 else _seq_objective(S_in, S_out + e, X, lam, T)
+            minus = _seq_objective(S_in - e, S_out, X, lam, T) if which == 0 else _seq_objective(S_in, S_out - e, X, lam, T)
+            fd[j] = (plus - minus) / (2 * h)
+        assert np.allclose(got - S, lr * fd, rtol=1e-5, atol=1e-9)
+    assert hist.shape == (1,) and hist[0] == _seq_objective(S_in, S_out, X, lam, T)
+
+
+def test_sequence_training_with_a_trivial_output_factor_is_the_plain_loop_on_token_sums():
+    """Output factor of width one, equal to 1 on every token, logit saturated: the layer gradient of a sample is the
+    sum of its input tokens (Eq. (2)), the mask is sigma(S_in), so the input logits must follow the plain loop on the
+    token sums; the history differs by the penalty lam * 1 of the output coordinate."""
+    rng = np.random.default_rng(22)
+    n, m, T, Tt, d = 10, 3, 4, 2, 6
+    X_in, Xt_in = rng.standard_normal((n, T, d)), rng.standard_normal((m, Tt, d))
+    S0 = 0.3 * rng.standard_normal(d)
+    temps, lam, lr = [1.0, 0.9, 0.8], 0.02, 0.6
+    a, b, hist = orc.selective_mask_train_factorized_seq(S0, [60.0], X_in, np.ones((n, T, 1)), Xt_in, np.ones((m, Tt, 1)),
+                                                         lam, lr, temps)
+    want, want_hist = orc.selective_mask_train(S0, X_in.sum(1), Xt_in.sum(1), lam, lr, temps)
+    assert np.allclose(a, want, rtol=1e-11, atol=1e-13) and np.allclose(hist, want_hist - lam, rtol=1e-11, atol=1e-13)
+    assert abs(b[0] - 60.0) < 1e-12
+
+
+def test_sequence_training_is_a_composition_of_its_steps_and_moves_both_vectors():
+    S_in, S_out, *X = _seq_problem(seed=23)
+    temps = [2.0, 0.25, 1.0]
+    a, b, hist = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.03, 0.4, temps)
+    a1, b1, h1 = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.03, 0.4, temps[:1])
+    a2, b2, h2 = orc.selective_mask_train_factorized_seq(a1, b1, *X, 0.03, 0.4, temps[1:])
+    assert np.array_equal(a, a2) and np.array_equal(b, b2) and np.array_equal(hist, np.concatenate([h1, h2]))
+    sa, sb, _ = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.03, 0.4, temps[::-1])
+    assert not np.allclose(sa, a) and not np.allclose(sb, b)
+    assert not np.allclose(a, S_in) and not np.allclose(b, S_out)
+    n0, _, h0 = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.03, 0.0, temps)
+    assert np.array_equal(n0, S_in) and h0[1] == _seq_objective(S_in, S_out, X, 0.03, temps[1])
+
+
+def test_sequence_training_small_steps_never_decrease_the_objective():
+    S_in, S_out, *X = _seq_problem(n=12, m=4, seed=24)
+    a, b, hist = orc.selective_mask_train_factorized_seq(S_in, S_out, *X, 0.01, 0.05, [1.0] * 40)
+    final = _seq_objective(a, b, X, 0.01, 1.0)
+    assert np.all(np.diff(hist) >= 0.0) and final >= hist[-1] and final > hist[0] + 1e-4
