@@ -472,6 +472,24 @@ grass_status grass_selective_mask_train_factorized(const float* Z_in, const floa
                                                    const double* host_temperatures, uint32_t steps,
                                                    double* objectives,
                                                    void* ws, size_t ws_bytes, grass_stream stream);
+/* grass_selective_mask_train_factorized_seq: that training loop for samples that
+ * are sequences of tokens (the layer gradient of a sample is the sum over its
+ * tokens of the Kronecker products, Eq. (2)); rows of Z_* are tokens as in
+ * grass_selective_mask_grad_factorized_seq, T = Tt = 1 is the call above.      */
+grass_status grass_selective_mask_train_factorized_seq_workspace_bytes(uint64_t n, uint64_t T, uint64_t m, uint64_t Tt,
+                                                                       uint64_t d_in, uint64_t d_out,
+                                                                       size_t* host_bytes);
+grass_status grass_selective_mask_train_factorized_seq(const float* Z_in, const float* Z_out, uint64_t n, uint64_t T,
+                                                       uint64_t ld_zin, uint64_t ld_zout,
+                                                       const float* Zt_in, const float* Zt_out, uint64_t m, uint64_t Tt,
+                                                       uint64_t ld_ztin, uint64_t ld_ztout,
+                                                       uint64_t d_in, uint64_t d_out,
+                                                       const float* A, uint64_t lda,
+                                                       float* S_in, float* S_out,
+                                                       double lambda, double lr,
+                                                       const double* host_temperatures, uint32_t steps,
+                                                       double* objectives,
+                                                       void* ws, size_t ws_bytes, grass_stream stream);
 grass_status grass_selective_mask_indices_workspace_bytes(uint64_t p, size_t* host_bytes);
 grass_status grass_selective_mask_indices(const float* S, uint64_t p, uint32_t k, int32_t* idx,
                                           uint32_t* count, void* ws, size_t ws_bytes, grass_stream stream);

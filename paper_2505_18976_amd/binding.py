@@ -96,6 +96,11 @@ SIGNATURES = {
     "grass_selective_mask_train_factorized": (_int, [_vp, _vp, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64, _u64,
                                                      _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double,
                                                      ctypes.POINTER(ctypes.c_double), _u32, _vp, _vp, _sz, _vp]),
+    "grass_selective_mask_train_factorized_seq_workspace_bytes": (_int, [_u64, _u64, _u64, _u64, _u64, _u64,
+                                                                         ctypes.POINTER(_sz)]),
+    "grass_selective_mask_train_factorized_seq": (_int, [_vp, _vp, _u64, _u64, _u64, _u64, _vp, _vp, _u64, _u64, _u64, _u64,
+                                                         _u64, _u64, _vp, _u64, _vp, _vp, ctypes.c_double, ctypes.c_double,
+                                                         ctypes.POINTER(ctypes.c_double), _u32, _vp, _vp, _sz, _vp]),
     "grass_selective_mask_indices_workspace_bytes": (_int, [_u64, ctypes.POINTER(_sz)]),
     "grass_selective_mask_indices": (_int, [_vp, _u64, _u32, _vp, _vp, _vp, _sz, _vp]),
     "factmask_linear_workspace_bytes": (_int, [_u64, _u64, _u32, _u32, ctypes.POINTER(_sz)]),
@@ -648,6 +653,29 @@ def grass_selective_mask_train_factorized(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S
         _ptr(Z_in), _ptr(Z_out), n, _ld(Z_in), _ld(Z_out), _ptr(Zt_in), _ptr(Zt_out), m, _ld(Zt_in), _ld(Zt_out), d_in, d_out,
         _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(lr), sched, steps, _ptr(objectives), _ptr(ws),
         ws.numel(), _stream()), "grass_selective_mask_train_factorized")
+    return S_in, S_out, objectives[:steps]
+
+
+def grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam: float, lr: float,
+                                              temperatures, objectives: torch.Tensor | None = None):
+    """grass_selective_mask_train_factorized on sequences ((samples, tokens, features) tensors).
+    Returns (S_in, S_out, objectives float64 [steps])."""
+    (zi, zo, zti, zto), n, T, m, Tt, d_in, d_out = _seq_shapes(Z_in, Z_out, Zt_in, Zt_out)
+    assert A.dtype == S_in.dtype == S_out.dtype == torch.float32 and A.shape == (m, n)
+    assert S_in.is_contiguous() and S_out.is_contiguous() and S_in.numel() == d_in and S_out.numel() == d_out
+    steps = len(temperatures)
+    sched = (ctypes.c_double * max(steps, 1))(*[float(t) for t in temperatures])
+    if objectives is None:
+        objectives = torch.empty(max(steps, 1), dtype=torch.float64, device=Z_in.device)
+    nbytes = _sz(0)
+    _check(load_library().grass_selective_mask_train_factorized_seq_workspace_bytes(n, T, m, Tt, d_in, d_out,
+                                                                                    ctypes.byref(nbytes)),
+           "grass_selective_mask_train_factorized_seq_workspace_bytes")
+    ws = _workspace(nbytes.value, Z_in.device)
+    _check(load_library().grass_selective_mask_train_factorized_seq(
+        _ptr(zi), _ptr(zo), n, T, _ld(zi), _ld(zo), _ptr(zti), _ptr(zto), m, Tt, _ld(zti), _ld(zto), d_in, d_out,
+        _ptr(A), _ld(A), _ptr(S_in), _ptr(S_out), float(lam), float(lr), sched, steps, _ptr(objectives), _ptr(ws),
+        ws.numel(), _stream()), "grass_selective_mask_train_factorized_seq")
     return S_in, S_out, objectives[:steps]
 
 

@@ -516,24 +516,26 @@ extern "C" grass_status grass_selective_mask_grad_factorized(
 
 // Training of the factorised mask: both logit vectors take a plain gradient-ascent step per temperature of the host
 // schedule, both derivatives taken at the logits before the step (the two updates run after both backward passes).
-extern "C" grass_status grass_selective_mask_train_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
-                                                                              uint64_t d_out, size_t* host_bytes) {
+// Samples are sequences of T (train) and Tt (test) tokens; one token each is the case the paper writes out.
+extern "C" grass_status grass_selective_mask_train_factorized_seq_workspace_bytes(uint64_t n, uint64_t T, uint64_t m,
+                                                                                  uint64_t Tt, uint64_t d_in, uint64_t d_out,
+                                                                                  size_t* host_bytes) {
     if (!host_bytes) return GRASS_EINVAL;
     SmSeq q;
-    grass_status st = check_sm_factorized(n, 1, m, 1, d_in, d_out, &q);
+    grass_status st = check_sm_factorized(n, T, m, Tt, d_in, d_out, &q);
     if (st != GRASS_OK) return st;
-    *host_bytes = sm_factorized_bytes(sm_layout(n, m, d_in > d_out ? d_in : d_out), q) + up256((size_t)d_in * 4) +
-                  up256((size_t)d_out * 4);
+    *host_bytes = sm_factorized_bytes(sm_layout(q.n_tok, q.m_tok, d_in > d_out ? d_in : d_out), q) +
+                  up256((size_t)d_in * 4) + up256((size_t)d_out * 4);
     return GRASS_OK;
 }
 
-extern "C" grass_status grass_selective_mask_train_factorized(
-    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
-    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
-    uint64_t lda, float* S_in, float* S_out, double lambda, double lr, const double* host_temperatures, uint32_t steps,
-    double* objectives, void* ws, size_t ws_bytes, grass_stream stream) {
+extern "C" grass_status grass_selective_mask_train_factorized_seq(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t T, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t Tt, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out,
+    const float* A, uint64_t lda, float* S_in, float* S_out, double lambda, double lr, const double* host_temperatures,
+    uint32_t steps, double* objectives, void* ws, size_t ws_bytes, grass_stream stream) {
     SmSeq q;
-    grass_status st = check_sm_factorized(n, 1, m, 1, d_in, d_out, &q);
+    grass_status st = check_sm_factorized(n, T, m, Tt, d_in, d_out, &q);
     if (st != GRASS_OK) return st;
     st = check_sm_factorized_args(q, d_in, d_out, Z_in, Z_out, ld_zin, ld_zout, Zt_in, Zt_out, ld_ztin, ld_ztout);
     if (st != GRASS_OK) return st;
@@ -541,7 +543,7 @@ extern "C" grass_status grass_selective_mask_train_factorized(
     if (!(lambda >= 0.0) || !(lr == lr) || (steps > 0 && !host_temperatures)) return GRASS_EINVAL;
     for (uint32_t i = 0; i < steps; ++i)
         if (!(host_temperatures[i] > 0.0)) return GRASS_EINVAL;
-    const SmLayout L = sm_layout(n, m, d_in > d_out ? d_in : d_out);
+    const SmLayout L = sm_layout(q.n_tok, q.m_tok, d_in > d_out ? d_in : d_out);
     const size_t fb = sm_factorized_bytes(L, q);
     if (!ws || ws_bytes < fb + up256((size_t)d_in * 4) + up256((size_t)d_out * 4) || !aligned(ws, 256))
         return GRASS_EWORKSPACE;
@@ -558,4 +560,19 @@ extern "C" grass_status grass_selective_mask_train_factorized(
         hipLaunchKernelGGL(sm_update_kernel, dim3((uint32_t)ceil_div(d_out, 256)), dim3(256), 0, hs, S_out, grad_out, d_out, lr);
     }
     return launch_status();
+}
+
+extern "C" grass_status grass_selective_mask_train_factorized_workspace_bytes(uint64_t n, uint64_t m, uint64_t d_in,
+                                                                              uint64_t d_out, size_t* host_bytes) {
+    return grass_selective_mask_train_factorized_seq_workspace_bytes(n, 1, m, 1, d_in, d_out, host_bytes);
+}
+
+extern "C" grass_status grass_selective_mask_train_factorized(
+    const float* Z_in, const float* Z_out, uint64_t n, uint64_t ld_zin, uint64_t ld_zout, const float* Zt_in,
+    const float* Zt_out, uint64_t m, uint64_t ld_ztin, uint64_t ld_ztout, uint64_t d_in, uint64_t d_out, const float* A,
+    uint64_t lda, float* S_in, float* S_out, double lambda, double lr, const double* host_temperatures, uint32_t steps,
+    double* objectives, void* ws, size_t ws_bytes, grass_stream stream) {
+    return grass_selective_mask_train_factorized_seq(Z_in, Z_out, n, 1, ld_zin, ld_zout, Zt_in, Zt_out, m, 1, ld_ztin, ld_ztout,
+                                                     d_in, d_out, A, lda, S_in, S_out, lambda, lr, host_temperatures, steps,
+                                                     objectives, ws, ws_bytes, stream);
 }

@@ -430,3 +430,60 @@ def test_selective_mask_factorized_sequences_argument_checks(grass):
     grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out, out=wide[:, :4])
     torch.cuda.synchronize()
     assert torch.equal(wide[:, :4], A) and bool((wide[:, 4:] == -7.0).all())
+
+
+@pytest.mark.parametrize("n,T,m,Tt,d_in,d_out,lam,lr,steps", [(6, 3, 2, 2, 5, 4, 0.05, 0.05, 5), (20, 7, 5, 9, 70, 33, 0.01, 0.02, 8),
+                                                              (40, 16, 9, 16, 260, 129, 1e-3, 0.01, 6)])
+def test_selective_mask_train_factorized_sequences_parity(grass, n, T, m, Tt, d_in, d_out, lam, lr, steps):
+    """The device-side training loop on sequences against the oracle's loop (drift bound of the other training tests),
+    and bit for bit against separate calls of the sequence gradient entry point with a host-side update."""
+    Z_in, Z_out, Zt_in, Zt_out, S_in0, S_out0 = _seq_tensors(n, T, m, Tt, d_in, d_out, seed=4300 + d_in)
+    S_in0, S_out0 = (0.3 * S_in0).contiguous(), (0.3 * S_out0).contiguous()
+    temps = np.geomspace(1.0, 0.5, steps)
+    A = grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out)
+    S_in, S_out = S_in0.clone(), S_out0.clone()
+    _, _, objs = grass.grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, S_in, S_out, lam, lr, temps)
+    torch.cuda.synchronize()
+    h = lambda t: t.cpu().numpy().astype(np.float64)
+    a, b = h(S_in0), h(S_out0)
+    path_in = path_out = 0.0
+    hist = []
+    for Tm in temps:
+        a2, b2, h1 = orc.selective_mask_train_factorized_seq(a, b, h(Z_in), h(Z_out), h(Zt_in), h(Zt_out), lam, lr, [Tm])
+        path_in += np.abs(a2 - a).max(); path_out += np.abs(b2 - b).max()
+        hist.append(h1[0]); a, b = a2, b2
+    assert np.abs(a - h(S_in0)).max() > 10 * 2e-4 * path_in and np.abs(b - h(S_out0)).max() > 10 * 2e-4 * path_out
+    assert np.abs(h(S_in) - a).max() <= 2e-4 * path_in + steps * 2.0 ** -23 * np.abs(a).max()
+    assert np.abs(h(S_out) - b).max() <= 2e-4 * path_out + steps * 2.0 ** -23 * np.abs(b).max()
+    assert np.abs(objs.cpu().numpy() - np.asarray(hist)).max() <= 1e-5 * max(1.0, np.abs(hist).max())
+    T_in, T_out = S_in0.clone(), S_out0.clone()
+    for Tm in temps:
+        gi, go, _ = grass.grass_selective_mask_grad_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, T_in, T_out, lam, float(Tm))
+        T_in = (T_in.double() + lr * gi.double()).float()
+        T_out = (T_out.double() + lr * go.double()).float()
+    torch.cuda.synchronize()
+    assert torch.equal(T_in, S_in) and torch.equal(T_out, S_out)
+
+
+def test_selective_mask_train_factorized_sequences_of_one_token_and_edge_cases(grass):
+    n, m, d_in, d_out = 60, 7, 300, 129
+    Z_in, Z_out, Zt_in, Zt_out, S_in0, S_out0 = _seq_tensors(n, 1, m, 1, d_in, d_out, seed=4400)
+    A = grass.grass_graddot_factorized(Z_in, Z_out, Zt_in, Zt_out)
+    temps = [1.0, 0.8, 0.6]
+    a_in, a_out = S_in0.clone(), S_out0.clone()
+    _, _, oa = grass.grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, a_in, a_out, 0.01, 0.5, temps)
+    b_in, b_out = S_in0.clone(), S_out0.clone()
+    _, _, ob = grass.grass_selective_mask_train_factorized(Z_in[:, 0], Z_out[:, 0], Zt_in[:, 0], Zt_out[:, 0], A, b_in, b_out,
+                                                           0.01, 0.5, temps)
+    torch.cuda.synchronize()
+    assert torch.equal(a_in, b_in) and torch.equal(a_out, b_out) and torch.equal(oa, ob)
+    assert not torch.equal(a_in, S_in0) and not torch.equal(a_out, S_out0)
+    # no steps: nothing moves; a non-positive temperature anywhere in the schedule is refused before any launch
+    c_in, c_out = S_in0.clone(), S_out0.clone()
+    grass.grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, c_in, c_out, 0.01, 0.5, [])
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, c_in, c_out, 0.01, 0.5, [1.0, 0.0])
+    with pytest.raises(grass.GrassError):
+        grass.grass_selective_mask_train_factorized_seq(Z_in, Z_out, Zt_in, Zt_out, A, c_in, c_out, -0.01, 0.5, [1.0])
+    torch.cuda.synchronize()
+    assert torch.equal(c_in, S_in0) and torch.equal(c_out, S_out0)
