@@ -23,7 +23,7 @@ hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uin
                        float* partials);
 uint32_t gemm_nt_f32_splits(const float* A, const float* B, uint64_t M, uint64_t N, uint64_t K, uint64_t lda, uint64_t ldb,
                             uint32_t max_splits);
-constexpr uint32_t kSmMaxSplits = 32;
+constexpr uint32_t kSmMaxSplits = 64;
 
 __device__ __forceinline__ float sigmoidf(float x) { return 1.0f / (1.0f + expf(-x)); }
 
@@ -41,12 +41,12 @@ __device__ __forceinline__ double block_sum(double v, double* red) {
     return r;
 }
 
-// Gtw[t][j] = Gt[t][j] * sigma_j^2 (S null: Gt[t][j]) for a block of 256 columns and all m rows; columns p..ld_w are
-// zero-filled.
-// sig_part[blockIdx.x] = sum of sigma_j over the block's columns.
-__global__ void __launch_bounds__(256) sm_weight_kernel(const float* Gt, uint64_t ldgt, uint64_t m, uint64_t p,
-                                                       const float* S, float inv_temp, float* Gtw, uint64_t ld_w,
-                                                       double* sig_part) {
+// Gtw[t][j] = Gt[t][j] * sigma_j^2 (S null: Gt[t][j]) for a block of 256 columns and the rows blockIdx.y,
+// blockIdx.y + gridDim.y, ...; columns p..ld_w are zero-filled.
+// sig_part[blockIdx.x] = sum of sigma_j over the block's columns (written by the first row group).
+__global__ void __launch_bounds__(256) sm_weight_kernel(const float* __restrict__ Gt, uint64_t ldgt, uint64_t m, uint64_t p,
+                                                       const float* __restrict__ S, float inv_temp,
+                                                       float* __restrict__ Gtw, uint64_t ld_w, double* sig_part) {
     __shared__ double red[256];
     const uint64_t j = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     float w = 0.0f, sig = 0.0f;
@@ -54,8 +54,15 @@ __global__ void __launch_bounds__(256) sm_weight_kernel(const float* Gt, uint64_
         if (S) { sig = sigmoidf(S[j] * inv_temp); w = sig * sig; }
         else w = 1.0f;                                     // no mask: plain inner products
     }
-    if (j < ld_w)
-        for (uint64_t t = 0; t < m; ++t) Gtw[t * ld_w + j] = j < p ? Gt[t * ldgt + j] * w : 0.0f;
+    if (j < ld_w) {
+        if (j < p) {
+#pragma unroll 4
+            for (uint64_t t = blockIdx.y; t < m; t += gridDim.y) Gtw[t * ld_w + j] = Gt[t * ldgt + j] * w;
+        } else {
+            for (uint64_t t = blockIdx.y; t < m; t += gridDim.y) Gtw[t * ld_w + j] = 0.0f;
+        }
+    }
+    if (blockIdx.y != 0) return;                           // uniform
     const double total = block_sum((double)sig, red);
     if (threadIdx.x == 0) sig_part[blockIdx.x] = total;
 }
@@ -97,14 +104,25 @@ __global__ void __launch_bounds__(256) sm_update_kernel(float* S, const float* g
 }
 
 // grad[j] = 2 sigma_j sigma_j' * sum_t Gt[t][j] R[t][j - j0] - lambda sigma_j' for the columns [j0, j0 + pc).
-__global__ void __launch_bounds__(256) sm_grad_kernel(const float* Gt, uint64_t ldgt, uint64_t m, const float* R,
-                                                     uint64_t ld_r, uint64_t j0, uint64_t pc, const float* S,
-                                                     float inv_temp, float lambda, float* grad) {
-    const uint64_t c = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (c >= pc) return;
+// A workgroup takes 64 columns; its four wavefronts sum the rows t = w, w + 4, ... in fp64 and the four partial sums
+// are added in a fixed order.
+__global__ void __launch_bounds__(256) sm_grad_kernel(const float* __restrict__ Gt, uint64_t ldgt, uint64_t m,
+                                                     const float* __restrict__ R, uint64_t ld_r, uint64_t j0, uint64_t pc,
+                                                     const float* __restrict__ S, float inv_temp, float lambda,
+                                                     float* __restrict__ grad) {
+    __shared__ double part[4][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint64_t c = (uint64_t)blockIdx.x * 64 + lane;
     const uint64_t j = j0 + c;
     double acc = 0.0;
-    for (uint64_t t = 0; t < m; ++t) acc += (double)Gt[t * ldgt + j] * (double)R[t * ld_r + c];
+    if (c < pc) {
+#pragma unroll 4
+        for (uint64_t t = w; t < m; t += 4) acc += (double)Gt[t * ldgt + j] * (double)R[t * ld_r + c];
+    }
+    part[w][lane] = acc;
+    __syncthreads();
+    if (w != 0 || c >= pc) return;
+    acc = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
     const float sig = sigmoidf(S[j] * inv_temp);
     const float dsig = sig * (1.0f - sig) * inv_temp;
     grad[j] = (float)(2.0 * (double)sig * (double)dsig * acc - (double)lambda * (double)dsig);
@@ -191,8 +209,8 @@ static grass_status sm_masked_scores(const SmLayout& L, unsigned char* base, con
                                      float* B, double* sig_part, hipStream_t hs) {
     float* Gtw = reinterpret_cast<float*>(base + L.off_gtw);
     const uint64_t ld_w = (p + 3) / 4 * 4;
-    hipLaunchKernelGGL(sm_weight_kernel, dim3((uint32_t)ceil_div(ld_w, 256)), dim3(256), 0, hs, Gt, ldgt, m, p, S, inv_temp, Gtw,
-                       ld_w, sig_part);
+    hipLaunchKernelGGL(sm_weight_kernel, dim3((uint32_t)ceil_div(ld_w, 256), (uint32_t)(m < 16 ? m : 16)), dim3(256), 0, hs, Gt,
+                       ldgt, m, p, S, inv_temp, Gtw, ld_w, sig_part);
     // The direct-to-LDS GEMM contracts over whole 64-byte slices.  With 16-byte aligned rows of G the bulk of the
     // contraction (p rounded down to a multiple of 16) goes through it and the last p % 16 columns are added by a
     // second, tiny product; otherwise one product over all p columns runs on the register-staged kernel.
@@ -241,7 +259,7 @@ static grass_status sm_backward(const SmLayout& L, unsigned char* base, const fl
             if (gemm_nt_f32(C, GTc, Rc, m, pc, L.n_pad, L.n_pad, L.n_pad, L.pc, 0, 0, hs, 1, nullptr) != hipSuccess)
                 return GRASS_EHIP;
         }
-        hipLaunchKernelGGL(sm_grad_kernel, dim3((uint32_t)ceil_div(pc, 256)), dim3(256), 0, hs, Gt, ldgt, m, Rc, L.pc, j0, pc,
+        hipLaunchKernelGGL(sm_grad_kernel, dim3((uint32_t)ceil_div(pc, 64)), dim3(256), 0, hs, Gt, ldgt, m, Rc, L.pc, j0, pc,
                            S, inv_temp, lambda, grad);
     }
     return GRASS_OK;
