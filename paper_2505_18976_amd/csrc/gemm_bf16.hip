@@ -222,18 +222,19 @@ struct GemmDmaArgs {
 // word, so K needs no padding for such an operand.
 __device__ __align__(16) const uint32_t g_dma_zeros[4] = {0u, 0u, 0u, 0u};
 
-// SKINNY (row-major operands only): the same 512 stage rows split 128 : 384, i.e. a 128 x 384 tile of C with the
-// wavefronts 2 x 4 over it, 64 x 96 = 2 x 3 MFMA tiles each.  For products with at most 128 (or 257 to 384) rows of A
-// - a handful of test gradients against many train gradients - the square tile would spend half of its matrix work
-// on rows that do not exist.
+// SKINNY (row-major A): for products with at most 128 (or 257 to 384) rows of A - a handful of test gradients against
+// many train gradients - the square tile would spend half of its matrix work on rows that do not exist.  With a
+// row-major B the same 512 stage rows split 128 : 384, i.e. a 128 x 384 tile of C with the wavefronts 2 x 4 over it,
+// 64 x 96 = 2 x 3 MFMA tiles each.  With a K-major B the stage keeps the square tile's image (B's 32 k-rows of 256
+// columns behind 256 row slots, of which A fills 128): a 128 x 256 tile of C, 64 x 64 per wavefront.
 template <bool F32, bool AKN, bool BKN, bool SKINNY = false>
 __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     static_assert(F32 || (!AKN && !BKN), "K-major operands are built for fp32 only");
-    static_assert(!SKINNY || (!AKN && !BKN), "the 128 x 384 tile is built for row-major operands only");
+    static_assert(!SKINNY || !AKN, "the tiles of 128 rows are built for a row-major A only");
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int ESZ = F32 ? 4 : 2;                 // bytes per element
     constexpr int SK = 64 / ESZ;                     // elements per slice (64-byte rows)
-    constexpr int TMk = SKINNY ? 128 : TM, TNk = SKINNY ? 384 : TN;      // tile of C; TMk + TNk = 512 stage rows
+    constexpr int TMk = SKINNY ? 128 : TM, TNk = SKINNY ? (BKN ? 256 : 384) : TN;      // tile of C
     constexpr int WM = TMk / 2, WN = TNk / 4;        // wavefront tile
     constexpr int MI = WM / 32, NJ = WN / 32;        // MFMA tiles per wavefront
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -270,6 +271,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     const uint64_t ng = (ng_all - split + gstride - 1) / gstride;          // >= 1: the host keeps splits <= ng_all
     const bool half_tail = (nk_all & 1) != 0 && (ng_all - 1) % gstride == split;   // this split owns the half group
     const bool is_a = wave * 64 < TMk;           // wavefront w moves stage rows 64w .. 64w+63: the A part comes first
+    const bool dma_idle = SKINNY && BKN && !is_a && wave < 4;      // 128 x 256 tile: stage rows 128..255 stay unused
     const bool kmajor = is_a ? AKN : BKN;        // uniform per wavefront
     const int wq = wave & 3;                     // K-major operands (square tile): wavefront within its operand
     const int op_row0 = is_a ? wave * 64 : wave * 64 - TMk;        // first row of this wavefront inside its operand's tile
@@ -297,6 +299,7 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
     }
     const int upper = (lane >> 2) & 1;        // row-major operand: chunk >= 4 for even j, chunk < 4 for odd j
     auto dma = [&](uint64_t group, int stage) {
+        if (dma_idle) return;                                                        // uniform per wavefront
         unsigned char* base = smem + stage * kDmaStageBytes + wave * 8192;
         const bool tail = half_tail && group == ng - 1;
         const uint64_t krow0 = ((uint64_t)split + group * gstride) * 32 + 8 * wq;   // K-major: first k-row of this wavefront
@@ -446,11 +449,11 @@ bool gemm_dma_eligible(bool f32, const void* A, const void* B, uint64_t K, uint6
 // enough tiles to do without K ranges costs (rounds of 256 tiles) x (tile area): 65,536 rows of B against 300 rows of
 // A are 512 square tiles = 2 rounds, but 513 tiles of 128 x 384 = 3 rounds, and the square tile wins although 41 % of
 // its rows are padding.  With few tiles the K ranges fill the chip either way and the smaller padding decides.
-static bool gemm_dma_skinny(uint64_t M, uint64_t N) {
+static bool gemm_dma_skinny(uint64_t M, uint64_t N, uint64_t tile_n = 384) {
     if (!(M <= 128 || (M > 256 && M <= 384))) return false;
-    const uint64_t sq = ceil_div(M, TM) * ceil_div(N, TN), sk = ceil_div(M, 128) * ceil_div(N, 384);
+    const uint64_t sq = ceil_div(M, TM) * ceil_div(N, TN), sk = ceil_div(M, 128) * ceil_div(N, tile_n);
     if (sq < 128) return true;
-    return ceil_div(sk, kNumCU) * (128 * 384) < ceil_div(sq, kNumCU) * (uint64_t)(TM * TN);
+    return ceil_div(sk, kNumCU) * (128 * tile_n) < ceil_div(sq, kNumCU) * (uint64_t)(TM * TN);
 }
 
 uint32_t gemm_dma_splits(uint64_t M, uint64_t N, uint64_t K, bool f32, uint32_t max_splits) {
@@ -498,9 +501,10 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
     a.m_read = M; a.n_read = n_read; a.k_rows = k_rows;
     a.accumulate = accumulate;
     a.lower_only = lower_only;
-    const bool skinny = !a_kn && !b_kn && !lower_only && gemm_dma_skinny(M, N);
+    const uint64_t skinny_n = b_kn ? 256 : 384;                           // a K-major B keeps the square tile's stage image
+    const bool skinny = !a_kn && !lower_only && gemm_dma_skinny(M, N, skinny_n);
     a.tiles_m = (uint32_t)ceil_div(M, skinny ? 128 : TM);
-    a.tiles_n = (uint32_t)ceil_div(N, skinny ? 384 : TN);
+    a.tiles_n = (uint32_t)ceil_div(N, skinny ? skinny_n : TN);
     const uint64_t slices = ceil_div(K, sk);
     if (splits < 1 || !partials) splits = 1;
     if (splits > ceil_div(slices, 2)) return false;                        // every split gets at least one group
@@ -512,14 +516,15 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
     if (total == 0 || total > 0x7FFFFFFFull) return false;
     int variant = !f32 ? 0 : (a_kn ? (b_kn ? 3 : -1) : (b_kn ? 2 : 1));
     if (variant < 0) return false;                                         // K-major A with row-major B: not built
-    if (skinny) variant = f32 ? 5 : 4;
-    static LdsOptIn opt_in[6];
-    const void* fns[6] = {reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false>),
+    if (skinny) variant = !f32 ? 4 : (b_kn ? 6 : 5);
+    static LdsOptIn opt_in[7];
+    const void* fns[7] = {reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<true, false, true>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<true, true, true>),
                           reinterpret_cast<const void*>(gemm_dma_kernel<false, false, false, true>),
-                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false, true>)};
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, false, true>),
+                          reinterpret_cast<const void*>(gemm_dma_kernel<true, false, true, true>)};
     *err = allow_large_lds(opt_in[variant], fns[variant]);
     if (*err != hipSuccess) return true;
     const size_t lds = (size_t)kDmaStages * kDmaStageBytes;
@@ -530,7 +535,8 @@ static bool launch_gemm_dma_any(bool f32, bool a_kn, bool b_kn, const void* A, c
         case 2: hipLaunchKernelGGL((gemm_dma_kernel<true, false, true>), grid, block, lds, st, a); break;
         case 3: hipLaunchKernelGGL((gemm_dma_kernel<true, true, true>), grid, block, lds, st, a); break;
         case 4: hipLaunchKernelGGL((gemm_dma_kernel<false, false, false, true>), grid, block, lds, st, a); break;
-        default: hipLaunchKernelGGL((gemm_dma_kernel<true, false, false, true>), grid, block, lds, st, a); break;
+        case 5: hipLaunchKernelGGL((gemm_dma_kernel<true, false, false, true>), grid, block, lds, st, a); break;
+        default: hipLaunchKernelGGL((gemm_dma_kernel<true, false, true, true>), grid, block, lds, st, a); break;
     }
     *err = hipGetLastError();
     return true;

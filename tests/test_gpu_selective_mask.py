@@ -37,7 +37,9 @@ def _problem(n, m, p, seed, pad=0):
                                                 (200, 130, 4096, 1e-3, 0.5, 0), (300, 140, 5002, 1e-4, 2.0, 2),
                                                 (130, 129, 70000, 1e-5, 1.0, 0),
                                                 # 16-byte aligned rows: the backward product reads G in place
-                                                (131, 128, 70004, 1e-5, 1.0, 0), (77, 260, 4098, 1e-3, 1.0, 2)])
+                                                (131, 128, 70004, 1e-5, 1.0, 0), (77, 260, 4098, 1e-3, 1.0, 2),
+                                                # 128 or 257..384 test rows: tiles of 128 rows in both products
+                                                (160, 128, 4352, 1e-3, 1.0, 0), (90, 300, 8200, 1e-3, 0.7, 0)])
 def test_selective_mask_grad_parity(grass, n, m, p, lam, temp, pad):
     G, Gt, S = _problem(n, m, p, seed=3000 + p, pad=pad)
     A = grass.grass_score(G, Gt, compute_mode=0)
