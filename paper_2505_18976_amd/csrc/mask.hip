@@ -30,6 +30,7 @@ struct SelectState {
 // LogitKeys: Selective Mask with an exact count (App. B.4 "ensuring exact k"): the largest logits first, so the key
 // is the bitwise complement of the order-preserving integer image of S_j (-0 is folded into +0), in the upper word.
 struct HashKeys {
+    static constexpr bool kClustered = false;                  // hashed keys: a wavefront's digits are all different
     uint64_t sub;
     __device__ __forceinline__ uint64_t operator()(uint64_t j) const { return sm(sub, j); }
 };
@@ -39,6 +40,7 @@ __device__ __forceinline__ uint64_t logit_key(float v) {
     return (uint64_t)(~u) << 32;                                // ascending key = descending logit
 }
 struct LogitKeys {
+    static constexpr bool kClustered = true;                   // logits: many keys share their leading digits
     const float* S;
     __device__ __forceinline__ uint64_t operator()(uint64_t j) const { return logit_key(S[j]); }
 };
@@ -55,6 +57,13 @@ __global__ void select_init_kernel(SelectState* st, unsigned long long prefix, u
     st->pad = 0;
 }
 
+// Counter of histogram bin b: neighbouring bins sit 32 words apart, in different 128-byte lines.  Keys that cluster in
+// a run of neighbouring bins (logits of similar size share their leading bits) then spread their additions over as
+// many lines as bins instead of queueing up on a few.
+__device__ __forceinline__ uint32_t hist_slot(uint32_t bin) { return ((bin & 2047u) << 5) | (bin >> 11); }
+__device__ __forceinline__ uint32_t hist_bin_of_slot(uint32_t slot) { return ((slot & 31u) << 11) | (slot >> 5); }
+static_assert(kHistBins == 65536, "hist_slot permutes 16-bit bins");
+
 // pass = 0..3: histogram of bits [48-16*pass, 64-16*pass) among keys whose
 // higher bits equal the prefix.
 template <class KeyFn>
@@ -67,7 +76,24 @@ __global__ void __launch_bounds__(256) select_hist_kernel(KeyFn kf, uint64_t p, 
     for (; j < p; j += stride) {
         const uint64_t key = kf(j);
         const bool in_class = pass == 0 ? true : ((key >> (shift + 16)) == prefix);
-        if (in_class) atomicAdd(&hist[(key >> shift) & 0xFFFFull], 1u);
+        const uint32_t bin = (uint32_t)((key >> shift) & 0xFFFFull);
+        if constexpr (KeyFn::kClustered) {
+            // Keys that cluster in a few bins would serialise on those counters: the lanes of a wavefront that share
+            // a bin send one addition of their number (a few rounds; whatever is left after eight adds singly).
+            bool todo = in_class;
+            for (int round = 0; round < 8; ++round) {
+                const unsigned long long pending = __ballot(todo);
+                if (pending == 0) break;                                        // uniform
+                const int leader = __ffsll((long long)pending) - 1;
+                const uint32_t lead_bin = (uint32_t)__shfl((int)bin, leader);
+                const unsigned long long same = __ballot(todo && bin == lead_bin);
+                if ((int)(threadIdx.x & 63) == leader) atomicAdd(&hist[hist_slot(lead_bin)], (uint32_t)__popcll(same));
+                if (bin == lead_bin) todo = false;
+            }
+            if (todo) atomicAdd(&hist[hist_slot(bin)], 1u);
+        } else {
+            if (in_class) atomicAdd(&hist[hist_slot(bin)], 1u);
+        }
     }
 }
 
@@ -77,23 +103,44 @@ __global__ void __launch_bounds__(1024) select_pick_kernel(SelectState* st, cons
     __shared__ uint32_t chosen_bin, chosen_before;
     const int t = threadIdx.x;
     constexpr int per = kHistBins / 1024;   // 64 bins per thread
-    uint32_t sum = 0;
-    for (int b = 0; b < per; ++b) sum += hist[t * per + b];
-    part[t] = sum;
+    // part[t] = count of the bins t*per .. t*per + per - 1; the counters are read in storage order (coalesced)
+    part[t] = 0;
     __syncthreads();
-    // inclusive scan over 1024 partial sums (Hillis-Steele)
-    for (int off = 1; off < 1024; off <<= 1) {
-        uint32_t v = (t >= off) ? part[t - off] : 0u;
+    uint32_t c[per];
+#pragma unroll
+    for (int q = 0; q < per; ++q) c[q] = hist[(uint32_t)t + 1024u * q];            // all loads in flight together
+#pragma unroll
+    for (int q = 0; q < per; ++q)
+        if (c[q]) atomicAdd(&part[hist_bin_of_slot((uint32_t)t + 1024u * q) / per], c[q]);
+    __syncthreads();
+    // inclusive scan over the 1024 partial sums: within each wavefront by shuffles, then the totals of the earlier
+    // wavefronts are added
+    __shared__ uint32_t wave_total[16];
+    {
+        const int lane = t & 63, w = t >> 6;
+        uint32_t v = part[t];
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const uint32_t u = (uint32_t)__shfl_up((int)v, off);
+            if (lane >= off) v += u;
+        }
+        if (lane == 63) wave_total[w] = v;
         __syncthreads();
-        part[t] += v;
+        uint32_t base = 0;
+        for (int q = 0; q < w; ++q) base += wave_total[q];
+        part[t] = v + base;
         __syncthreads();
     }
     const uint32_t need = st->need;
     const uint32_t before = (t == 0) ? 0u : part[t - 1];
     if (before < need && need <= part[t]) {
         uint32_t run = before;
+        uint32_t mine[per];
+#pragma unroll
+        for (int b = 0; b < per; ++b) mine[b] = hist[hist_slot((uint32_t)(t * per + b))];     // loads in flight together
+#pragma unroll
         for (int b = 0; b < per; ++b) {
-            const uint32_t c = hist[t * per + b];
+            const uint32_t c = mine[b];
             if (run < need && need <= run + c) {
                 chosen_bin = (uint32_t)(t * per + b);
                 chosen_before = run;
