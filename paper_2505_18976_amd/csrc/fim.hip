@@ -23,20 +23,60 @@ hipError_t gemm_nt_f32(const float* A, const float* B, float* C, uint64_t M, uin
 // (splits == 0) or the sum, in ascending order, of `splits` dense k x k partial products.
 __global__ void __launch_bounds__(256) fim_finish_kernel(float* F, uint64_t ldf, uint32_t k, float scale,
                                                         const float* partials, uint32_t splits) {
-    const uint32_t b = blockIdx.x * 64 + (threadIdx.x & 63);
-    const uint32_t a0 = blockIdx.y * 64;
-    if (blockIdx.x > blockIdx.y || b >= k) return;
-    for (uint32_t a = a0 + (threadIdx.x >> 6); a < a0 + 64 && a < k; a += 4) {
-        if (a < b) continue;
-        float v;
-        if (splits == 0) v = F[(uint64_t)a * ldf + b];
-        else {
-            v = 0.0f;
-            for (uint32_t s = 0; s < splits; ++s) v += partials[((uint64_t)s * k + a) * k + b];
+    // one 64 x 64 tile on or below the diagonal per workgroup; the mirrored tile is written from an LDS copy so that
+    // both stores run along rows
+    __shared__ float tile[64][65];
+    if (blockIdx.x > blockIdx.y) return;
+    const uint32_t a0 = blockIdx.y * 64, b0 = blockIdx.x * 64;
+    const uint32_t c = threadIdx.x & 63, r0 = threadIdx.x >> 6;
+    // phase 1: a thread owns 4 adjacent columns of 4 rows (16-byte loads when the columns exist and are aligned)
+    {
+        const uint32_t c4 = (threadIdx.x & 15) * 4, rr = threadIdx.x >> 4;
+        const bool vec = b0 + c4 + 4 <= k && k % 4 == 0 && ldf % 4 == 0 && ((uintptr_t)F & 15) == 0 &&
+                         ((uintptr_t)partials & 15) == 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t r = rr + 16 * i, a = a0 + r;
+            if (a >= k) continue;
+            float v[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+            if (vec) {
+                if (splits == 0) {
+                    const float4 q = *reinterpret_cast<const float4*>(F + (uint64_t)a * ldf + b0 + c4);
+                    v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+                }
+                for (uint32_t s = 0; s < splits; ++s) {
+                    const float4 q = *reinterpret_cast<const float4*>(partials + ((uint64_t)s * k + a) * k + b0 + c4);
+                    v[0] += q.x; v[1] += q.y; v[2] += q.z; v[3] += q.w;
+                }
+            } else {
+                for (int e = 0; e < 4; ++e) {
+                    const uint32_t bb = b0 + c4 + e;
+                    if (bb >= k) continue;
+                    if (splits == 0) v[e] = F[(uint64_t)a * ldf + bb];
+                    for (uint32_t s = 0; s < splits; ++s) v[e] += partials[((uint64_t)s * k + a) * k + bb];
+                }
+            }
+            const bool whole = vec && a >= b0 + c4 + 3;          // all four on or below the diagonal
+            if (whole) {
+                float4 q;
+                q.x = v[0] * scale; q.y = v[1] * scale; q.z = v[2] * scale; q.w = v[3] * scale;
+                *reinterpret_cast<float4*>(F + (uint64_t)a * ldf + b0 + c4) = q;
+            }
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const uint32_t bb = b0 + c4 + e;
+                if (bb >= k || a < bb) continue;                 // above the diagonal: not computed, not stored
+                const float w = v[e] * scale;
+                if (!whole) F[(uint64_t)a * ldf + bb] = w;
+                tile[r][c4 + e] = w;
+            }
         }
-        v *= scale;
-        F[(uint64_t)a * ldf + b] = v;
-        F[(uint64_t)b * ldf + a] = v;
+    }
+    __syncthreads();
+    // element (b0 + r, a0 + c) of the upper triangle = element (a0 + c, b0 + r) of the lower one
+    for (uint32_t r = r0; r < 64; r += 4) {
+        const uint32_t row = b0 + r, col = a0 + c;
+        if (row < k && col < k && col > row) F[(uint64_t)row * ldf + col] = tile[c][r];
     }
 }
 
