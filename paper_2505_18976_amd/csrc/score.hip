@@ -70,7 +70,7 @@ __device__ __forceinline__ float4 load4(const float* base, uint64_t ld, uint64_t
 }
 
 template <int MODE, int V>
-__global__ void __launch_bounds__(kGemmThreads) gemm_nt_kernel(GemmArgs a) {
+__global__ void __launch_bounds__(kGemmThreads) __attribute__((amdgpu_waves_per_eu(3, 3))) gemm_nt_kernel(GemmArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
