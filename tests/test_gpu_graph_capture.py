@@ -71,3 +71,92 @@ def test_compression_chain_replays_from_a_graph(grass):
         torch.cuda.synchronize()
         for got, ref in zip((out_a, out_u, out_f, scores), want):
             assert torch.equal(got, ref), replay      # same kernels, same fixed reduction order: bit for bit
+
+
+def test_cache_and_attribute_stage_replays_from_a_graph(grass):
+    """FIM, damped inverse (fp64 Cholesky, tens of dependent launches), iFVP and the score product of the preconditioned
+    rows, captured as one graph and replayed on new compressed gradients in the same buffers."""
+    dev = torch.device("cuda:0")
+    N, k, M, lam = 1500, 320, 40, 1e-2
+    G = synth.compressed_gradients(N, k, seed=70, device=dev)
+    test_rows = synth.dense_normal(M, k, seed=71, device=dev)
+    F = torch.empty((k, k), dtype=torch.float32, device=dev)
+    W = torch.empty((k, k), dtype=torch.float32, device=dev)
+    pre = torch.empty((N, k), dtype=torch.float32, device=dev)
+    scores = torch.empty((M, N), dtype=torch.float32, device=dev)
+    info = torch.zeros(1, dtype=torch.int32, device=dev)
+    ws_f = torch.empty(max(grass.grass_fim_workspace_bytes(N, k), 256), dtype=torch.uint8, device=dev)
+    ws_i = torch.empty(max(grass.grass_fim_inverse_workspace_bytes(k), 256), dtype=torch.uint8, device=dev)
+    ws_s = torch.empty(max(grass.grass_score_workspace_bytes(N, M, k, 0), 256), dtype=torch.uint8, device=dev)
+
+    def chain():
+        grass.grass_fim(G, out=F, ws=ws_f)
+        grass.grass_fim_inverse(F, lam, out=W, info=info, ws=ws_i)
+        grass.grass_ifvp(G, W, out=pre)
+        grass.grass_score(pre, test_rows, compute_mode=0, out=scores, ws=ws_s)
+
+    def eager():
+        chain()
+        torch.cuda.synchronize()
+        return [t.clone() for t in (F, W, pre, scores)]
+
+    want = eager()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for replay in range(3):
+        if replay:
+            G.copy_(synth.compressed_gradients(N, k, seed=70 + replay, device=dev))
+            want = eager()
+        for t in (F, W, pre, scores):
+            t.fill_(float("nan"))
+        info.fill_(-1)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert int(info.item()) == 0, replay
+        for got, ref in zip((F, W, pre, scores), want):
+            assert torch.equal(got, ref), replay
+
+
+def test_selective_mask_training_replays_from_a_graph(grass):
+    """The device-side training loop (its temperature schedule is read on the host at capture time) as one graph:
+    every replay restarts from the same logits on new gradients and must match the eager run bit for bit."""
+    dev = torch.device("cuda:0")
+    n, m, p, steps = 140, 128, 5004, 6
+    G, Gt, _ = synth.planted_gradients(n, m, p, 64, seed=80, device=dev)
+    S0 = synth.dense_normal(1, p, seed=81, device=dev, std=0.1).reshape(-1).contiguous()
+    S = S0.clone()
+    A = torch.empty((m, n), dtype=torch.float32, device=dev)
+    objs = torch.empty(steps, dtype=torch.float64, device=dev)
+    temps = np.geomspace(1.0, 0.6, steps)
+    ws_a = torch.empty(max(grass.grass_score_workspace_bytes(n, m, p, 0), 256), dtype=torch.uint8, device=dev)
+    ws_t = torch.empty(grass.grass_selective_mask_train_workspace_bytes(n, m, p), dtype=torch.uint8, device=dev)
+
+    def chain():
+        grass.grass_score(G, Gt, compute_mode=0, out=A, ws=ws_a)
+        grass.grass_selective_mask_train(G, Gt, A, S, 1e-4, 50.0, temps, objectives=objs, ws=ws_t)
+
+    def eager():
+        S.copy_(S0)
+        chain()
+        torch.cuda.synchronize()
+        return S.clone(), objs.clone()
+
+    want = eager()
+    assert not torch.equal(want[0], S0)
+    S.copy_(S0)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        chain()
+    for replay in range(3):
+        if replay:
+            G2, Gt2, _ = synth.planted_gradients(n, m, p, 64, seed=80 + replay, device=dev)
+            G.copy_(G2); Gt.copy_(Gt2)
+            want = eager()
+        S.copy_(S0)
+        objs.fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(S, want[0]) and torch.equal(objs, want[1]), replay
