@@ -641,6 +641,7 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
             return launch_status();
         }
     }
+    uint32_t ranges_used = 0;                 // partial products the first chunk initialises; later chunks use no more
     for (uint64_t r0 = 0; r0 < N; r0 += rows) {
         const uint32_t rc = (uint32_t)(r0 + rows <= N ? rows : N - r0);
         const uint32_t rc_pad = (rc + 15) / 16 * 16;                 // the GEMM contracts over whole 64-byte slices
@@ -648,9 +649,12 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
                            rc_pad, k, Gt, rows);
         hipError_t e;
         if (splits > 1) {
-            // a short last chunk uses fewer ranges; the first chunk (accumulate = 0) initialises all of them
+            // a short chunk uses fewer ranges: the first chunk (accumulate = 0) initialises the ones it uses, a
+            // shorter last chunk adds to a subset of them, and only those are summed at the end (a first chunk that
+            // is itself short - few rows in all - must not leave the sum reading partial products nobody wrote)
             uint32_t s_cur = splits;
             if ((uint64_t)rc_pad / 16 < (uint64_t)s_cur * 32) s_cur = rc_pad / 16 / 32;
+            if (r0 == 0) ranges_used = s_cur >= 2 ? s_cur : 1;
             if (s_cur >= 2)
                 e = gemm_nt_f32(Gt, Gt, nullptr, k, k, rc_pad, rows, rows, k, r0 != 0, 1, hs, s_cur, partials);
             else
@@ -661,7 +665,7 @@ extern "C" grass_status grass_fim(const float* G, uint64_t N, uint32_t k, uint64
         if (e != hipSuccess) return GRASS_EHIP;
     }
     hipLaunchKernelGGL(fim_finish_kernel, dim3((k + 63) / 64, (k + 63) / 64), dim3(256), 0, hs, F, ldf, k,
-                       (float)(1.0 / (double)N), partials, splits > 1 ? splits : 0);
+                       (float)(1.0 / (double)N), partials, splits > 1 ? ranges_used : 0);
     return launch_status();
 }
 

@@ -52,6 +52,19 @@ def test_fim_respects_leading_dimensions(grass):
     assert torch.all(out[:, k:] == 7.0)
 
 
+@pytest.mark.parametrize("N,k,ld", [(1000, 576, 577), (1510, 576, 579), (1000, 300, 301), (2020, 1100, 1101), (16390, 576, 577)])
+def test_fim_short_inputs_with_unaligned_rows(grass, N, k, ld):
+    """Rows that are not 16-byte aligned go through transposed chunks; a first chunk too short for all the K ranges the
+    workspace was laid out for must only sum the partial products it wrote (row counts just below a multiple of 512 are
+    the case), and a short last chunk after a full one adds to a subset of them."""
+    big = synth.compressed_gradients(N, ld, seed=2200 + k, device=_dev())
+    G = big[:, :k]
+    F = grass.grass_fim(G)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(F).all()) and torch.equal(F, F.T)
+    assert orc.max_rel_err(F.cpu().numpy(), orc.fim(G.cpu().numpy())) <= 1e-5
+
+
 def _inverse_case(k, lam, seed, N=None):
     N = N or 2 * k + 3
     G = synth.compressed_gradients(N, k, seed=seed, device="cpu").numpy().astype(np.float64)
