@@ -252,6 +252,12 @@ __global__ void __launch_bounds__(kBf16Threads) gemm_dma_kernel(GemmDmaArgs a) {
         while (tm * (tm + 1) / 2 > logical) --tm;
         while ((tm + 1) * (tm + 2) / 2 <= logical) ++tm;
         tn = logical - tm * (tm + 1) / 2;
+    } else if (total % 256 == 0 && a.tiles_m % 8 == 0 && a.tiles_n % 4 == 0 && a.tiles_m >= 16) {
+        // Tall products: the 32 tiles that run on an XCD at a time form a block of 8 x 4 tiles (12 operand tiles
+        // for its L2 to hold per K group) instead of a run of 32 along M (33 operand tiles).
+        const uint32_t block = logical >> 5, within = logical & 31, blocks_m = a.tiles_m / 8;
+        tm = (block % blocks_m) * 8 + (within & 7);
+        tn = (block / blocks_m) * 4 + (within >> 3);
     } else {
         tn = logical / a.tiles_m;
         tm = logical % a.tiles_m;

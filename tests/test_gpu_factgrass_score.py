@@ -238,7 +238,8 @@ def test_logra_with_selection_matrices_matches_factgrass_mask_stage(grass):
 SCORE_CASES = [(1, 1, 1), (5, 3, 7), (130, 129, 33), (256, 128, 64), (300, 200, 1000), (1024, 512, 4096), (257, 64, 70),
                (200, 130, 8192), (130, 129, 12304), (129, 3, 5000),      # few tiles, long K: split over K ranges
                (128, 128, 16), (256, 256, 48), (384, 130, 4112),         # an odd number of 64-byte slices: half group last
-               (1000, 128, 8192), (700, 100, 4096), (400, 300, 4096), (2048, 384, 1040), (513, 257, 4112)]   # few test rows: 128 x 384 tiles
+               (1000, 128, 8192), (700, 100, 4096), (400, 300, 4096), (2048, 384, 1040), (513, 257, 4112),   # few test rows: 128 x 384 tiles
+               (4096, 4096, 96), (2048, 8192, 64)]      # many tile rows: tiles dealt to the XCDs in blocks of 8 x 4
 
 
 @pytest.mark.parametrize("N,M,K", SCORE_CASES)
@@ -260,7 +261,8 @@ def test_score_parity(grass, N, M, K, mode, with_ws):
 
 
 BF16_SCORE_CASES = [(1, 1, 8), (300, 200, 1000), (256, 256, 64), (257, 255, 72), (1024, 512, 4096), (700, 1024, 136),
-                    (256, 256, 32), (300, 260, 96), (384, 130, 4128)]       # odd numbers of 64-byte slices
+                    (256, 256, 32), (300, 260, 96), (384, 130, 4128),       # odd numbers of 64-byte slices
+                    (4096, 4096, 128), (1024, 16384, 64)]                   # many tile rows (blocks of 8 x 4 tiles per XCD)
 
 
 @pytest.mark.parametrize("N,M,K", BF16_SCORE_CASES)
